@@ -1,0 +1,155 @@
+/*
+ * helix_attn.h -- C ABI of the MI355X (gfx950) library for the attention phase of Helix Parallelism.
+ *
+ * What the calls compute (Helix Parallelism, Sec. 2.1.1 "KV partitioning (KVP)", Fig. 4 top,
+ * Sec. 2.2 first paragraphs): during decode every KVP rank holds one slice of the KV cache along
+ * the sequence dimension, runs exact softmax attention of the single new query token against its
+ * slice, and emits a partial attention output plus one log-sum-exp scalar per (token, head); the
+ * fragments of all ranks are then rescaled by their log-sum-exp and summed, which reconstructs the
+ * exact softmax-normalised attention over the unsharded cache.  Q query heads share K KV heads
+ * (GQA/MQA) or a single latent that is both key and value (MLA) (Sec. 1, Sec. 3).
+ *
+ *     partial, per shard i, sequence b, query head h (kv head = h / (Q/K)):
+ *         s_t   = scale * <q[b,h,:], k_i[b,kv,t,:]>                  t in the shard
+ *         lse_i = ln sum_t exp(s_t)                                   natural log, scale inside
+ *         O_i   = sum_t exp(s_t - lse_i) * v_i[b,kv,t,:]              normalised within the shard
+ *     combine:
+ *         w_i = exp(lse_i - max_j lse_j) ;  O = sum_i w_i O_i / sum_i w_i ;
+ *         LSE = max_j lse_j + ln sum_i w_i
+ *
+ * No causal mask: the one decode query attends to every token a shard holds (the new token's K/V
+ * is appended before attention, Sec. 2.3).
+ *
+ * General conventions
+ *   - All pointers are DEVICE pointers unless a parameter says "host".  The structs themselves
+ *     (helix_problem, helix_kv_shard, the shard array) are host memory, read during the call.
+ *   - The caller owns every buffer, including the workspace.  The library allocates nothing,
+ *     never synchronises, never reads device memory from the host; all work is enqueued on the
+ *     HIP stream passed as `hip_stream` (a hipStream_t; NULL = the default stream).
+ *   - Every call returns a helix_status.  Arguments are validated on the host before anything
+ *     is launched, so an error return means no kernel ran.
+ *   - Supported shapes: (dk,dv) = (64,64) or (128,128) with bf16 K/V and any Q/K group size
+ *     (the GQA path), and (dk,dv) = (576,512) with v_aliases_k = 1, kv_heads = 1, bf16 or
+ *     e4m3 + per-token fp32 scale (the MLA path).  q is always bf16.
+ *   - Alignment: q, k, v rows must start on 16-byte boundaries: base pointers 16-byte aligned and
+ *     all strides multiples of 16 bytes.
+ */
+#ifndef HELIX_ATTN_H
+#define HELIX_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HELIX_OK = 0,
+    HELIX_ERR_NULL = 1,        /* a required pointer is NULL */
+    HELIX_ERR_SHAPE = 2,       /* sizes, strides or alignment that make no sense */
+    HELIX_ERR_UNSUPPORTED = 3, /* a combination the kernels do not implement */
+    HELIX_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or smaller than helix_attn_workspace_bytes */
+    HELIX_ERR_LAUNCH = 5       /* the HIP runtime refused a launch */
+} helix_status;
+
+typedef enum {
+    HELIX_KV_BF16 = 0,
+    HELIX_KV_FP8_E4M3 = 1      /* OCP e4m3 codes, value = code * kv_scale[token] */
+} helix_kv_dtype;
+
+#define HELIX_MAX_SHARDS 1024
+
+/* The problem of Sec. 1 / Appendix A: B sequences, Q query heads sharing K KV heads. */
+typedef struct helix_problem {
+    int32_t batch;        /* B >= 1 */
+    int32_t q_heads;      /* Q >= 1 */
+    int32_t kv_heads;     /* K >= 1, Q % K == 0; query head h reads kv head h / (Q/K) */
+    int32_t dk;           /* key / query width */
+    int32_t dv;           /* value width */
+    int32_t v_aliases_k;  /* 1 = MLA latent: the value row is the first dv entries of the key row */
+    int32_t kv_dtype;     /* helix_kv_dtype */
+    float scale;          /* softmax scale, multiplies q.k before the exponential; finite, > 0 */
+    int32_t split_tokens; /* 0 = automatic.  Otherwise the number of shard tokens one workgroup
+                             streams (rounded up to the kernel's block size): a tuning knob that
+                             changes neither results' meaning nor the workspace formula's validity */
+} helix_problem;
+
+/* One KV-sequence shard = the slice of the cache one KVP rank holds (Sec. 2.1.1).
+ * Key element (b, kh, t, d), t counted from the shard's first token of sequence b, lives at
+ *     k + b*k_stride_b + kh*k_stride_h + (tok_off[b] + t)*k_stride_t + d        (in elements)
+ * and values / scales follow the same scheme with their own strides (scale: token stride 1). */
+typedef struct helix_kv_shard {
+    const void *k;          /* bf16 or e4m3 */
+    const void *v;          /* same dtype; must be NULL iff v_aliases_k */
+    const float *kv_scale;  /* e4m3 only: one fp32 per (b, kh, token); NULL for bf16 */
+    int64_t k_stride_b, k_stride_h, k_stride_t;
+    int64_t v_stride_b, v_stride_h, v_stride_t;
+    int64_t s_stride_b, s_stride_h;
+    const int64_t *tok_off; /* [B] row of the shard's first token of sequence b (ragged / packed
+                               storage, or a view into an unsharded cache); NULL = 0 */
+    const int32_t *len;     /* [B] tokens of sequence b in THIS shard; 0 is allowed */
+    int32_t max_len;        /* host copy of an upper bound of len[b] (sizes the grid); >= 0 */
+} helix_kv_shard;
+
+/* Bytes of workspace helix_attn_partial / helix_attn_decode need for `n_shards` shards whose
+ * max_len are all <= `max_len`.  Returns 0 if the problem is invalid or unsupported.
+ * The workspace must be 256-byte aligned; its contents are scratch. */
+size_t helix_attn_workspace_bytes(const helix_problem *problem, int32_t n_shards, int32_t max_len);
+
+/* Sec. 2.1.1: one rank's work.  Attention of q over one shard.
+ *   q          bf16 [B,Q,dk] contiguous
+ *   o_partial  fp32 [B,Q,dv]: O_i, normalised within the shard (zeros where len[b] == 0)
+ *   lse        fp32 [B,Q]: lse_i (-inf where len[b] == 0)                                   */
+int helix_attn_partial(const helix_problem *problem, const void *q, const helix_kv_shard *shard,
+                       float *o_partial, float *lse,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Sec. 2.1.1 / Sec. 2.2: the rescale-and-sum every rank applies to the fragments it received.
+ * Only batch, q_heads and dv of `problem` are read.
+ *   o_partials    fp32 [N,B,Q,dv],  lses fp32 [N,B,Q]
+ *   o             fp32 [B,Q,dv]
+ *   lse_out       fp32 [B,Q] or NULL: LSE of the whole context
+ *   argmax_shard  int32 [B,Q] or NULL: lowest shard index holding the largest lses value (0 if all
+ *                 are -inf); decided on the fp32 values as stored
+ * Shards with lse = -inf get weight 0 whatever their partial holds; if all are -inf, o = 0 and
+ * lse_out = -inf.  May run in place on nothing: o must not overlap o_partials. */
+int helix_attn_combine(const helix_problem *problem, int32_t n_shards,
+                       const float *o_partials, const float *lses,
+                       float *o, float *lse_out, int32_t *argmax_shard, void *hip_stream);
+
+/* Whole decode attention on one GPU: helix_attn_partial for each of the N shards (one launch),
+ * then helix_attn_combine.  n_shards == 1 is attention over an unsharded cache (the short-context
+ * degenerate case KVP = 1, Sec. 5).
+ *   shards      host array [N]
+ *   o           fp32 [B,Q,dv]
+ *   lse_out     fp32 [B,Q] or NULL
+ *   o_partials  fp32 [N,B,Q,dv] or NULL, lses fp32 [N,B,Q] or NULL: the per-shard fragments a rank
+ *               would send; both or neither.  When NULL they live in the workspace. */
+int helix_attn_decode(const helix_problem *problem, const void *q,
+                      const helix_kv_shard *shards, int32_t n_shards,
+                      float *o, float *lse_out, float *o_partials, float *lses,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Sec. 2.1.1: the contiguous KVP cut of every sequence into N slices, as device-side integer
+ * bookkeeping.  Slice width c_b = 16 * ceil(ceil(L_b / N) / 16) tokens (whole 16-token blocks, the
+ * append granule of Sec. 2.3); shard i of sequence b = [min(i*c_b, L_b), min((i+1)*c_b, L_b)).
+ *   seq_len    int32 [B], every entry >= 0
+ *   seq_base   int64 [B] or NULL: row of sequence b's first token in packed storage, added to the
+ *              offsets so that shard_off can serve directly as helix_kv_shard.tok_off
+ *   shard_off  int64 [N,B],  shard_len int32 [N,B]                                           */
+int helix_shard_layout(const int32_t *seq_len, const int64_t *seq_base, int32_t batch,
+                       int32_t n_shards, int64_t *shard_off, int32_t *shard_len, void *hip_stream);
+
+/* How the library would cut the work: tokens per workgroup and workgroups of the attention launch
+ * for the given shards' max_len (host array [N]).  For benchmarks and tests; launches nothing. */
+int helix_attn_plan(const helix_problem *problem, const int32_t *max_lens, int32_t n_shards,
+                    int32_t *split_tokens, int64_t *workgroups);
+
+/* Static, NUL-terminated description of a status code. */
+const char *helix_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HELIX_ATTN_H */

@@ -1,0 +1,247 @@
+"""ctypes binding of include/helix_attn.h: same names, argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch provides device memory and the current stream); every
+step of the path runs inside the library's kernels.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import torch
+
+KV_BF16 = 0
+KV_FP8_E4M3 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libhelix_attn.so")
+_lib = None
+
+
+class HelixError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({helix_status_string(status)})")
+
+
+class _CProblem(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("q_heads", ctypes.c_int32), ("kv_heads", ctypes.c_int32),
+                ("dk", ctypes.c_int32), ("dv", ctypes.c_int32), ("v_aliases_k", ctypes.c_int32),
+                ("kv_dtype", ctypes.c_int32), ("scale", ctypes.c_float), ("split_tokens", ctypes.c_int32)]
+
+
+class _CShard(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("kv_scale", ctypes.c_void_p),
+                ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_t", ctypes.c_int64),
+                ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
+                ("s_stride_b", ctypes.c_int64), ("s_stride_h", ctypes.c_int64),
+                ("tok_off", ctypes.c_void_p), ("len", ctypes.c_void_p), ("max_len", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libhelix_attn.so (built by ``paper_2507_07120_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is not built: run `python -m paper_2507_07120_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.helix_status_string.restype = ctypes.c_char_p
+    lib.helix_status_string.argtypes = [ctypes.c_int]
+    lib.helix_attn_workspace_bytes.restype = ctypes.c_size_t
+    lib.helix_attn_workspace_bytes.argtypes = [ctypes.POINTER(_CProblem), i32, i32]
+    lib.helix_attn_plan.restype = ctypes.c_int
+    lib.helix_attn_plan.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(i32), i32,
+                                    ctypes.POINTER(i32), ctypes.POINTER(i64)]
+    lib.helix_attn_partial.restype = ctypes.c_int
+    lib.helix_attn_partial.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), vp, vp,
+                                       vp, ctypes.c_size_t, vp]
+    lib.helix_attn_combine.restype = ctypes.c_int
+    lib.helix_attn_combine.argtypes = [ctypes.POINTER(_CProblem), i32, vp, vp, vp, vp, vp, vp]
+    lib.helix_attn_decode.restype = ctypes.c_int
+    lib.helix_attn_decode.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), i32,
+                                      vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.helix_shard_layout.restype = ctypes.c_int
+    lib.helix_shard_layout.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def helix_status_string(status: int) -> str:
+    return load_library().helix_status_string(int(status)).decode()
+
+
+@dataclass
+class Problem:
+    """helix_problem: B sequences, Q query heads sharing K KV heads (or one MLA latent)."""
+    batch: int
+    q_heads: int
+    kv_heads: int
+    dk: int
+    dv: int
+    scale: float
+    v_aliases_k: bool = False
+    kv_dtype: int = KV_BF16
+    split_tokens: int = 0
+
+    def c(self) -> _CProblem:
+        return _CProblem(self.batch, self.q_heads, self.kv_heads, self.dk, self.dv, int(self.v_aliases_k),
+                         self.kv_dtype, self.scale, self.split_tokens)
+
+
+@dataclass
+class KVShard:
+    """helix_kv_shard.  ``k``/``v`` are device tensors whose element (b,kh,t,d) sits at
+    data_ptr + (b*stride_b + kh*stride_h + (tok_off[b]+t)*stride_t + d) elements."""
+    k: torch.Tensor
+    v: Optional[torch.Tensor]
+    len: torch.Tensor                      # int32 [B] on the device
+    max_len: int
+    k_strides: Sequence[int]               # (b, h, t) in elements
+    v_strides: Sequence[int] = (0, 0, 0)
+    kv_scale: Optional[torch.Tensor] = None
+    s_strides: Sequence[int] = (0, 0)
+    tok_off: Optional[torch.Tensor] = None  # int64 [B] on the device
+
+    @staticmethod
+    def from_padded(k: torch.Tensor, v: Optional[torch.Tensor], lens: torch.Tensor, max_len: int,
+                    tok_off: Optional[torch.Tensor] = None, kv_scale: Optional[torch.Tensor] = None) -> "KVShard":
+        """k [B,K,S,dk] (v [B,K,S,dv] or None for MLA, kv_scale [B,K,S]) possibly strided views."""
+        assert k.dim() == 4 and k.stride(3) == 1
+        vs = (0, 0, 0)
+        if v is not None:
+            assert v.dim() == 4 and v.stride(3) == 1
+            vs = (v.stride(0), v.stride(1), v.stride(2))
+        ss = (0, 0)
+        if kv_scale is not None:
+            assert kv_scale.dim() == 3 and kv_scale.stride(2) == 1
+            ss = (kv_scale.stride(0), kv_scale.stride(1))
+        return KVShard(k, v, lens, int(max_len), (k.stride(0), k.stride(1), k.stride(2)), vs, kv_scale, ss, tok_off)
+
+    @staticmethod
+    def from_packed(k: torch.Tensor, lens: torch.Tensor, max_len: int, tok_off: torch.Tensor,
+                    kv_scale: Optional[torch.Tensor] = None) -> "KVShard":
+        """k [rows, dk] packed token rows of all sequences (single latent head); the value aliases the key."""
+        assert k.dim() == 2 and k.stride(1) == 1
+        return KVShard(k, None, lens, int(max_len), (0, 0, k.stride(0)), (0, 0, 0), kv_scale, (0, 0), tok_off)
+
+    def c(self) -> _CShard:
+        def ptr(t):
+            return None if t is None else t.data_ptr()
+        assert self.len.dtype == torch.int32 and self.len.is_contiguous()
+        if self.tok_off is not None:
+            assert self.tok_off.dtype == torch.int64 and self.tok_off.is_contiguous()
+        if self.kv_scale is not None:
+            assert self.kv_scale.dtype == torch.float32
+        return _CShard(ptr(self.k), ptr(self.v), ptr(self.kv_scale), *[int(x) for x in self.k_strides],
+                       *[int(x) for x in self.v_strides], *[int(x) for x in self.s_strides],
+                       ptr(self.tok_off), ptr(self.len), int(self.max_len))
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise HelixError(status, where)
+
+
+def _f32(t: torch.Tensor, shape, name: str):
+    assert t.dtype == torch.float32 and t.is_contiguous() and tuple(t.shape) == tuple(shape), \
+        f"{name}: expected contiguous float32 {tuple(shape)}, got {t.dtype} {tuple(t.shape)}"
+
+
+def helix_attn_workspace_bytes(problem: Problem, n_shards: int, max_len: int) -> int:
+    p = problem.c()
+    return int(load_library().helix_attn_workspace_bytes(ctypes.byref(p), n_shards, max_len))
+
+
+def helix_attn_plan(problem: Problem, max_lens: Sequence[int]):
+    """(split_tokens, workgroups) the library would use; launches nothing."""
+    p = problem.c()
+    arr = (ctypes.c_int32 * len(max_lens))(*[int(x) for x in max_lens])
+    st, wg = ctypes.c_int32(0), ctypes.c_int64(0)
+    _check(load_library().helix_attn_plan(ctypes.byref(p), arr, len(max_lens), ctypes.byref(st), ctypes.byref(wg)),
+           "helix_attn_plan")
+    return st.value, wg.value
+
+
+def helix_attn_partial(problem: Problem, q: torch.Tensor, shard: KVShard, o_partial: torch.Tensor,
+                       lse: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    assert q.dtype == torch.bfloat16 and q.is_contiguous()
+    assert tuple(q.shape) == (problem.batch, problem.q_heads, problem.dk)
+    _f32(o_partial, (problem.batch, problem.q_heads, problem.dv), "o_partial")
+    _f32(lse, (problem.batch, problem.q_heads), "lse")
+    p, s = problem.c(), shard.c()
+    _check(load_library().helix_attn_partial(ctypes.byref(p), q.data_ptr(), ctypes.byref(s), o_partial.data_ptr(),
+                                             lse.data_ptr(), workspace.data_ptr(),
+                                             workspace.numel() * workspace.element_size(), _stream_ptr(stream)),
+           "helix_attn_partial")
+
+
+def helix_attn_combine(problem: Problem, o_partials: torch.Tensor, lses: torch.Tensor, o: torch.Tensor,
+                       lse_out: Optional[torch.Tensor] = None, argmax_shard: Optional[torch.Tensor] = None,
+                       stream=None) -> None:
+    n = o_partials.shape[0]
+    _f32(o_partials, (n, problem.batch, problem.q_heads, problem.dv), "o_partials")
+    _f32(lses, (n, problem.batch, problem.q_heads), "lses")
+    _f32(o, (problem.batch, problem.q_heads, problem.dv), "o")
+    if lse_out is not None:
+        _f32(lse_out, (problem.batch, problem.q_heads), "lse_out")
+    if argmax_shard is not None:
+        assert argmax_shard.dtype == torch.int32 and argmax_shard.is_contiguous()
+        assert tuple(argmax_shard.shape) == (problem.batch, problem.q_heads)
+    p = problem.c()
+    _check(load_library().helix_attn_combine(ctypes.byref(p), n, o_partials.data_ptr(), lses.data_ptr(), o.data_ptr(),
+                                             None if lse_out is None else lse_out.data_ptr(),
+                                             None if argmax_shard is None else argmax_shard.data_ptr(),
+                                             _stream_ptr(stream)),
+           "helix_attn_combine")
+
+
+def helix_attn_decode(problem: Problem, q: torch.Tensor, shards: Sequence[KVShard], o: torch.Tensor,
+                      workspace: torch.Tensor, lse_out: Optional[torch.Tensor] = None,
+                      o_partials: Optional[torch.Tensor] = None, lses: Optional[torch.Tensor] = None,
+                      stream=None) -> None:
+    n = len(shards)
+    assert q.dtype == torch.bfloat16 and q.is_contiguous()
+    assert tuple(q.shape) == (problem.batch, problem.q_heads, problem.dk)
+    _f32(o, (problem.batch, problem.q_heads, problem.dv), "o")
+    if lse_out is not None:
+        _f32(lse_out, (problem.batch, problem.q_heads), "lse_out")
+    if o_partials is not None:
+        _f32(o_partials, (n, problem.batch, problem.q_heads, problem.dv), "o_partials")
+    if lses is not None:
+        _f32(lses, (n, problem.batch, problem.q_heads), "lses")
+    p = problem.c()
+    arr = (_CShard * n)(*[s.c() for s in shards])
+    _check(load_library().helix_attn_decode(ctypes.byref(p), q.data_ptr(), arr, n, o.data_ptr(),
+                                            None if lse_out is None else lse_out.data_ptr(),
+                                            None if o_partials is None else o_partials.data_ptr(),
+                                            None if lses is None else lses.data_ptr(),
+                                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                            _stream_ptr(stream)),
+           "helix_attn_decode")
+
+
+def helix_shard_layout(seq_len: torch.Tensor, n_shards: int, shard_off: torch.Tensor, shard_len: torch.Tensor,
+                       seq_base: Optional[torch.Tensor] = None, stream=None) -> None:
+    B = seq_len.numel()
+    assert seq_len.dtype == torch.int32 and seq_len.is_contiguous()
+    assert shard_off.dtype == torch.int64 and shard_off.is_contiguous() and tuple(shard_off.shape) == (n_shards, B)
+    assert shard_len.dtype == torch.int32 and shard_len.is_contiguous() and tuple(shard_len.shape) == (n_shards, B)
+    if seq_base is not None:
+        assert seq_base.dtype == torch.int64 and seq_base.is_contiguous() and seq_base.numel() == B
+    _check(load_library().helix_shard_layout(seq_len.data_ptr(), None if seq_base is None else seq_base.data_ptr(),
+                                             B, n_shards, shard_off.data_ptr(), shard_len.data_ptr(),
+                                             _stream_ptr(stream)),
+           "helix_shard_layout")

@@ -1,0 +1,87 @@
+// Shared device-side types and helpers of the gfx950 decode-attention kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace helix {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kMaxLaunchShards = 16;   // shard descriptors travel by value in the kernel arguments
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// One KV shard as the kernels see it (Sec. 2.1.1: the slice of the cache one KVP rank holds).
+struct ShardDev {
+    const void* k;
+    const void* v;
+    const float* kv_scale;
+    const int64_t* tok_off;
+    const int32_t* len;
+    int64_t k_sb, k_sh, k_st;
+    int64_t v_sb, v_sh, v_st;
+    int64_t s_sb, s_sh;
+    int32_t split_base;   // index of this shard's first split among all splits of the call
+    int32_t n_splits;     // ceil(max_len / split_tokens)
+    int32_t unit_base;    // first workgroup of this shard in the launch
+    int32_t pad;
+};
+
+// Arguments of an attention launch over up to kMaxLaunchShards shards.
+struct AttnArgs {
+    const uint16_t* q;    // bf16 [B,Q,dk]
+    float* ws_o;          // split records: un-normalised sum_t p_t v_t, [split][B][Q][dv]
+    float* ws_m;          // integer power-of-two reference exponent of the record, [split][B][Q]
+    float* ws_l;          // sum_t p_t, [split][B][Q]
+    int32_t B, Q, K, g;
+    int32_t head_tiles;   // ceil(g / heads per workgroup)
+    int32_t split_tokens; // tokens of a shard one workgroup streams
+    float scale_log2e;    // softmax scale * log2(e)
+    int32_t n_shards;
+    ShardDev shard[kMaxLaunchShards];
+};
+
+__device__ __forceinline__ uint32_t as_u32(float x) { return __builtin_bit_cast(uint32_t, x); }
+__device__ __forceinline__ float as_f32(uint32_t x) { return __builtin_bit_cast(float, x); }
+
+// Two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
+{
+    f32x2 v = {lo, hi};
+    bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
+// 2^(t - m) for an integer-valued m, computed so that the significand of the result depends on t
+// only: 2^frac(t) scaled by the exact power 2^(floor(t) - m).  Different running references m
+// (another shard split, another tile order) therefore give bit-identical weights up to the
+// exponent, which is what keeps sharded and unsharded runs within fp32 summation noise.
+__device__ __forceinline__ float exp2_rel(float t, float m)
+{
+    float fl = __builtin_floorf(t);
+    float e = __builtin_amdgcn_exp2f(t - fl);
+    return __builtin_ldexpf(e, (int)(fl - m));
+}
+
+__device__ __forceinline__ float wave_xor_max_16_32(float x)
+{
+    x = fmaxf(x, __shfl_xor(x, 16));
+    x = fmaxf(x, __shfl_xor(x, 32));
+    return x;
+}
+
+__device__ __forceinline__ float wave_xor_sum_16_32(float x)
+{
+    x += __shfl_xor(x, 16);
+    x += __shfl_xor(x, 32);
+    return x;
+}
+
+}  // namespace helix

@@ -1,0 +1,292 @@
+// Split-KV decode attention for GQA/MQA groups on gfx950: steps "score tile", "online softmax
+// update" and "P.V tile" of the per-shard attention of Helix's attention phase (Sec. 2.1.1), for
+// bf16 K/V with dk == dv in {64, 128}.
+//
+// Work decomposition.  One workgroup (4 wavefronts) streams `split_tokens` consecutive tokens of
+// one (shard, sequence, kv head) and serves up to 16 query heads of that kv head's group.  The
+// four waves take alternating 32-token blocks, each keeping its own running (m, l, O), and merge
+// through LDS at the end into ONE un-normalised record per workgroup; a second small kernel merges
+// the records of a shard (merge_combine.hpp).
+//
+// Data path.  K and V go from HBM straight into the registers of the MFMA that consumes them --
+// the path is HBM-bound (16 flop/byte at a group of 16) and nothing is read twice, so LDS staging
+// would only add a hop.
+//   scores   S^T[token,head] = K[token,:] . Q^T        v_mfma_f32_16x16x32_bf16, A = K rows as
+//            loaded (lane = token r, 8 consecutive dims of k-chunk kc), B = Q held in registers.
+//   weights  p = 2^(s*log2e*scale - m) with an INTEGER running reference m (exp2_rel): rescales of
+//            O and l are exact powers of two and p's significand does not depend on how the
+//            sequence was split.  The accumulator lane that holds a score column holds the same
+//            head's O column, so no cross-lane traffic is needed beyond one 4-lane max.
+//   P.V      O^T[dv,head] += V^T[dv,token] . P^T[token,head].  The A operand needs 8 tokens of ONE
+//            value column per lane, while memory has 8 columns of one token per 16-byte load:
+//            every lane loads the same 8 columns of its 8 tokens (each instruction covers four
+//            full 256-byte rows) and transposes the 8x8 block of 16-bit elements in registers
+//            with v_perm_b32 -- one VALU op per loaded dword.
+//            p is split into bf16 hi + bf16 lo (two MFMAs): a single bf16 rounding of p would
+//            cost ~1.7e-3 relative L2 error on O, above the 1e-3 parity bar; the split leaves ~1e-5.
+#pragma once
+#include "common.hpp"
+
+namespace helix {
+
+template <int D>
+struct GqaCfg {
+    static constexpr int KS = D / 32;    // k-steps of the score MFMA
+    static constexpr int CPL = D / 16;   // value columns per lane
+    static constexpr int VDW = CPL / 2;  // dwords per lane per V token
+    static constexpr int TB = 32;        // tokens per wave block
+};
+
+template <int D>
+struct GqaBlock {
+    bf16x8 k[2][GqaCfg<D>::KS];          // two 16-token score tiles
+    uint32_t v[8][GqaCfg<D>::VDW];       // 8 tokens x CPL columns
+};
+
+template <int N>
+__device__ __forceinline__ void load_dwords(uint32_t (&dst)[N], const char* p)
+{
+    if constexpr (N == 4) {
+        u32x4 t = *reinterpret_cast<const u32x4*>(p);
+        dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w;
+    } else if constexpr (N == 2) {
+        u32x2 t = *reinterpret_cast<const u32x2*>(p);
+        dst[0] = t.x; dst[1] = t.y;
+    } else {
+        static_assert(N == 2 || N == 4, "unsupported value width");
+    }
+}
+
+// Loads the block of 32 tokens starting at shard token `tb`.  kblk / vblk point at the block's
+// first token row (wave-uniform); tokens >= t1 are redirected to the last valid row so that every
+// address stays inside the shard (their weights are forced to zero later).
+template <int D, bool TAIL>
+__device__ __forceinline__ void gqa_load_block(GqaBlock<D>& blk, const char* kblk, const char* vblk,
+                                               uint32_t k_row_bytes, uint32_t v_row_bytes,
+                                               int r, int kc, int n_valid)
+{
+    using C = GqaCfg<D>;
+#pragma unroll
+    for (int a = 0; a < 2; a++) {
+        int tok = a * 16 + r;
+        if (TAIL) tok = min(tok, n_valid - 1);
+        const char* p = kblk + (uint32_t)tok * k_row_bytes + (uint32_t)kc * 16u;
+#pragma unroll
+        for (int s = 0; s < C::KS; s++)
+            blk.k[a][s] = *reinterpret_cast<const bf16x8*>(p + s * 64);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        int tok = (j >> 2) * 16 + kc * 4 + (j & 3);
+        if (TAIL) tok = min(tok, n_valid - 1);
+        const char* p = vblk + (uint32_t)tok * v_row_bytes + (uint32_t)r * (C::CPL * 2);
+        load_dwords<C::VDW>(blk.v[j], p);
+    }
+}
+
+template <int D>
+struct GqaState {
+    float m;                          // integer-valued running reference exponent (or -inf)
+    float l;                          // this lane's share of sum_t p_t for head r
+    f32x4 o[GqaCfg<D>::CPL];          // O^T tiles: o[c][i] = O[head r][dv = (kc*4+i)*CPL + c]
+};
+
+template <int D, bool TAIL>
+__device__ __forceinline__ void gqa_compute_block(GqaState<D>& st, const GqaBlock<D>& blk,
+                                                  const bf16x8 (&qb)[GqaCfg<D>::KS],
+                                                  float scale_log2e, int kc, int n_valid)
+{
+    using C = GqaCfg<D>;
+    // scores: lane (r,kc) gets head r, tokens a*16 + kc*4 + i
+    float t[8];
+#pragma unroll
+    for (int a = 0; a < 2; a++) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < C::KS; s++)
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(blk.k[a][s], qb[s], acc, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; i++) t[a * 4 + i] = acc[i] * scale_log2e;
+    }
+    bool valid[8];
+    if (TAIL) {
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+            valid[e] = ((e >> 2) * 16 + kc * 4 + (e & 3)) < n_valid;
+            t[e] = valid[e] ? t[e] : -INFINITY;
+        }
+    }
+    float bmax = t[0];
+#pragma unroll
+    for (int e = 1; e < 8; e++) bmax = fmaxf(bmax, t[e]);
+    bmax = wave_xor_max_16_32(bmax);
+    const float m_new = fmaxf(st.m, __builtin_ceilf(bmax));
+    if (__any(m_new != st.m)) {
+        const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);   // exact power of two, 0 from -inf
+        st.l *= alpha;
+#pragma unroll
+        for (int c = 0; c < C::CPL; c++) st.o[c] *= alpha;
+        st.m = m_new;
+    }
+    // weights and their bf16 hi/lo split, packed as the MFMA's B operand (8 tokens of head r)
+    uint32_t phi[4], plo[4];
+    float lsum = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        float p0, p1;
+        if (TAIL) {
+            p0 = valid[e] ? exp2_rel(t[e], m_new) : 0.f;
+            p1 = valid[e + 1] ? exp2_rel(t[e + 1], m_new) : 0.f;
+        } else {
+            p0 = exp2_rel(t[e], m_new);
+            p1 = exp2_rel(t[e + 1], m_new);
+        }
+        const uint32_t h = pack_bf16_rne(p0, p1);
+        const float r0 = p0 - as_f32(h << 16);
+        const float r1 = p1 - as_f32(h & 0xffff0000u);
+        const uint32_t lo = pack_bf16_rne(r0, r1);
+        phi[e >> 1] = h;
+        plo[e >> 1] = lo;
+        // l sums exactly what the MFMAs will see, so O/l carries no bias from the split
+        lsum += (as_f32(h << 16) + as_f32(lo << 16)) + (as_f32(h & 0xffff0000u) + as_f32(lo & 0xffff0000u));
+    }
+    st.l += lsum;
+    const bf16x8 bhi = __builtin_bit_cast(bf16x8, u32x4{phi[0], phi[1], phi[2], phi[3]});
+    const bf16x8 blo = __builtin_bit_cast(bf16x8, u32x4{plo[0], plo[1], plo[2], plo[3]});
+    // P.V: transpose this lane's 8 tokens x CPL columns into CPL operands of 8 tokens each
+#pragma unroll
+    for (int c = 0; c < C::CPL; c++) {
+        const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+        u32x4 a;
+        a.x = __builtin_amdgcn_perm(blk.v[1][c >> 1], blk.v[0][c >> 1], sel);
+        a.y = __builtin_amdgcn_perm(blk.v[3][c >> 1], blk.v[2][c >> 1], sel);
+        a.z = __builtin_amdgcn_perm(blk.v[5][c >> 1], blk.v[4][c >> 1], sel);
+        a.w = __builtin_amdgcn_perm(blk.v[7][c >> 1], blk.v[6][c >> 1], sel);
+        const bf16x8 va = __builtin_bit_cast(bf16x8, a);
+        st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bhi, st.o[c], 0, 0, 0);
+        st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, blo, st.o[c], 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ float max_of_waves(const float (&m)[4][16], int r)
+{
+    return fmaxf(fmaxf(m[0][r], m[1][r]), fmaxf(m[2][r], m[3][r]));
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void gqa_decode_kernel(const AttnArgs a)
+{
+    using C = GqaCfg<D>;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, kc = lane >> 4;
+
+    // which (shard, split, sequence, kv head, head tile) this workgroup serves
+    int u = blockIdx.x, si = 0;
+    while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
+    const ShardDev& sh = a.shard[si];
+    u -= sh.unit_base;
+    const int split = u % sh.n_splits;
+    int rest = u / sh.n_splits;
+    const int ht = rest % a.head_tiles; rest /= a.head_tiles;
+    const int kh = rest % a.K;
+    const int b = rest / a.K;
+
+    const int len = sh.len[b];
+    const int t0 = split * a.split_tokens;
+    const int t1 = min(t0 + a.split_tokens, len);
+    const int h0 = kh * a.g + ht * 16;
+    const int nh = min(16, a.g - ht * 16);
+    const size_t rec = ((size_t)(sh.split_base + split) * a.B + b) * a.Q + h0;
+
+    if (t0 >= len) {              // nothing to attend to: an empty record
+        if (tid < nh) { a.ws_m[rec + tid] = -INFINITY; a.ws_l[rec + tid] = 0.f; }
+        return;
+    }
+
+    // Q as the score MFMA's B operand: lane (r,kc) holds head r, dims s*32 + kc*8 .. +8
+    bf16x8 qb[C::KS];
+    {
+        const uint16_t* qrow = a.q + ((size_t)b * a.Q + h0 + min(r, nh - 1)) * D + kc * 8;
+#pragma unroll
+        for (int s = 0; s < C::KS; s++) {
+            u32x4 w = *reinterpret_cast<const u32x4*>(qrow + s * 32);
+            if (r >= nh) w = u32x4{0, 0, 0, 0};
+            qb[s] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
+    const int64_t tok0 = (sh.tok_off ? sh.tok_off[b] : 0) + t0;
+    const char* kbase = reinterpret_cast<const char*>(sh.k) + 2 * ((int64_t)b * sh.k_sb + (int64_t)kh * sh.k_sh + tok0 * sh.k_st);
+    const char* vbase = reinterpret_cast<const char*>(sh.v) + 2 * ((int64_t)b * sh.v_sb + (int64_t)kh * sh.v_sh + tok0 * sh.v_st);
+    const uint32_t k_row_bytes = (uint32_t)sh.k_st * 2u, v_row_bytes = (uint32_t)sh.v_st * 2u;
+
+    GqaState<D> st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int c = 0; c < C::CPL; c++) st.o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // this wave's blocks: wave, wave+4, wave+8, ... of the split; all but possibly the last are full
+    const int n_tok = t1 - t0;
+    const int n_full = n_tok / C::TB;                 // full blocks in the split
+    const int n_blk = (n_tok + C::TB - 1) / C::TB;
+    const size_t k_blk_bytes = (size_t)C::TB * k_row_bytes, v_blk_bytes = (size_t)C::TB * v_row_bytes;
+
+    GqaBlock<D> b0, b1;
+    int j = wave;
+    // software pipeline over full blocks, two register sets
+    if (j < n_full) gqa_load_block<D, false>(b0, kbase + j * k_blk_bytes, vbase + j * v_blk_bytes, k_row_bytes, v_row_bytes, r, kc, C::TB);
+    while (j < n_full) {
+        const int j1 = j + 4;
+        if (j1 < n_full) gqa_load_block<D, false>(b1, kbase + j1 * k_blk_bytes, vbase + j1 * v_blk_bytes, k_row_bytes, v_row_bytes, r, kc, C::TB);
+        gqa_compute_block<D, false>(st, b0, qb, a.scale_log2e, kc, C::TB);
+        if (j1 >= n_full) { j = j1; break; }
+        const int j2 = j1 + 4;
+        if (j2 < n_full) gqa_load_block<D, false>(b0, kbase + j2 * k_blk_bytes, vbase + j2 * v_blk_bytes, k_row_bytes, v_row_bytes, r, kc, C::TB);
+        gqa_compute_block<D, false>(st, b1, qb, a.scale_log2e, kc, C::TB);
+        j = j2;
+    }
+    // the ragged last block, if any, belongs to wave (n_full % 4)
+    if (n_blk > n_full && (n_full & 3) == wave) {
+        const int nv = n_tok - n_full * C::TB;
+        gqa_load_block<D, true>(b0, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, k_row_bytes, v_row_bytes, r, kc, nv);
+        gqa_compute_block<D, true>(st, b0, qb, a.scale_log2e, kc, nv);
+    }
+
+    // ---- merge the four waves' states into one record ----
+    __shared__ float sm_m[4][16];
+    __shared__ float sm_l[4][16];
+    __shared__ float sm_o[4][16][D];
+    st.l = wave_xor_sum_16_32(st.l);
+    if (kc == 0) { sm_m[wave][r] = st.m; sm_l[wave][r] = st.l; }
+    __syncthreads();
+    const float M = max_of_waves(sm_m, r);
+    const float f = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - M);
+#pragma unroll
+    for (int c = 0; c < C::CPL; c++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) sm_o[wave][r][(kc * 4 + i) * C::CPL + c] = st.o[c][i] * f;
+    __syncthreads();
+    if (tid < nh) {
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; w++) {
+            const float mw = sm_m[w][tid];
+            L += (mw == -INFINITY) ? 0.f : sm_l[w][tid] * __builtin_amdgcn_exp2f(mw - max_of_waves(sm_m, tid));
+        }
+        a.ws_m[rec + tid] = max_of_waves(sm_m, tid);
+        a.ws_l[rec + tid] = L;
+    }
+    float* out = a.ws_o + rec * D;
+    for (int idx = tid * 4; idx < nh * D; idx += 256 * 4) {
+        const int hh = idx / D, col = idx % D;
+        f32x4 s0 = *reinterpret_cast<const f32x4*>(&sm_o[0][hh][col]);
+        f32x4 s1 = *reinterpret_cast<const f32x4*>(&sm_o[1][hh][col]);
+        f32x4 s2 = *reinterpret_cast<const f32x4*>(&sm_o[2][hh][col]);
+        f32x4 s3 = *reinterpret_cast<const f32x4*>(&sm_o[3][hh][col]);
+        *reinterpret_cast<f32x4*>(out + idx) = (s0 + s1) + (s2 + s3);
+    }
+}
+
+}  // namespace helix

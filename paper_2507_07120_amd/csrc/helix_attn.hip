@@ -1,0 +1,340 @@
+// C ABI of the Helix decode-attention library for MI355X (gfx950): host-side validation, work
+// planning, workspace carving and kernel launches.  See include/helix_attn.h for the contract.
+#include "../../include/helix_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "common.hpp"
+#include "gqa_decode.hpp"
+#include "merge_combine.hpp"
+
+namespace {
+
+using namespace helix;
+
+enum class Path { Gqa64, Gqa128, Mla };
+
+struct Plan {
+    Path path;
+    int32_t heads_per_wg;   // query heads one workgroup serves
+    int32_t head_tiles;     // workgroups per (b, kv head) along the group
+    int32_t granule;        // split_tokens is a multiple of this
+    int32_t split_tokens;
+    int64_t total_splits;   // over all shards
+    int64_t workgroups;
+};
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_problem(const helix_problem* p, Path* path)
+{
+    if (!p) return HELIX_ERR_NULL;
+    if (p->batch < 1 || p->q_heads < 1 || p->kv_heads < 1 || p->dk < 1 || p->dv < 1) return HELIX_ERR_SHAPE;
+    if (p->q_heads % p->kv_heads != 0) return HELIX_ERR_SHAPE;
+    if (!(p->scale > 0.f) || !std::isfinite(p->scale)) return HELIX_ERR_SHAPE;
+    if (p->split_tokens < 0) return HELIX_ERR_SHAPE;
+    if (p->kv_dtype != HELIX_KV_BF16 && p->kv_dtype != HELIX_KV_FP8_E4M3) return HELIX_ERR_UNSUPPORTED;
+    if (p->v_aliases_k != 0 && p->v_aliases_k != 1) return HELIX_ERR_SHAPE;
+    if (p->v_aliases_k && p->dv > p->dk) return HELIX_ERR_SHAPE;
+    if ((int64_t)p->batch * p->q_heads > (int64_t)1 << 24) return HELIX_ERR_SHAPE;
+    if (!p->v_aliases_k && p->kv_dtype == HELIX_KV_BF16 && p->dk == p->dv && (p->dk == 64 || p->dk == 128)) {
+        *path = p->dk == 64 ? Path::Gqa64 : Path::Gqa128;
+        return HELIX_OK;
+    }
+    if (p->v_aliases_k && p->dk == 576 && p->dv == 512 && p->kv_heads == 1) {
+        *path = Path::Mla;
+        return HELIX_ERR_UNSUPPORTED;   // MLA kernels are not built yet
+    }
+    return HELIX_ERR_UNSUPPORTED;
+}
+
+// Cuts the launch into workgroups.  The streaming kernels are HBM-bound with no reuse, so the only
+// concerns are enough workgroups to keep all 256 CUs loading (several thousand) and split records
+// that stay small next to the KV bytes a workgroup streams.
+int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_t n, Plan* plan)
+{
+    plan->path = path;
+    plan->heads_per_wg = 16;
+    plan->granule = 128;                                  // 4 waves x 32-token blocks
+    const int g = p->q_heads / p->kv_heads;
+    plan->head_tiles = (int32_t)ceil_div(g, plan->heads_per_wg);
+    const int64_t rows = (int64_t)p->batch * p->kv_heads * plan->head_tiles;
+    int64_t total = 0;
+    for (int i = 0; i < n; i++) {
+        if (max_lens[i] < 0) return HELIX_ERR_SHAPE;
+        total += max_lens[i];
+    }
+    int64_t split;
+    if (p->split_tokens > 0) {
+        split = ceil_div(p->split_tokens, plan->granule) * plan->granule;
+    } else {
+        const int64_t target_wgs = 4096;
+        split = ceil_div(ceil_div(rows * total, target_wgs), plan->granule) * plan->granule;
+        split = std::min<int64_t>(std::max<int64_t>(split, 512), 16384);
+    }
+    plan->split_tokens = (int32_t)split;
+    plan->total_splits = 0;
+    for (int i = 0; i < n; i++) plan->total_splits += std::max<int64_t>(1, ceil_div(max_lens[i], split));
+    plan->workgroups = plan->total_splits * rows;
+    if (plan->workgroups > (int64_t)1 << 30) return HELIX_ERR_SHAPE;
+    return HELIX_OK;
+}
+
+struct Workspace {
+    float* ws_o;
+    float* ws_m;
+    float* ws_l;
+    float* part_o;
+    float* part_lse;
+    size_t bytes;
+};
+
+// Carves a workspace for `total_splits` records and `n` shard partials.  base may be NULL (sizing).
+Workspace carve(const helix_problem* p, int64_t total_splits, int32_t n, void* base)
+{
+    const size_t bq = (size_t)p->batch * p->q_heads;
+    char* c = static_cast<char*>(base);
+    size_t off = 0;
+    Workspace w;
+    w.ws_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * p->dv * 4, 256);
+    w.ws_m = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * 4, 256);
+    w.ws_l = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * 4, 256);
+    w.part_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * p->dv * 4, 256);
+    w.part_lse = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * 4, 256);
+    w.bytes = off;
+    return w;
+}
+
+int check_shard(const helix_problem* p, const helix_kv_shard* s)
+{
+    if (!s->k || !s->len) return HELIX_ERR_NULL;
+    if (p->v_aliases_k ? s->v != nullptr : s->v == nullptr) return p->v_aliases_k ? HELIX_ERR_SHAPE : HELIX_ERR_NULL;
+    const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
+    if (fp8 ? s->kv_scale == nullptr : false) return HELIX_ERR_NULL;
+    if (s->max_len < 0) return HELIX_ERR_SHAPE;
+    const int64_t esz = fp8 ? 1 : 2, mult = 16 / esz;
+    if (s->k_stride_t < p->dk || s->k_stride_t > ((int64_t)1 << 24) || s->k_stride_b < 0 || s->k_stride_h < 0) return HELIX_ERR_SHAPE;
+    if (s->k_stride_t % mult || s->k_stride_b % mult || s->k_stride_h % mult) return HELIX_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(s->k) % 16) return HELIX_ERR_SHAPE;
+    if (!p->v_aliases_k) {
+        if (s->v_stride_t < p->dv || s->v_stride_t > ((int64_t)1 << 24) || s->v_stride_b < 0 || s->v_stride_h < 0) return HELIX_ERR_SHAPE;
+        if (s->v_stride_t % mult || s->v_stride_b % mult || s->v_stride_h % mult) return HELIX_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(s->v) % 16) return HELIX_ERR_SHAPE;
+    }
+    if (fp8 && (s->s_stride_b < 0 || s->s_stride_h < 0)) return HELIX_ERR_SHAPE;
+    return HELIX_OK;
+}
+
+int launch_status()
+{
+    return hipGetLastError() == hipSuccess ? HELIX_OK : HELIX_ERR_LAUNCH;
+}
+
+template <int DV>
+int launch_combine(const float* o_parts, const float* lses, float* o, float* lse_out, int32_t* argmax,
+                   int32_t n, int64_t rows, hipStream_t stream)
+{
+    constexpr int RPB = 256 / (DV / 4);
+    const unsigned grid = (unsigned)ceil_div(rows, RPB);
+    hipLaunchKernelGGL((combine_kernel<DV>), dim3(grid), dim3(256), 0, stream, o_parts, lses, o, lse_out, argmax, n, rows);
+    return launch_status();
+}
+
+int combine_any(int32_t dv, const float* o_parts, const float* lses, float* o, float* lse_out, int32_t* argmax,
+                int32_t n, int64_t rows, hipStream_t stream)
+{
+    switch (dv) {
+        case 64: return launch_combine<64>(o_parts, lses, o, lse_out, argmax, n, rows, stream);
+        case 128: return launch_combine<128>(o_parts, lses, o, lse_out, argmax, n, rows, stream);
+        case 512: return launch_combine<512>(o_parts, lses, o, lse_out, argmax, n, rows, stream);
+        default: return HELIX_ERR_UNSUPPORTED;
+    }
+}
+
+// Attention over `n` shards into per-shard partials (o_part [n,B,Q,dv], lse_part [n,B,Q]).
+int run_partials(const helix_problem* p, const Plan& plan, const void* q, const helix_kv_shard* shards, int32_t n,
+                 const Workspace& ws, float* o_part, float* lse_part, hipStream_t stream)
+{
+    const int g = p->q_heads / p->kv_heads;
+    const int64_t rows = (int64_t)p->batch * p->kv_heads * plan.head_tiles;
+    int32_t split_base = 0;
+    for (int32_t s0 = 0; s0 < n; s0 += kMaxLaunchShards) {
+        const int32_t cnt = std::min<int32_t>(kMaxLaunchShards, n - s0);
+        AttnArgs a;
+        std::memset(&a, 0, sizeof a);
+        MergeArgs m;
+        std::memset(&m, 0, sizeof m);
+        a.q = static_cast<const uint16_t*>(q);
+        a.ws_o = ws.ws_o; a.ws_m = ws.ws_m; a.ws_l = ws.ws_l;
+        a.B = p->batch; a.Q = p->q_heads; a.K = p->kv_heads; a.g = g;
+        a.head_tiles = plan.head_tiles;
+        a.split_tokens = plan.split_tokens;
+        a.scale_log2e = p->scale * kLog2e;
+        a.n_shards = cnt;
+        int64_t units = 0;
+        for (int32_t i = 0; i < cnt; i++) {
+            const helix_kv_shard& s = shards[s0 + i];
+            ShardDev& d = a.shard[i];
+            d.k = s.k; d.v = s.v; d.kv_scale = s.kv_scale; d.tok_off = s.tok_off; d.len = s.len;
+            d.k_sb = s.k_stride_b; d.k_sh = s.k_stride_h; d.k_st = s.k_stride_t;
+            d.v_sb = s.v_stride_b; d.v_sh = s.v_stride_h; d.v_st = s.v_stride_t;
+            d.s_sb = s.s_stride_b; d.s_sh = s.s_stride_h;
+            d.n_splits = (int32_t)std::max<int64_t>(1, ceil_div(s.max_len, plan.split_tokens));
+            d.split_base = split_base;
+            d.unit_base = (int32_t)units;
+            m.split_base[i] = split_base;
+            m.n_splits[i] = d.n_splits;
+            split_base += d.n_splits;
+            units += (int64_t)d.n_splits * rows;
+        }
+        switch (plan.path) {
+            case Path::Gqa64:
+                hipLaunchKernelGGL((gqa_decode_kernel<64>), dim3((unsigned)units), dim3(256), 0, stream, a);
+                break;
+            case Path::Gqa128:
+                hipLaunchKernelGGL((gqa_decode_kernel<128>), dim3((unsigned)units), dim3(256), 0, stream, a);
+                break;
+            default:
+                return HELIX_ERR_UNSUPPORTED;
+        }
+        if (int rc = launch_status()) return rc;
+        m.ws_o = ws.ws_o; m.ws_m = ws.ws_m; m.ws_l = ws.ws_l;
+        m.o_part = o_part; m.lse_part = lse_part;
+        m.B = p->batch; m.Q = p->q_heads; m.n_shards = cnt; m.shard0 = s0;
+        const unsigned mrows = (unsigned)((int64_t)cnt * p->batch * p->q_heads);
+        switch (p->dv) {
+            case 64: hipLaunchKernelGGL((merge_splits_kernel<64>), dim3(mrows), dim3(256), 0, stream, m); break;
+            case 128: hipLaunchKernelGGL((merge_splits_kernel<128>), dim3(mrows), dim3(256), 0, stream, m); break;
+            case 512: hipLaunchKernelGGL((merge_splits_kernel<512>), dim3(mrows), dim3(256), 0, stream, m); break;
+            default: return HELIX_ERR_UNSUPPORTED;
+        }
+        if (int rc = launch_status()) return rc;
+    }
+    return HELIX_OK;
+}
+
+int prepare(const helix_problem* p, const helix_kv_shard* shards, int32_t n, void* workspace, size_t workspace_bytes,
+            Plan* plan, Workspace* ws)
+{
+    Path path;
+    if (int rc = check_problem(p, &path)) return rc;
+    if (!shards) return HELIX_ERR_NULL;
+    if (n < 1 || n > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
+    int32_t max_lens[HELIX_MAX_SHARDS];
+    for (int32_t i = 0; i < n; i++) {
+        if (int rc = check_shard(p, &shards[i])) return rc;
+        max_lens[i] = shards[i].max_len;
+    }
+    if (int rc = make_plan(p, path, max_lens, n, plan)) return rc;
+    *ws = carve(p, plan->total_splits, n, workspace);
+    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || ws->bytes > workspace_bytes) return HELIX_ERR_WORKSPACE;
+    return HELIX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* helix_status_string(int status)
+{
+    switch (status) {
+        case HELIX_OK: return "ok";
+        case HELIX_ERR_NULL: return "a required pointer is NULL";
+        case HELIX_ERR_SHAPE: return "invalid shape, stride or alignment";
+        case HELIX_ERR_UNSUPPORTED: return "unsupported combination of head widths / dtype";
+        case HELIX_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case HELIX_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, int32_t n_shards,
+                    int32_t* split_tokens, int64_t* workgroups)
+{
+    Path path;
+    if (int rc = check_problem(problem, &path)) return rc;
+    if (!max_lens) return HELIX_ERR_NULL;
+    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
+    Plan plan;
+    if (int rc = make_plan(problem, path, max_lens, n_shards, &plan)) return rc;
+    if (split_tokens) *split_tokens = plan.split_tokens;
+    if (workgroups) *workgroups = plan.workgroups;
+    return HELIX_OK;
+}
+
+size_t helix_attn_workspace_bytes(const helix_problem* problem, int32_t n_shards, int32_t max_len)
+{
+    Path path;
+    if (check_problem(problem, &path) != HELIX_OK) return 0;
+    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS || max_len < 0) return 0;
+    // The plan's split count grows when shards are shorter than max_len (smaller splits keep the
+    // workgroup count up), so size for the worst case over all max_len_i <= max_len.
+    int32_t lens[HELIX_MAX_SHARDS];
+    for (int i = 0; i < n_shards; i++) lens[i] = max_len;
+    Plan plan;
+    if (make_plan(problem, path, lens, n_shards, &plan) != HELIX_OK) return 0;
+    const int64_t rows = (int64_t)problem->batch * problem->kv_heads * plan.head_tiles;
+    int64_t worst = plan.total_splits;
+    if (problem->split_tokens == 0) worst = std::max<int64_t>(worst, ceil_div(4096, rows) + n_shards);
+    return carve(problem, worst, n_shards, nullptr).bytes;
+}
+
+int helix_attn_partial(const helix_problem* problem, const void* q, const helix_kv_shard* shard,
+                       float* o_partial, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!q || !o_partial || !lse) return HELIX_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(q) % 16 || reinterpret_cast<uintptr_t>(o_partial) % 16) return HELIX_ERR_SHAPE;
+    Plan plan;
+    Workspace ws;
+    if (int rc = prepare(problem, shard, 1, workspace, workspace_bytes, &plan, &ws)) return rc;
+    return run_partials(problem, plan, q, shard, 1, ws, o_partial, lse, static_cast<hipStream_t>(hip_stream));
+}
+
+int helix_attn_combine(const helix_problem* problem, int32_t n_shards, const float* o_partials, const float* lses,
+                       float* o, float* lse_out, int32_t* argmax_shard, void* hip_stream)
+{
+    if (!problem || !o_partials || !lses || !o) return HELIX_ERR_NULL;
+    if (problem->batch < 1 || problem->q_heads < 1 || n_shards < 1 || n_shards > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(o_partials) % 16 || reinterpret_cast<uintptr_t>(o) % 16) return HELIX_ERR_SHAPE;
+    const int64_t rows = (int64_t)problem->batch * problem->q_heads;
+    return combine_any(problem->dv, o_partials, lses, o, lse_out, argmax_shard, n_shards, rows,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int helix_attn_decode(const helix_problem* problem, const void* q, const helix_kv_shard* shards, int32_t n_shards,
+                      float* o, float* lse_out, float* o_partials, float* lses,
+                      void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!q || !o) return HELIX_ERR_NULL;
+    if ((o_partials == nullptr) != (lses == nullptr)) return HELIX_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(q) % 16 || reinterpret_cast<uintptr_t>(o) % 16 ||
+        reinterpret_cast<uintptr_t>(o_partials) % 16) return HELIX_ERR_SHAPE;
+    Plan plan;
+    Workspace ws;
+    if (int rc = prepare(problem, shards, n_shards, workspace, workspace_bytes, &plan, &ws)) return rc;
+    float* po = o_partials ? o_partials : ws.part_o;
+    float* pl = lses ? lses : ws.part_lse;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (int rc = run_partials(problem, plan, q, shards, n_shards, ws, po, pl, stream)) return rc;
+    const int64_t rows = (int64_t)problem->batch * problem->q_heads;
+    return combine_any(problem->dv, po, pl, o, lse_out, nullptr, n_shards, rows, stream);
+}
+
+int helix_shard_layout(const int32_t* seq_len, const int64_t* seq_base, int32_t batch, int32_t n_shards,
+                       int64_t* shard_off, int32_t* shard_len, void* hip_stream)
+{
+    if (!seq_len || !shard_off || !shard_len) return HELIX_ERR_NULL;
+    if (batch < 1 || n_shards < 1 || n_shards > HELIX_MAX_SHARDS || (int64_t)batch * n_shards > (int64_t)1 << 30) return HELIX_ERR_SHAPE;
+    const int total = batch * n_shards;
+    hipLaunchKernelGGL(helix::shard_layout_kernel, dim3((total + 255) / 256), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), seq_len, seq_base, batch, n_shards, shard_off, shard_len);
+    return launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,99 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments before launching anything (so these run without a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def hx():
+    import paper_2507_07120_amd as hx_
+    if not os.path.exists(hx_.library_path()):
+        from paper_2507_07120_amd import build
+        build.build()
+    hx_.load_library()
+    return hx_
+
+
+def test_every_declared_symbol_is_exported(hx):
+    header = open(os.path.join(ROOT, "include", "helix_attn.h")).read()
+    names = set(re.findall(r"\b(helix_[a-z_]+)\s*\(", header))
+    assert {"helix_attn_partial", "helix_attn_combine", "helix_attn_decode"} <= names
+    lib = ctypes.CDLL(hx.library_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+
+
+def test_status_strings(hx):
+    assert hx.helix_status_string(0) == "ok"
+    assert all(hx.helix_status_string(s) for s in range(0, 7))
+
+
+def test_problem_validation_without_gpu(hx):
+    ok = hx.Problem(16, 16, 1, 128, 128, 0.088)
+    assert hx.helix_attn_workspace_bytes(ok, 1, 131072) > 0
+    split, wgs = hx.helix_attn_plan(ok, [131072])
+    assert split % 128 == 0 and wgs >= 256
+    # Q not a multiple of K, zero batch, bad scale, unsupported widths
+    for bad in [hx.Problem(1, 7, 2, 128, 128, 0.1), hx.Problem(0, 8, 2, 128, 128, 0.1),
+                hx.Problem(1, 8, 2, 128, 128, float("nan")), hx.Problem(1, 8, 2, 128, 128, -1.0),
+                hx.Problem(1, 8, 2, 96, 96, 0.1), hx.Problem(1, 8, 2, 128, 64, 0.1)]:
+        assert hx.helix_attn_workspace_bytes(bad, 1, 1024) == 0
+        with pytest.raises(hx.HelixError):
+            hx.helix_attn_plan(bad, [1024])
+    assert hx.helix_attn_workspace_bytes(ok, 0, 1024) == 0
+    assert hx.helix_attn_workspace_bytes(ok, 1, -5) == 0
+
+
+def test_workspace_bound_covers_shorter_shards(hx):
+    """The sizing call must cover any set of shards no longer than max_len."""
+    lib = hx.load_library()
+    for prob in [hx.Problem(16, 16, 1, 128, 128, 0.088), hx.Problem(4, 64, 8, 128, 128, 0.088),
+                 hx.Problem(1, 8, 2, 64, 64, 0.125), hx.Problem(2, 40, 2, 64, 64, 0.125, split_tokens=256)]:
+        for n, max_len in [(1, 131072), (16, 65536), (4, 1024), (8, 100)]:
+            bound = hx.helix_attn_workspace_bytes(prob, n, max_len)
+            for lens in [[max_len] * n, [max_len // 3] * n, [1] * n, [0] * n, [max_len] + [7] * (n - 1)]:
+                split, wgs = hx.helix_attn_plan(prob, lens)
+                g = prob.q_heads // prob.kv_heads
+                rows = prob.batch * prob.kv_heads * ((g + 15) // 16)
+                splits = wgs // rows
+                need = splits * prob.batch * prob.q_heads * (prob.dv + 2) * 4
+                assert need <= bound, (prob, n, max_len, lens)
+    del lib
+
+
+def test_null_and_shape_errors_return_codes(hx):
+    lib = hx.load_library()
+    p = hx.Problem(1, 8, 2, 64, 64, 0.125).c()
+    # NULL q / outputs: status 1, nothing launched
+    assert lib.helix_attn_partial(ctypes.byref(p), None, None, None, None, None, 0, None) == 1
+    assert lib.helix_attn_combine(ctypes.byref(p), 4, None, None, None, None, None, None) == 1
+    assert lib.helix_attn_decode(ctypes.byref(p), None, None, 4, None, None, None, None, None, 0, None) == 1
+    assert lib.helix_shard_layout(None, None, 4, 4, None, None, None) == 1
+    assert lib.helix_attn_partial(None, 16, None, 16, 16, None, 0, None) == 1
+    # a shard with a NULL key pointer, a misaligned one, a bad stride, a missing workspace
+    from paper_2507_07120_amd.binding import _CShard
+    fake = 0x100000
+    def shard(**kw):
+        d = dict(k=fake, v=fake, kv_scale=None, k_stride_b=0, k_stride_h=64 * 1024, k_stride_t=64,
+                 v_stride_b=0, v_stride_h=64 * 1024, v_stride_t=64, s_stride_b=0, s_stride_h=0,
+                 tok_off=None, len=fake, max_len=1024)
+        d.update(kw)
+        return _CShard(**d)
+    def partial(s, ws=fake, ws_bytes=1 << 30):
+        return lib.helix_attn_partial(ctypes.byref(p), fake, ctypes.byref(s), fake, fake, ws, ws_bytes, None)
+    assert partial(shard(k=None)) == 1
+    assert partial(shard(k=fake + 2)) == 2
+    assert partial(shard(k_stride_t=60)) == 2
+    assert partial(shard(v_stride_t=65)) == 2
+    assert partial(shard(max_len=-1)) == 2
+    assert partial(shard(), ws=None) == 4
+    assert partial(shard(), ws_bytes=16) == 4
+    assert partial(shard(), ws=fake + 8) == 4
+    arr = (_CShard * 1)(shard())
+    assert lib.helix_attn_decode(ctypes.byref(p), fake, arr, 0, fake, None, None, None, fake, 1 << 30, None) == 2
+    assert lib.helix_attn_decode(ctypes.byref(p), fake, arr, 1, fake, None, fake, None, fake, 1 << 30, None) == 1
