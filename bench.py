@@ -1,0 +1,199 @@
+"""Benchmark of the Helix decode-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gqa_share] [--split-tokens T]
+
+One step = one pass of the whole hot path over one batch of synthetic input already resident in
+HBM: the KVP shard layout kernel, the streaming attention over every shard, the merge of the split
+records into per-shard (O_i, lse_i), and the LSE combine.  Prints ONE JSON line.  The metric is the
+achieved HBM rate of KV streaming: algorithmic KV bytes of the step (Appendix A's numerator for the
+workload's shapes) divided by the step time.
+"""
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def kv_bytes_per_step(w, lens) -> int:
+    """Algorithmic bytes: every stored K and V element of every token is read exactly once; an MLA
+    latent row serves as key and value and counts once; fp8 rows carry one fp32 scale."""
+    tokens = int(sum(int(x) for x in lens))
+    if w.mla:
+        per_token = w.dk * (1 if w.fp8 else 2) + (4 if w.fp8 else 0)
+    else:
+        per_token = (w.dk + w.dv) * 2
+    return tokens * w.K * per_token
+
+
+def flops_per_step(w, lens) -> int:
+    tokens = int(sum(int(x) for x in lens))
+    return 2 * (w.dk + w.dv) * tokens * w.Q
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs from the HIP runtime torch loaded (ctypes)."""
+
+    def __init__(self, n):
+        import torch
+        path = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        self.hip = ctypes.CDLL(path)
+        self.start = [ctypes.c_void_p() for _ in range(n)]
+        self.stop = [ctypes.c_void_p() for _ in range(n)]
+        for e in self.start + self.stop:
+            assert self.hip.hipEventCreate(ctypes.byref(e)) == 0
+
+    def elapsed_ms(self, i) -> float:
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.start[i], self.stop[i])
+        assert rc == 0, f"hipEventElapsedTime -> {rc}"
+        return ms.value
+
+    def destroy(self):
+        for e in self.start + self.stop:
+            self.hip.hipEventDestroy(e)
+
+
+def cpu_baseline(w, inp, budget_rows):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same
+    workload: whole (b, h) rows over the full shard length."""
+    import numpy as np
+    import oracle
+    import synth
+    g = w.Q // w.K
+    rows = [(b, h) for b in range(w.B) for h in range(w.Q)]
+    if budget_rows > 0:
+        rows = rows[:budget_rows]
+    nb = rows[-1][0] + 1
+    q = synth.bits(inp.q[:nb])
+    k = synth.bits(inp.k[:nb])
+    v = synth.bits(inp.v[:nb]) if inp.v is not None else None
+    lens = inp.lens[:nb].numpy()
+    t0 = time.perf_counter()
+    oracle.attention(q, k, v, lens, w.scale, kv_heads=w.K, dv=w.dv, rows=rows)
+    dt = time.perf_counter() - t0
+    # bytes the sample stands for: each (b,h) row reads its KV head's tokens; a group of g rows
+    # shares one KV head, so the sample covers len(rows)/g KV-head streams
+    per_token = w.dk * 2 if w.mla else (w.dk + w.dv) * 2
+    sample_bytes = sum(int(lens[b]) for b, _ in rows) * per_token / g
+    return {"value": sample_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{len(rows)} of {w.B * w.Q} (b,h) rows x {int(lens[0])} tokens, fp64, {dt:.1f} s",
+            "seconds": dt}
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gqa_share")
+    ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="(b,h) rows the oracle is timed on; 0 = the whole workload")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all KV shards live on it; there is no collective "
+              "path). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2507_07120_amd as hx
+    import synth
+    from paper_2507_07120_amd import harness
+
+    hx.load_library()                       # raises if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    inp = synth.make_inputs(w, dev)
+    prob = harness.problem_for(w, args.split_tokens)
+    lens_dev = inp.lens.to(dev)
+    seq_base = inp.seq_off[:-1].to(dev) if inp.seq_off is not None else None
+    N = w.n_shards
+    shard_off = torch.empty((N, w.B), dtype=torch.int64, device=dev)
+    shard_len = torch.empty((N, w.B), dtype=torch.int32, device=dev)
+    ss = harness.make_shards(inp.k, inp.v, lens_dev, N, kv_scale=inp.kv_scale, seq_base=seq_base)
+    ws = harness.workspace_for(prob, N, max(ss.max_lens), dev)
+    o = torch.empty((w.B, w.Q, w.dv), device=dev)
+    lse = torch.empty((w.B, w.Q), device=dev)
+    split_tokens, workgroups = hx.helix_attn_plan(prob, ss.max_lens)
+
+    def step():
+        hx.helix_shard_layout(lens_dev, N, shard_off, shard_len, seq_base=seq_base)
+        hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = HipEvents(args.steps)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        hx.helix_attn_set_profile_events(ev.start[i], ev.stop[i])
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    hx.helix_attn_set_profile_events(None, None)
+    kern_ms = sorted(ev.elapsed_ms(i) for i in range(args.steps))
+    ev.destroy()
+    kern_avg_ms = sum(kern_ms) / len(kern_ms)
+
+    ms_per_step = dt / args.steps * 1e3
+    kv_bytes = kv_bytes_per_step(w, inp.lens.tolist())
+    flops = flops_per_step(w, inp.lens.tolist())
+    value = kv_bytes / (ms_per_step * 1e-3) / 1e9
+    bound_mfma = w.mla
+    if bound_mfma:
+        achieved = flops / (kern_avg_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS}
+    else:
+        achieved = kv_bytes / (kern_avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS}
+    roof["traffic"] = read_traffic(args.workload)
+    roof["kernel"] = "mla_decode_kernel" if w.mla else f"gqa_decode_kernel<{w.dk}>"
+    roof["kernel_us_avg"] = kern_avg_ms * 1e3
+    roof["kernel_us_min"] = kern_ms[0] * 1e3
+    roof["algorithmic_bytes"] = kv_bytes
+    roof["hbm_gbs_of_kernel"] = kv_bytes / (kern_avg_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "KV-shard decode attention achieved HBM GB/s (% of peak); us per decode step",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "us_per_step": ms_per_step * 1e3,
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "q_heads": w.Q, "kv_heads": w.K, "dk": w.dk, "dv": w.dv,
+                   "n_shards": N, "tokens_per_step": int(sum(inp.lens.tolist())) * w.K,
+                   "kv_dtype": "e4m3+fp32 scale" if w.fp8 else "bf16",
+                   "split_tokens": split_tokens, "workgroups": workgroups},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, inp, args.cpu_rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

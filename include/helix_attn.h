@@ -146,6 +146,13 @@ int helix_shard_layout(const int32_t *seq_len, const int64_t *seq_base, int32_t 
 int helix_attn_plan(const helix_problem *problem, const int32_t *max_lens, int32_t n_shards,
                     int32_t *split_tokens, int64_t *workgroups);
 
+/* Instrumentation for benchmarks: while both are non-NULL (hipEvent_t handles), every following
+ * helix_attn_partial / helix_attn_decode records `start` immediately before and `stop` immediately
+ * after its streaming attention kernel launches, on the call's stream, so the caller can read that
+ * kernel's duration with hipEventElapsedTime.  Pass NULL, NULL to switch it off (the default).
+ * Process-wide state, not thread-safe; the events stay owned by the caller. */
+int helix_attn_set_profile_events(void *start_event, void *stop_event);
+
 /* Static, NUL-terminated description of a status code. */
 const char *helix_status_string(int status);
 

@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     helix_attn_decode,
     helix_attn_partial,
     helix_attn_plan,
+    helix_attn_set_profile_events,
     helix_attn_workspace_bytes,
     helix_shard_layout,
     helix_status_string,

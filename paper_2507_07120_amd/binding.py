@@ -51,6 +51,13 @@ def load_library():
         raise RuntimeError(f"{_LIB_PATH} is not built: run `python -m paper_2507_07120_amd.build` "
                            "(there is no fallback path)")
     lib = ctypes.CDLL(_LIB_PATH)
+    # torch (imported above) has already loaded its bundled HIP runtime under the soname this
+    # library needs, so both share ONE runtime: torch's stream handles are valid here and
+    # torch.cuda.synchronize() covers the library's kernels.  A second copy would break both.
+    with open("/proc/self/maps") as f:
+        runtimes = {line.split()[-1] for line in f if "libamdhip64" in line}
+    if len(runtimes) != 1:
+        raise RuntimeError(f"expected exactly one HIP runtime in the process, found {sorted(runtimes)}")
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.helix_status_string.restype = ctypes.c_char_p
     lib.helix_status_string.argtypes = [ctypes.c_int]
@@ -69,6 +76,8 @@ def load_library():
                                       vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.helix_shard_layout.restype = ctypes.c_int
     lib.helix_shard_layout.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    lib.helix_attn_set_profile_events.restype = ctypes.c_int
+    lib.helix_attn_set_profile_events.argtypes = [vp, vp]
     _lib = lib
     return lib
 
@@ -245,3 +254,8 @@ def helix_shard_layout(seq_len: torch.Tensor, n_shards: int, shard_off: torch.Te
                                              B, n_shards, shard_off.data_ptr(), shard_len.data_ptr(),
                                              _stream_ptr(stream)),
            "helix_shard_layout")
+
+
+def helix_attn_set_profile_events(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """Raw hipEvent_t handles (or None, None) recorded around the streaming attention kernel."""
+    _check(load_library().helix_attn_set_profile_events(start_event, stop_event), "helix_attn_set_profile_events")

@@ -14,11 +14,24 @@ HIPCC_FLAGS = [
 ]
 
 
+def _torch_lib_dir() -> str:
+    import torch
+    return os.path.join(os.path.dirname(torch.__file__), "lib")
+
+
 def build(verbose: bool = False) -> str:
+    """Compiles csrc/helix_attn.hip for gfx950.
+
+    The library is linked against the HIP runtime that PyTorch ships (torch/lib/libamdhip64.so), not
+    the one under /opt/rocm: callers hand over torch's device pointers and stream handles, and a
+    second copy of the runtime in the process would neither know those streams nor be covered by
+    torch.cuda.synchronize().
+    """
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB, SRC]
+    tl = _torch_lib_dir()
+    cmd = [hipcc] + HIPCC_FLAGS + ["-no-hip-rt", "-o", LIB, SRC, "-L" + tl, "-lamdhip64", "-Wl,-rpath," + tl]
     if verbose:
-        cmd.insert(1, "-save-temps=obj")
+        print(" ".join(cmd))
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(line for line in res.stderr.splitlines() if noise not in line)

@@ -131,6 +131,8 @@ int check_shard(const helix_problem* p, const helix_kv_shard* s)
     return HELIX_OK;
 }
 
+hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;   // helix_attn_set_profile_events
+
 int launch_status()
 {
     return hipGetLastError() == hipSuccess ? HELIX_OK : HELIX_ERR_LAUNCH;
@@ -193,6 +195,7 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             split_base += d.n_splits;
             units += (int64_t)d.n_splits * rows;
         }
+        if (g_prof_start && g_prof_stop && s0 == 0) (void)hipEventRecord(g_prof_start, stream);
         switch (plan.path) {
             case Path::Gqa64:
                 hipLaunchKernelGGL((gqa_decode_kernel<64>), dim3((unsigned)units), dim3(256), 0, stream, a);
@@ -204,6 +207,7 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
                 return HELIX_ERR_UNSUPPORTED;
         }
         if (int rc = launch_status()) return rc;
+        if (g_prof_start && g_prof_stop && s0 + cnt >= n) (void)hipEventRecord(g_prof_stop, stream);
         m.ws_o = ws.ws_o; m.ws_m = ws.ws_m; m.ws_l = ws.ws_l;
         m.o_part = o_part; m.lse_part = lse_part;
         m.B = p->batch; m.Q = p->q_heads; m.n_shards = cnt; m.shard0 = s0;
@@ -252,6 +256,14 @@ const char* helix_status_string(int status)
         case HELIX_ERR_LAUNCH: return "HIP launch failed";
         default: return "unknown status";
     }
+}
+
+int helix_attn_set_profile_events(void* start_event, void* stop_event)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return HELIX_ERR_NULL;
+    g_prof_start = static_cast<hipEvent_t>(start_event);
+    g_prof_stop = static_cast<hipEvent_t>(stop_event);
+    return HELIX_OK;
 }
 
 int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, int32_t n_shards,
