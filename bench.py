@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--workload", default="gqa_share")
     ap.add_argument("--split-tokens", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (torch copy_) before the timed loop, so that a "
+                         "rocprofv3 --pmc run holds a kernel of known traffic to scale the counters by")
     ap.add_argument("--cpu-rows", type=int, default=0, help="(b,h) rows the oracle is timed on; 0 = the whole workload")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -142,6 +145,13 @@ def main():
         hx.helix_shard_layout(lens_dev, N, shard_off, shard_len, seq_base=seq_base)
         hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
 
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

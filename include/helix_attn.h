@@ -113,7 +113,7 @@ int helix_attn_partial(const helix_problem *problem, const void *q, const helix_
  *   argmax_shard  int32 [B,Q] or NULL: lowest shard index holding the largest lses value (0 if all
  *                 are -inf); decided on the fp32 values as stored
  * Shards with lse = -inf get weight 0 whatever their partial holds; if all are -inf, o = 0 and
- * lse_out = -inf.  May run in place on nothing: o must not overlap o_partials. */
+ * lse_out = -inf.  o must not overlap o_partials. */
 int helix_attn_combine(const helix_problem *problem, int32_t n_shards,
                        const float *o_partials, const float *lses,
                        float *o, float *lse_out, int32_t *argmax_shard, void *hip_stream);

@@ -104,6 +104,7 @@ def test_tiny_gqa_config(hx, oracle):
     (4, 8, 8, 64, 300, 8, [300, 0, 17, 128], 128),       # MHA (group 1), an empty sequence, empty shards
     (1, 16, 1, 128, 16, 4, [16], 0),                     # fewer 16-token blocks than shards
     (2, 16, 2, 128, 2049, 1, [2049, 2048], 512),         # one shard, tail of one token
+    (2, 8, 2, 128, 1500, 20, [1500, 640], 0),            # more shards than one launch carries
 ])
 def test_gqa_shapes_against_oracle(hx, oracle, B, Q, K, D, S, N, lens, split):
     w = synth.Workload("case", B=B, Q=Q, K=K, dk=D, dv=D, n_shards=N, scale=1 / math.sqrt(D), seed=77 + S, seq_len=S)
