@@ -12,6 +12,7 @@
 #include "common.hpp"
 #include "gqa_decode.hpp"
 #include "merge_combine.hpp"
+#include "mla_decode.hpp"
 
 namespace {
 
@@ -52,7 +53,7 @@ int check_problem(const helix_problem* p, Path* path)
     }
     if (p->v_aliases_k && p->dk == 576 && p->dv == 512 && p->kv_heads == 1) {
         *path = Path::Mla;
-        return HELIX_ERR_UNSUPPORTED;   // MLA kernels are not built yet
+        return HELIX_OK;
     }
     return HELIX_ERR_UNSUPPORTED;
 }
@@ -65,8 +66,8 @@ int check_problem(const helix_problem* p, Path* path)
 int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_t n, Plan* plan)
 {
     plan->path = path;
-    plan->heads_per_wg = 16;
-    plan->granule = 128;                                  // 4 waves x 32-token blocks
+    plan->heads_per_wg = path == Path::Mla ? 128 : 16;
+    plan->granule = path == Path::Mla ? 32 : 128;         // MLA: 32-token tiles; GQA: 4 waves x 32-token blocks
     const int g = p->q_heads / p->kv_heads;
     plan->head_tiles = (int32_t)ceil_div(g, plan->heads_per_wg);
     const int64_t rows = (int64_t)p->batch * p->kv_heads * plan->head_tiles;
@@ -212,6 +213,16 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             case Path::Gqa128:
                 hipLaunchKernelGGL((gqa_decode_kernel<128>), dim3((unsigned)units), dim3(256), 0, stream, a);
                 break;
+            case Path::Mla: {
+                const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
+                auto kern = fp8 ? mla_decode_kernel<true> : mla_decode_kernel<false>;
+                // more than the default 64 KB of LDS per workgroup has to be asked for
+                if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        MlaCfg::LDS_BYTES) != hipSuccess)
+                    return HELIX_ERR_LAUNCH;
+                hipLaunchKernelGGL(kern, dim3((unsigned)units), dim3(256), MlaCfg::LDS_BYTES, stream, a);
+                break;
+            }
             default:
                 return HELIX_ERR_UNSUPPORTED;
         }

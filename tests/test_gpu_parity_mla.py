@@ -1,0 +1,129 @@
+"""GPU parity of the MLA path (576-wide latent key, first 512 entries as value, 128 query heads on one
+latent; bf16 or e4m3 + per-token scale; padded or ragged packed storage) against the CPU oracle,
+through the C ABI.  Same tolerances as the GQA tests."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+from test_gpu_parity_gqa import O_MAX_ABS, O_REL_L2, SHARD_VS_UNSHARDED, check_lse, check_o
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hx():
+    import paper_2507_07120_amd as hx_
+    hx_.load_library()
+    assert torch.cuda.is_available()
+    return hx_
+
+
+def run_mla(hx, oracle, w, inp, n_shards, split_tokens=0, check_partials=True):
+    from paper_2507_07120_amd import harness
+    dev = "cuda"
+    prob = harness.problem_for(w, split_tokens)
+    lens_dev = inp.lens.to(dev)
+    packed = inp.seq_off is not None
+    seq_base = inp.seq_off[:-1].to(dev) if packed else None
+    ss = harness.make_shards(inp.k, None, lens_dev, n_shards, kv_scale=inp.kv_scale, seq_base=seq_base)
+    off_ref, len_ref = oracle.shard_layout(inp.lens.numpy(), n_shards)
+    base = inp.seq_off[:-1].numpy()[None, :] if packed else 0
+    assert np.array_equal(ss.shard_off.cpu().numpy(), off_ref + base)
+    assert np.array_equal(ss.shard_len.cpu().numpy(), len_ref)
+    ws = harness.workspace_for(prob, n_shards, max(ss.max_lens), dev)
+    o = torch.full((w.B, w.Q, w.dv), float("nan"), device=dev)
+    lse = torch.full((w.B, w.Q), float("nan"), device=dev)
+    o_parts = torch.full((n_shards, w.B, w.Q, w.dv), float("nan"), device=dev)
+    lses = torch.full((n_shards, w.B, w.Q), float("nan"), device=dev)
+    hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse, o_partials=o_parts, lses=lses)
+    torch.cuda.synchronize()
+
+    qb, kb = synth.bits(inp.q), synth.bits(inp.k)
+    sc = None if inp.kv_scale is None else inp.kv_scale.cpu().numpy()
+    lens = inp.lens.numpy()
+    tok_off = inp.seq_off[:-1].numpy() if packed else None
+    o_ref, lse_ref = oracle.attention(qb, kb, None, lens, w.scale, kv_heads=1, dv=w.dv, kv_scale=sc, tok_off=tok_off)
+    check_o(o.cpu().numpy(), o_ref, f"{w.name} N={n_shards} combined O")
+    check_lse(lse.cpu().numpy(), lse_ref, f"{w.name} N={n_shards} combined LSE")
+    if check_partials:
+        for i in range(n_shards):
+            lo, hi = off_ref[i], off_ref[i] + len_ref[i]
+            op_ref, lp_ref = oracle.attention(qb, kb, None, lens, w.scale, kv_heads=1, dv=w.dv, kv_scale=sc,
+                                              tok_off=tok_off, t_lo=lo, t_hi=hi)
+            nz = len_ref[i] > 0
+            gp = o_parts[i].cpu().numpy()
+            if nz.any():
+                check_o(gp[nz], op_ref[nz], f"{w.name} shard {i} partial O")
+            assert np.all(gp[~nz] == 0)
+            check_lse(lses[i].cpu().numpy(), lp_ref, f"{w.name} shard {i} partial LSE")
+    amax = torch.empty((w.B, w.Q), dtype=torch.int32, device=dev)
+    o2 = torch.empty_like(o)
+    hx.helix_attn_combine(prob, o_parts, lses, o2, argmax_shard=amax)
+    torch.cuda.synchronize()
+    assert torch.equal(o2, o)
+    assert np.array_equal(amax.cpu().numpy(), oracle.argmax_f32(lses.cpu().numpy()))
+    return o, lse
+
+
+@pytest.mark.parametrize("B,Q,S,N,lens,split", [
+    (2, 128, 700, 2, [700, 333], 0),          # several tiles and a ragged tail
+    (1, 128, 2100, 3, [2100], 128),           # forced small splits -> many records
+    (2, 64, 97, 1, [97, 1], 0),               # 64 heads (padded head tile), a 1-token sequence
+    (1, 160, 400, 4, [400], 0),               # 160 heads -> two head tiles, the second padded
+    (3, 128, 64, 8, [64, 0, 33], 0),          # empty sequence, empty shards
+])
+def test_mla_bf16_against_oracle(hx, oracle, B, Q, S, N, lens, split):
+    w = synth.Workload("mla_case", B=B, Q=Q, K=1, dk=576, dv=512, n_shards=N, scale=1 / math.sqrt(192), seed=300 + S,
+                       seq_len=S, mla=True)
+    inp = synth.make_inputs(w, "cuda")
+    inp.lens = torch.tensor(lens, dtype=torch.int32)
+    has = np.array(lens) > 0
+    if not has.all():
+        # rows without tokens: checked separately (O = 0, LSE = -inf); compare the rest
+        o, lse = run_mla_allow_empty(hx, oracle, w, inp, N, split)
+        return
+    o_n, _ = run_mla(hx, oracle, w, inp, N, split_tokens=split)
+    o_1, _ = run_mla(hx, oracle, w, inp, 1, split_tokens=split, check_partials=False)
+    assert (o_n - o_1).abs().max().item() <= SHARD_VS_UNSHARDED
+
+
+def run_mla_allow_empty(hx, oracle, w, inp, n_shards, split):
+    from paper_2507_07120_amd import harness
+    prob = harness.problem_for(w, split)
+    ss = harness.make_shards(inp.k, None, inp.lens.cuda(), n_shards)
+    ws = harness.workspace_for(prob, n_shards, max(ss.max_lens), "cuda")
+    o = torch.full((w.B, w.Q, w.dv), float("nan"), device="cuda")
+    lse = torch.full((w.B, w.Q), float("nan"), device="cuda")
+    hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+    torch.cuda.synchronize()
+    lens = inp.lens.numpy()
+    o_ref, lse_ref = oracle.attention(synth.bits(inp.q), synth.bits(inp.k), None, lens, w.scale, kv_heads=1, dv=w.dv)
+    has = lens > 0
+    check_o(o.cpu().numpy()[has], o_ref[has], "MLA with empty sequences")
+    check_lse(lse.cpu().numpy(), lse_ref, "MLA with empty sequences LSE")
+    assert np.all(o.cpu().numpy()[~has] == 0)
+    return o, lse
+
+
+@pytest.mark.parametrize("B,lo,hi,N,split", [
+    (4, 40, 900, 8, 0),                        # ragged packed e4m3, uneven tail shards
+    (3, 1, 70, 2, 0),
+    (2, 1500, 3000, 3, 256),
+])
+def test_mla_fp8_ragged_against_oracle(hx, oracle, B, lo, hi, N, split):
+    w = synth.scaled(synth.WORKLOADS["mla_fp8_ragged"], B=B, len_range=(lo, hi), n_shards=N, seed=500 + hi)
+    inp = synth.make_inputs(w, "cuda")
+    o_n, _ = run_mla(hx, oracle, w, inp, N, split_tokens=split)
+    o_1, _ = run_mla(hx, oracle, w, inp, 1, split_tokens=split, check_partials=False)
+    assert (o_n - o_1).abs().max().item() <= SHARD_VS_UNSHARDED
+
+
+def test_mla_fp8_padded_storage(hx, oracle):
+    w = synth.Workload("mla_fp8_pad", B=2, Q=128, K=1, dk=576, dv=512, n_shards=2, scale=1 / math.sqrt(192), seed=41,
+                       seq_len=300, mla=True, fp8=True)
+    inp = synth.make_inputs(w, "cuda")
+    inp.lens = torch.tensor([300, 123], dtype=torch.int32)
+    run_mla(hx, oracle, w, inp, 2)
