@@ -66,7 +66,7 @@ int check_problem(const helix_problem* p, Path* path)
 int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_t n, Plan* plan)
 {
     plan->path = path;
-    plan->heads_per_wg = path == Path::Mla ? 128 : 16;
+    plan->heads_per_wg = path == Path::Mla ? MlaCfg::HPW : 16;
     plan->granule = path == Path::Mla ? 32 : 128;         // MLA: 32-token tiles; GQA: 4 waves x 32-token blocks
     const int g = p->q_heads / p->kv_heads;
     plan->head_tiles = (int32_t)ceil_div(g, plan->heads_per_wg);
@@ -86,7 +86,7 @@ int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_
     plan->split_tokens = (int32_t)split;
     plan->total_splits = 0;
     for (int i = 0; i < n; i++) plan->total_splits += std::max<int64_t>(1, ceil_div(max_lens[i], split));
-    plan->workgroups = plan->total_splits * rows;
+    plan->workgroups = plan->total_splits * rows;   // MLA launches pad this per shard to whole groups of 8
     if (plan->workgroups > (int64_t)1 << 30) return HELIX_ERR_SHAPE;
     return HELIX_OK;
 }
@@ -203,7 +203,8 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             m.split_base[i] = split_base;
             m.n_splits[i] = d.n_splits;
             split_base += d.n_splits;
-            units += (int64_t)d.n_splits * rows;
+            units += plan.path == Path::Mla ? mla_units_of_shard(d.n_splits, p->batch, plan.head_tiles)
+                                            : (int64_t)d.n_splits * rows;
         }
         if (g_prof_start && g_prof_stop && s0 == 0) (void)hipEventRecord(g_prof_start, stream);
         switch (plan.path) {

@@ -6,23 +6,25 @@
 // This is the dense contraction of the path (242 flop per latent byte in bf16, 480 in e4m3): it is
 // MFMA-bound, so the design question is how to feed the matrix cores, not HBM.
 //
-//   Workgroup = 4 wavefronts = one CU, all 128 heads, a run of `split_tokens` latent rows, in
-//   tiles of 32 tokens.  Each latent tile is read from HBM once, parked in LDS (row stride padded
-//   to 1184 B so that MFMA-operand reads of 16 rows x 64 B hit 64 distinct banks) and used twice:
+//   Workgroup = 4 wavefronts = one CU, HPW = 64 of the heads, a run of `split_tokens` latent rows in
+//   tiles of 32 tokens.  (All 128 heads in one workgroup would need 256 accumulator + 144 query
+//   registers per lane and left the compiler spilling; with 64 heads the two workgroups of a token
+//   range sit on the same XCD and the second one's latent reads hit that XCD's L2.)  Each latent
+//   tile is parked in LDS (row stride padded to 1184 B so that MFMA-operand reads of 16 rows x 64 B
+//   hit 64 distinct banks) and used twice:
 //
-//   scores  S^T[token, head] = K . Q^T      wave w owns heads 32w..32w+31 with its Q slice
-//           (32 x 576 bf16 = 144 VGPRs) stationary in registers; every K operand read from LDS
-//           (16 tokens x 32 dims) feeds two MFMAs (two 16-head tiles).
-//   softmax per wave on its own 32 heads, integer running reference exponent as in the GQA kernel;
+//   scores  S^T[token, head] = K . Q^T      wave w owns heads 16w..16w+15 of the workgroup with its
+//           Q slice (16 x 576 bf16 = 72 VGPRs) stationary in registers; K operands come from LDS.
+//   softmax per wave on its own heads, integer running reference exponent as in the GQA kernel;
 //           the weights (bf16 hi + lo) and the per-head rescale factors go to LDS.
 //   P.V     O^T[dv, head] += V^T . P^T     wave w owns value columns 128w..128w+127 for ALL heads
-//           (128 x 128 fp32 accumulators = 256 registers).  V^T operands come straight out of the
-//           row-major latent tile with the transposing LDS read (ds_read_b64_tr_b16), P^T operands
-//           from the weights the four waves just wrote.
+//           of the workgroup (64 x 128 fp32 accumulators = 128 registers).  V^T operands come
+//           straight out of the row-major latent tile with the transposing LDS read
+//           (ds_read_b64_tr_b16), P^T operands from the weights the four waves just wrote.
 //
-//   LDS traffic per 32-token tile and wave: 36 KB (K) + 16 KB (V, read twice) + 16 KB (P) + 4 KB
-//   (P writes) over 3200 MFMA cycles = 90 B/clk per CU, a third of the 256 B/clk the CU's LDS
-//   delivers for 128-bit reads (measured 214-223 B/clk).
+//   LDS traffic per 32-token tile and wave: 36 KB (K) + 8 KB (V) + 8 KB (P) + 2 KB (P writes) over
+//   1600 MFMA cycles = 135 B/clk per CU, half of the 256 B/clk the CU's LDS delivers for 128-bit
+//   reads (measured 214-223 B/clk).
 //
 // e4m3 latent: codes are widened to bf16 (exact) on their way into LDS; the per-token scale f_t
 // multiplies the score (s_t = f_t * q.k8_t) and the weight that meets the values (p_t * f_t), while
@@ -39,12 +41,15 @@ struct MlaCfg {
     static constexpr int KS = DK / 32;            // 18 k-steps of the score MFMA
     static constexpr int NBUF = 3;                // latent tiles in flight in LDS
     static constexpr int TILE_BYTES = T * ROW;    // 37888
-    static constexpr int P_BYTES = 128 * T * 2;   // one of hi / lo: [128 heads][32 tokens] bf16
+    static constexpr int HPW = 64;                // heads per workgroup
+    static constexpr int NHT = HPW / 16;          // head tiles of the P.V product
+    static constexpr int QHT = HPW / 64;          // head tiles per wave in the score product
+    static constexpr int P_BYTES = HPW * T * 2;   // one of hi / lo: [HPW heads][32 tokens] bf16
     // LDS map
     static constexpr int OFF_K = 0;
     static constexpr int OFF_P = NBUF * TILE_BYTES;               // [2 buffers][hi, lo]
-    static constexpr int OFF_ALPHA = OFF_P + 2 * 2 * P_BYTES;     // [2][128] fp32
-    static constexpr int OFF_FLAG = OFF_ALPHA + 2 * 128 * 4;      // [2][4] int
+    static constexpr int OFF_ALPHA = OFF_P + 2 * 2 * P_BYTES;     // [2][HPW] fp32
+    static constexpr int OFF_FLAG = OFF_ALPHA + 2 * HPW * 4;      // [2][4] int
     static constexpr int OFF_SCALE = OFF_FLAG + 2 * 4 * 4;        // [NBUF][32] fp32 per-token scales
     static constexpr int LDS_BYTES = OFF_SCALE + NBUF * T * 4;
 };
@@ -80,7 +85,7 @@ struct MlaStage {
             const int row = ch / CHUNKS_PER_ROW, cc = ch % CHUNKS_PER_ROW;
             regs[j] = u32x4{0, 0, 0, 0};
             if (ch < CHUNKS && row < n_valid)
-                regs[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + (size_t)row * row_bytes + cc * 16));
+                regs[j] = *reinterpret_cast<const u32x4*>(src + (size_t)row * row_bytes + cc * 16);   // plain load: the sibling workgroup re-reads it from L2
         }
         if (FP8) scale = (tid < n_valid && tid < MlaCfg::T) ? scales[tid] : 0.f;
     }
@@ -114,6 +119,14 @@ struct MlaStage {
     }
 };
 
+// Workgroups of one shard are numbered so that the head tiles of the same token range are 8 apart:
+// consecutive workgroup ids go round-robin over the 8 XCDs, so ids that differ by 8 share an XCD
+// and with it an L2.  Shards are padded to a multiple of 8 token ranges (padding workgroups exit).
+__host__ __device__ inline int mla_units_of_shard(int n_splits, int B, int head_tiles)
+{
+    return (n_splits * B + 7) / 8 * 8 * head_tiles;
+}
+
 template <bool FP8>
 __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
 {
@@ -124,21 +137,23 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
     const int lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, kc = lane >> 4;
 
-    // which (shard, split, sequence, head tile of 128) this workgroup serves
+    // which (shard, split, sequence, head tile of HPW heads) this workgroup serves
     int u = blockIdx.x, si = 0;
     while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
     const ShardDev& sh = a.shard[si];
     u -= sh.unit_base;
-    const int split = u % sh.n_splits;
-    int rest = u / sh.n_splits;
-    const int ht128 = rest % a.head_tiles;
-    const int b = rest / a.head_tiles;
+    const int grp = u / (8 * a.head_tiles), j8 = u % (8 * a.head_tiles);
+    const int logical = grp * 8 + (j8 & 7);
+    const int htw = j8 >> 3;
+    if (logical >= sh.n_splits * a.B) return;         // padding workgroup
+    const int split = logical % sh.n_splits;
+    const int b = logical / sh.n_splits;
 
     const int len = sh.len[b];
     const int t0 = split * a.split_tokens;
     const int t1 = min(t0 + a.split_tokens, len);
-    const int h0 = ht128 * 128;                       // first head of this workgroup
-    const int nh = min(128, a.Q - h0);                // real heads (the rest is zero padding)
+    const int h0 = htw * C::HPW;                      // first head of this workgroup
+    const int nh = min(C::HPW, a.Q - h0);             // real heads (the rest is zero padding)
     const size_t rec = ((size_t)(sh.split_base + split) * a.B + b) * a.Q + h0;
 
     if (t0 >= len) {
@@ -146,18 +161,17 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
         return;
     }
 
-    // Q slice of this wave as the score MFMA's B operand: lane (r,kc) holds head 32w + 16*ht + r,
-    // dims 32*ks + 8*kc .. +8
-    bf16x8 qb[2][C::KS];
-#pragma unroll
-    for (int ht = 0; ht < 2; ht++) {
-        const int hl = wave * 32 + ht * 16 + r;
+    // Q slice of this wave as the score MFMA's B operand: lane (r,kc) holds head 16w + r of the
+    // workgroup, dims 32*ks + 8*kc .. +8
+    bf16x8 qb[C::KS];
+    {
+        const int hl = wave * 16 + r;
         const uint16_t* qrow = a.q + ((size_t)b * a.Q + h0 + min(hl, nh - 1)) * C::DK + kc * 8;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ks++) {
             u32x4 w = *reinterpret_cast<const u32x4*>(qrow + ks * 32);
             if (hl >= nh) w = u32x4{0, 0, 0, 0};
-            qb[ht][ks] = __builtin_bit_cast(bf16x8, w);
+            qb[ks] = __builtin_bit_cast(bf16x8, w);
         }
     }
 
@@ -170,13 +184,13 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
     const int n_tok = t1 - t0;
     const int n_tiles = (n_tok + C::T - 1) / C::T;
 
-    float m_run[2] = {-INFINITY, -INFINITY};          // heads 32w+r and 32w+16+r
-    float l_run[2] = {0.f, 0.f};
-    f32x4 acc[8][8];                                  // [dv tile][head tile]: O^T[128w + 16*dvt + 4*kc + i][16*ht + r]
+    float m_run = -INFINITY;                          // head 16w + r
+    float l_run = 0.f;
+    f32x4 acc[8][C::NHT];                             // [dv tile][head tile]: O^T[128w + 16*dvt + 4*kc + i][16*ht + r]
 #pragma unroll
     for (int d = 0; d < 8; d++)
 #pragma unroll
-        for (int h = 0; h < 8; h++) acc[d][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int h = 0; h < C::NHT; h++) acc[d][h] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     MlaStage<FP8> stage;
     stage.load(kbase, row_bytes, sbase, min(C::T, n_tok), tid);
@@ -194,20 +208,16 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
             stage.load(kbase + (size_t)(it + 1) * C::T * row_bytes, row_bytes, FP8 ? sbase + (it + 1) * C::T : nullptr,
                        min(C::T, n_tok - (it + 1) * C::T), tid);
 
-        // ---- scores of this wave's 32 heads against the tile's 32 tokens ----
-        f32x4 s[2][2];                                // [token tile][head tile]
-#pragma unroll
-        for (int tt = 0; tt < 2; tt++)
-#pragma unroll
-            for (int ht = 0; ht < 2; ht++) s[tt][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // ---- scores of this wave's 16 heads against the tile's 32 tokens ----
+        f32x4 s[2];                                   // [token tile]: lane (r,kc) gets head r, tokens 16tt + 4kc + i
+        s[0] = s[1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < C::KS; ks++) {
 #pragma unroll
             for (int tt = 0; tt < 2; tt++) {
                 const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(
                                                                  ktile + (tt * 16 + r) * C::ROW + ks * 64 + kc * 16));
-                s[tt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb[0][ks], s[tt][0], 0, 0, 0);
-                s[tt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb[1][ks], s[tt][1], 0, 0, 0);
+                s[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb[ks], s[tt], 0, 0, 0);
             }
         }
 
@@ -222,28 +232,27 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
                 for (int i = 0; i < 4; i++) fscale[tt][i] = f[i];
             }
         }
-        bool changed = false;
-#pragma unroll
-        for (int ht = 0; ht < 2; ht++) {
+        {
             float t[2][4];
             float bmax = -INFINITY;
 #pragma unroll
             for (int tt = 0; tt < 2; tt++)
 #pragma unroll
                 for (int i = 0; i < 4; i++) {
-                    float x = s[tt][ht][i] * a.scale_log2e;
+                    float x = s[tt][i] * a.scale_log2e;
                     if (FP8) x *= fscale[tt][i];
                     if (tt * 16 + kc * 4 + i >= n_valid) x = -INFINITY;
                     t[tt][i] = x;
                     bmax = fmaxf(bmax, x);
                 }
             bmax = wave_xor_max_16_32(bmax);
-            const float m_new = fmaxf(m_run[ht], __builtin_ceilf(bmax));     // finite: token 0 of a tile is valid
-            const float alpha = __builtin_amdgcn_exp2f(m_run[ht] - m_new);   // exact power of two; 0 from -inf
-            changed |= (m_new != m_run[ht]);
-            m_run[ht] = m_new;
+            const float m_new = fmaxf(m_run, __builtin_ceilf(bmax));         // finite: token 0 of a tile is valid
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);       // exact power of two; 0 from -inf
+            const bool any = __any(m_new != m_run);
+            m_run = m_new;
             if (kc == 0) *reinterpret_cast<__attribute__((address_space(3))) float*>(
-                smem + C::OFF_ALPHA + (pb * 128 + wave * 32 + ht * 16 + r) * 4) = alpha;
+                smem + C::OFF_ALPHA + (pb * C::HPW + wave * 16 + r) * 4) = alpha;
+            if (lane == 0) *reinterpret_cast<__attribute__((address_space(3))) int*>(smem + C::OFF_FLAG + (pb * 4 + wave) * 4) = any ? 1 : 0;
             float lsum = 0.f;
 #pragma unroll
             for (int tt = 0; tt < 2; tt++) {
@@ -257,15 +266,11 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
                 const uint32_t h01 = pack_bf16_rne(p[0], p[1]), h23 = pack_bf16_rne(p[2], p[3]);
                 const uint32_t l01 = pack_bf16_rne(p[0] - as_f32(h01 << 16), p[1] - as_f32(h01 & 0xffff0000u));
                 const uint32_t l23 = pack_bf16_rne(p[2] - as_f32(h23 << 16), p[3] - as_f32(h23 & 0xffff0000u));
-                const int off = (wave * 32 + ht * 16 + r) * (C::T * 2) + (tt * 16 + kc * 4) * 2;
+                const int off = (wave * 16 + r) * (C::T * 2) + (tt * 16 + kc * 4) * 2;
                 *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(phi + off) = u32x2{h01, h23};
                 *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(plo + off) = u32x2{l01, l23};
             }
-            l_run[ht] = l_run[ht] * alpha + lsum;
-        }
-        {
-            const bool any = __any(changed);
-            if (lane == 0) *reinterpret_cast<__attribute__((address_space(3))) int*>(smem + C::OFF_FLAG + (pb * 4 + wave) * 4) = any ? 1 : 0;
+            l_run = l_run * alpha + lsum;
         }
         // next tile into its LDS buffer: that buffer was last read two tiles ago, before the previous barrier
         if (has_next)
@@ -277,52 +282,48 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
             const auto fl = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(smem + C::OFF_FLAG + pb * 16);
             if (fl.x | fl.y | fl.z | fl.w) {
 #pragma unroll
-                for (int h = 0; h < 8; h++) {
+                for (int h = 0; h < C::NHT; h++) {
                     const float al = *reinterpret_cast<const __attribute__((address_space(3))) float*>(
-                        smem + C::OFF_ALPHA + (pb * 128 + h * 16 + r) * 4);
+                        smem + C::OFF_ALPHA + (pb * C::HPW + h * 16 + r) * 4);
 #pragma unroll
                     for (int d = 0; d < 8; d++) acc[d][h] *= al;
                 }
             }
         }
 
-        // ---- O^T[value cols of this wave, all heads] += V^T . P^T ----
+        // ---- O^T[value cols of this wave, all heads of the workgroup] += V^T . P^T ----
+        bf16x8 bh[C::NHT], bl[C::NHT];
 #pragma unroll
-        for (int hg = 0; hg < 2; hg++) {
-            bf16x8 bh[4], bl[4];
+        for (int h = 0; h < C::NHT; h++) {
+            const int off = (h * 16 + r) * (C::T * 2) + kc * 16;
+            bh[h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(phi + off));
+            bl[h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(plo + off));
+        }
 #pragma unroll
-            for (int h4 = 0; h4 < 4; h4++) {
-                const int off = ((hg * 4 + h4) * 16 + r) * (C::T * 2) + kc * 16;
-                bh[h4] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(phi + off));
-                bl[h4] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(plo + off));
-            }
+        for (int d = 0; d < 8; d++) {
+            // V^T operand: lane (r,kc) ends up with value column 128w + 16d + r, tokens 8kc .. 8kc+7
+            const lds_byte* vp = ktile + (kc * 8 + (r >> 2)) * C::ROW + (wave * 128 + d * 16 + (r & 3) * 4) * 2;
+            const u32x2 v0 = lds_read_tr16(vp);
+            const u32x2 v1 = lds_read_tr16(vp + 4 * C::ROW);
+            const bf16x8 va = __builtin_bit_cast(bf16x8, u32x4{v0.x, v0.y, v1.x, v1.y});
 #pragma unroll
-            for (int d = 0; d < 8; d++) {
-                // V^T operand: lane (r,kc) ends up with value column 128w + 16d + r, tokens 8kc .. 8kc+7
-                const lds_byte* vp = ktile + (kc * 8 + (r >> 2)) * C::ROW + (wave * 128 + d * 16 + (r & 3) * 4) * 2;
-                const u32x2 v0 = lds_read_tr16(vp);
-                const u32x2 v1 = lds_read_tr16(vp + 4 * C::ROW);
-                const bf16x8 va = __builtin_bit_cast(bf16x8, u32x4{v0.x, v0.y, v1.x, v1.y});
-#pragma unroll
-                for (int h4 = 0; h4 < 4; h4++) {
-                    acc[d][hg * 4 + h4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bh[h4], acc[d][hg * 4 + h4], 0, 0, 0);
-                    acc[d][hg * 4 + h4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bl[h4], acc[d][hg * 4 + h4], 0, 0, 0);
-                }
+            for (int h = 0; h < C::NHT; h++) {
+                acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bh[h], acc[d][h], 0, 0, 0);
+                acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bl[h], acc[d][h], 0, 0, 0);
             }
         }
     }
 
     // ---- the workgroup's record: un-normalised O, reference exponent and normaliser per head ----
-#pragma unroll
-    for (int ht = 0; ht < 2; ht++) {
-        const float l = wave_xor_sum_16_32(l_run[ht]);
-        const int hl = wave * 32 + ht * 16 + r;
-        if (kc == 0 && hl < nh) { a.ws_m[rec + hl] = m_run[ht]; a.ws_l[rec + hl] = l; }
+    {
+        const float l = wave_xor_sum_16_32(l_run);
+        const int hl = wave * 16 + r;
+        if (kc == 0 && hl < nh) { a.ws_m[rec + hl] = m_run; a.ws_l[rec + hl] = l; }
     }
-    // every wave's reference exponents are the final ones only for its own heads; the accumulators
-    // of all heads were rescaled tile by tile with the owners' factors, so they already match them.
+    // a wave knows the final reference exponent only of its own heads, but the accumulators of all
+    // heads were rescaled tile by tile with the owners' factors, so they already match them.
 #pragma unroll
-    for (int h = 0; h < 8; h++) {
+    for (int h = 0; h < C::NHT; h++) {
         const int hl = h * 16 + r;
         if (hl < nh) {
             float* orow = a.ws_o + (rec + hl) * C::DV + wave * 128 + kc * 4;
