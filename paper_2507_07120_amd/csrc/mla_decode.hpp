@@ -15,8 +15,8 @@
 //
 //   scores  S^T[token, head] = K . Q^T      wave w owns heads 16w..16w+15 of the workgroup with its
 //           Q slice (16 x 576 bf16 = 72 VGPRs) stationary in registers; K operands come from LDS.
-//   softmax per wave on its own heads, integer running reference exponent as in the GQA kernel;
-//           the weights (bf16 hi + lo) and the per-head rescale factors go to LDS.
+//   softmax per wave on its own heads with an integer reference exponent that stays fixed for the
+//           whole run of tokens (see the kernel); the weights (bf16 hi + lo) go to LDS.
 //   P.V     O^T[dv, head] += V^T . P^T     wave w owns value columns 128w..128w+127 for ALL heads
 //           of the workgroup (64 x 128 fp32 accumulators = 128 registers).  V^T operands come
 //           straight out of the row-major latent tile with the transposing LDS read
@@ -48,8 +48,7 @@ struct MlaCfg {
     // LDS map
     static constexpr int OFF_K = 0;
     static constexpr int OFF_P = NBUF * TILE_BYTES;               // [2 buffers][hi, lo]
-    static constexpr int OFF_ALPHA = OFF_P + 2 * 2 * P_BYTES;     // [2][HPW] fp32
-    static constexpr int OFF_FLAG = OFF_ALPHA + 2 * HPW * 4;      // [2][4] int
+    static constexpr int OFF_FLAG = OFF_P + 2 * 2 * P_BYTES;      // [2][4] int: a wave asks for a restart
     static constexpr int OFF_SCALE = OFF_FLAG + 2 * 4 * 4;        // [NBUF][32] fp32 per-token scales
     static constexpr int LDS_BYTES = OFF_SCALE + NBUF * T * 4;
 };
@@ -184,44 +183,40 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
     const int n_tok = t1 - t0;
     const int n_tiles = (n_tok + C::T - 1) / C::T;
 
-    float m_run = -INFINITY;                          // head 16w + r
+    float m_run = -INFINITY;                          // reference exponent of head 16w + r (integer-valued)
+    float m_floor = -INFINITY;                        // lower bound for it after a restart
     float l_run = 0.f;
     f32x4 acc[8][C::NHT];                             // [dv tile][head tile]: O^T[128w + 16*dvt + 4*kc + i][16*ht + r]
-#pragma unroll
-    for (int d = 0; d < 8; d++)
-#pragma unroll
-        for (int h = 0; h < C::NHT; h++) acc[d][h] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    MlaStage<FP8> stage;
-    stage.load(kbase, row_bytes, sbase, min(C::T, n_tok), tid);
-    stage.store(smem + C::OFF_K, smem + C::OFF_SCALE, tid);
-    __syncthreads();
-
-    for (int it = 0; it < n_tiles; it++) {
-        const int kb = it % C::NBUF, pb = it & 1;
-        lds_byte* ktile = smem + C::OFF_K + kb * C::TILE_BYTES;
-        lds_byte* phi = smem + C::OFF_P + pb * 2 * C::P_BYTES;
-        lds_byte* plo = phi + C::P_BYTES;
-        const int n_valid = min(C::T, n_tok - it * C::T);
-        const bool has_next = it + 1 < n_tiles;
-        if (has_next)
-            stage.load(kbase + (size_t)(it + 1) * C::T * row_bytes, row_bytes, FP8 ? sbase + (it + 1) * C::T : nullptr,
-                       min(C::T, n_tok - (it + 1) * C::T), tid);
-
-        // ---- scores of this wave's 16 heads against the tile's 32 tokens ----
-        f32x4 s[2];                                   // [token tile]: lane (r,kc) gets head r, tokens 16tt + 4kc + i
+    // Scores of this wave's 16 heads against the 32 tokens of a latent tile in LDS.  The K operand
+    // reads run PD operands ahead of the MFMAs that consume them (one wave per SIMD: nothing else
+    // hides the LDS latency).
+    auto scores = [&](const lds_byte* ktile, f32x4 (&s)[2]) {
+        constexpr int NOP = 2 * C::KS, PD = 8;
+        bf16x8 kop[NOP];
+        const lds_byte* kp = ktile + r * C::ROW + kc * 16;
+        auto rd = [&](int o) {   // operand o = 2*ks + tt: rows 16tt + r, dims 32ks + 8kc .. +8
+            return __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(
+                                                  kp + (o & 1) * 16 * C::ROW + (o >> 1) * 64));
+        };
         s[0] = s[1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ks++) {
+        for (int o = 0; o < PD; o++) kop[o] = rd(o);
+        __builtin_amdgcn_sched_group_barrier(0x100, PD, 0);      // PD LDS reads up front ...
 #pragma unroll
-            for (int tt = 0; tt < 2; tt++) {
-                const bf16x8 ka = __builtin_bit_cast(bf16x8, *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(
-                                                                 ktile + (tt * 16 + r) * C::ROW + ks * 64 + kc * 16));
-                s[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb[ks], s[tt], 0, 0, 0);
-            }
+        for (int o = 0; o < NOP; o++) {
+            s[o & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[o], qb[o >> 1], s[o & 1], 0, 0, 0);
+            if (o + PD < NOP) kop[o + PD] = rd(o + PD);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // ... then MFMA, read, MFMA, read, ...
+            if (o + PD < NOP) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+    };
 
-        // ---- softmax on the wave's heads; weights and rescale factors to LDS ----
+    // Softmax of one tile's scores on the wave's own heads: new integer reference exponent, the
+    // rescale factor for everybody's accumulators, weights as bf16 hi + lo into LDS.
+    auto softmax = [&](const f32x4 (&s)[2], int kb, int pb, int n_valid, bool first) {
+        lds_byte* phi = smem + C::OFF_P + pb * 2 * C::P_BYTES;
+        lds_byte* plo = phi + C::P_BYTES;
         float fscale[2][4];                           // e4m3: per-token scales of this lane's tokens
         if (FP8) {
 #pragma unroll
@@ -232,66 +227,64 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
                 for (int i = 0; i < 4; i++) fscale[tt][i] = f[i];
             }
         }
-        {
-            float t[2][4];
-            float bmax = -INFINITY;
+        float t[2][4];
+        float bmax = -INFINITY;
 #pragma unroll
-            for (int tt = 0; tt < 2; tt++)
+        for (int tt = 0; tt < 2; tt++)
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    float x = s[tt][i] * a.scale_log2e;
-                    if (FP8) x *= fscale[tt][i];
-                    if (tt * 16 + kc * 4 + i >= n_valid) x = -INFINITY;
-                    t[tt][i] = x;
-                    bmax = fmaxf(bmax, x);
-                }
-            bmax = wave_xor_max_16_32(bmax);
-            const float m_new = fmaxf(m_run, __builtin_ceilf(bmax));         // finite: token 0 of a tile is valid
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);       // exact power of two; 0 from -inf
-            const bool any = __any(m_new != m_run);
-            m_run = m_new;
-            if (kc == 0) *reinterpret_cast<__attribute__((address_space(3))) float*>(
-                smem + C::OFF_ALPHA + (pb * C::HPW + wave * 16 + r) * 4) = alpha;
-            if (lane == 0) *reinterpret_cast<__attribute__((address_space(3))) int*>(smem + C::OFF_FLAG + (pb * 4 + wave) * 4) = any ? 1 : 0;
-            float lsum = 0.f;
-#pragma unroll
-            for (int tt = 0; tt < 2; tt++) {
-                float p[4];
-#pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    p[i] = (t[tt][i] == -INFINITY) ? 0.f : exp2_rel(t[tt][i], m_new);
-                    lsum += p[i];
-                    if (FP8) p[i] *= fscale[tt][i];
-                }
-                const uint32_t h01 = pack_bf16_rne(p[0], p[1]), h23 = pack_bf16_rne(p[2], p[3]);
-                const uint32_t l01 = pack_bf16_rne(p[0] - as_f32(h01 << 16), p[1] - as_f32(h01 & 0xffff0000u));
-                const uint32_t l23 = pack_bf16_rne(p[2] - as_f32(h23 << 16), p[3] - as_f32(h23 & 0xffff0000u));
-                const int off = (wave * 16 + r) * (C::T * 2) + (tt * 16 + kc * 4) * 2;
-                *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(phi + off) = u32x2{h01, h23};
-                *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(plo + off) = u32x2{l01, l23};
+            for (int i = 0; i < 4; i++) {
+                float x = s[tt][i] * a.scale_log2e;
+                if (FP8) x *= fscale[tt][i];
+                if (tt * 16 + kc * 4 + i >= n_valid) x = -INFINITY;
+                t[tt][i] = x;
+                bmax = fmaxf(bmax, x);
             }
-            l_run = l_run * alpha + lsum;
-        }
-        // next tile into its LDS buffer: that buffer was last read two tiles ago, before the previous barrier
-        if (has_next)
-            stage.store(smem + C::OFF_K + ((it + 1) % C::NBUF) * C::TILE_BYTES, smem + C::OFF_SCALE + ((it + 1) % C::NBUF) * C::T * 4, tid);
-        __syncthreads();
-
-        // ---- rescale the accumulators if any head's reference moved ----
-        {
-            const auto fl = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(smem + C::OFF_FLAG + pb * 16);
-            if (fl.x | fl.y | fl.z | fl.w) {
+        bmax = wave_xor_max_16_32(bmax);
+        // Reference exponent: fixed for the whole run of tokens at kHeadroom octaves above the first
+        // tile's maximum (or at m_floor after a restart), so the 128 accumulator registers of every
+        // wave never need a rescale inside the loop.  Any integer reference gives the same result up
+        // to fp32 rounding of the sums: weights are exact powers of two times a significand that
+        // does not depend on the reference.  A later tile whose maximum exceeds the reference by
+        // more than kLimit octaves (weights near 2^64; never seen on real logits) raises the flag
+        // that makes the whole workgroup start the run over with a higher reference.
+        constexpr float kHeadroom = 32.f, kLimit = 64.f;
+        const float top = __builtin_ceilf(bmax);                         // finite: token 0 of a tile is valid
+        if (first) m_run = fmaxf(top + kHeadroom, m_floor);
+        const bool over = top > m_run + kLimit;
+        if (over) m_floor = top + kHeadroom;
+        const bool any = __any(over);
+        if (lane == 0) *reinterpret_cast<__attribute__((address_space(3))) int*>(smem + C::OFF_FLAG + (pb * 4 + wave) * 4) = any ? 1 : 0;
+        const float m_new = m_run;
+        float lsum = 0.f;
 #pragma unroll
-                for (int h = 0; h < C::NHT; h++) {
-                    const float al = *reinterpret_cast<const __attribute__((address_space(3))) float*>(
-                        smem + C::OFF_ALPHA + (pb * C::HPW + h * 16 + r) * 4);
+        for (int tt = 0; tt < 2; tt++) {
+            float p[4];
 #pragma unroll
-                    for (int d = 0; d < 8; d++) acc[d][h] *= al;
-                }
+            for (int i = 0; i < 4; i++) {
+                p[i] = (t[tt][i] == -INFINITY) ? 0.f : exp2_rel(t[tt][i], m_new);
+                lsum += p[i];
+                if (FP8) p[i] *= fscale[tt][i];
             }
+            const uint32_t h01 = pack_bf16_rne(p[0], p[1]), h23 = pack_bf16_rne(p[2], p[3]);
+            const uint32_t l01 = pack_bf16_rne(p[0] - as_f32(h01 << 16), p[1] - as_f32(h01 & 0xffff0000u));
+            const uint32_t l23 = pack_bf16_rne(p[2] - as_f32(h23 << 16), p[3] - as_f32(h23 & 0xffff0000u));
+            const int off = (wave * 16 + r) * (C::T * 2) + (tt * 16 + kc * 4) * 2;
+            *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(phi + off) = u32x2{h01, h23};
+            *reinterpret_cast<__attribute__((address_space(3))) u32x2*>(plo + off) = u32x2{l01, l23};
         }
+        l_run += lsum;
+    };
 
-        // ---- O^T[value cols of this wave, all heads of the workgroup] += V^T . P^T ----
+    // Did any wave ask for a restart while it computed the weights of tile `pb`?  (workgroup-uniform)
+    auto overflowed = [&](int pb) {
+        const auto fl = *reinterpret_cast<const __attribute__((address_space(3))) u32x4*>(smem + C::OFF_FLAG + pb * 16);
+        return (fl.x | fl.y | fl.z | fl.w) != 0;
+    };
+
+    // O^T[value cols of this wave, all heads of the workgroup] += V^T . P^T for one tile.
+    auto pv = [&](const lds_byte* ktile, int pb) {
+        const lds_byte* phi = smem + C::OFF_P + pb * 2 * C::P_BYTES;
+        const lds_byte* plo = phi + C::P_BYTES;
         bf16x8 bh[C::NHT], bl[C::NHT];
 #pragma unroll
         for (int h = 0; h < C::NHT; h++) {
@@ -307,11 +300,63 @@ __global__ __launch_bounds__(256, 1) void mla_decode_kernel(const AttnArgs a)
             const u32x2 v1 = lds_read_tr16(vp + 4 * C::ROW);
             const bf16x8 va = __builtin_bit_cast(bf16x8, u32x4{v0.x, v0.y, v1.x, v1.y});
 #pragma unroll
-            for (int h = 0; h < C::NHT; h++) {
-                acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bh[h], acc[d][h], 0, 0, 0);
-                acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bl[h], acc[d][h], 0, 0, 0);
-            }
+            for (int h = 0; h < C::NHT; h++) acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bh[h], acc[d][h], 0, 0, 0);
+#pragma unroll
+            for (int h = 0; h < C::NHT; h++) acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bl[h], acc[d][h], 0, 0, 0);
         }
+    };
+
+    auto ktile_of = [&](int it) { return smem + C::OFF_K + (it % C::NBUF) * C::TILE_BYTES; };
+    auto stage_load = [&](MlaStage<FP8>& st, int it) {
+        st.load(kbase + (size_t)it * C::T * row_bytes, row_bytes, FP8 ? sbase + it * C::T : nullptr,
+                min(C::T, n_tok - it * C::T), tid);
+    };
+    auto stage_store = [&](const MlaStage<FP8>& st, int it) {
+        st.store(ktile_of(it), smem + C::OFF_SCALE + (it % C::NBUF) * C::T * 4, tid);
+    };
+
+    // Pipeline over tiles, one barrier per tile.  In iteration `it` a wave computes the scores of
+    // tile it, then runs the MFMAs of P.V for tile it-1 in the same straight-line block as the VALU
+    // work of tile it's softmax, so the matrix pipe stays fed while the exponentials issue.
+    //   LDS tiles: it-1 (values), it (keys), it+1 (being filled) -> three buffers; weights of tile
+    //   it-1 are read while those of tile it are written -> two buffers.
+    // The outer loop runs once unless a reference exponent turned out too low (see the softmax).
+    for (;;) {
+        l_run = 0.f;
+#pragma unroll
+        for (int d = 0; d < 8; d++)
+#pragma unroll
+            for (int h = 0; h < C::NHT; h++) acc[d][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+        MlaStage<FP8> stage;
+        stage_load(stage, 0);
+        stage_store(stage, 0);
+        if (n_tiles > 1) stage_load(stage, 1);
+        __syncthreads();
+        {
+            f32x4 s[2];
+            scores(ktile_of(0), s);
+            softmax(s, 0, 0, min(C::T, n_tok), true);
+        }
+        if (n_tiles > 1) stage_store(stage, 1);
+        __syncthreads();
+        bool restart = false;
+        int it = 1;
+        for (; it < n_tiles; it++) {
+            const bool has_next = it + 1 < n_tiles;
+            if (has_next) stage_load(stage, it + 1);
+            f32x4 s[2];
+            scores(ktile_of(it), s);
+            if (__builtin_expect(overflowed((it - 1) & 1), 0)) { restart = true; break; }
+            pv(ktile_of(it - 1), (it - 1) & 1);
+            softmax(s, it % C::NBUF, it & 1, min(C::T, n_tok - it * C::T), false);
+            if (has_next) stage_store(stage, it + 1);
+            __syncthreads();
+        }
+        if (!restart && !overflowed((n_tiles - 1) & 1)) {
+            pv(ktile_of(n_tiles - 1), (n_tiles - 1) & 1);
+            break;
+        }
+        __syncthreads();                              // everybody has left the LDS buffers: start over
     }
 
     // ---- the workgroup's record: un-normalised O, reference exponent and normaliser per head ----

@@ -127,3 +127,19 @@ def test_mla_fp8_padded_storage(hx, oracle):
     inp = synth.make_inputs(w, "cuda")
     inp.lens = torch.tensor([300, 123], dtype=torch.int32)
     run_mla(hx, oracle, w, inp, 2)
+
+
+def test_mla_reference_restart_on_exploding_scores(hx, oracle):
+    """A key far down the run that is aligned with one head's query and scores >100 octaves above
+    everything in the first tile: the kernel's fixed reference exponent is too low and the workgroup
+    must start over with a higher one.  Two such keys of growing size force two restarts."""
+    w = synth.Workload("mla_explode", B=1, Q=128, K=1, dk=576, dv=512, n_shards=1, scale=1 / math.sqrt(192), seed=77,
+                       seq_len=400, mla=True)
+    inp = synth.make_inputs(w, "cuda")
+    inp.k[0, 0, 150] = (inp.q[0, 5].float() * 2.0).to(torch.bfloat16)      # head 5: ~120 octaves
+    inp.k[0, 0, 300] = (inp.q[0, 77].float() * 6.0).to(torch.bfloat16)     # head 77: ~360 octaves
+    o, lse = run_mla(hx, oracle, w, inp, 1)
+    assert torch.isfinite(o).all() and torch.isfinite(lse).all()
+    # heads 5 and 77 are (numerically) one-hot on their keys
+    v150 = inp.k[0, 0, 150, :512].float()
+    assert (o[0, 5] - v150).abs().max().item() <= 2e-3
