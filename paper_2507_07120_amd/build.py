@@ -10,6 +10,11 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 VALU ops out of scalar float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # no implicit fused multiply-add: the softmax weights are split into bf16 hi + lo, and an ulp-level
+    # change of a weight near a rounding boundary of the lo part moves the result by 2^-17; with
+    # contraction the compiler fuses differently in different code paths (full tile / ragged tile),
+    # which would make the same token's weight depend on where a shard boundary falls
+    "-ffp-contract=off",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

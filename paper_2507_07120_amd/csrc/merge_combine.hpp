@@ -65,9 +65,15 @@ __device__ __forceinline__ void shard_row_stats(const float* __restrict__ ws_m, 
     for (int k = 0; k < S::SL; k++) L += sm.l[k];
 }
 
+// lse = (M + log2 L) ln 2.  M is an integer and may sit far from the true maximum (the MLA kernel
+// keeps 32 octaves of headroom), so M and log2 L can cancel: L is split into 2^e * mant first, M + e
+// is exact, and only log2(mant) in (-1, 0] carries a rounding error.
 __device__ __forceinline__ float lse_of(float M, float L)
 {
-    return (L > 0.f) ? (M + __builtin_log2f(L)) * kLn2 : -INFINITY;
+    if (!(L > 0.f)) return -INFINITY;
+    const float e = (float)__builtin_amdgcn_frexp_expf(L);
+    const float mant = __builtin_amdgcn_frexp_mantf(L);
+    return ((M + e) + __builtin_log2f(mant)) * kLn2;
 }
 
 // The normalised partial O_i of the row: sum_j O_j 2^(m_j - M) / L.  Valid in threads tid < TPR
