@@ -1,0 +1,139 @@
+"""The benchmark configurations at FULL size, in the launch configuration bench.py times (automatic
+work split): sampled (b, h) rows against the CPU oracle, integer metadata bit-exact, and the GPU's
+sharded-then-combined output against its own unsharded output (max-abs 1e-5) where the
+configuration has several shards."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from test_gpu_parity_gqa import O_MAX_ABS, O_REL_L2, LSE_MAX_ABS, SHARD_VS_UNSHARDED
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hx():
+    import paper_2507_07120_amd as hx_
+    hx_.load_library()
+    assert torch.cuda.is_available()
+    return hx_
+
+
+def decode(hx, w, inp, n_shards, want_parts=False):
+    from paper_2507_07120_amd import harness
+    dev = "cuda"
+    prob = harness.problem_for(w)
+    seq_base = inp.seq_off[:-1].to(dev) if inp.seq_off is not None else None
+    ss = harness.make_shards(inp.k, inp.v, inp.lens.to(dev), n_shards, kv_scale=inp.kv_scale, seq_base=seq_base)
+    ws = harness.workspace_for(prob, n_shards, max(ss.max_lens), dev)
+    o = torch.full((w.B, w.Q, w.dv), float("nan"), device=dev)
+    lse = torch.full((w.B, w.Q), float("nan"), device=dev)
+    parts = lses = None
+    if want_parts:
+        parts = torch.empty((n_shards, w.B, w.Q, w.dv), device=dev)
+        lses = torch.empty((n_shards, w.B, w.Q), device=dev)
+    hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse, o_partials=parts, lses=lses)
+    torch.cuda.synchronize()
+    return o, lse, parts, lses, ss
+
+
+def oracle_rows(oracle, w, inp, rows):
+    """The oracle on the sampled (b,h) rows only; copies just those sequences to the host."""
+    out_o, out_l = [], []
+    for b, h in rows:
+        q = synth.bits(inp.q[b:b + 1])
+        if inp.seq_off is not None:                                   # packed ragged latent
+            lo, hi = int(inp.seq_off[b]), int(inp.seq_off[b + 1])
+            k = synth.bits(inp.k[lo:hi])
+            sc = inp.kv_scale[lo:hi].cpu().numpy() if inp.kv_scale is not None else None
+            o, l = oracle.attention(q, k, None, np.array([hi - lo], np.int32), w.scale, kv_heads=1, dv=w.dv,
+                                    kv_scale=sc, tok_off=np.zeros(1, np.int64), rows=[(0, h)])
+        else:
+            g = w.Q // w.K
+            kh = h // g
+            k = synth.bits(inp.k[b:b + 1, kh:kh + 1])
+            v = synth.bits(inp.v[b:b + 1, kh:kh + 1]) if inp.v is not None else None
+            # a one-KV-head problem holding exactly this row's group: head index within the group
+            qg = np.ascontiguousarray(q[:, kh * g:(kh + 1) * g])
+            o, l = oracle.attention(qg, k, v, inp.lens[b:b + 1].numpy(), w.scale, kv_heads=1, dv=w.dv, rows=[(0, h - kh * g)])
+        out_o.append(o[0])
+        out_l.append(l[0])
+    return np.stack(out_o), np.array(out_l)
+
+
+def check_rows(o, lse, o_ref, lse_ref, rows, what):
+    got = np.stack([o[b, h].cpu().numpy() for b, h in rows]).astype(np.float64)
+    gl = np.array([lse[b, h].item() for b, h in rows])
+    err = np.abs(got - o_ref).max()
+    rel = np.linalg.norm(got - o_ref) / np.linalg.norm(o_ref)
+    lerr = np.abs(gl - lse_ref).max()
+    print(f"{what}: O max-abs {err:.3e} rel-L2 {rel:.3e}  LSE max-abs {lerr:.3e}")
+    assert err <= O_MAX_ABS and rel <= O_REL_L2 and lerr <= LSE_MAX_ABS, what
+
+
+def test_gqa_share_full(hx, oracle):
+    w = synth.WORKLOADS["gqa_share"]
+    inp = synth.make_inputs(w, "cuda")
+    o, lse, _, _, _ = decode(hx, w, inp, 1)
+    assert torch.isfinite(o).all() and torch.isfinite(lse).all()
+    rows = [(0, 0), (3, 7), (9, 15), (15, 4)]
+    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    check_rows(o, lse, o_ref, lse_ref, rows, "gqa_share full size")
+
+
+def test_mla_share_full(hx, oracle):
+    w = synth.WORKLOADS["mla_share"]
+    inp = synth.make_inputs(w, "cuda")
+    o, lse, _, _, _ = decode(hx, w, inp, 1)
+    assert torch.isfinite(o).all() and torch.isfinite(lse).all()
+    rows = [(0, 0), (0, 77), (17, 127), (31, 64)]
+    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    check_rows(o, lse, o_ref, lse_ref, rows, "mla_share full size")
+
+
+def test_gqa_full_sharded_vs_unsharded_and_oracle(hx, oracle):
+    """1M-token context in 16 shards of 65536 with 1% of the keys scaled x8, all on one GPU."""
+    w = synth.WORKLOADS["gqa_full"]
+    inp = synth.make_inputs(w, "cuda")
+    o16, lse16, parts, lses, ss = decode(hx, w, inp, 16, want_parts=True)
+    off_ref, len_ref = oracle.shard_layout(inp.lens.numpy(), 16)
+    assert np.array_equal(ss.shard_off.cpu().numpy(), off_ref) and np.array_equal(ss.shard_len.cpu().numpy(), len_ref)
+    assert np.all(len_ref == 65536)
+    o1, lse1, _, _, _ = decode(hx, w, inp, 1)
+    d = (o16 - o1).abs().max().item()
+    print(f"gqa_full: sharded(16) vs unsharded max-abs {d:.3e}, |o| max {o1.abs().max().item():.3f}")
+    assert d <= SHARD_VS_UNSHARDED
+    assert (lse16 - lse1).abs().max().item() <= 1e-5
+    am = torch.empty((w.B, w.Q), dtype=torch.int32, device="cuda")
+    o2 = torch.empty_like(o16)
+    from paper_2507_07120_amd import harness
+    hx.helix_attn_combine(harness.problem_for(w), parts, lses, o2, argmax_shard=am)
+    torch.cuda.synchronize()
+    assert torch.equal(o2, o16)
+    assert np.array_equal(am.cpu().numpy(), oracle.argmax_f32(lses.cpu().numpy()))
+    rows = [(0, 0), (2, 37), (3, 63)]
+    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    check_rows(o16, lse16, o_ref, lse_ref, rows, "gqa_full sharded")
+    check_rows(o1, lse1, o_ref, lse_ref, rows, "gqa_full unsharded")
+
+
+def test_mla_fp8_ragged_full(hx, oracle):
+    """B=64 ragged lengths in [16384, 262144], e4m3 latent + per-token scale, 8 shards with uneven tails."""
+    w = synth.WORKLOADS["mla_fp8_ragged"]
+    inp = synth.make_inputs(w, "cuda")
+    lens = inp.lens.numpy()
+    assert lens.min() >= 16384 and lens.max() <= 262144
+    o8, lse8, _, _, ss = decode(hx, w, inp, 8)
+    off_ref, len_ref = oracle.shard_layout(lens, 8)
+    assert np.array_equal(ss.shard_off.cpu().numpy(), off_ref + inp.seq_off[:-1].numpy()[None, :])
+    assert np.array_equal(ss.shard_len.cpu().numpy(), len_ref)
+    assert torch.isfinite(o8).all() and torch.isfinite(lse8).all()
+    o1, lse1, _, _, _ = decode(hx, w, inp, 1)
+    d = (o8 - o1).abs().max().item()
+    print(f"mla_fp8_ragged: sharded(8) vs unsharded max-abs {d:.3e}")
+    assert d <= SHARD_VS_UNSHARDED
+    b_short, b_long = int(lens.argmin()), int(lens.argmax())
+    rows = [(b_short, 3), (b_long, 100), (7, 64)]
+    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    check_rows(o8, lse8, o_ref, lse_ref, rows, "mla_fp8_ragged sharded")
