@@ -63,30 +63,37 @@ class HipEvents:
             self.hip.hipEventDestroy(e)
 
 
-def cpu_baseline(w, inp, budget_rows):
+def cpu_baseline(w, inp, budget_macs=1.5e11):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same
-    workload: whole (b, h) rows over the full shard length."""
+    workload: the first nb sequences with all their heads over their full length, nb chosen so that
+    the sample is at most ~budget_macs multiply-adds (10-30 s of CPU work at most)."""
     import numpy as np
     import oracle
     import synth
-    g = w.Q // w.K
-    rows = [(b, h) for b in range(w.B) for h in range(w.Q)]
-    if budget_rows > 0:
-        rows = rows[:budget_rows]
-    nb = rows[-1][0] + 1
+    lens = inp.lens.numpy()
+    if w.fp8:
+        budget_macs /= 8          # decoding e4m3 codes element by element is that much slower in the oracle
+    per_seq = lens.astype(np.float64) * w.Q * (w.dk + w.dv)
+    nb = int(max(1, min(w.B, np.searchsorted(np.cumsum(per_seq), budget_macs, side="right"))))
     q = synth.bits(inp.q[:nb])
-    k = synth.bits(inp.k[:nb])
-    v = synth.bits(inp.v[:nb]) if inp.v is not None else None
-    lens = inp.lens[:nb].numpy()
+    kw = dict(kv_heads=w.K, dv=w.dv)
+    if inp.seq_off is not None:                       # packed ragged latent
+        hi = int(inp.seq_off[nb])
+        k, v = synth.bits(inp.k[:hi]), None
+        kw["tok_off"] = inp.seq_off[:nb].numpy()
+        if inp.kv_scale is not None:
+            kw["kv_scale"] = inp.kv_scale[:hi].cpu().numpy()
+    else:
+        k = synth.bits(inp.k[:nb])
+        v = synth.bits(inp.v[:nb]) if inp.v is not None else None
+        if inp.kv_scale is not None:
+            kw["kv_scale"] = inp.kv_scale[:nb].cpu().numpy()
     t0 = time.perf_counter()
-    oracle.attention(q, k, v, lens, w.scale, kv_heads=w.K, dv=w.dv, rows=rows)
+    oracle.attention(q, k, v, lens[:nb], w.scale, **kw)
     dt = time.perf_counter() - t0
-    # bytes the sample stands for: each (b,h) row reads its KV head's tokens; a group of g rows
-    # shares one KV head, so the sample covers len(rows)/g KV-head streams
-    per_token = w.dk * 2 if w.mla else (w.dk + w.dv) * 2
-    sample_bytes = sum(int(lens[b]) for b, _ in rows) * per_token / g
+    sample_bytes = kv_bytes_per_step(w, lens[:nb])
     return {"value": sample_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"{len(rows)} of {w.B * w.Q} (b,h) rows x {int(lens[0])} tokens, fp64, {dt:.1f} s",
+            "sample": f"first {nb} of {w.B} sequences, all {w.Q} heads, {int(lens[:nb].sum())} tokens, fp64, {dt:.1f} s",
             "seconds": dt}
 
 
@@ -112,7 +119,6 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) before the timed loop, so that a "
                          "rocprofv3 --pmc run holds a kernel of known traffic to scale the counters by")
-    ap.add_argument("--cpu-rows", type=int, default=0, help="(b,h) rows the oracle is timed on; 0 = the whole workload")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all KV shards live on it; there is no collective "
@@ -201,7 +207,7 @@ def main():
         "roofline": roof,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, inp, args.cpu_rows)
+        out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out))
 
 

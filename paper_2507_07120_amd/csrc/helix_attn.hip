@@ -32,6 +32,8 @@ struct Plan {
 
 constexpr int64_t kTargetWorkgroups = 256;   // CUs of an MI355X
 constexpr int64_t kMinSplitTokens = 512;
+constexpr int64_t kTargetWorkgroupsMla = 256;
+constexpr int64_t kMinSplitTokensMla = 4096;
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -80,8 +82,12 @@ int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_
     if (p->split_tokens > 0) {
         split = ceil_div(p->split_tokens, plan->granule) * plan->granule;
     } else {
-        split = ceil_div(ceil_div(rows * total, kTargetWorkgroups), plan->granule) * plan->granule;
-        split = std::max<int64_t>(split, kMinSplitTokens);
+        // MLA: 4096 tokens keep the 128 KB record of a workgroup below 3% of the latent bytes it reads.
+        // (More, smaller workgroups were measured slower on both MLA workloads, ragged included.)
+        const int64_t target = path == Path::Mla ? kTargetWorkgroupsMla : kTargetWorkgroups;
+        const int64_t floor_tokens = path == Path::Mla ? kMinSplitTokensMla : kMinSplitTokens;
+        split = ceil_div(ceil_div(rows * total, target), plan->granule) * plan->granule;
+        split = std::max<int64_t>(split, floor_tokens);
     }
     plan->split_tokens = (int32_t)split;
     plan->total_splits = 0;
@@ -326,7 +332,8 @@ size_t helix_attn_workspace_bytes(const helix_problem* problem, int32_t n_shards
     if (make_plan(problem, path, lens, n_shards, &plan) != HELIX_OK) return 0;
     const int64_t rows = (int64_t)problem->batch * problem->kv_heads * plan.head_tiles;
     int64_t worst = plan.total_splits;
-    if (problem->split_tokens == 0) worst = std::max<int64_t>(worst, ceil_div(kTargetWorkgroups, rows) + n_shards);
+    if (problem->split_tokens == 0)
+        worst = std::max<int64_t>(worst, ceil_div(path == Path::Mla ? kTargetWorkgroupsMla : kTargetWorkgroups, rows) + n_shards);
     return carve(problem, worst, n_shards, nullptr).bytes;
 }
 
