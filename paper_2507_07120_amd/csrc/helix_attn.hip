@@ -227,7 +227,7 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
                 if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                         MlaCfg::LDS_BYTES) != hipSuccess)
                     return HELIX_ERR_LAUNCH;
-                hipLaunchKernelGGL(kern, dim3((unsigned)units), dim3(256), MlaCfg::LDS_BYTES, stream, a);
+                hipLaunchKernelGGL(kern, dim3((unsigned)units), dim3(MlaCfg::THREADS), MlaCfg::LDS_BYTES, stream, a);
                 break;
             }
             default:
