@@ -161,13 +161,22 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ev = HipEvents(args.steps)
+    # timed region: exactly K steps, nothing else on the stream
     t0 = time.perf_counter()
+    for i in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    # the same K steps again with a hipEvent pair recorded around the streaming kernel of every step
+    # (the event packets sit between the kernels and cost a few microseconds per step, so they stay
+    # out of the region `value` is computed from; that region's own duration is reported alongside)
+    ev = HipEvents(args.steps)
+    t1 = time.perf_counter()
     for i in range(args.steps):
         hx.helix_attn_set_profile_events(ev.start[i], ev.stop[i])
         step()
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt_hooked = time.perf_counter() - t1
     hx.helix_attn_set_profile_events(None, None)
     kern_ms = sorted(ev.elapsed_ms(i) for i in range(args.steps))
     ev.destroy()
@@ -197,6 +206,7 @@ def main():
         "metric": "KV-shard decode attention achieved HBM GB/s (% of peak); us per decode step",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "us_per_step": ms_per_step * 1e3,
+        "us_per_step_with_event_hooks": dt_hooked / args.steps * 1e6,
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",

@@ -206,18 +206,6 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
         return;
     }
 
-    // Q as the score MFMA's B operand: lane (r,kc) holds head r, dims s*32 + kc*8 .. +8
-    bf16x8 qb[C::KS];
-    {
-        const uint16_t* qrow = a.q + ((size_t)b * a.Q + h0 + min(r, nh - 1)) * D + kc * 8;
-#pragma unroll
-        for (int s = 0; s < C::KS; s++) {
-            u32x4 w = *reinterpret_cast<const u32x4*>(qrow + s * 32);
-            if (r >= nh) w = u32x4{0, 0, 0, 0};
-            qb[s] = __builtin_bit_cast(bf16x8, w);
-        }
-    }
-
     const int64_t tok0 = (sh.tok_off ? sh.tok_off[b] : 0) + t0;
     const char* kbase = reinterpret_cast<const char*>(sh.k) + 2 * ((int64_t)b * sh.k_sb + (int64_t)kh * sh.k_sh + tok0 * sh.k_st);
     const char* vbase = reinterpret_cast<const char*>(sh.v) + 2 * ((int64_t)b * sh.v_sb + (int64_t)kh * sh.v_sh + tok0 * sh.v_st);
@@ -243,8 +231,22 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
     const int nw = n_full > wave ? (n_full - wave + 3) / 4 : 0;
     auto kptr = [&](int i) { return kbase + (size_t)(wave + 4 * i) * k_blk_bytes; };
     auto vptr = [&](int i) { return vbase + (size_t)(wave + 4 * i) * v_blk_bytes; };
+    if (nw > 0) gqa_load_block<D, false>(b0, kptr(0), vptr(0), k_row_bytes, v_row_bytes, r, kc, C::TB);
+
+    // (fetched after the first K/V block is on its way: the stream does not depend on Q)
+    // Q as the score MFMA's B operand: lane (r,kc) holds head r, dims s*32 + kc*8 .. +8
+    bf16x8 qb[C::KS];
+    {
+        const uint16_t* qrow = a.q + ((size_t)b * a.Q + h0 + min(r, nh - 1)) * D + kc * 8;
+#pragma unroll
+        for (int s = 0; s < C::KS; s++) {
+            u32x4 w = *reinterpret_cast<const u32x4*>(qrow + s * 32);
+            if (r >= nh) w = u32x4{0, 0, 0, 0};
+            qb[s] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
     if (nw > 0) {
-        gqa_load_block<D, false>(b0, kptr(0), vptr(0), k_row_bytes, v_row_bytes, r, kc, C::TB);
         int i = 0;
         for (; i + 2 < nw; i += 2) {
             gqa_load_block<D, false>(b1, kptr(i + 1), vptr(i + 1), k_row_bytes, v_row_bytes, r, kc, C::TB);

@@ -25,45 +25,10 @@ template <int DV>
 struct MergeSmem {
     static constexpr int TPR = DV / 4;   // threads covering one row with float4
     static constexpr int SL = 256 / TPR; // split lanes working side by side
-    float red[4];
+    float m[SL];
     float l[SL];
     float o[SL][DV];
 };
-
-// Reference exponent M = max_j m_j and normaliser L = sum_j l_j 2^(m_j - M) of one (shard, b, h)
-// row over its split records.  Records carry an integer reference exponent m (a float holding an
-// integer, or -inf for "no tokens"), so every rescale 2^(m_j - M) is exact.  All 256 threads call
-// it and all get the same bits.
-template <int DV>
-__device__ __forceinline__ void shard_row_stats(const float* __restrict__ ws_m, const float* __restrict__ ws_l,
-                                                int sb, int nsp, int bq, int rem, MergeSmem<DV>& sm, float& M, float& L)
-{
-    using S = MergeSmem<DV>;
-    const int tid = threadIdx.x;
-    float mloc = -INFINITY;
-    for (int j = tid; j < nsp; j += 256) mloc = fmaxf(mloc, ws_m[(size_t)(sb + j) * bq + rem]);
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, off));
-    __syncthreads();                       // previous users of sm are done
-    if ((tid & 63) == 0) sm.red[tid >> 6] = mloc;
-    __syncthreads();
-    M = fmaxf(fmaxf(sm.red[0], sm.red[1]), fmaxf(sm.red[2], sm.red[3]));
-    const int sl = tid / S::TPR;
-    if (tid % S::TPR == 0) {
-        float lacc = 0.f;
-        if (M != -INFINITY)
-            for (int j = sl; j < nsp; j += S::SL) {
-                const size_t rec = (size_t)(sb + j) * bq + rem;
-                const float mj = ws_m[rec];
-                if (mj != -INFINITY) lacc += ws_l[rec] * __builtin_amdgcn_exp2f(mj - M);
-            }
-        sm.l[sl] = lacc;
-    }
-    __syncthreads();
-    L = 0.f;
-#pragma unroll
-    for (int k = 0; k < S::SL; k++) L += sm.l[k];
-}
 
 // lse = (M + log2 L) ln 2.  M is an integer and may sit far from the true maximum (the MLA kernel
 // keeps 32 octaves of headroom), so M and log2 L can cancel: L is split into 2^e * mant first, M + e
@@ -76,31 +41,54 @@ __device__ __forceinline__ float lse_of(float M, float L)
     return ((M + e) + __builtin_log2f(mant)) * kLn2;
 }
 
-// The normalised partial O_i of the row: sum_j O_j 2^(m_j - M) / L.  Valid in threads tid < TPR
-// (4 columns each).
+// Folds the split records of one (shard, b, h) row: M = max_j m_j, L = sum_j l_j 2^(m_j - M),
+// O = sum_j O_j 2^(m_j - M) / L.  Records carry an integer reference exponent m (a float holding an
+// integer, or -inf for "no tokens"), so every rescale is an exact power of two and the running
+// maximum below changes no bit of the result.  One pass: all three loads of a record are issued
+// together (an empty record's O was never written and is discarded after the load).
+// Returns the normalised O (valid in threads tid < TPR, 4 columns each); M and L in all threads.
 template <int DV>
-__device__ __forceinline__ f32x4 shard_row_output(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
-                                                  int sb, int nsp, int bq, int rem, MergeSmem<DV>& sm, float M, float L)
+__device__ __forceinline__ f32x4 merge_row(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
+                                           const float* __restrict__ ws_l, int sb, int nsp, int bq, int rem,
+                                           MergeSmem<DV>& sm, float& M, float& L)
 {
     using S = MergeSmem<DV>;
     const int tid = threadIdx.x;
     const int sl = tid / S::TPR, c4 = (tid % S::TPR) * 4;
+    float Mt = -INFINITY, Lt = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (M != -INFINITY) {
-        for (int j = sl; j < nsp; j += S::SL) {
-            const size_t rec = (size_t)(sb + j) * bq + rem;
-            const float mj = ws_m[rec];
-            if (mj == -INFINITY) continue;            // empty record: its O was never written
-            acc += *reinterpret_cast<const f32x4*>(ws_o + rec * DV + c4) * __builtin_amdgcn_exp2f(mj - M);
+    for (int j = sl; j < nsp; j += S::SL) {
+        const size_t rec = (size_t)(sb + j) * bq + rem;
+        const float mj = ws_m[rec];
+        const float lj = ws_l[rec];
+        const f32x4 oj = *reinterpret_cast<const f32x4*>(ws_o + rec * DV + c4);
+        if (mj == -INFINITY) continue;
+        if (mj > Mt) {
+            const float f = __builtin_amdgcn_exp2f(Mt - mj);   // 0 from -inf
+            acc *= f;
+            Lt *= f;
+            Mt = mj;
         }
+        const float g = __builtin_amdgcn_exp2f(mj - Mt);
+        acc += oj * g;
+        Lt += lj * g;
     }
-    __syncthreads();
+    __syncthreads();                       // previous users of sm are done
     *reinterpret_cast<f32x4*>(&sm.o[sl][c4]) = acc;
+    if (c4 == 0) { sm.m[sl] = Mt; sm.l[sl] = Lt; }
     __syncthreads();
-    f32x4 s = {0.f, 0.f, 0.f, 0.f};
-    if (tid < S::TPR) {
+    M = -INFINITY;
 #pragma unroll
-        for (int k = 0; k < S::SL; k++) s += *reinterpret_cast<const f32x4*>(&sm.o[k][c4]);
+    for (int k = 0; k < S::SL; k++) M = fmaxf(M, sm.m[k]);
+    L = 0.f;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (M != -INFINITY) {
+#pragma unroll
+        for (int k = 0; k < S::SL; k++) {
+            const float f = __builtin_amdgcn_exp2f(sm.m[k] - M);   // 0 for a lane without records
+            L += sm.l[k] * f;
+            if (tid < S::TPR) s += *reinterpret_cast<const f32x4*>(&sm.o[k][c4]) * f;
+        }
         s *= (L > 0.f) ? 1.f / L : 0.f;
     }
     return s;
@@ -116,8 +104,7 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(const MergeArgs a)
     const int bq = a.B * a.Q;
     const int i = row / bq, rem = row % bq;
     float M, L;
-    shard_row_stats<DV>(a.ws_m, a.ws_l, a.split_base[i], a.n_splits[i], bq, rem, sm, M, L);
-    const f32x4 o = shard_row_output<DV>(a.ws_o, a.ws_m, a.split_base[i], a.n_splits[i], bq, rem, sm, M, L);
+    const f32x4 o = merge_row<DV>(a.ws_o, a.ws_m, a.ws_l, a.split_base[i], a.n_splits[i], bq, rem, sm, M, L);
     const size_t orow = (size_t)(a.shard0 + i) * bq + rem;
     if (tid < MergeSmem<DV>::TPR) *reinterpret_cast<f32x4*>(a.o_part + orow * DV + tid * 4) = o;
     if (tid == 0) a.lse_part[orow] = lse_of(M, L);
@@ -144,32 +131,48 @@ template <int DV>
 __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs f)
 {
     __shared__ MergeSmem<DV> sm;
-    __shared__ float sh_M[kMaxLaunchShards], sh_L[kMaxLaunchShards];
     const MergeArgs& a = f.m;
     const int tid = threadIdx.x;
     const int rem = blockIdx.x;          // b*Q + h
     const int bq = a.B * a.Q;
+    constexpr int TPR = MergeSmem<DV>::TPR;
+    if (a.n_shards == 1) {               // the combine of one fragment is the fragment itself, bit for bit
+        float M, L;
+        const f32x4 o = merge_row<DV>(a.ws_o, a.ws_m, a.ws_l, a.split_base[0], a.n_splits[0], bq, rem, sm, M, L);
+        if (tid < TPR) {
+            *reinterpret_cast<f32x4*>(a.o_part + (size_t)rem * DV + tid * 4) = o;
+            *reinterpret_cast<f32x4*>(f.o + (size_t)rem * DV + tid * 4) = o;
+        }
+        if (tid == 0) {
+            const float lse = lse_of(M, L);
+            a.lse_part[rem] = lse;
+            if (f.lse_out) f.lse_out[rem] = lse;
+        }
+        return;
+    }
+    __shared__ float sh_lse[kMaxLaunchShards];
     float top = -INFINITY;
     for (int i = 0; i < a.n_shards; i++) {
         float M, L;
-        shard_row_stats<DV>(a.ws_m, a.ws_l, a.split_base[i], a.n_splits[i], bq, rem, sm, M, L);
-        if (tid == 0) { sh_M[i] = M; sh_L[i] = L; a.lse_part[(size_t)i * bq + rem] = lse_of(M, L); }
-        top = fmaxf(top, lse_of(M, L));
+        const f32x4 o = merge_row<DV>(a.ws_o, a.ws_m, a.ws_l, a.split_base[i], a.n_splits[i], bq, rem, sm, M, L);
+        const float lse = lse_of(M, L);
+        if (tid < TPR) *reinterpret_cast<f32x4*>(a.o_part + ((size_t)i * bq + rem) * DV + tid * 4) = o;
+        if (tid == 0) { a.lse_part[(size_t)i * bq + rem] = lse; sh_lse[i] = lse; }
+        top = fmaxf(top, lse);
     }
     __syncthreads();
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float wsum = 0.f;
-    for (int i = 0; i < a.n_shards; i++) {
-        const float M = sh_M[i], L = sh_L[i];
-        const f32x4 o = shard_row_output<DV>(a.ws_o, a.ws_m, a.split_base[i], a.n_splits[i], bq, rem, sm, M, L);
-        if (tid < MergeSmem<DV>::TPR) {
-            *reinterpret_cast<f32x4*>(a.o_part + ((size_t)i * bq + rem) * DV + tid * 4) = o;
-            const float li = lse_of(M, L);
-            if (li != -INFINITY) combine_accumulate(acc, wsum, o, li, top);
+    // second loop: every thread re-reads its own columns of every fragment (it wrote them itself)
+    if (tid < TPR) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float wsum = 0.f;
+        if (top != -INFINITY) {
+            for (int i = 0; i < a.n_shards; i++) {
+                const float li = sh_lse[i];
+                if (li == -INFINITY) continue;
+                combine_accumulate(acc, wsum, *reinterpret_cast<const f32x4*>(a.o_part + ((size_t)i * bq + rem) * DV + tid * 4), li, top);
+            }
+            acc *= 1.f / wsum;
         }
-    }
-    if (tid < MergeSmem<DV>::TPR) {
-        if (top != -INFINITY) acc *= 1.f / wsum;
         *reinterpret_cast<f32x4*>(f.o + (size_t)rem * DV + tid * 4) = acc;
         if (tid == 0 && f.lse_out) f.lse_out[rem] = (top != -INFINITY) ? top + __logf(wsum) : -INFINITY;
     }
