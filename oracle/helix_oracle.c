@@ -183,7 +183,7 @@ int helix_oracle_attention(const oracle_problem *p, const int64_t *t_lo, const i
 }
 
 /*
- * Combine of N shard partials (Sec. 2.1.1: every rank "rescales and sums" the fragments):
+ * Combine of N shard partials (Sec. 2.1.1: every rank rescales the received fragments and adds them up):
  *     lse* = max_i lse_i ; w_i = exp(lse_i - lse*) ; O = sum_i w_i O_i / sum_i w_i ;
  *     LSE = lse* + ln sum_i w_i .
  * It follows from exp(lse_i) = sum over shard i of exp(s_t): the shard's share of the global
