@@ -268,7 +268,8 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         return s;                                     // lane (r,kc): head r, tokens 16th + 4kc + i
     };
 
-    // exponents (base 2) of the wave's scores, masked beyond the ragged end of the tile
+    // exponents (base 2) of the wave's scores, masked beyond the ragged end of the tile; returns this
+    // lane's maximum over its 4 tokens (-inf if none is valid)
     auto exponents = [&](const f32x4& s, int kb, int n_valid, float (&t)[4], float (&fs)[4]) {
         if (FP8) {
             const f32x4 f = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
@@ -285,7 +286,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             t[i] = x;
             bmax = fmaxf(bmax, x);
         }
-        return wave_xor_max_16_32(bmax);              // max over the wave's 16 tokens for head r (-inf if none valid)
+        return bmax;
     };
 
     // weights of the wave's scores for the fixed reference, as bf16 hi + lo into LDS buffer pb
@@ -307,13 +308,14 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         *reinterpret_cast<lds_u32x2*>(ph + C::P_BYTES) = u32x2{l01, l23};
     };
 
-    // Softmax of a tile after the first: the reference stays; a score more than kLimit octaves above
-    // it raises this wave's restart flag (all lanes store the same word: no divergent branch).
+    // Softmax of a tile after the first.  The reference stays, so no maximum has to be agreed on
+    // across lanes: every lane only checks its own 4 scores against the limit, and a ballot turns
+    // that into this wave's restart flag (all lanes store the same word: no divergent branch).
     auto softmax = [&](const f32x4& s, int kb, int pb, int n_valid) {
         float t[4], fs[4];
         const float top = __builtin_ceilf(exponents(s, kb, n_valid, t, fs));
         const bool over = top > m_ref + C::kLimit;
-        if (over) m_floor = top + C::kHeadroom;
+        if (over) m_floor = fmaxf(m_floor, top + C::kHeadroom);
         *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG + (pb * C::WAVES + wave) * 4) = __any(over) ? 1 : 0;
         weights(t, fs, pb);
     };
@@ -383,7 +385,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         {
             const f32x4 s = scores(ktile_of(0));
             float t[4], fs[4];
-            const float top = exponents(s, 0, min(C::T, n_tok), t, fs);
+            const float top = wave_xor_max_16_32(exponents(s, 0, min(C::T, n_tok), t, fs));   // over the wave's 16 tokens
             // the two waves that share these heads exchange the maxima of their token halves
             if (kc == 0) *reinterpret_cast<lds_f32*>(smem + C::OFF_TOP + (th * C::HPW + hq * 16 + r) * 4) = top;
             __syncthreads();
@@ -417,6 +419,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         }
         // Start over.  Heads share their reference between two waves: publish the raised floors.
         __syncthreads();                              // everybody has left the tile loop and the LDS buffers
+        m_floor = wave_xor_max_16_32(m_floor);        // the four lanes of a head saw different tokens
         if (kc == 0) *reinterpret_cast<lds_f32*>(smem + C::OFF_TOP + (th * C::HPW + hq * 16 + r) * 4) = m_floor;
         __syncthreads();
         m_floor = fmaxf(*reinterpret_cast<const lds_f32*>(smem + C::OFF_TOP + (hq * 16 + r) * 4),
