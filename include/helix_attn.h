@@ -141,6 +141,30 @@ int helix_attn_decode(const helix_problem *problem, const void *q,
 int helix_shard_layout(const int32_t *seq_len, const int64_t *seq_base, int32_t batch,
                        int32_t n_shards, int64_t *shard_off, int32_t *shard_len, void *hip_stream);
 
+#define HELIX_APPEND_BLOCK 16   /* decode tokens a KVP rank receives before the next rank takes over */
+
+/* Sec. 2.3 (distributed KV concatenation): which KVP rank stores the K/V of decode token
+ * `decode_index` (0 = the first token generated after prefill): HELIX_APPEND_BLOCK consecutive tokens go
+ * to rank 0, the next HELIX_APPEND_BLOCK to rank 1, ..., cycling over the n_shards ranks.  Host-only
+ * integer arithmetic; returns -1 for n_shards < 1 or a negative index. */
+int32_t helix_kv_append_owner(int64_t decode_index, int32_t n_shards);
+
+/* Sec. 2.3: staggered KV append.  Writes the new token's K (and V) row of every sequence and KV head
+ * into the shard of rank helix_kv_append_owner(decode_index, n_shards), at token position len[b] of
+ * that shard (after the shard's tok_off[b]), and then increments that shard's len[b].
+ *   shards      host array [N]; only the owner's descriptor is used.  Its k / v / kv_scale / len
+ *               memory is WRITTEN by this call although the struct declares it const.
+ *   k_new       device, KV dtype of the problem, [B,K,dk] contiguous
+ *   v_new       device [B,K,dv], or NULL iff v_aliases_k
+ *   scale_new   device fp32 [B,K], e4m3 only (NULL for bf16)
+ *   capacity    tokens per (sequence, kv head) the owner's storage can hold, counted from tok_off[b]; a
+ *               sequence that is already full is left untouched and *overflow (device int32, may
+ *               be NULL) is set to 1
+ * The caller keeps its host-side max_len of the owner shard up to date (+1 per call). */
+int helix_kv_append(const helix_problem *problem, const helix_kv_shard *shards, int32_t n_shards,
+                    int64_t decode_index, const void *k_new, const void *v_new, const float *scale_new,
+                    int32_t capacity, int32_t *overflow, void *hip_stream);
+
 /* How the library would cut the work: tokens per workgroup and workgroups of the attention launch
  * for the given shards' max_len (host array [N]).  For benchmarks and tests; launches nothing. */
 int helix_attn_plan(const helix_problem *problem, const int32_t *max_lens, int32_t n_shards,

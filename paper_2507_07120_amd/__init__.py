@@ -17,6 +17,8 @@ from .binding import (  # noqa: F401
     helix_attn_plan,
     helix_attn_set_profile_events,
     helix_attn_workspace_bytes,
+    helix_kv_append,
+    helix_kv_append_owner,
     helix_shard_layout,
     helix_status_string,
     library_path,

@@ -76,6 +76,10 @@ def load_library():
                                       vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.helix_shard_layout.restype = ctypes.c_int
     lib.helix_shard_layout.argtypes = [vp, vp, i32, i32, vp, vp, vp]
+    lib.helix_kv_append_owner.restype = ctypes.c_int32
+    lib.helix_kv_append_owner.argtypes = [i64, i32]
+    lib.helix_kv_append.restype = ctypes.c_int
+    lib.helix_kv_append.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(_CShard), i32, i64, vp, vp, vp, i32, vp, vp]
     lib.helix_attn_set_profile_events.restype = ctypes.c_int
     lib.helix_attn_set_profile_events.argtypes = [vp, vp]
     _lib = lib
@@ -259,3 +263,29 @@ def helix_shard_layout(seq_len: torch.Tensor, n_shards: int, shard_off: torch.Te
 def helix_attn_set_profile_events(start_event: Optional[int], stop_event: Optional[int]) -> None:
     """Raw hipEvent_t handles (or None, None) recorded around the streaming attention kernel."""
     _check(load_library().helix_attn_set_profile_events(start_event, stop_event), "helix_attn_set_profile_events")
+
+
+def helix_kv_append_owner(decode_index: int, n_shards: int) -> int:
+    return int(load_library().helix_kv_append_owner(int(decode_index), int(n_shards)))
+
+
+def helix_kv_append(problem: Problem, shards: Sequence[KVShard], decode_index: int, k_new: torch.Tensor,
+                    v_new: Optional[torch.Tensor], capacity: int, scale_new: Optional[torch.Tensor] = None,
+                    overflow: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Appends one decode token per sequence to the round-robin owner shard (its storage and len are written)."""
+    n = len(shards)
+    assert k_new.is_contiguous() and tuple(k_new.shape) == (problem.batch, problem.kv_heads, problem.dk)
+    if v_new is not None:
+        assert v_new.is_contiguous() and tuple(v_new.shape) == (problem.batch, problem.kv_heads, problem.dv)
+    if scale_new is not None:
+        assert scale_new.dtype == torch.float32 and scale_new.is_contiguous()
+    if overflow is not None:
+        assert overflow.dtype == torch.int32 and overflow.numel() == 1
+    p = problem.c()
+    arr = (_CShard * n)(*[s.c() for s in shards])
+    _check(load_library().helix_kv_append(ctypes.byref(p), arr, n, int(decode_index), k_new.data_ptr(),
+                                          None if v_new is None else v_new.data_ptr(),
+                                          None if scale_new is None else scale_new.data_ptr(),
+                                          int(capacity), None if overflow is None else overflow.data_ptr(),
+                                          _stream_ptr(stream)),
+           "helix_kv_append")

@@ -380,6 +380,42 @@ int helix_attn_decode(const helix_problem* problem, const void* q, const helix_k
     return combine_any(problem->dv, po, pl, o, lse_out, nullptr, n_shards, rows, stream);
 }
 
+int32_t helix_kv_append_owner(int64_t decode_index, int32_t n_shards)
+{
+    if (n_shards < 1 || decode_index < 0) return -1;
+    return (int32_t)((decode_index / HELIX_APPEND_BLOCK) % n_shards);
+}
+
+int helix_kv_append(const helix_problem* problem, const helix_kv_shard* shards, int32_t n_shards,
+                    int64_t decode_index, const void* k_new, const void* v_new, const float* scale_new,
+                    int32_t capacity, int32_t* overflow, void* hip_stream)
+{
+    Path path;
+    if (int rc = check_problem(problem, &path)) return rc;
+    if (!shards || !k_new) return HELIX_ERR_NULL;
+    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS || decode_index < 0 || capacity < 0) return HELIX_ERR_SHAPE;
+    const helix_kv_shard& s = shards[helix_kv_append_owner(decode_index, n_shards)];
+    if (int rc = check_shard(problem, &s)) return rc;
+    const bool fp8 = problem->kv_dtype == HELIX_KV_FP8_E4M3;
+    if (problem->v_aliases_k ? v_new != nullptr : v_new == nullptr) return problem->v_aliases_k ? HELIX_ERR_SHAPE : HELIX_ERR_NULL;
+    if (fp8 ? scale_new == nullptr : scale_new != nullptr) return fp8 ? HELIX_ERR_NULL : HELIX_ERR_SHAPE;
+    AppendArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.sh.k = s.k; a.sh.v = s.v; a.sh.kv_scale = s.kv_scale; a.sh.tok_off = s.tok_off; a.sh.len = s.len;
+    a.sh.k_sb = s.k_stride_b; a.sh.k_sh = s.k_stride_h; a.sh.k_st = s.k_stride_t;
+    a.sh.v_sb = s.v_stride_b; a.sh.v_sh = s.v_stride_h; a.sh.v_st = s.v_stride_t;
+    a.sh.s_sb = s.s_stride_b; a.sh.s_sh = s.s_stride_h;
+    a.k_new = static_cast<const uint8_t*>(k_new);
+    a.v_new = static_cast<const uint8_t*>(v_new);
+    a.scale_new = scale_new;
+    a.len = const_cast<int32_t*>(s.len);
+    a.overflow = overflow;
+    a.K = problem->kv_heads; a.dk = problem->dk; a.dv = problem->dv; a.esz = fp8 ? 1 : 2; a.capacity = capacity;
+    hipLaunchKernelGGL(helix::kv_append_kernel, dim3((unsigned)problem->batch), dim3(256), 0,
+                       static_cast<hipStream_t>(hip_stream), a);
+    return launch_status();
+}
+
 int helix_shard_layout(const int32_t* seq_len, const int64_t* seq_base, int32_t batch, int32_t n_shards,
                        int64_t* shard_off, int32_t* shard_len, void* hip_stream)
 {

@@ -228,4 +228,48 @@ __global__ void shard_layout_kernel(const int32_t* __restrict__ seq_len, const i
     shard_len[idx] = (int32_t)(hi - lo);
 }
 
+// Staggered KV append (Sec. 2.3): one workgroup per sequence copies the new token's row of every KV
+// head into the owner shard at position len[b] and bumps len[b].  Pure byte copies: esz bytes per
+// element, rows of dk (and dv) elements.
+struct AppendArgs {
+    ShardDev sh;          // the owner shard
+    const uint8_t* k_new; // [B][K][dk]
+    const uint8_t* v_new; // [B][K][dv] or NULL
+    const float* scale_new;
+    int32_t* len;         // the owner's len array (writable alias of sh.len)
+    int32_t* overflow;
+    int32_t K, dk, dv, esz, capacity;
+};
+
+__global__ __launch_bounds__(256) void kv_append_kernel(const AppendArgs a)
+{
+    const int b = blockIdx.x, tid = threadIdx.x;
+    __shared__ int s_len;
+    if (tid == 0) s_len = a.len[b];
+    __syncthreads();
+    const int len = s_len;
+    if (len >= a.capacity) {
+        if (tid == 0 && a.overflow) *a.overflow = 1;
+        return;
+    }
+    const int64_t tok = (a.sh.tok_off ? a.sh.tok_off[b] : 0) + len;
+    uint8_t* kdst = const_cast<uint8_t*>(static_cast<const uint8_t*>(a.sh.k));
+    uint8_t* vdst = const_cast<uint8_t*>(static_cast<const uint8_t*>(a.sh.v));
+    float* sdst = const_cast<float*>(a.sh.kv_scale);
+    const int krow = a.dk * a.esz, vrow = a.dv * a.esz;
+    for (int i = tid; i < a.K * krow; i += 256) {
+        const int kh = i / krow, x = i % krow;
+        kdst[((int64_t)b * a.sh.k_sb + (int64_t)kh * a.sh.k_sh + tok * a.sh.k_st) * a.esz + x] = a.k_new[((int64_t)b * a.K + kh) * krow + x];
+    }
+    if (a.v_new)
+        for (int i = tid; i < a.K * vrow; i += 256) {
+            const int kh = i / vrow, x = i % vrow;
+            vdst[((int64_t)b * a.sh.v_sb + (int64_t)kh * a.sh.v_sh + tok * a.sh.v_st) * a.esz + x] = a.v_new[((int64_t)b * a.K + kh) * vrow + x];
+        }
+    if (a.scale_new)
+        for (int kh = tid; kh < a.K; kh += 256)
+            sdst[(int64_t)b * a.sh.s_sb + (int64_t)kh * a.sh.s_sh + tok] = a.scale_new[(int64_t)b * a.K + kh];
+    if (tid == 0) a.len[b] = len + 1;     // every thread took its copy of the old length before the barrier
+}
+
 }  // namespace helix

@@ -102,3 +102,11 @@ def test_null_and_shape_errors_return_codes(hx):
     arr = (_CShard * 1)(shard())
     assert lib.helix_attn_decode(ctypes.byref(p), fake, arr, 0, fake, None, None, None, fake, 1 << 30, None) == 2
     assert lib.helix_attn_decode(ctypes.byref(p), fake, arr, 1, fake, None, fake, None, fake, 1 << 30, None) == 1
+
+
+def test_append_owner_matches_the_oracle_rule(hx, oracle):
+    """Sec. 2.3: 16 decode tokens per rank, round robin -- host integer arithmetic, bit-exact."""
+    for n in [1, 2, 3, 8, 16, 64]:
+        for t in list(range(0, 300)) + [10 ** 6, 2 ** 40 + 17]:
+            assert hx.helix_kv_append_owner(t, n) == oracle.round_robin_owner(t, n)
+    assert hx.helix_kv_append_owner(-1, 4) == -1 and hx.helix_kv_append_owner(3, 0) == -1
