@@ -7,37 +7,49 @@
 // MFMA-bound, so the design question is how to feed the matrix cores, not HBM.
 //
 // What was measured on MI355X and shaped the kernel:
-//   * one wavefront per SIMD issues a 16x16x32 bf16 MFMA only every ~21 cycles and cannot overlap its
-//     own VALU work with its MFMAs (each extra VALU op costs ~3.5 cycles); two wavefronts per SIMD
-//     reach the 16-cycle rate and hide each other's VALU and LDS waits -> 8 wavefronts per CU, at
-//     most 256 registers each;
-//   * LDS delivers ~220 B/clk per CU for 128-bit reads with 8 wavefronts, but only if the 16 rows x
-//     64 B of an MFMA operand hit distinct banks: latent rows are padded from 1152 to 1184 bytes;
-//   * ds_read_b64_tr_b16 hands out the transposed (value-column-major) operand straight from the
-//     row-major latent tile; global_load_lds_dwordx4 copies 16 bytes per lane from global memory
-//     into LDS without touching registers.
+//   * one wavefront per SIMD issues a 16x16x32 bf16 MFMA only every ~21 cycles; two per SIMD reach
+//     the 16-cycle rate -> 8 wavefronts per CU, at most 256 registers each;
+//   * a wavefront draws at most ~36 B/clk from LDS (a 1 KB operand read every ~28 cycles), all eight
+//     together ~210-245 B/clk, and only if the 16 rows x 64 B of an MFMA operand hit distinct banks:
+//     at the natural row stride of 1152 bytes they run 4-way conflicted; XOR-ing the 16-byte chunk
+//     index with (row & 7) removes the conflicts without padding.  The transposing read
+//     (ds_read_b64_tr_b16) is as fast per byte as the 128-bit read and hands out the value-column-
+//     major operand straight from the row-major latent tile;
+//   * every operand byte a wave reads is used by ONE score MFMA but by 2 x (head tiles) P.V MFMAs,
+//     so the P.V side is where sharing a wave's reads across more heads pays;
+//   * global_load_lds_dwordx4 copies 16 bytes per lane from global memory into LDS without touching
+//     registers.  When the compiler knows about an LDS DMA in flight it drains it (vmcnt(0)) before
+//     the next transposing LDS read, and a spilled register is reloaded by a vector memory load
+//     that waits behind every DMA in flight: the DMA is issued from inline assembly and waited for
+//     explicitly, and the tile loop must not spill;
+//   * the time of this kernel depends on the DATA (all-zero latents run 30 % faster than random
+//     ones at the same instruction stream): the part lowers its clock under the switching power of
+//     the matrix cores and LDS, so executed MFMAs and LDS bytes per useful flop are what counts.
 //
-// Workgroup = 8 wavefronts = one CU, HPW = 64 heads, a run of `split_tokens` latent rows in tiles of
-// 32 tokens.  (The two workgroups that cover the 128 heads of a token range are numbered 8 apart, so
-// they sit on the same XCD and the second one's latent reads hit that XCD's L2.)
-//   scores   S^T[token, head] = K . Q^T: wave w = (hq, th) owns heads 16hq..16hq+15 and tokens
-//            16th..16th+15 of every tile; its Q slice (16 x 576 bf16 = 72 registers) never moves,
-//            the K operands come from LDS.
-//   softmax  per wave on its 16x16 scores with an integer reference exponent that is FIXED for the
-//            whole run (set 32 octaves above the first tile's maximum): no rescale of accumulators
-//            inside the loop, ever; if a later tile exceeds the reference by more than 64 octaves
-//            the workgroup starts the run over with a higher reference (never seen on real logits,
-//            exercised by a test).  Weights go to LDS as bf16 hi + lo.
-//   P.V      O^T[dv, head] += V^T . P^T: wave w owns value columns 64w..64w+63 for all 64 heads
-//            (64 accumulator registers); V^T operands via the transposing LDS read, P^T operands
-//            from the weights all eight waves just wrote.
-//   The four waves with th = 0 run scores -> softmax -> P.V(previous tile), the four with th = 1
-//   run P.V(previous tile) -> scores -> softmax: the two waves of a SIMD are always in different
-//   phases, so one's exponentials issue under the other's MFMAs.  One barrier per tile.
+// Workgroup = 8 wavefronts = one CU, HPW = 128 heads (all heads of the usual MLA configuration: the
+// latent is read from HBM and copied into LDS once), a run of `split_tokens` latent rows in tiles
+// of 32 tokens kept in a ring of three LDS slots (in use, next, in flight).  Per tile:
+//   S phase  scores S^T[token, head] = K . Q^T: wave w owns heads 16w..16w+15 and both token halves
+//            (two independent MFMA chains); its Q slice (16 x 576 bf16 = 72 registers) never moves,
+//            the K operands come from LDS.  Softmax stays inside the wave, with an integer reference
+//            exponent that is FIXED for the whole run (32 octaves above the first tile's maximum): no
+//            rescale of accumulators, no cross-lane maximum in the loop.  A tile that exceeds the
+//            reference by more than 64 octaves raises a flag; the workgroup then redoes the run with
+//            a reference raised above everything it saw (never on real logits, exercised by a test).
+//            The lane's 8 weights go to LDS as bf16 hi + lo, already in the P.V operand's layout.
+//   barrier
+//   P phase  O^T[dv, head] += V^T . P^T: waves 2p and 2p+1 share heads 32p..32p+31 and split the value
+//            columns (256 each: 16 column tiles x 2 head tiles = 128 accumulator registers); the
+//            weights of the pair's 32 heads are held in registers, every V^T operand read feeds four
+//            MFMAs.  The DMA requests for the tile two ahead are spread between the MFMAs.
+//   barrier
+// Each wave copies 4 rows of every tile and awaits only its own share before the barrier that
+// publishes it.
 //
-// e4m3 latent: codes are widened to bf16 (exact) on their way into LDS; the per-token scale f_t
-// multiplies the score (s_t = f_t * q.k8_t) and the weight that meets the values (p_t * f_t), while
-// the normaliser sums the plain p_t.
+// e4m3 latent: the raw codes are DMA-ed into a per-wave staging area and widened to bf16 (exact) by
+// the wave that requested them when the tile is due; the per-token scale f_t multiplies the score
+// (s_t = f_t * q.k8_t) and the weight that meets the values (p_t * f_t), while the normaliser sums the
+// plain p_t.
 #pragma once
 #include "common.hpp"
 
@@ -46,25 +58,28 @@ namespace helix {
 struct MlaCfg {
     static constexpr int DK = 576, DV = 512;
     static constexpr int T = 32;                  // tokens per tile
-    static constexpr int ROW = 1184;              // LDS bytes per latent row (1152 + 32 pad)
+    static constexpr int ROW = 1152;              // LDS bytes per latent row; chunk c of row r sits at chunk c ^ (r & 7)
     static constexpr int KS = DK / 32;            // 18 k-steps of the score MFMA
-    static constexpr int NBUF = 3;                // latent tiles in LDS: values (it-1), keys (it), in flight (it+1)
-    static constexpr int TILE_BYTES = T * ROW;    // 37888
-    static constexpr int HPW = 64;                // heads per workgroup
-    static constexpr int NHT = HPW / 16;          // head tiles
+    static constexpr int NBUF = 3;                // latent tiles in LDS: in use, next, in flight
+    static constexpr int TILE_BYTES = T * ROW;    // 36864
     static constexpr int WAVES = 8;
+    static constexpr int HPW = 16 * WAVES;        // heads per workgroup: every wave scores 16 heads
     static constexpr int THREADS = WAVES * 64;
-    static constexpr int DVT = DV / 16 / WAVES;   // value-column tiles per wave (4)
-    static constexpr int P_BYTES = HPW * T * 2;   // one of hi / lo: [HPW heads][32 tokens] bf16
+    static constexpr int NHT = 2;                 // head tiles of a wave pair
+    static constexpr int DVT = DV / 16 / 2;       // value-column tiles per wave (16): a pair splits the columns
+    static constexpr int P_BYTES = NHT * 16 * T * 2;   // one of hi / lo of one pair: [32 heads][32 weights] bf16
+    static constexpr int AHEAD = 2;               // tiles between a tile's request and its first use
     // LDS map
     static constexpr int OFF_K = 0;
-    static constexpr int OFF_P = NBUF * TILE_BYTES;               // [2 buffers][hi, lo]
-    static constexpr int OFF_FLAG = OFF_P + 2 * 2 * P_BYTES;      // [2][8] int: a wave asks for a restart
-    static constexpr int OFF_TOP = OFF_FLAG + 2 * WAVES * 4;      // [2 token halves][HPW] fp32: first-tile maxima / final l
-    static constexpr int OFF_SCALE = OFF_TOP + 2 * HPW * 4;       // [NBUF][32] fp32 per-token scales
-    static constexpr int LDS_BYTES = OFF_SCALE + NBUF * T * 4;
+    static constexpr int OFF_P = NBUF * TILE_BYTES;               // [pair][hi, lo]
+    static constexpr int OFF_FLAG = OFF_P + (WAVES / 2) * 2 * P_BYTES;   // int: a wave saw a score beyond the limit
+    static constexpr int OFF_SCALE = OFF_FLAG + 16;               // [NBUF][32] fp32 per-token scales
+    static constexpr int OFF_DMA = OFF_SCALE + NBUF * T * 4;      // [THREADS][8] u32: per-lane source offsets of the tile DMA (5 used)
+    static constexpr int OFF_STAGE = OFF_DMA + THREADS * 32;      // [WAVES][4 rows][576] e4m3 codes on their way in
+    static constexpr int LDS_BYTES = OFF_STAGE + T * DK;
     static constexpr float kHeadroom = 32.f, kLimit = 64.f;
 };
+static_assert(MlaCfg::LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 
 typedef __attribute__((address_space(3))) uint8_t lds_byte;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -82,6 +97,35 @@ __device__ __forceinline__ u32x2 lds_read_tr16(const lds_byte* p)
     return __builtin_bit_cast(u32x2, v);
 }
 
+// The lane id behind a compiler barrier.  Per-lane LDS addresses derived from it are recomputed where
+// they are used (a handful of VALU instructions per phase) instead of being hoisted out of the tile
+// loop, where a dozen of them would sit in registers the kernel does not have.
+__device__ __forceinline__ int mla_opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+// Byte offset of (row, 16-byte chunk c) inside an LDS tile.
+__device__ __forceinline__ int mla_swz(int row, int c) { return row * MlaCfg::ROW + ((c ^ (row & 7)) << 4); }
+
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it leaves global loads and
+// LDS DMA in flight.
+__device__ __forceinline__ void mla_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Waits until at most N of this wave's vector memory loads (LDS DMA included) are outstanding.
+template <int N>
+__device__ __forceinline__ void mla_wait_vm()
+{
+    static_assert(N >= 0 && N < 16, "low four bits of the counter field");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
+
 // Workgroups of one shard are numbered so that the head tiles of the same token range are 8 apart:
 // consecutive workgroup ids go round-robin over the 8 XCDs, so ids that differ by 8 share an XCD
 // and with it an L2.  Shards are padded to a multiple of 8 token ranges (padding workgroups exit).
@@ -91,96 +135,154 @@ __host__ __device__ inline int mla_units_of_shard(int n_splits, int B, int head_
 }
 
 // bf16 latent tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l of a
-// wave instruction deposits its 16 bytes at the instruction's LDS base + 16*l; inactive lanes write
-// nothing -- checked on the device).  The padded tile is a run of 32 x 74 sixteen-byte positions
-// (72 data chunks + 2 pad per row) = 37 wave instructions, dealt 5 per wave.
+// wave instruction deposits its 16 bytes at M0 + 16*l; inactive lanes write nothing -- checked on
+// the device).  Wave w copies rows 4w..4w+3 of every tile: 288 sixteen-byte chunks = 4.5 wave
+// instructions (the fifth with 32 lanes).  LDS position (row, cpos) receives the global chunk
+// cpos ^ (row & 7) of that row (72 chunks per row is a multiple of 8, so the XOR stays inside it).
+// The instruction is written as inline assembly so that the compiler does not track it: a tracked
+// LDS DMA makes it drain the counter before unrelated LDS reads.  Waiting is explicit (mla_wait_vm);
+// M0 is otherwise unused in this kernel.
 struct MlaDma {
-    static constexpr int POS_PER_ROW = MlaCfg::ROW / 16;                    // 74
-    static constexpr int INSTRS = MlaCfg::T * POS_PER_ROW / 64;             // 37
-    static constexpr int PER_WAVE = (INSTRS + MlaCfg::WAVES - 1) / MlaCfg::WAVES;   // 5
-    static_assert(MlaCfg::T * POS_PER_ROW % 64 == 0, "tile must be whole wave instructions");
+    static constexpr int ROWS = MlaCfg::T / MlaCfg::WAVES;                  // 4
+    static constexpr int CHUNKS = ROWS * (MlaCfg::ROW / 16);                // 288
+    static constexpr int INSTRS = (CHUNKS + 63) / 64;                       // 5 per wave and tile
+    static constexpr int SHARE_BYTES = ROWS * MlaCfg::ROW;                  // 4608
+    static_assert(INSTRS == 5, "size of the offset table");
 
-    // Starts the copy of the tile at `src` (n_valid rows) into LDS buffer `dst`.  `wave` is uniform.
-    static __device__ __forceinline__ void issue(const char* src, uint32_t row_bytes, int n_valid, lds_byte* dst, int wave, int lane)
+    // Row within the tile of chunk q (< 320) of wave `wave`: q / 72 by multiplication.
+    static __device__ __forceinline__ int row_of(int wave, int q) { return wave * ROWS + ((q * 911) >> 16); }
+
+    // The source offset of a lane's chunk within a tile depends on the lane and the part only.  The
+    // five offsets live in an LDS table (32 bytes per thread) and are fetched at the start of every
+    // phase that issues DMA: held across the tile loop they would be five registers the kernel does
+    // not have, and a spilled offset is reloaded with a vector memory load that waits behind every
+    // DMA in flight.
+    struct Offsets { u32x4 a; uint32_t b; };
+    static __device__ __forceinline__ void init(lds_byte* table, uint32_t row_bytes, int wave, int lane, int tid)
     {
-        // The per-lane offsets are the same for every tile: the compiler hoists them out of the tile
-        // loop (five registers), which leaves ~8 instructions per DMA instead of ~20.
-        const int pos = wave * PER_WAVE * 64 + lane;
-        int row = pos / POS_PER_ROW, c = pos - row * POS_PER_ROW;
+        uint32_t o[INSTRS];
 #pragma unroll
-        for (int j = 0; j < PER_WAVE; j++) {
-            if (wave * PER_WAVE + j < INSTRS) {
-                if (c < 72 && row < n_valid)
-                    __builtin_amdgcn_global_load_lds(
-                        (const __attribute__((address_space(1))) void*)(src + ((uint32_t)row * row_bytes + (uint32_t)c * 16u)),
-                        dst + (wave * PER_WAVE + j) * 1024, 16, 0, 0);
-            }
-            c += 64;                                  // next instruction: 64 positions further
-            if (c >= POS_PER_ROW) { c -= POS_PER_ROW; row++; }
+        for (int j = 0; j < INSTRS; j++) {
+            const int q = j * 64 + lane, row = min(row_of(wave, q), wave * ROWS + ROWS - 1), cpos = q % 72;
+            o[j] = (uint32_t)row * row_bytes + (uint32_t)((cpos ^ (row & 7)) << 4);
         }
+        *reinterpret_cast<lds_u32x4*>(table + tid * 32) = u32x4{o[0], o[1], o[2], o[3]};
+        *reinterpret_cast<__attribute__((address_space(3))) uint32_t*>(table + tid * 32 + 16) = o[4];
+    }
+    static __device__ __forceinline__ Offsets fetch(const lds_byte* table, int tid)
+    {
+        Offsets f;
+        tid = mla_opaque(tid);
+        f.a = *reinterpret_cast<const lds_u32x4*>(table + tid * 32);
+        f.b = *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(table + tid * 32 + 16);
+        return f;
+    }
+
+    // Requests part j (one wave instruction, j < INSTRS) of this wave's rows of the tile at `src`
+    // (n_valid rows); `dst` = LDS byte address of the wave's share of the slot.  `src`, `dst`,
+    // `wave` are uniform.
+    static __device__ __forceinline__ void issue_part(int j, const Offsets& f, const char* src, int n_valid, uint32_t dst, int wave, int lane)
+    {
+        const uint32_t off = j < 4 ? f.a[j] : f.b;
+        bool live = j * 64 + 63 < CHUNKS || lane < CHUNKS - j * 64;
+        if (n_valid != MlaCfg::T) {                       // ragged last tile of a run (rare): per-lane row test
+            int l = lane;
+            asm volatile("" : "+v"(l));                  // keeps this arithmetic out of the tile loop's preheader
+            live = live && row_of(wave, j * 64 + l) < n_valid;
+        }
+        if (live)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(dst + j * 1024), "v"(off), "s"(src) : "memory");
     }
 
     // Zero-fills the rows a ragged tile does not have (their weights are zero, but 0 * garbage could
-    // be NaN) and waits for the copy to land; call before the barrier that publishes the tile.
-    static __device__ __forceinline__ void commit(int n_valid, lds_byte* dst, int wave, int lane)
+    // be NaN); the DMA skipped exactly these positions.
+    static __device__ __forceinline__ void zero_fill(int n_valid, lds_byte* tile, int wave, int lane)
     {
         if (n_valid < MlaCfg::T) {
-            const int pos0 = wave * PER_WAVE * 64 + lane;
+            uint32_t z = 0;
+            asm volatile("" : "+v"(lane), "+v"(z));          // nothing of this rare path is to live in the tile loop's registers
 #pragma unroll
-            for (int j = 0; j < PER_WAVE; j++) {
-                const int pos = pos0 + j * 64;
-                const int row = pos / POS_PER_ROW, c = pos - row * POS_PER_ROW;
-                if (wave * PER_WAVE + j < INSTRS && c < 72 && row >= n_valid)
-                    *reinterpret_cast<lds_u32x4*>(dst + pos * 16) = u32x4{0, 0, 0, 0};
+            for (int j = 0; j < INSTRS; j++) {
+                const int q = j * 64 + lane;
+                if (q < CHUNKS && row_of(wave, q) >= n_valid)
+                    *reinterpret_cast<lds_u32x4*>(tile + wave * SHARE_BYTES + q * 16) = u32x4{z, z, z, z};
             }
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);                                 // vmcnt(0): the DMA counts as a vector memory load
     }
 };
 
-// e4m3 latent tiles pass through registers: 16 codes per 16-byte chunk become 16 bf16 (exact: e4m3
-// has 3 mantissa bits and a 4-bit exponent) and go to LDS with ordinary stores.
-struct MlaStageFp8 {
-    static constexpr int CHUNKS_PER_ROW = 36;
-    static constexpr int CHUNKS = MlaCfg::T * CHUNKS_PER_ROW;               // 1152
-    static constexpr int PER_THREAD = (CHUNKS + MlaCfg::THREADS - 1) / MlaCfg::THREADS;   // 3
-    u32x4 regs[PER_THREAD];
-    float scale;                                                            // thread t < 32 holds token t's scale
+// e4m3 latent tiles: wave w DMAs the raw codes of rows 4w..4w+3 (2304 bytes = 2.25 wave
+// instructions) into its own staging area plus the four per-token scales straight into the scale
+// slot, and later widens its rows to bf16 (exact: e4m3 has 3 mantissa bits and a 4-bit exponent)
+// into the swizzled tile.  Staging is private to the wave: no barrier between request and conversion.
+struct MlaDmaFp8 {
+    static constexpr int ROWS = MlaDma::ROWS;
+    static constexpr int CHUNKS_PER_ROW = MlaCfg::DK / 16;                  // 36
+    static constexpr int CHUNKS = ROWS * CHUNKS_PER_ROW;                    // 144
+    static constexpr int INSTRS = (CHUNKS + 63) / 64;                       // 3 for the codes, one more for the scales
+    static constexpr int PARTS = INSTRS + 1;
+    static constexpr int SHARE_BYTES = ROWS * MlaCfg::DK;                   // 2304
 
-    __device__ __forceinline__ void load(const char* src, uint32_t row_bytes, const float* scales, int n_valid, int tid)
+    static __device__ __forceinline__ int row_of(int wave, int q) { return wave * ROWS + ((q * 1821) >> 16); }   // q / 36 for q < 192
+
+    static __device__ __forceinline__ void init(lds_byte* table, uint32_t row_bytes, int wave, int lane, int tid)
     {
+        uint32_t o[INSTRS];
 #pragma unroll
-        for (int j = 0; j < PER_THREAD; j++) {
-            const int ch = tid + MlaCfg::THREADS * j;
-            const int row = ch / CHUNKS_PER_ROW, cc = ch % CHUNKS_PER_ROW;
-            regs[j] = u32x4{0, 0, 0, 0};
-            if (ch < CHUNKS && row < n_valid)
-                regs[j] = *reinterpret_cast<const u32x4*>(src + (size_t)row * row_bytes + cc * 16);
+        for (int j = 0; j < INSTRS; j++) {
+            const int q = j * 64 + lane, row = min(row_of(wave, q), wave * ROWS + ROWS - 1), cpos = q % CHUNKS_PER_ROW;
+            o[j] = (uint32_t)row * row_bytes + (uint32_t)(cpos << 4);
         }
-        scale = (tid < n_valid && tid < MlaCfg::T) ? scales[tid] : 0.f;
+        *reinterpret_cast<lds_u32x4*>(table + tid * 32) = u32x4{o[0], o[1], o[2], 0};
     }
 
-    __device__ __forceinline__ void store(lds_byte* dst, lds_byte* dst_scale, int tid) const
+    // part j < INSTRS: codes; part INSTRS: scales.  `stage`, `scale_dst` = LDS byte addresses of the
+    // wave's staging area and of the tile's scale slot; `src`, `scales` = the tile in global memory.
+    static __device__ __forceinline__ void issue_part(int j, const MlaDma::Offsets& f, const char* src, const float* scales, int n_valid,
+                                                      uint32_t stage, uint32_t scale_dst, int wave, int lane)
     {
+        if (j < INSTRS) {
+            bool live = j * 64 + 63 < CHUNKS || lane < CHUNKS - j * 64;
+            if (n_valid != MlaCfg::T) {
+                int l = lane;
+                asm volatile("" : "+v"(l));
+                live = live && row_of(wave, j * 64 + l) < n_valid;
+            }
+            if (live)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                             :: "s"(stage + j * 1024), "v"(f.a[j]), "s"(src) : "memory");
+        } else {
+            if (lane < ROWS && wave * ROWS + lane < n_valid)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                             :: "s"(scale_dst + wave * ROWS * 4), "v"((uint32_t)lane * 4u), "s"(scales + wave * ROWS) : "memory");
+        }
+    }
+
+    // After the wave's DMA has landed: widen its rows into the tile; rows the tile does not have
+    // become zeros with scale zero.
+    static __device__ __forceinline__ void convert(int n_valid, const lds_byte* stage, lds_byte* tile, lds_byte* scale_slot, int wave, int lane)
+    {
+        lane = mla_opaque(lane);                          // addresses recomputed here, not carried through the tile loop
 #pragma unroll
-        for (int j = 0; j < PER_THREAD; j++) {
-            const int ch = tid + MlaCfg::THREADS * j;
-            const int row = ch / CHUNKS_PER_ROW, cc = ch % CHUNKS_PER_ROW;
-            if (ch >= CHUNKS) continue;
+        for (int j = 0; j < INSTRS; j++) {
+            const int q = j * 64 + lane;
+            if (q >= CHUNKS) continue;
+            const int row = row_of(wave, q), cc = q - (row - wave * ROWS) * CHUNKS_PER_ROW;
+            u32x4 w = {0, 0, 0, 0};
+            if (row < n_valid) w = *reinterpret_cast<const lds_u32x4*>(stage + q * 16);
             uint32_t o[8];
 #pragma unroll
             for (int d = 0; d < 4; d++) {
-                const uint32_t w = regs[j][d];
-                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
-                const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w, true);
+                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[d], false);
+                const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[d], true);
                 o[2 * d] = pack_bf16_rne(lo.x, lo.y);
                 o[2 * d + 1] = pack_bf16_rne(hi.x, hi.y);
             }
-            auto* q = reinterpret_cast<lds_u32x4*>(dst + row * MlaCfg::ROW + cc * 32);
-            q[0] = u32x4{o[0], o[1], o[2], o[3]};
-            q[1] = u32x4{o[4], o[5], o[6], o[7]};
+            *reinterpret_cast<lds_u32x4*>(tile + mla_swz(row, 2 * cc)) = u32x4{o[0], o[1], o[2], o[3]};
+            *reinterpret_cast<lds_u32x4*>(tile + mla_swz(row, 2 * cc + 1)) = u32x4{o[4], o[5], o[6], o[7]};
         }
-        if (tid < MlaCfg::T) *reinterpret_cast<lds_f32*>(dst_scale + tid * 4) = scale;
+        if (lane < ROWS && wave * ROWS + lane >= n_valid) *reinterpret_cast<lds_f32*>(scale_slot + (wave * ROWS + lane) * 4) = 0.f;
     }
 };
 
@@ -194,19 +296,23 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps wave-dependent addresses in SGPRs
     const int r = lane & 15, kc = lane >> 4;
-    const int hq = wave & 3, th = wave >> 2;                      // score tile of this wave: head tile, token half
+    const int pair = wave >> 1, half = wave & 1;                  // waves 2p, 2p+1 share heads 32p..32p+31
 
     // which (shard, split, sequence, head tile of HPW heads) this workgroup serves
     int u = blockIdx.x, si = 0;
     while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
     const ShardDev& sh = a.shard[si];
     u -= sh.unit_base;
-    const int grp = u / (8 * a.head_tiles), j8 = u % (8 * a.head_tiles);
-    const int logical = grp * 8 + (j8 & 7);
+    const int ug = u / (8 * a.head_tiles), j8 = u % (8 * a.head_tiles);
+    const int logical = ug * 8 + (j8 & 7);
     const int htw = j8 >> 3;
     if (logical >= sh.n_splits * a.B) return;         // padding workgroup
-    const int split = logical % sh.n_splits;
-    const int b = logical / sh.n_splits;
+    // Split index slow, sequence fast, and the sequence rotated by 3 per split: consecutive workgroup
+    // ids go to different XCDs, so every XCD sees every split index and a mix of sequences.  With
+    // ragged lengths the high split indices are mostly empty; were they tied to fixed XCDs (split =
+    // id mod n_splits), those XCDs would idle while the ones serving split 0 do all the work.
+    const int split = logical / a.B;
+    const int b = (logical % a.B + 3 * split) % a.B;
 
     const int len = sh.len[b];
     const int t0 = split * a.split_tokens;
@@ -220,11 +326,11 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         return;
     }
 
-    // Q slice of this wave as the score MFMA's B operand: lane (r,kc) holds head 16hq + r of the
+    // Q slice of this wave as the score MFMA's B operand: lane (r,kc) holds head 16*wave + r of the
     // workgroup, dims 32*ks + 8*kc .. +8
+    const int hl = wave * 16 + r;                     // this lane's head within the workgroup
     bf16x8 qb[C::KS];
     {
-        const int hl = hq * 16 + r;
         const uint16_t* qrow = a.q + ((size_t)b * a.Q + h0 + min(hl, nh - 1)) * C::DK + kc * 8;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ks++) {
@@ -243,130 +349,172 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     const int n_tok = t1 - t0;
     const int n_tiles = (n_tok + C::T - 1) / C::T;
 
-    float m_ref = -INFINITY;                          // reference exponent of head 16hq + r (integer-valued)
-    float m_floor = -INFINITY;                        // lower bound for it after a restart
-    float l_run = 0.f;                                // this lane's share of sum p over the wave's token halves
-    f32x4 acc[C::DVT][C::NHT];                        // O^T[64w + 16d + 4kc + i][16h + r]
+    float m_ref = -INFINITY;                          // reference exponent of head hl (integer-valued)
+    float m_floor = -INFINITY;                        // lower bound for it in a repeated run
+    float l_run = 0.f;                                // this lane's share of sum p (tokens 4kc+i, 16+4kc+i of every tile)
+    f32x4 acc[C::DVT][C::NHT];                        // O^T[256half + 16d + 4kc + i][32pair + 16h + r]
 
-    auto ktile_of = [&](int it) { return smem + C::OFF_K + (it % C::NBUF) * C::TILE_BYTES; };
+    auto ktile_of = [&](int slot) { return smem + C::OFF_K + slot * C::TILE_BYTES; };      // slot = tile index mod NBUF
+    auto next_slot = [](int slot) { return slot + 1 == C::NBUF ? 0 : slot + 1; };
+    auto valid_of = [&](int it) { return min(C::T, n_tok - it * C::T); };
 
-    // Scores of this wave's 16 heads against its 16 tokens of a latent tile in LDS.  The K operand
-    // reads run PD operands ahead of the MFMAs that consume them.
-    auto scores = [&](const lds_byte* ktile) {
-        constexpr int PD = 4;
-        bf16x8 kop[C::KS];
-        const lds_byte* kp = ktile + (th * 16 + r) * C::ROW + kc * 16;
-        auto rd = [&](int ks) { return __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(kp + ks * 64)); };
-        f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    // Scores of this wave's 16 heads against both token halves of a latent tile in LDS: two
+    // independent MFMA chains.  Chunk 4ks + kc of row 16half + r sits at chunk (4ks + kc) ^ f,
+    // f = row & 7 = r & 7: the low two bits of f permute kc, bit 2 swaps k-steps 2j and 2j+1 -> one
+    // per-lane base, +-64 bytes, immediates for ks and the half.  Reads run PD k-steps ahead.
+    auto scores = [&](const lds_byte* ktile, f32x4& s0, f32x4& s1) {
+        constexpr int PD = 3;
+        bf16x8 k0[C::KS], k1[C::KS];
+        const int l = mla_opaque(lane), r = l & 15, kc = l >> 4;
+        const int f = r & 7;
+        const lds_byte* kp = ktile + r * C::ROW + ((kc ^ (f & 3)) << 4);
+        const int flip = (f & 4) << 4;
+        auto rd = [&](int ks, int half) {
+            const lds_byte* q = ((ks & 1) ? kp - flip : kp + flip) + half * 16 * C::ROW;
+            return __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(q + ks * 64));
+        };
+        s0 = f32x4{0.f, 0.f, 0.f, 0.f};
+        s1 = s0;
 #pragma unroll
-        for (int o = 0; o < PD; o++) kop[o] = rd(o);
+        for (int o = 0; o < PD; o++) { k0[o] = rd(o, 0); k1[o] = rd(o, 1); }
 #pragma unroll
         for (int o = 0; o < C::KS; o++) {
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop[o], qb[o], s, 0, 0, 0);
-            if (o + PD < C::KS) kop[o + PD] = rd(o + PD);
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0[o], qb[o], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[o], qb[o], s1, 0, 0, 0);
+            if (o + PD < C::KS) { k0[o + PD] = rd(o + PD, 0); k1[o + PD] = rd(o + PD, 1); }
+            __builtin_amdgcn_sched_barrier(0);        // keep the reads PD k-steps ahead
         }
-        return s;                                     // lane (r,kc): head r, tokens 16th + 4kc + i
+        // lane (r,kc): head r; s0[i] = token 4kc + i, s1[i] = token 16 + 4kc + i
     };
 
-    // exponents (base 2) of the wave's scores, masked beyond the ragged end of the tile; returns this
-    // lane's maximum over its 4 tokens (-inf if none is valid)
-    auto exponents = [&](const f32x4& s, int kb, int n_valid, float (&t)[4], float (&fs)[4]) {
+    // exponents (base 2) of the lane's 8 scores, masked beyond the ragged end of the tile; returns
+    // their maximum (-inf if none is valid)
+    auto exponents = [&](const f32x4& s0, const f32x4& s1, int kb, int n_valid, float (&t)[8], float (&fs)[8]) {
         if (FP8) {
-            const f32x4 f = *reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(
-                smem + C::OFF_SCALE + kb * C::T * 4 + (th * 16 + kc * 4) * 4);
+            const auto* sc = reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(smem + C::OFF_SCALE + kb * C::T * 4);
+            const int kq = mla_opaque(lane) >> 4;
+            const f32x4 f0 = sc[kq], f1 = sc[4 + kq];
 #pragma unroll
-            for (int i = 0; i < 4; i++) fs[i] = f[i];
+            for (int i = 0; i < 4; i++) { fs[i] = f0[i]; fs[4 + i] = f1[i]; }
         }
         float bmax = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            float x = s[i] * a.scale_log2e;
+        for (int i = 0; i < 8; i++) {
+            float x = (i < 4 ? s0[i] : s1[i - 4]) * a.scale_log2e;
             if (FP8) x *= fs[i];
-            if (th * 16 + kc * 4 + i >= n_valid) x = -INFINITY;
+            if ((i >> 2) * 16 + kc * 4 + (i & 3) >= n_valid) x = -INFINITY;
             t[i] = x;
             bmax = fmaxf(bmax, x);
         }
         return bmax;
     };
 
-    // weights of the wave's scores for the fixed reference, as bf16 hi + lo into LDS buffer pb
-    auto weights = [&](const float (&t)[4], const float (&fs)[4], int pb) {
-        float p[4];
+    // Softmax of the wave's scores, entirely inside the wave: the lane's 8 weights are exactly the 8
+    // k-slots of lane (r,kc) in the P.V MFMA's B operand if slot e < 4 means token 4kc + e and slot
+    // e >= 4 token 16 + 4kc + e - 4 -- the V^T operand is read to match.  The reference is fixed, so
+    // no maximum has to be agreed on across lanes: every lane checks its own scores against the
+    // limit, a ballot turns that into the workgroup's redo flag.
+    auto softmax = [&](const f32x4& s0, const f32x4& s1, int kb, int n_valid) {
+        float t[8], fs[8], p[8];
+        const float top = __builtin_ceilf(exponents(s0, s1, kb, n_valid, t, fs));
+        const bool over = top > m_ref + C::kLimit;
+        if (over) m_floor = fmaxf(m_floor, top + C::kHeadroom);
+        if (__any(over)) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 1;
         float lsum = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            p[i] = (t[i] == -INFINITY) ? 0.f : exp2_rel(t[i], m_ref);
+        for (int i = 0; i < 8; i++) {
+            p[i] = exp2_rel(fmaxf(t[i], m_ref - 200.f), m_ref);   // masked (-inf) scores land 200 octaves down: exactly 0
             lsum += p[i];
             if (FP8) p[i] *= fs[i];
         }
         l_run += lsum;
-        const uint32_t h01 = pack_bf16_rne(p[0], p[1]), h23 = pack_bf16_rne(p[2], p[3]);
-        const uint32_t l01 = pack_bf16_rne(p[0] - as_f32(h01 << 16), p[1] - as_f32(h01 & 0xffff0000u));
-        const uint32_t l23 = pack_bf16_rne(p[2] - as_f32(h23 << 16), p[3] - as_f32(h23 & 0xffff0000u));
-        lds_byte* ph = smem + C::OFF_P + pb * 2 * C::P_BYTES + (hq * 16 + r) * (C::T * 2) + (th * 16 + kc * 4) * 2;
-        *reinterpret_cast<lds_u32x2*>(ph) = u32x2{h01, h23};
-        *reinterpret_cast<lds_u32x2*>(ph + C::P_BYTES) = u32x2{l01, l23};
-    };
-
-    // Softmax of a tile after the first.  The reference stays, so no maximum has to be agreed on
-    // across lanes: every lane only checks its own 4 scores against the limit, and a ballot turns
-    // that into this wave's restart flag (all lanes store the same word: no divergent branch).
-    auto softmax = [&](const f32x4& s, int kb, int pb, int n_valid) {
-        float t[4], fs[4];
-        const float top = __builtin_ceilf(exponents(s, kb, n_valid, t, fs));
-        const bool over = top > m_ref + C::kLimit;
-        if (over) m_floor = fmaxf(m_floor, top + C::kHeadroom);
-        *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG + (pb * C::WAVES + wave) * 4) = __any(over) ? 1 : 0;
-        weights(t, fs, pb);
-    };
-
-    // Did any wave ask for a restart while it computed the weights of tile buffer `pb`?  (uniform)
-    auto overflowed = [&](int pb) {
-        const auto f0 = *reinterpret_cast<const lds_u32x4*>(smem + C::OFF_FLAG + pb * 32);
-        const auto f1 = *reinterpret_cast<const lds_u32x4*>(smem + C::OFF_FLAG + pb * 32 + 16);
-        return (f0.x | f0.y | f0.z | f0.w | f1.x | f1.y | f1.z | f1.w) != 0;
-    };
-
-    // O^T[value cols of this wave, all heads of the workgroup] += V^T . P^T for one tile.  The four
-    // V^T operands stay in registers; the weights are fetched one head tile at a time (hi, lo).
-    auto pv = [&](const lds_byte* ktile, int pb) {
-        const lds_byte* pp = smem + C::OFF_P + pb * 2 * C::P_BYTES + r * (C::T * 2) + kc * 16;
-        // V^T operand: lane (r,kc) ends up with value column 64w + 16d + r, tokens 8kc .. 8kc+7
-        const lds_byte* vp = ktile + (kc * 8 + (r >> 2)) * C::ROW + (wave * 64 + (r & 3) * 4) * 2;
-        bf16x8 va[C::DVT];
+        u32x4 hi, lo;
 #pragma unroll
-        for (int d = 0; d < C::DVT; d++) {
-            const u32x2 v0 = lds_read_tr16(vp + d * 32), v1 = lds_read_tr16(vp + d * 32 + 4 * C::ROW);
-            va[d] = __builtin_bit_cast(bf16x8, u32x4{v0.x, v0.y, v1.x, v1.y});
+        for (int j = 0; j < 4; j++) {
+            hi[j] = pack_bf16_rne(p[2 * j], p[2 * j + 1]);
+            lo[j] = pack_bf16_rne(p[2 * j] - as_f32(hi[j] << 16), p[2 * j + 1] - as_f32(hi[j] & 0xffff0000u));
         }
-        bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(pp));
-        bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(pp + C::P_BYTES));
+        const int l = mla_opaque(lane);
+        lds_byte* pw = smem + C::OFF_P + pair * 2 * C::P_BYTES + (half * 16 + (l & 15)) * (C::T * 2) + (l >> 4) * 16;
+        *reinterpret_cast<lds_u32x4*>(pw) = hi;
+        *reinterpret_cast<lds_u32x4*>(pw + C::P_BYTES) = lo;
+    };
+
+    // O^T[value columns of this wave, 32 heads of the pair] += V^T . P^T for one tile.  The weights
+    // (two head tiles, hi and lo) stay in registers, the V^T operands stream through transposing
+    // reads.  Lane (r,kc) supplies rows 4kc + r/4 (first read) and 16 + that (second read), value
+    // columns 256half + 16d + 4(r%4) .. +3 = chunk 32half + 2d + (r%4)/2, byte 8*(r&1) within it;
+    // row & 7 is the same for both reads and touches the low three chunk bits: four per-lane bases
+    // (d % 4), immediates for d / 4 and the second row.  `between(j)` runs after the j-th group of
+    // three column tiles (the caller spreads its DMA requests there).
+    auto pv = [&](const lds_byte* ktile, auto&& between) {
+        const int l = mla_opaque(lane), r = l & 15, kc = l >> 4;
+        const lds_byte* pp = smem + C::OFF_P + pair * 2 * C::P_BYTES + r * (C::T * 2) + kc * 16;
+        bf16x8 bh[C::NHT], bl[C::NHT];
 #pragma unroll
         for (int h = 0; h < C::NHT; h++) {
-            const bf16x8 ch = bh, cl = bl;
-            if (h + 1 < C::NHT) {
-                bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(pp + (h + 1) * 16 * (C::T * 2)));
-                bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(pp + (h + 1) * 16 * (C::T * 2) + C::P_BYTES));
-            }
+            bh[h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(pp + h * 16 * (C::T * 2)));
+            bl[h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(pp + h * 16 * (C::T * 2) + C::P_BYTES));
+        }
+        const int vrow = 4 * kc + (r >> 2), vf = vrow & 7, cb = (r & 3) >> 1;
+        const lds_byte* vb = ktile + vrow * C::ROW + ((r & 1) << 3) + half * 512;
+        const lds_byte* ve[4];
 #pragma unroll
-            for (int d = 0; d < C::DVT; d++) acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[d], ch, acc[d][h], 0, 0, 0);
+        for (int e = 0; e < 4; e++) ve[e] = vb + (((2 * e + cb) ^ vf) << 4);
+        auto rd = [&](int d) {
+            const lds_byte* p0 = ve[d & 3] + (d >> 2) * 128;
+            const u32x2 v0 = lds_read_tr16(p0), v1 = lds_read_tr16(p0 + 16 * C::ROW);
+            return __builtin_bit_cast(bf16x8, u32x4{v0.x, v0.y, v1.x, v1.y});
+        };
+        constexpr int PD = 3;
+        bf16x8 va[C::DVT];
 #pragma unroll
-            for (int d = 0; d < C::DVT; d++) acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[d], cl, acc[d][h], 0, 0, 0);
+        for (int d = 0; d < PD; d++) va[d] = rd(d);
+#pragma unroll
+        for (int d = 0; d < C::DVT; d++) {
+#pragma unroll
+            for (int h = 0; h < C::NHT; h++) acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[d], bh[h], acc[d][h], 0, 0, 0);
+#pragma unroll
+            for (int h = 0; h < C::NHT; h++) acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[d], bl[h], acc[d][h], 0, 0, 0);
+            if (d + PD < C::DVT) va[d + PD] = rd(d + PD);
+            if (d % 3 == 1) between(d / 3);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // Tile `it` on its way into LDS: e4m3 rows pass through registers, bf16 rows are copied by the
-    // LDS DMA.  issue() starts the loads, commit() completes the tile as far as this thread is
-    // concerned; a barrier then publishes it.
-    MlaStageFp8 stage;
-    auto stage_issue = [&](int it) {
-        const int nv = min(C::T, n_tok - it * C::T);
-        if constexpr (FP8) stage.load(kbase + (size_t)it * C::T * row_bytes, row_bytes, sbase + it * C::T, nv, tid);
-        else MlaDma::issue(kbase + (size_t)it * C::T * row_bytes, row_bytes, nv, ktile_of(it), wave, lane);
+    // Tile `it` on its way into LDS slot `slot`.  stage_begin() fetches the lane's source offsets,
+    // stage_issue_part() requests one part, stage_commit() completes the tile as far as this wave
+    // is concerned (its own requests have landed; e4m3 rows are widened); a barrier then publishes it.
+    constexpr int AHEAD = C::AHEAD;
+    constexpr int PARTS = FP8 ? MlaDmaFp8::PARTS : MlaDma::INSTRS;
+    static_assert(AHEAD == 2 && C::NBUF == 3, "ring arithmetic: tile it+2 goes where tile it-1 was");
+    if constexpr (FP8) MlaDmaFp8::init(smem + C::OFF_DMA, row_bytes, wave, lane, tid);
+    else MlaDma::init(smem + C::OFF_DMA, row_bytes, wave, lane, tid);
+    MlaDma::Offsets dma_off;                              // valid from stage_begin() to the last part of that phase
+    auto stage_begin = [&]() { dma_off = MlaDma::fetch(smem + C::OFF_DMA, tid); };
+    auto stage_issue_part = [&](int it, int slot, int j) {
+        const char* src = kbase + (size_t)it * C::T * row_bytes;
+        if constexpr (FP8)
+            MlaDmaFp8::issue_part(j, dma_off, src, sbase + it * C::T, valid_of(it), (uint32_t)(uintptr_t)(smem + C::OFF_STAGE) + wave * MlaDmaFp8::SHARE_BYTES,
+                                  (uint32_t)(uintptr_t)(smem + C::OFF_SCALE) + slot * C::T * 4, wave, lane);
+        else
+            MlaDma::issue_part(j, dma_off, src, valid_of(it), (uint32_t)(uintptr_t)ktile_of(slot) + wave * MlaDma::SHARE_BYTES, wave, lane);
     };
-    auto stage_commit = [&](int it) {
-        if constexpr (FP8) stage.store(ktile_of(it), smem + C::OFF_SCALE + (it % C::NBUF) * C::T * 4, tid);
-        else MlaDma::commit(min(C::T, n_tok - it * C::T), ktile_of(it), wave, lane);
+    auto stage_issue = [&](int it, int slot) {
+        stage_begin();
+#pragma unroll
+        for (int j = 0; j < PARTS; j++) stage_issue_part(it, slot, j);
+    };
+    // `newer` = whole tiles (5 instructions per wave) requested after this one, which may stay in flight
+    auto stage_commit = [&](int it, int slot, int newer) {
+        if constexpr (FP8) {
+            mla_wait_vm<0>();
+            MlaDmaFp8::convert(valid_of(it), smem + C::OFF_STAGE + wave * MlaDmaFp8::SHARE_BYTES, ktile_of(slot), smem + C::OFF_SCALE + slot * C::T * 4, wave, lane);
+        } else {
+            MlaDma::zero_fill(valid_of(it), ktile_of(slot), wave, lane);
+            if (newer == 1) mla_wait_vm<MlaDma::INSTRS>();
+            else mla_wait_vm<0>();
+        }
     };
 
     // The outer loop runs once unless the reference exponent turned out too low.
@@ -376,74 +524,68 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         for (int d = 0; d < C::DVT; d++)
 #pragma unroll
             for (int h = 0; h < C::NHT; h++) acc[d][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (tid == 0) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 0;
 
-        // ---- tile 0: fixes the reference exponent of every head ----
-        stage_issue(0);
-        stage_commit(0);
-        __syncthreads();
-        if (n_tiles > 1) stage_issue(1);
+        // ---- first tiles on their way; tile 0 fixes the reference exponent of every head ----
+        if constexpr (FP8) {
+            // the staging area holds one tile: tile 1 is requested once tile 0 has been widened
+            stage_issue(0, 0);
+            stage_commit(0, 0, 0);
+            if (n_tiles > 1) stage_issue(1, 1);
+        } else {
+            // a tile counts as whole unless it is the last of the run
+            stage_issue(0, 0);
+            if (n_tiles > 1) stage_issue(1, 1);
+            stage_commit(0, 0, n_tiles > 2 ? 1 : 0);
+        }
+        mla_barrier();
         {
-            const f32x4 s = scores(ktile_of(0));
-            float t[4], fs[4];
-            const float top = wave_xor_max_16_32(exponents(s, 0, min(C::T, n_tok), t, fs));   // over the wave's 16 tokens
-            // the two waves that share these heads exchange the maxima of their token halves
-            if (kc == 0) *reinterpret_cast<lds_f32*>(smem + C::OFF_TOP + (th * C::HPW + hq * 16 + r) * 4) = top;
-            __syncthreads();
-            const float top2 = fmaxf(*reinterpret_cast<const lds_f32*>(smem + C::OFF_TOP + (hq * 16 + r) * 4),
-                                     *reinterpret_cast<const lds_f32*>(smem + C::OFF_TOP + (C::HPW + hq * 16 + r) * 4));
-            m_ref = fmaxf(__builtin_ceilf(top2) + C::kHeadroom, m_floor);        // finite: token 0 is valid
-            *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG + wave * 4) = 0;
-            weights(t, fs, 0);
+            float t[8], fs[8];
+            f32x4 s0, s1;
+            scores(ktile_of(0), s0, s1);
+            const float top = wave_xor_max_16_32(exponents(s0, s1, 0, valid_of(0), t, fs));
+            m_ref = fmaxf(__builtin_ceilf(top) + C::kHeadroom, m_floor);          // finite: token 0 is valid
         }
-        if (n_tiles > 1) stage_commit(1);
-        __syncthreads();
 
-        // ---- tiles 1 .. n-1, one barrier each; P.V runs one tile behind the scores ----
-        bool restart = false;
-        for (int it = 1; it < n_tiles; it++) {
-            const bool has_next = it + 1 < n_tiles;
-            if (has_next) stage_issue(it + 1);
-            const int nv = min(C::T, n_tok - it * C::T);
-            if (__builtin_expect(overflowed((it - 1) & 1), 0)) { restart = true; break; }
-            {
-                const f32x4 s = scores(ktile_of(it));
-                softmax(s, it % C::NBUF, it & 1, nv);
-                pv(ktile_of(it - 1), (it - 1) & 1);
+        // ---- the tile loop ----
+        for (int it = 0, slot = 0; it < n_tiles; it++) {
+            const int slot1 = next_slot(slot), slot2 = next_slot(slot1);
+            {   // S phase
+                f32x4 s0, s1;
+                scores(ktile_of(slot), s0, s1);
+                softmax(s0, s1, slot, valid_of(it));
+                if (it + 1 < n_tiles) stage_commit(it + 1, slot1, 0);
             }
-            if (has_next) stage_commit(it + 1);
-            __syncthreads();
+            mla_barrier();
+            {   // P phase
+                const bool more = it + AHEAD < n_tiles;
+                if (more) stage_begin();
+                pv(ktile_of(slot), [&](int j) { if (more && j < PARTS) stage_issue_part(it + AHEAD, slot2, j); });
+            }
+            mla_barrier();
+            slot = slot1;
         }
-        if (!restart && !overflowed((n_tiles - 1) & 1)) {
-            pv(ktile_of(n_tiles - 1), (n_tiles - 1) & 1);
-            break;
-        }
-        // Start over.  Heads share their reference between two waves: publish the raised floors.
-        __syncthreads();                              // everybody has left the tile loop and the LDS buffers
-        m_floor = wave_xor_max_16_32(m_floor);        // the four lanes of a head saw different tokens
-        if (kc == 0) *reinterpret_cast<lds_f32*>(smem + C::OFF_TOP + (th * C::HPW + hq * 16 + r) * 4) = m_floor;
-        __syncthreads();
-        m_floor = fmaxf(*reinterpret_cast<const lds_f32*>(smem + C::OFF_TOP + (hq * 16 + r) * 4),
-                        *reinterpret_cast<const lds_f32*>(smem + C::OFF_TOP + (C::HPW + hq * 16 + r) * 4));
-        __syncthreads();
+
+        if (__builtin_expect(*reinterpret_cast<const lds_i32*>(smem + C::OFF_FLAG) == 0, 1)) break;
+        // Some score went beyond the limit: run again with references above everything seen
+        // (the four lanes of a head saw different tokens).
+        m_floor = wave_xor_max_16_32(m_floor);
+        mla_barrier();                                // everybody has read the flag before it is cleared
     }
 
     // ---- the workgroup's record: un-normalised O, reference exponent and normaliser per head ----
     {
-        const float l = wave_xor_sum_16_32(l_run);    // this wave's token halves
-        __syncthreads();
-        if (th == 1 && kc == 0) *reinterpret_cast<lds_f32*>(smem + C::OFF_TOP + (hq * 16 + r) * 4) = l;
-        __syncthreads();
-        const int hl = hq * 16 + r;
-        if (th == 0 && kc == 0 && hl < nh) {
+        const float l = wave_xor_sum_16_32(l_run);
+        if (kc == 0 && hl < nh) {
             a.ws_m[rec + hl] = m_ref;
-            a.ws_l[rec + hl] = l + *reinterpret_cast<const lds_f32*>(smem + C::OFF_TOP + hl * 4);
+            a.ws_l[rec + hl] = l;
         }
     }
 #pragma unroll
     for (int h = 0; h < C::NHT; h++) {
-        const int hl = h * 16 + r;
-        if (hl < nh) {
-            float* orow = a.ws_o + (rec + hl) * C::DV + wave * 64 + kc * 4;
+        const int ho = pair * 32 + h * 16 + r;
+        if (ho < nh) {
+            float* orow = a.ws_o + (rec + ho) * C::DV + half * 256 + kc * 4;
 #pragma unroll
             for (int d = 0; d < C::DVT; d++) *reinterpret_cast<f32x4*>(orow + d * 16) = acc[d][h];
         }
