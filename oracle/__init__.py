@@ -14,6 +14,7 @@ shard_layout     how a sequence of L tokens is cut into N contiguous KVP shards.
 round_robin_owner  which KVP rank stores decode token t under staggered appends (Sec. 2.3).
 kv_read_seconds  Appendix A's KV-cache read-time formula.
 e4m3_value       OCP E4M3 code -> value, from the format definition.
+e2m1_value, e8m0_value   OCP microscaling FP4 element and shared scale codes -> values.
 
 Inputs are the exact stored bits: bf16 as uint16 arrays, e4m3 as uint8 arrays plus fp32 scales.
 """
@@ -26,6 +27,7 @@ from . import build as _build
 
 KV_BF16 = 0
 KV_FP8_E4M3 = 1
+KV_MXFP4 = 2
 
 _lib = None
 
@@ -42,6 +44,7 @@ class _Problem(ctypes.Structure):
         ("kv_scale", ctypes.c_void_p),
         ("s_sb", ctypes.c_int64), ("s_sh", ctypes.c_int64),
         ("tok_off", ctypes.c_void_p), ("len", ctypes.c_void_p),
+        ("k_mx", ctypes.c_void_p), ("v_mx", ctypes.c_void_p),
     ]
 
 
@@ -51,6 +54,9 @@ def lib():
         _lib = ctypes.CDLL(_build.build())
         _lib.helix_oracle_e4m3_value.restype = ctypes.c_double
         _lib.helix_oracle_e4m3_value.argtypes = [ctypes.c_uint8]
+        for name in ("helix_oracle_e2m1_value", "helix_oracle_e8m0_value"):
+            getattr(_lib, name).restype = ctypes.c_double
+            getattr(_lib, name).argtypes = [ctypes.c_uint8]
         _lib.helix_oracle_attention.restype = ctypes.c_int
         _lib.helix_oracle_combine.restype = ctypes.c_int
         _lib.helix_oracle_argmax_f32.restype = ctypes.c_int
@@ -67,12 +73,22 @@ def e4m3_value(code: int) -> float:
     return lib().helix_oracle_e4m3_value(int(code) & 0xFF)
 
 
+def e2m1_value(code: int) -> float:
+    """OCP microscaling FP4 element (E2M1) code 0..15 -> value."""
+    return lib().helix_oracle_e2m1_value(int(code) & 0xF)
+
+
+def e8m0_value(code: int) -> float:
+    """OCP microscaling shared scale (E8M0) code -> 2^(code-127), NaN for 255."""
+    return lib().helix_oracle_e8m0_value(int(code) & 0xFF)
+
+
 def _ptr(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 
 
 def attention(q, k, v, lens, scale, *, kv_heads, dv=None, kv_scale=None, tok_off=None,
-              t_lo=None, t_hi=None, rows=None):
+              t_lo=None, t_hi=None, rows=None, mx=None):
     """Exact softmax attention of one decode query per sequence.
 
     q         uint16 [B,Q,dk]   bf16 bits
@@ -84,6 +100,8 @@ def attention(q, k, v, lens, scale, *, kv_heads, dv=None, kv_scale=None, tok_off
     tok_off   int64 [B] row of sequence b's first token (ragged packed storage), or None
     t_lo,t_hi int64 [B] restrict to tokens [t_lo,t_hi) -- one shard; None = whole sequence
     rows      optional list of (b,h) pairs to evaluate instead of all B*Q rows
+    mx        (k_mx, v_mx) uint8 E8M0 scales [B,K,T,dk/32], [B,K,T,dv/32]: k, v are then MXFP4 codes,
+              uint8 [B,K,T,dk/2] and [B,K,T,dv/2], two E2M1 elements per byte (even element low nibble)
 
     Returns (o float64 [B,Q,dv] or [n_rows,dv], lse float64 [B,Q] or [n_rows]).
     """
@@ -91,15 +109,17 @@ def attention(q, k, v, lens, scale, *, kv_heads, dv=None, kv_scale=None, tok_off
     assert q.dtype == np.uint16 and q.ndim == 3
     B, Q, dk = q.shape
     K = int(kv_heads)
-    fp8 = k.dtype == np.uint8
+    fp4 = mx is not None
+    fp8 = k.dtype == np.uint8 and not fp4
     assert k.dtype in (np.uint16, np.uint8)
     assert k.flags.c_contiguous
     packed = k.ndim == 2
+    epb = 2 if fp4 else 1                                  # elements per stored unit
     if packed:
-        assert tok_off is not None and K == 1
+        assert tok_off is not None and K == 1 and not fp4
         k_sb, k_sh, k_st = 0, 0, k.shape[1]
     else:
-        assert k.ndim == 4 and k.shape[0] == B and k.shape[1] == K and k.shape[3] == dk
+        assert k.ndim == 4 and k.shape[0] == B and k.shape[1] == K and k.shape[3] * epb == dk
         k_sb, k_sh, k_st = K * k.shape[2] * dk, k.shape[2] * dk, dk
     alias = v is None
     if alias:
@@ -107,7 +127,7 @@ def attention(q, k, v, lens, scale, *, kv_heads, dv=None, kv_scale=None, tok_off
         v_sb = v_sh = v_st = 0
     else:
         assert v.dtype == k.dtype and v.flags.c_contiguous and v.ndim == k.ndim
-        dv = v.shape[-1]
+        dv = v.shape[-1] * epb
         if packed:
             v_sb, v_sh, v_st = 0, 0, dv
         else:
@@ -124,9 +144,18 @@ def attention(q, k, v, lens, scale, *, kv_heads, dv=None, kv_scale=None, tok_off
     t_lo_a = None if t_lo is None else np.ascontiguousarray(t_lo, dtype=np.int64)
     t_hi_a = None if t_hi is None else np.ascontiguousarray(t_hi, dtype=np.int64)
 
-    p = _Problem(B, Q, K, dk, dv, int(alias), KV_FP8_E4M3 if fp8 else KV_BF16, float(scale),
+    k_mx = v_mx = None
+    if fp4:
+        assert k.dtype == np.uint8 and dk % 32 == 0 and dv % 32 == 0
+        k_mx, v_mx = mx
+        assert k_mx.dtype == np.uint8 and k_mx.flags.c_contiguous and k_mx.shape == k.shape[:3] + (dk // 32,)
+        if not alias:
+            assert v_mx.dtype == np.uint8 and v_mx.flags.c_contiguous and v_mx.shape == v.shape[:3] + (dv // 32,)
+
+    p = _Problem(B, Q, K, dk, dv, int(alias), KV_MXFP4 if fp4 else KV_FP8_E4M3 if fp8 else KV_BF16, float(scale),
                  _ptr(q), _ptr(k), _ptr(v), k_sb, k_sh, k_st, v_sb, v_sh, v_st,
-                 _ptr(kv_scale) if fp8 else None, s_sb, s_sh, _ptr(tok_off_a), _ptr(lens))
+                 _ptr(kv_scale) if fp8 else None, s_sb, s_sh, _ptr(tok_off_a), _ptr(lens),
+                 _ptr(k_mx), _ptr(v_mx))
     if rows is None:
         n_rows, rb, rh = 0, None, None
         o = np.empty((B, Q, dv), dtype=np.float64)

@@ -21,8 +21,8 @@
  *
  * Pins (tests/test_oracle_pins.py): brute force against a high-precision evaluator, shard-split
  * identity, constant V, equal keys, single token, zero query, duplicated cache, key shift, GQA/MLA
- * structure, the e4m3 code table against the format definition, the combine's closed forms, and a
- * float64 library softmax.
+ * structure, the e4m3 / e2m1 / e8m0 code tables against the format definitions, MXFP4 input against the
+ * same values given as bf16, the combine's closed forms, and a float64 library softmax.
  */
 #include <math.h>
 #include <stdint.h>
@@ -34,6 +34,7 @@
 
 #define ORACLE_KV_BF16 0
 #define ORACLE_KV_FP8_E4M3 1
+#define ORACLE_KV_MXFP4 2
 
 /* bfloat16: the upper 16 bits of an IEEE binary32. */
 static double bf16_value(uint16_t bits)
@@ -61,6 +62,25 @@ double helix_oracle_e4m3_value(uint8_t code)
     return sign ? -mag : mag;
 }
 
+/* OCP microscaling FP4 element E2M1: 1 sign, 2 exponent (bias 1), 1 mantissa bit; no infinity, no
+ * NaN; exponent 0 is subnormal: m/2 * 2^0.  The magnitudes are 0, 0.5, 1, 1.5, 2, 3, 4, 6. */
+double helix_oracle_e2m1_value(uint8_t code)
+{
+    int sign = (code >> 3) & 1;
+    int e = (code >> 1) & 0x3;
+    int m = code & 0x1;
+    double mag = e == 0 ? (double)m / 2.0 : ldexp(1.0 + (double)m / 2.0, e - 1);
+    return sign ? -mag : mag;
+}
+
+/* OCP microscaling shared scale E8M0: an unsigned power of two 2^(code - 127); code 255 is NaN. */
+double helix_oracle_e8m0_value(uint8_t code)
+{
+    if (code == 0xFF)
+        return NAN;
+    return ldexp(1.0, (int)code - 127);
+}
+
 typedef struct {
     int32_t B, Q, K, dk, dv;
     int32_t v_aliases_k;      /* 1: value row = first dv entries of the key row (MLA latent) */
@@ -74,12 +94,22 @@ typedef struct {
     int64_t s_sb, s_sh;
     const int64_t *tok_off;   /* [B] first token row of sequence b, or NULL for 0 */
     const int32_t *len;       /* [B] number of tokens sequence b attends to */
+    /* MXFP4 only (the FP4 of the paper's evaluation, Sec. 3: microscaling formats): k / v hold E2M1
+     * codes, two per byte, element index idx in the low (idx even) or high (idx odd) nibble of byte
+     * idx/2; every 32 consecutive elements of a row share the E8M0 scale at index idx/32 of
+     * k_mx / v_mx (strides are multiples of 32 elements) */
+    const uint8_t *k_mx, *v_mx;
 } oracle_problem;
 
-static double kv_elem(const oracle_problem *p, const void *base, int64_t idx)
+static double kv_elem(const oracle_problem *p, const void *base, const uint8_t *mx, int64_t idx)
 {
     if (p->kv_dtype == ORACLE_KV_BF16)
         return bf16_value(((const uint16_t *)base)[idx]);
+    if (p->kv_dtype == ORACLE_KV_MXFP4) {
+        uint8_t byte = ((const uint8_t *)base)[idx / 2];
+        uint8_t code = (idx & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 0xF);
+        return helix_oracle_e8m0_value(mx[idx / 32]) * helix_oracle_e2m1_value(code);
+    }
     return helix_oracle_e4m3_value(((const uint8_t *)base)[idx]);
 }
 
@@ -115,7 +145,7 @@ static void attend_row(const oracle_problem *p, int b, int h, int64_t t_lo, int6
         int64_t kidx = (int64_t)b * p->k_sb + (int64_t)kh * p->k_sh + (row0 + t) * p->k_st;
         double dot = 0.0;
         for (int d = 0; d < dk; d++)
-            dot += qd[d] * kv_elem(p, p->k, kidx + d);
+            dot += qd[d] * kv_elem(p, p->k, p->k_mx, kidx + d);
         if (p->kv_dtype == ORACLE_KV_FP8_E4M3)
             dot *= (double)p->kv_scale[(int64_t)b * p->s_sb + (int64_t)kh * p->s_sh + row0 + t];
         s[t] = p->scale * dot;
@@ -129,6 +159,7 @@ static void attend_row(const oracle_problem *p, int b, int h, int64_t t_lo, int6
     for (int64_t t = 0; t < n; t++) {
         double w = exp(s[t] - m);
         const void *vbase = p->v_aliases_k ? p->k : p->v;
+        const uint8_t *vmx = p->v_aliases_k ? p->k_mx : p->v_mx;
         int64_t vidx = p->v_aliases_k
                            ? (int64_t)b * p->k_sb + (int64_t)kh * p->k_sh + (row0 + t) * p->k_st
                            : (int64_t)b * p->v_sb + (int64_t)kh * p->v_sh + (row0 + t) * p->v_st;
@@ -137,7 +168,7 @@ static void attend_row(const oracle_problem *p, int b, int h, int64_t t_lo, int6
             f = (double)p->kv_scale[(int64_t)b * p->s_sb + (int64_t)kh * p->s_sh + row0 + t];
         l += w;
         for (int j = 0; j < dv; j++)
-            o[j] += w * (f * kv_elem(p, vbase, vidx + j));
+            o[j] += w * (f * kv_elem(p, vbase, vmx, vidx + j));
     }
     for (int j = 0; j < dv; j++)
         o[j] /= l;
@@ -164,6 +195,12 @@ int helix_oracle_attention(const oracle_problem *p, const int64_t *t_lo, const i
         return -1;
     if (p->kv_dtype == ORACLE_KV_FP8_E4M3 && !p->kv_scale)
         return -1;
+    if (p->kv_dtype == ORACLE_KV_MXFP4) {
+        if (!p->k_mx || (!p->v_aliases_k && !p->v_mx))
+            return -1;
+        if (p->k_sb % 32 || p->k_sh % 32 || p->k_st % 32 || p->v_sb % 32 || p->v_sh % 32 || p->v_st % 32)
+            return -1;
+    }
     const int64_t total = n_rows > 0 ? n_rows : (int64_t)p->B * p->Q;
     int nth = 1;
 #ifdef _OPENMP

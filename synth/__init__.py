@@ -1,8 +1,8 @@
 """Seeded synthetic inputs for the Helix decode-attention tests and bench.
 
 Serves both the CPU oracle and the HIP library and contains none of the method's arithmetic: only
-random draws, rounding to the storage formats (bf16, e4m3 + per-token scale) and the shapes of the
-five workloads.  Every value is a pure function of (seed, tag, flat index) through a counter-based
+random draws, rounding to the storage formats (bf16, e4m3 + per-token scale, MXFP4) and the shapes of
+the workloads.  Every value is a pure function of (seed, tag, flat index) through a counter-based
 hash, so tensors can be produced chunk by chunk on any torch device.  Transcendentals differ by an
 ulp between devices, so a tensor is generated ONCE and its *bits* are handed to both sides.
 
@@ -119,6 +119,42 @@ def normal_e4m3_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", row
     return codes, scale
 
 
+def quantize_mxfp4(x: torch.Tensor):
+    """Rounds rows to the OCP microscaling FP4 format: blocks of 32 consecutive entries of the last
+    axis share one E8M0 scale 2^(floor(log2 max|x|) - 2) (2 = exponent of the largest E2M1 value, 6),
+    entries become round-to-nearest-even(x / scale) on the E2M1 grid {0, .5, 1, 1.5, 2, 3, 4, 6},
+    saturating.  An all-zero block gets scale code 127.  Returns (codes uint8 [..., D/2], two
+    entries per byte with the even one in the low nibble; scales uint8 [..., D/32]).  This is input
+    preparation: both the oracle and the GPU consume codes and scales, never ``x``."""
+    D = x.shape[-1]
+    assert D % 32 == 0
+    xf = x.to(torch.float32).reshape(*x.shape[:-1], D // 32, 32)
+    amax = xf.abs().amax(dim=-1)
+    _, e = torch.frexp(amax)                               # amax = m * 2^e, m in [0.5, 1)
+    shared = torch.where(amax > 0, e - 1 - 2, torch.zeros_like(e)).clamp_(-127, 127)
+    y = torch.ldexp(xf, -shared[..., None])
+    a = y.abs()
+    q = torch.where(a < 2, torch.round(a * 2) * 0.5, torch.where(a < 4, torch.round(a), torch.round(a * 0.5) * 2))
+    q = q.clamp_(max=6.0)
+    # magnitude -> code: 0, .5, 1, 1.5 are code = 2*value; 2, 3 -> 4, 5; 4, 6 -> 6, 7
+    code = torch.where(q < 2, q * 2, torch.where(q < 4, q + 2, q * 0.5 + 4)).to(torch.uint8)
+    code = code | ((y < 0) | ((y == 0) & torch.signbit(y))).to(torch.uint8) * 8
+    code = code.reshape(*x.shape[:-1], D // 2, 2)
+    packed = code[..., 0] | (code[..., 1] << 4)
+    return packed, (shared + 127).to(torch.uint8)
+
+
+def normal_mxfp4_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", row_chunk: int = 1 << 17):
+    """rows x dim N(0,1) values in MXFP4; returns (codes uint8 [rows, dim/2], scales uint8 [rows, dim/32])."""
+    codes = torch.empty((rows, dim // 2), dtype=torch.uint8, device=device)
+    scales = torch.empty((rows, dim // 32), dtype=torch.uint8, device=device)
+    for r in range(0, rows, row_chunk):
+        c = min(row_chunk, rows - r)
+        x = normal_f32(seed, tag, r * dim, c * dim, device).view(c, dim)
+        codes[r:r + c], scales[r:r + c] = quantize_mxfp4(x)
+    return codes, scales
+
+
 TAG_Q, TAG_K, TAG_V, TAG_PEAK, TAG_LEN = 1, 2, 3, 4, 5
 
 
@@ -138,6 +174,7 @@ class Workload:
     len_range: Optional[tuple] = None      # (lo, hi) inclusive for ragged lengths
     mla: bool = False                      # value = first dv entries of the key row
     fp8: bool = False                      # e4m3 codes + per-token fp32 scale
+    fp4: bool = False                      # MXFP4: e2m1 codes, one e8m0 scale per 32 entries of a row
     peak_prob: float = 0.0                 # fraction of key rows multiplied by peak_factor
     peak_factor: float = 1.0
     note: str = ""
@@ -162,6 +199,10 @@ WORKLOADS = {
     "mla_fp8_ragged": Workload("mla_fp8_ragged", B=64, Q=128, K=1, dk=576, dv=512, n_shards=8,
                                scale=1 / math.sqrt(192), seed=1005, len_range=(16384, 262144),
                                mla=True, fp8=True),
+    # the GQA share with the KV cache in MXFP4 (the precision of the paper's evaluation, Sec. 3) and a
+    # 4x longer context, which keeps the cache near 1 GiB: KVP=8 of a 4M-token context
+    "gqa_share_mxfp4": Workload("gqa_share_mxfp4", B=16, Q=16, K=1, dk=128, dv=128, n_shards=1,
+                                scale=1 / math.sqrt(128), seed=1006, seq_len=524288, fp4=True),
 }
 
 
@@ -183,6 +224,8 @@ class Inputs:
     kv_scale: Optional[torch.Tensor]
     lens: torch.Tensor                      # int32 [B], CPU
     seq_off: Optional[torch.Tensor]         # int64 [B+1], CPU (ragged only)
+    k_mx: Optional[torch.Tensor] = None     # MXFP4 only: uint8 [B,K,S,dk/32] block scales (k, v are uint8 codes)
+    v_mx: Optional[torch.Tensor] = None
 
 
 def make_inputs(w: Workload, device="cpu") -> Inputs:
@@ -201,6 +244,12 @@ def make_inputs(w: Workload, device="cpu") -> Inputs:
     S = w.seq_len
     lens = torch.full((w.B,), S, dtype=torch.int32)
     kv_scale = None
+    if w.fp4:
+        assert not w.mla and not w.fp8
+        kc, ks = normal_mxfp4_rows(w.seed, TAG_K, w.B * w.K * S, w.dk, device)
+        vc, vs = normal_mxfp4_rows(w.seed, TAG_V, w.B * w.K * S, w.dv, device)
+        return Inputs(w, q, kc.view(w.B, w.K, S, w.dk // 2), vc.view(w.B, w.K, S, w.dv // 2), None, lens, None,
+                      ks.view(w.B, w.K, S, w.dk // 32), vs.view(w.B, w.K, S, w.dv // 32))
     if w.fp8:
         codes, sc = normal_e4m3_rows(w.seed, TAG_K, w.B * w.K * S, w.dk, device)
         k, kv_scale = codes.view(w.B, w.K, S, w.dk), sc.view(w.B, w.K, S)

@@ -445,3 +445,88 @@ def test_appendix_a_kv_read_time(oracle):
             B, K, Hsz, S, bp, bw, TPA, KVP, sec = line.split()
             got = oracle.kv_read_seconds(int(B), int(K), int(Hsz), int(S), float(bp), float(bw), int(TPA), int(KVP))
             assert abs(got - float(sec)) <= 1e-15
+
+
+# ---------------------------------------------------------------- P13 MXFP4 storage (FP4 of the paper's evaluation, Sec. 3)
+def test_mxfp4_tables_against_format_definition(oracle):
+    with open(os.path.join(GOLDEN, "mxfp4_values.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            kind, code, val = line.split()
+            got = (oracle.e2m1_value if kind == "e2m1" else oracle.e8m0_value)(int(code, 16))
+            if val == "nan":
+                assert math.isnan(got)
+            else:
+                assert got == float(val) and math.copysign(1, got) == math.copysign(1, float(val)), (kind, code)
+    # closed form of the scale: successive codes double
+    for c in range(0, 254):
+        assert oracle.e8m0_value(c + 1) == 2.0 * oracle.e8m0_value(c)
+
+
+def _mxfp4_random(rng, shape_rows, D):
+    """Random MXFP4 codes / scales and their values: every product 2^(s-127) * e2m1 with s near 127 is
+    exactly representable in bf16, so the same tensor can be handed over as bf16 bits."""
+    grid = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0])
+    nib = rng.integers(0, 16, size=shape_rows + (D,)).astype(np.uint8)
+    sc = rng.integers(120, 134, size=shape_rows + (D // 32,)).astype(np.uint8)
+    vals = np.where(nib & 8, -1.0, 1.0) * grid[nib & 7] * np.exp2(np.repeat(sc.astype(np.float64), 32, axis=-1) - 127.0)
+    packed = (nib[..., 0::2] | (nib[..., 1::2] << 4)).astype(np.uint8)
+    return packed, sc, vals
+
+
+def test_mxfp4_attention_equals_the_same_values_given_as_bf16(oracle):
+    """Ties the MXFP4 read path (nibble order, scale index, strides) to the pinned bf16 path: identical
+    element values must give identical results, bit for bit."""
+    rng = np.random.default_rng(16)
+    B, Q, K, D, S = 2, 4, 2, 64, 37
+    q, _ = bf16_bits(rng.standard_normal((B, Q, D)))
+    kc, ks, kv = _mxfp4_random(rng, (B, K, S), D)
+    vc, vs, vv = _mxfp4_random(rng, (B, K, S), D)
+    kb, kf = bf16_bits(kv)
+    vb, vf = bf16_bits(vv)
+    assert np.array_equal(kf, kv) and np.array_equal(vf, vv)               # exactly representable
+    lens = np.array([S, S - 9], np.int32)
+    o4, l4 = oracle.attention(q, kc, vc, lens, 0.3, kv_heads=K, mx=(ks, vs))
+    o16, l16 = oracle.attention(q, kb, vb, lens, 0.3, kv_heads=K)
+    assert np.array_equal(o4, o16) and np.array_equal(l4, l16)
+    # a shard of it as well
+    t_lo, t_hi = np.array([5, 0], np.int64), np.array([30, 11], np.int64)
+    o4s, l4s = oracle.attention(q, kc, vc, lens, 0.3, kv_heads=K, mx=(ks, vs), t_lo=t_lo, t_hi=t_hi)
+    o16s, l16s = oracle.attention(q, kb, vb, lens, 0.3, kv_heads=K, t_lo=t_lo, t_hi=t_hi)
+    assert np.array_equal(o4s, o16s) and np.array_equal(l4s, l16s)
+
+
+def test_mxfp4_single_token_returns_the_decoded_value_row(oracle):
+    """S = 1: the output is the value row itself -- element j of the row must come from nibble j%2 of
+    byte j/2 and scale j/32 (a transposed nibble or a shifted scale index fails here)."""
+    D = 64
+    nib = (np.arange(D) * 7 + 3) % 16
+    packed = (nib[0::2] | (nib[1::2] << 4)).astype(np.uint8).reshape(1, 1, 1, D // 2)
+    sc = np.array([126, 129], np.uint8).reshape(1, 1, 1, 2)
+    q = np.zeros((1, 1, D), np.uint16)
+    o, lse = oracle.attention(q, packed, packed, np.array([1], np.int32), 1.0, kv_heads=1, mx=(sc, sc))
+    grid = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    want = [(-1.0 if n & 8 else 1.0) * grid[n & 7] * (0.5 if j < 32 else 4.0) for j, n in enumerate(nib)]
+    assert np.array_equal(o[0, 0], np.array(want)) and lse[0, 0] == 0.0
+
+
+def test_mxfp4_quantiser_round_trip_properties(oracle):
+    """The input generator's quantiser against the format: decoded values are within half a grid step
+    of the source (a quarter of the block scale times the local spacing), and the largest entry of a
+    block lands on 4 or 6 times the scale."""
+    import synth
+    x = synth.normal_f32(3, 9, 0, 64 * 128, "cpu").view(64, 128)
+    codes, scales = synth.quantize_mxfp4(x)
+    codes, scales = codes.numpy(), scales.numpy()
+    dec = np.empty((64, 128))
+    for r in range(64):
+        for j in range(128):
+            dec[r, j] = oracle.e8m0_value(scales[r, j // 32]) * oracle.e2m1_value(int(codes[r, j // 2]) >> (4 * (j & 1)))
+    xs = x.numpy().astype(np.float64)
+    X = np.repeat(np.array([[oracle.e8m0_value(s) for s in row] for row in scales]), 32, axis=1)
+    a = np.abs(xs) / X
+    step = np.where(a < 2, 0.5, np.where(a < 4, 1.0, 2.0))
+    assert np.all(np.abs(dec - xs) <= np.where(a > 6, a - 6 + 1e-12, step / 2 + 1e-12) * X)
+    top = np.abs(dec).reshape(64, 4, 32).max(-1) / np.array([[oracle.e8m0_value(s) for s in row] for row in scales])
+    assert np.all((top == 4.0) | (top == 6.0))
