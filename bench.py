@@ -26,10 +26,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 def kv_bytes_per_step(w, lens) -> int:
     """Algorithmic bytes: every stored K and V element of every token is read exactly once; an MLA
-    latent row serves as key and value and counts once; fp8 rows carry one fp32 scale."""
+    latent row serves as key and value and counts once; fp8 rows carry one fp32 scale, MXFP4 rows
+    half a byte per element plus one scale byte per 32 elements."""
     tokens = int(sum(int(x) for x in lens))
     if w.mla:
         per_token = w.dk * (1 if w.fp8 else 2) + (4 if w.fp8 else 0)
+    elif getattr(w, "fp4", False):
+        per_token = (w.dk + w.dv) // 2 + (w.dk + w.dv) // 32
     else:
         per_token = (w.dk + w.dv) * 2
     return tokens * w.K * per_token
@@ -71,8 +74,8 @@ def cpu_baseline(w, inp, budget_macs=1.5e11):
     import oracle
     import synth
     lens = inp.lens.numpy()
-    if w.fp8:
-        budget_macs /= 8          # decoding e4m3 codes element by element is that much slower in the oracle
+    if w.fp8 or getattr(w, "fp4", False):
+        budget_macs /= 8          # decoding codes element by element is that much slower in the oracle
     per_seq = lens.astype(np.float64) * w.Q * (w.dk + w.dv)
     nb = int(max(1, min(w.B, np.searchsorted(np.cumsum(per_seq), budget_macs, side="right"))))
     q = synth.bits(inp.q[:nb])
@@ -88,6 +91,8 @@ def cpu_baseline(w, inp, budget_macs=1.5e11):
         v = synth.bits(inp.v[:nb]) if inp.v is not None else None
         if inp.kv_scale is not None:
             kw["kv_scale"] = inp.kv_scale[:nb].cpu().numpy()
+        if inp.k_mx is not None:
+            kw["mx"] = (inp.k_mx[:nb].cpu().numpy(), inp.v_mx[:nb].cpu().numpy())
     t0 = time.perf_counter()
     oracle.attention(q, k, v, lens[:nb], w.scale, **kw)
     dt = time.perf_counter() - t0
@@ -141,7 +146,8 @@ def main():
     N = w.n_shards
     shard_off = torch.empty((N, w.B), dtype=torch.int64, device=dev)
     shard_len = torch.empty((N, w.B), dtype=torch.int32, device=dev)
-    ss = harness.make_shards(inp.k, inp.v, lens_dev, N, kv_scale=inp.kv_scale, seq_base=seq_base)
+    ss = harness.make_shards(inp.k, inp.v, lens_dev, N, kv_scale=inp.kv_scale, seq_base=seq_base,
+                             mx=None if inp.k_mx is None else (inp.k_mx, inp.v_mx))
     ws = harness.workspace_for(prob, N, max(ss.max_lens), dev)
     o = torch.empty((w.B, w.Q, w.dv), device=dev)
     lse = torch.empty((w.B, w.Q), device=dev)
@@ -196,7 +202,7 @@ def main():
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS}
     roof["traffic"] = read_traffic(args.workload)
-    roof["kernel"] = "mla_decode_kernel" if w.mla else f"gqa_decode_kernel<{w.dk}>"
+    roof["kernel"] = "mla_decode_kernel" if w.mla else "gqa_mxfp4_kernel" if getattr(w, "fp4", False) else f"gqa_decode_kernel<{w.dk}>"
     roof["kernel_us_avg"] = kern_avg_ms * 1e3
     roof["kernel_us_min"] = kern_ms[0] * 1e3
     roof["algorithmic_bytes"] = kv_bytes
@@ -212,7 +218,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "q_heads": w.Q, "kv_heads": w.K, "dk": w.dk, "dv": w.dv,
                    "n_shards": N, "tokens_per_step": int(sum(inp.lens.tolist())) * w.K,
-                   "kv_dtype": "e4m3+fp32 scale" if w.fp8 else "bf16",
+                   "kv_dtype": "e4m3+fp32 scale" if w.fp8 else "mxfp4 (e2m1 + e8m0 per 32)" if getattr(w, "fp4", False) else "bf16",
                    "split_tokens": split_tokens, "workgroups": workgroups},
         "roofline": roof,
     }

@@ -29,8 +29,9 @@
  *   - Every call returns a helix_status.  Arguments are validated on the host before anything
  *     is launched, so an error return means no kernel ran.
  *   - Supported shapes: (dk,dv) = (64,64) or (128,128) with bf16 K/V and any Q/K group size
- *     (the GQA path), and (dk,dv) = (576,512) with v_aliases_k = 1, kv_heads = 1, bf16 or
- *     e4m3 + per-token fp32 scale (the MLA path).  q is always bf16.
+ *     (the GQA path), (128,128) with MXFP4 K/V (the FP4 of the paper's evaluation, Sec. 3), and
+ *     (dk,dv) = (576,512) with v_aliases_k = 1, kv_heads = 1, bf16 or e4m3 + per-token fp32
+ *     scale (the MLA path).  q is always bf16.
  *   - Alignment: q, k, v rows must start on 16-byte boundaries: base pointers 16-byte aligned and
  *     all strides multiples of 16 bytes.
  */
@@ -55,7 +56,11 @@ typedef enum {
 
 typedef enum {
     HELIX_KV_BF16 = 0,
-    HELIX_KV_FP8_E4M3 = 1      /* OCP e4m3 codes, value = code * kv_scale[token] */
+    HELIX_KV_FP8_E4M3 = 1,     /* OCP e4m3 codes, value = code * kv_scale[token] */
+    HELIX_KV_MXFP4 = 2         /* OCP microscaling FP4 (the precision Sec. 3 evaluates in): E2M1 codes, two per byte
+                                  (even element in the low nibble); every 32 consecutive elements of a
+                                  row share one E8M0 scale byte; value = 2^(scale - 127) * e2m1(code).
+                                  Scale codes 0 and 255 (2^-127, NaN) are not supported. */
 } helix_kv_dtype;
 
 #define HELIX_MAX_SHARDS 1024
@@ -78,11 +83,15 @@ typedef struct helix_problem {
 /* One KV-sequence shard = the slice of the cache one KVP rank holds (Sec. 2.1.1).
  * Key element (b, kh, t, d), t counted from the shard's first token of sequence b, lives at
  *     k + b*k_stride_b + kh*k_stride_h + (tok_off[b] + t)*k_stride_t + d        (in elements)
- * and values / scales follow the same scheme with their own strides (scale: token stride 1). */
+ * and values / scales follow the same scheme with their own strides (scale: token stride 1).
+ * MXFP4: strides still count ELEMENTS (two per byte); the code of element index e sits in byte e/2
+ * of k (v), its block scale in byte e/32 of k_scale_mx (v_scale_mx).  Token rows must be dense
+ * (k_stride_t == dk, v_stride_t == dv), the other strides multiples of 128, the scale arrays
+ * 4-byte aligned. */
 typedef struct helix_kv_shard {
     const void *k;          /* bf16 or e4m3 */
     const void *v;          /* same dtype; must be NULL iff v_aliases_k */
-    const float *kv_scale;  /* e4m3 only: one fp32 per (b, kh, token); NULL for bf16 */
+    const float *kv_scale;  /* e4m3 only: one fp32 per (b, kh, token); NULL otherwise */
     int64_t k_stride_b, k_stride_h, k_stride_t;
     int64_t v_stride_b, v_stride_h, v_stride_t;
     int64_t s_stride_b, s_stride_h;
@@ -90,6 +99,8 @@ typedef struct helix_kv_shard {
                                storage, or a view into an unsharded cache); NULL = 0 */
     const int32_t *len;     /* [B] tokens of sequence b in THIS shard; 0 is allowed */
     int32_t max_len;        /* host copy of an upper bound of len[b] (sizes the grid); >= 0 */
+    const uint8_t *k_scale_mx; /* MXFP4 only: E8M0 block scales of k; NULL otherwise */
+    const uint8_t *v_scale_mx; /* MXFP4 only: E8M0 block scales of v; NULL otherwise */
 } helix_kv_shard;
 
 /* Bytes of workspace helix_attn_partial / helix_attn_decode need for `n_shards` shards whose
@@ -164,6 +175,14 @@ int32_t helix_kv_append_owner(int64_t decode_index, int32_t n_shards);
 int helix_kv_append(const helix_problem *problem, const helix_kv_shard *shards, int32_t n_shards,
                     int64_t decode_index, const void *k_new, const void *v_new, const float *scale_new,
                     int32_t capacity, int32_t *overflow, void *hip_stream);
+
+/* The same for an MXFP4 cache (helix_kv_append returns HELIX_ERR_UNSUPPORTED for it):
+ *   k_codes, v_codes    device uint8 [B,K,dk/2], [B,K,dv/2]: the new rows' E2M1 codes
+ *   k_scales, v_scales  device uint8 [B,K,dk/32], [B,K,dv/32]: their E8M0 block scales */
+int helix_kv_append_mxfp4(const helix_problem *problem, const helix_kv_shard *shards, int32_t n_shards,
+                          int64_t decode_index, const void *k_codes, const void *v_codes,
+                          const uint8_t *k_scales, const uint8_t *v_scales,
+                          int32_t capacity, int32_t *overflow, void *hip_stream);
 
 /* How the library would cut the work: tokens per workgroup and workgroups of the attention launch
  * for the given shards' max_len (host array [N]).  For benchmarks and tests; launches nothing. */

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     HelixError,
     KV_BF16,
     KV_FP8_E4M3,
+    KV_MXFP4,
     KVShard,
     Problem,
     helix_attn_combine,
@@ -18,6 +19,7 @@ from .binding import (  # noqa: F401
     helix_attn_set_profile_events,
     helix_attn_workspace_bytes,
     helix_kv_append,
+    helix_kv_append_mxfp4,
     helix_kv_append_owner,
     helix_shard_layout,
     helix_status_string,

@@ -12,6 +12,7 @@ import torch
 
 KV_BF16 = 0
 KV_FP8_E4M3 = 1
+KV_MXFP4 = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libhelix_attn.so")
@@ -35,7 +36,8 @@ class _CShard(ctypes.Structure):
                 ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_t", ctypes.c_int64),
                 ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
                 ("s_stride_b", ctypes.c_int64), ("s_stride_h", ctypes.c_int64),
-                ("tok_off", ctypes.c_void_p), ("len", ctypes.c_void_p), ("max_len", ctypes.c_int32)]
+                ("tok_off", ctypes.c_void_p), ("len", ctypes.c_void_p), ("max_len", ctypes.c_int32),
+                ("k_scale_mx", ctypes.c_void_p), ("v_scale_mx", ctypes.c_void_p)]
 
 
 def library_path() -> str:
@@ -80,6 +82,8 @@ def load_library():
     lib.helix_kv_append_owner.argtypes = [i64, i32]
     lib.helix_kv_append.restype = ctypes.c_int
     lib.helix_kv_append.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(_CShard), i32, i64, vp, vp, vp, i32, vp, vp]
+    lib.helix_kv_append_mxfp4.restype = ctypes.c_int
+    lib.helix_kv_append_mxfp4.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(_CShard), i32, i64, vp, vp, vp, vp, i32, vp, vp]
     lib.helix_attn_set_profile_events.restype = ctypes.c_int
     lib.helix_attn_set_profile_events.argtypes = [vp, vp]
     _lib = lib
@@ -121,6 +125,8 @@ class KVShard:
     kv_scale: Optional[torch.Tensor] = None
     s_strides: Sequence[int] = (0, 0)
     tok_off: Optional[torch.Tensor] = None  # int64 [B] on the device
+    k_scale_mx: Optional[torch.Tensor] = None   # MXFP4: uint8 block scales, k / v are uint8 codes and
+    v_scale_mx: Optional[torch.Tensor] = None   # the strides count elements (two per byte)
 
     @staticmethod
     def from_padded(k: torch.Tensor, v: Optional[torch.Tensor], lens: torch.Tensor, max_len: int,
@@ -136,6 +142,18 @@ class KVShard:
             assert kv_scale.dim() == 3 and kv_scale.stride(2) == 1
             ss = (kv_scale.stride(0), kv_scale.stride(1))
         return KVShard(k, v, lens, int(max_len), (k.stride(0), k.stride(1), k.stride(2)), vs, kv_scale, ss, tok_off)
+
+    @staticmethod
+    def from_mxfp4(k: torch.Tensor, v: torch.Tensor, k_mx: torch.Tensor, v_mx: torch.Tensor, lens: torch.Tensor,
+                   max_len: int, tok_off: Optional[torch.Tensor] = None) -> "KVShard":
+        """k [B,K,S,dk/2], v [B,K,S,dv/2] uint8 codes, k_mx [B,K,S,dk/32], v_mx [B,K,S,dv/32] uint8 scales,
+        all contiguous in their last two axes; strides are handed over in elements."""
+        for t, m in ((k, k_mx), (v, v_mx)):
+            assert t.dtype == torch.uint8 and m.dtype == torch.uint8 and t.dim() == 4 and m.dim() == 4
+            assert t.stride(3) == 1 and m.is_contiguous() and t.is_contiguous()
+            assert m.shape[:3] == t.shape[:3] and m.shape[3] * 16 == t.shape[3]
+        return KVShard(k, v, lens, int(max_len), tuple(2 * x for x in (k.stride(0), k.stride(1), k.stride(2))),
+                       tuple(2 * x for x in (v.stride(0), v.stride(1), v.stride(2))), None, (0, 0), tok_off, k_mx, v_mx)
 
     @staticmethod
     def from_packed(k: torch.Tensor, lens: torch.Tensor, max_len: int, tok_off: torch.Tensor,
@@ -154,7 +172,7 @@ class KVShard:
             assert self.kv_scale.dtype == torch.float32
         return _CShard(ptr(self.k), ptr(self.v), ptr(self.kv_scale), *[int(x) for x in self.k_strides],
                        *[int(x) for x in self.v_strides], *[int(x) for x in self.s_strides],
-                       ptr(self.tok_off), ptr(self.len), int(self.max_len))
+                       ptr(self.tok_off), ptr(self.len), int(self.max_len), ptr(self.k_scale_mx), ptr(self.v_scale_mx))
 
 
 def _stream_ptr(stream) -> Optional[int]:
@@ -289,3 +307,23 @@ def helix_kv_append(problem: Problem, shards: Sequence[KVShard], decode_index: i
                                           int(capacity), None if overflow is None else overflow.data_ptr(),
                                           _stream_ptr(stream)),
            "helix_kv_append")
+
+
+def helix_kv_append_mxfp4(problem: Problem, shards: Sequence[KVShard], decode_index: int, k_codes: torch.Tensor,
+                          v_codes: torch.Tensor, k_scales: torch.Tensor, v_scales: torch.Tensor, capacity: int,
+                          overflow: Optional[torch.Tensor] = None, stream=None) -> None:
+    """helix_kv_append for an MXFP4 cache: code rows [B,K,d/2] and their block scales [B,K,d/32] (uint8)."""
+    n = len(shards)
+    B, K = problem.batch, problem.kv_heads
+    for t, shape in ((k_codes, (B, K, problem.dk // 2)), (v_codes, (B, K, problem.dv // 2)),
+                     (k_scales, (B, K, problem.dk // 32)), (v_scales, (B, K, problem.dv // 32))):
+        assert t.dtype == torch.uint8 and t.is_contiguous() and tuple(t.shape) == shape
+    if overflow is not None:
+        assert overflow.dtype == torch.int32 and overflow.numel() == 1
+    p = problem.c()
+    arr = (_CShard * n)(*[s.c() for s in shards])
+    _check(load_library().helix_kv_append_mxfp4(ctypes.byref(p), arr, n, int(decode_index), k_codes.data_ptr(),
+                                                v_codes.data_ptr(), k_scales.data_ptr(), v_scales.data_ptr(),
+                                                int(capacity), None if overflow is None else overflow.data_ptr(),
+                                                _stream_ptr(stream)),
+           "helix_kv_append_mxfp4")

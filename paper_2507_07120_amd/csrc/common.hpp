@@ -32,6 +32,8 @@ struct ShardDev {
     int32_t n_splits;     // ceil(max_len / split_tokens)
     int32_t unit_base;    // first workgroup of this shard in the launch
     int32_t pad;
+    const uint8_t* k_mx;  // MXFP4 only: E8M0 block scales, index = element index / 32
+    const uint8_t* v_mx;
 };
 
 // Arguments of an attention launch over up to kMaxLaunchShards shards.

@@ -93,10 +93,14 @@ struct GqaState {
     f32x4 o[GqaCfg<D>::CPL];          // O^T tiles: o[c][i] = O[head r][dv = (kc*4+i)*CPL + c]
 };
 
-template <int D, bool TAIL>
-__device__ __forceinline__ void gqa_compute_block(GqaState<D>& st, const GqaBlock<D>& blk,
-                                                  const bf16x8 (&qb)[GqaCfg<D>::KS],
-                                                  float scale_log2e, int kc, int n_valid)
+// One 32-token block: scores, online softmax update, P.V.  `kop(a, s)` supplies the score MFMA's A
+// operand (16-token tile a, k-step s), `vop(c)` the P.V MFMA's A operand for value column c of the
+// lane (8 tokens of that column); the callers differ in how the operands come out of the loaded
+// block (bf16 as loaded / transposed, MXFP4 converted on the fly).
+template <int D, bool TAIL, class KOp, class VOp>
+__device__ __forceinline__ void gqa_compute_core(GqaState<D>& st, KOp&& kop, VOp&& vop,
+                                                 const bf16x8 (&qb)[GqaCfg<D>::KS],
+                                                 float scale_log2e, int kc, int n_valid)
 {
     using C = GqaCfg<D>;
     // scores: lane (r,kc) gets head r, tokens a*16 + kc*4 + i
@@ -106,7 +110,7 @@ __device__ __forceinline__ void gqa_compute_block(GqaState<D>& st, const GqaBloc
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < C::KS; s++)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(blk.k[a][s], qb[s], acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop(a, s), qb[s], acc, 0, 0, 0);
 #pragma unroll
         for (int i = 0; i < 4; i++) t[a * 4 + i] = acc[i] * scale_log2e;
     }
@@ -155,24 +159,88 @@ __device__ __forceinline__ void gqa_compute_block(GqaState<D>& st, const GqaBloc
     st.l += lsum;
     const bf16x8 bhi = __builtin_bit_cast(bf16x8, u32x4{phi[0], phi[1], phi[2], phi[3]});
     const bf16x8 blo = __builtin_bit_cast(bf16x8, u32x4{plo[0], plo[1], plo[2], plo[3]});
-    // P.V: transpose this lane's 8 tokens x CPL columns into CPL operands of 8 tokens each
+    // P.V
 #pragma unroll
     for (int c = 0; c < C::CPL; c++) {
-        const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-        u32x4 a;
-        a.x = __builtin_amdgcn_perm(blk.v[1][c >> 1], blk.v[0][c >> 1], sel);
-        a.y = __builtin_amdgcn_perm(blk.v[3][c >> 1], blk.v[2][c >> 1], sel);
-        a.z = __builtin_amdgcn_perm(blk.v[5][c >> 1], blk.v[4][c >> 1], sel);
-        a.w = __builtin_amdgcn_perm(blk.v[7][c >> 1], blk.v[6][c >> 1], sel);
-        const bf16x8 va = __builtin_bit_cast(bf16x8, a);
+        const bf16x8 va = vop(c);
         st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, bhi, st.o[c], 0, 0, 0);
         st.o[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, blo, st.o[c], 0, 0, 0);
     }
 }
 
+// Column c of the lane's 8 tokens out of 8 registers that each hold one token's columns (2p, 2p+1)
+// as a bf16 pair: the 8x8 transpose of 16-bit elements, one v_perm_b32 per output dword.
+__device__ __forceinline__ bf16x8 gqa_column_of_pairs(const uint32_t (&t)[8], int c)
+{
+    const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+    u32x4 a;
+    a.x = __builtin_amdgcn_perm(t[1], t[0], sel);
+    a.y = __builtin_amdgcn_perm(t[3], t[2], sel);
+    a.z = __builtin_amdgcn_perm(t[5], t[4], sel);
+    a.w = __builtin_amdgcn_perm(t[7], t[6], sel);
+    return __builtin_bit_cast(bf16x8, a);
+}
+
+// bf16 block: K operands as loaded; V: this lane's 8 tokens x CPL columns transposed into CPL operands.
+template <int D, bool TAIL>
+__device__ __forceinline__ void gqa_compute_block(GqaState<D>& st, const GqaBlock<D>& blk,
+                                                  const bf16x8 (&qb)[GqaCfg<D>::KS],
+                                                  float scale_log2e, int kc, int n_valid)
+{
+    gqa_compute_core<D, TAIL>(
+        st, [&](int a, int s) { return blk.k[a][s]; },
+        [&](int c) {
+            const uint32_t t[8] = {blk.v[0][c >> 1], blk.v[1][c >> 1], blk.v[2][c >> 1], blk.v[3][c >> 1],
+                                   blk.v[4][c >> 1], blk.v[5][c >> 1], blk.v[6][c >> 1], blk.v[7][c >> 1]};
+            return gqa_column_of_pairs(t, c);
+        },
+        qb, scale_log2e, kc, n_valid);
+}
+
 __device__ __forceinline__ float max_of_waves(const float (&m)[4][16], int r)
 {
     return fmaxf(fmaxf(m[0][r], m[1][r]), fmaxf(m[2][r], m[3][r]));
+}
+
+// Merges the four waves' running states of a workgroup into ONE un-normalised record (sum p v, integer
+// reference exponent, sum p) and writes it to the workspace.  Called by all 256 threads.
+template <int D>
+__device__ __forceinline__ void gqa_emit_record(GqaState<D>& st, const AttnArgs& a, size_t rec, int nh,
+                                                int tid, int wave, int r, int kc)
+{
+    using C = GqaCfg<D>;
+    __shared__ float sm_m[4][16];
+    __shared__ float sm_l[4][16];
+    __shared__ float sm_o[4][16][D];
+    st.l = wave_xor_sum_16_32(st.l);
+    if (kc == 0) { sm_m[wave][r] = st.m; sm_l[wave][r] = st.l; }
+    __syncthreads();
+    const float M = max_of_waves(sm_m, r);
+    const float f = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - M);
+#pragma unroll
+    for (int c = 0; c < C::CPL; c++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) sm_o[wave][r][(kc * 4 + i) * C::CPL + c] = st.o[c][i] * f;
+    __syncthreads();
+    if (tid < nh) {
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; w++) {
+            const float mw = sm_m[w][tid];
+            L += (mw == -INFINITY) ? 0.f : sm_l[w][tid] * __builtin_amdgcn_exp2f(mw - max_of_waves(sm_m, tid));
+        }
+        a.ws_m[rec + tid] = max_of_waves(sm_m, tid);
+        a.ws_l[rec + tid] = L;
+    }
+    float* out = a.ws_o + rec * D;
+    for (int idx = tid * 4; idx < nh * D; idx += 256 * 4) {
+        const int hh = idx / D, col = idx % D;
+        f32x4 s0 = *reinterpret_cast<const f32x4*>(&sm_o[0][hh][col]);
+        f32x4 s1 = *reinterpret_cast<const f32x4*>(&sm_o[1][hh][col]);
+        f32x4 s2 = *reinterpret_cast<const f32x4*>(&sm_o[2][hh][col]);
+        f32x4 s3 = *reinterpret_cast<const f32x4*>(&sm_o[3][hh][col]);
+        *reinterpret_cast<f32x4*>(out + idx) = (s0 + s1) + (s2 + s3);
+    }
 }
 
 template <int D>
@@ -269,39 +337,7 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
         gqa_compute_block<D, true>(st, b0, qb, a.scale_log2e, kc, nv);
     }
 
-    // ---- merge the four waves' states into one record ----
-    __shared__ float sm_m[4][16];
-    __shared__ float sm_l[4][16];
-    __shared__ float sm_o[4][16][D];
-    st.l = wave_xor_sum_16_32(st.l);
-    if (kc == 0) { sm_m[wave][r] = st.m; sm_l[wave][r] = st.l; }
-    __syncthreads();
-    const float M = max_of_waves(sm_m, r);
-    const float f = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - M);
-#pragma unroll
-    for (int c = 0; c < C::CPL; c++)
-#pragma unroll
-        for (int i = 0; i < 4; i++) sm_o[wave][r][(kc * 4 + i) * C::CPL + c] = st.o[c][i] * f;
-    __syncthreads();
-    if (tid < nh) {
-        float L = 0.f;
-#pragma unroll
-        for (int w = 0; w < 4; w++) {
-            const float mw = sm_m[w][tid];
-            L += (mw == -INFINITY) ? 0.f : sm_l[w][tid] * __builtin_amdgcn_exp2f(mw - max_of_waves(sm_m, tid));
-        }
-        a.ws_m[rec + tid] = max_of_waves(sm_m, tid);
-        a.ws_l[rec + tid] = L;
-    }
-    float* out = a.ws_o + rec * D;
-    for (int idx = tid * 4; idx < nh * D; idx += 256 * 4) {
-        const int hh = idx / D, col = idx % D;
-        f32x4 s0 = *reinterpret_cast<const f32x4*>(&sm_o[0][hh][col]);
-        f32x4 s1 = *reinterpret_cast<const f32x4*>(&sm_o[1][hh][col]);
-        f32x4 s2 = *reinterpret_cast<const f32x4*>(&sm_o[2][hh][col]);
-        f32x4 s3 = *reinterpret_cast<const f32x4*>(&sm_o[3][hh][col]);
-        *reinterpret_cast<f32x4*>(out + idx) = (s0 + s1) + (s2 + s3);
-    }
+    gqa_emit_record<D>(st, a, rec, nh, tid, wave, r, kc);
 }
 
 }  // namespace helix

@@ -1,0 +1,222 @@
+// Split-KV decode attention for GQA/MQA groups with the KV cache in MXFP4 -- the FP4 the paper's
+// evaluation assumes for KV states (Sec. 3; microscaling formats: E2M1 elements, blocks of 32 along a
+// row sharing one E8M0 power-of-two scale).  dk == dv == 128: a token's key or value row is 64 bytes
+// of codes plus 4 scale bytes, 3.8x fewer HBM bytes per token than bf16.
+//
+// Same decomposition and the same arithmetic after dequantisation as the bf16 kernel
+// (gqa_decode.hpp): one workgroup of 4 waves per (shard, sequence, kv head, split), waves take
+// alternating 32-token blocks, scores / integer-reference softmax / P.V on 16x16x32 bf16 MFMAs.
+// What differs is how the operands get into registers:
+//   K   lane (r = token, kc) loads the 16 bytes holding dims 32kc .. 32kc+31 of its token: exactly
+//       one scale block.  The score contraction does not care about the order of the dims as long
+//       as Q agrees, so k-step s takes dims 32kc + 8s .. +8 from every lane (Q is loaded to match)
+//       instead of 32s + 8kc .. +8.  One wave instruction covers 16 whole rows.
+//   V   lane (r, kc) owns value columns 8r .. 8r+7 (4 bytes per token, scale block r/4) of its 8
+//       tokens, as in the bf16 kernel; the 8x8 transpose happens after the conversion.
+//   dequantisation  v_cvt_scalef32_pk_bf16_fp4 turns one byte (two codes, low nibble first --
+//       checked on the device for all 256 bytes) into two bf16 times a float scale: exact, because
+//       an E2M1 value has one mantissa bit and the scale is a power of two.  64 conversions per lane
+//       and 32-token block, each right before the MFMA that consumes its result.
+//   scales  K: one dword (the 4 block scales of a token) per lane, byte kc selected; V: two 16-byte
+//       loads cover the 4 scales of the lane's 8 tokens, byte r/4 selected; the code becomes the float's
+//       exponent field (codes 1..254).
+// A block is only 4.3 KB per wave, so three waves per SIMD are kept resident (at most 168 registers,
+// two raw blocks of 26 registers each); loads are never issued under a condition of their own (the
+// index is clamped instead), which keeps the compiler's wait counts exact.
+#pragma once
+#include "gqa_decode.hpp"
+
+namespace helix {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));       // 16-byte loads that are only dword aligned
+
+struct Mx4Raw {
+    u32x4 k[2];        // codes of dims 32kc..32kc+31 of tokens r, 16 + r
+    uint32_t ks[2];    // their tokens' 4 block scales
+    uint32_t v[8];     // codes of columns 8r..8r+7 of the lane's 8 tokens
+    u32x4 vs[2];       // block scales of tokens 4kc..4kc+3 and 16 + 4kc .. +3 (4 bytes each)
+};
+
+constexpr int kMxRow = 64;     // code bytes per 128-wide row
+constexpr int kMxScaleRow = 4; // scale bytes per row
+
+// Loads the block of 32 tokens whose first rows are kblk / vblk (codes) and ksc / vsc (scales).
+// TAIL: tokens >= n_valid are redirected to the last valid row (their weights are zero later).
+template <bool TAIL>
+__device__ __forceinline__ void mx4_load_block(Mx4Raw& raw, const char* kblk, const char* vblk, const char* ksc, const char* vsc,
+                                               uint32_t k_row_bytes, uint32_t v_row_bytes, int r, int kc, int n_valid)
+{
+#pragma unroll
+    for (int a = 0; a < 2; a++) {
+        int tok = a * 16 + r;
+        if (TAIL) tok = min(tok, n_valid - 1);
+        raw.k[a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kblk + (uint32_t)tok * k_row_bytes + (uint32_t)kc * 16u));
+        raw.ks[a] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(ksc + (uint32_t)tok * (k_row_bytes / 16u)));
+    }
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        int tok = (j >> 2) * 16 + kc * 4 + (j & 3);
+        if (TAIL) tok = min(tok, n_valid - 1);
+        raw.v[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(vblk + (uint32_t)tok * v_row_bytes + (uint32_t)r * 4u));
+    }
+    if (TAIL) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const int tok = min((j >> 2) * 16 + kc * 4 + (j & 3), n_valid - 1);
+            raw.vs[j >> 2][j & 3] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(vsc + (uint32_t)tok * (v_row_bytes / 16u)));
+        }
+    } else {
+        // rows of a value block that are contiguous in memory have contiguous scale rows
+#pragma unroll
+        for (int a = 0; a < 2; a++)
+            raw.vs[a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(vsc + (uint32_t)(a * 16 + kc * 4) * (v_row_bytes / 16u)));
+    }
+}
+
+// 2^(code - 127) of byte `which` of a dword of E8M0 scales, for codes 1..254: the code is the
+// exponent field of the float.  Rotating right by 8*which + 9 moves the byte to bits 23..30.
+__device__ __forceinline__ float mx4_scale(uint32_t four, int which)
+{
+    return as_f32(__builtin_amdgcn_alignbit(four, four, 8u * (uint32_t)which + 9u) & 0x7F800000u);
+}
+
+__device__ __forceinline__ uint32_t mx4_pair(uint32_t codes, float scale, int byte)
+{
+    bf16x2_t p;
+    switch (byte) {
+        case 0: p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 0); break;
+        case 1: p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 1); break;
+        case 2: p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 2); break;
+        default: p = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(codes, scale, 3); break;
+    }
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+// One 32-token block straight from the raw codes: every operand is converted right before the MFMA
+// that consumes it (K: 4 conversions per k-step; V: the byte holding columns 2p, 2p+1 of the lane's 8
+// tokens -> 8 conversions, then the 16-bit transpose), so no dequantised copy of the block is kept --
+// that copy would cost 64 registers and the third wave per SIMD.
+template <bool TAIL>
+__device__ __forceinline__ void mx4_compute_block(GqaState<128>& st, const Mx4Raw& raw, const bf16x8 (&qb)[4],
+                                                  float scale_log2e, int r, int kc, int n_valid)
+{
+    float ksc[2], vsc[8];
+#pragma unroll
+    for (int a = 0; a < 2; a++) ksc[a] = mx4_scale(raw.ks[a], kc);
+#pragma unroll
+    for (int j = 0; j < 8; j++) vsc[j] = mx4_scale(raw.vs[j >> 2][j & 3], r >> 2);
+    uint32_t pairs[8];            // columns (2p, 2p+1) of the lane's 8 tokens, refreshed at every even column
+    gqa_compute_core<128, TAIL>(
+        st,
+        [&](int a, int s) {
+            const uint32_t w = raw.k[a][s];
+            return __builtin_bit_cast(bf16x8, u32x4{mx4_pair(w, ksc[a], 0), mx4_pair(w, ksc[a], 1), mx4_pair(w, ksc[a], 2), mx4_pair(w, ksc[a], 3)});
+        },
+        [&](int c) {
+            if ((c & 1) == 0) {
+#pragma unroll
+                for (int j = 0; j < 8; j++) pairs[j] = mx4_pair(raw.v[j], vsc[j], c >> 1);
+            }
+            return gqa_column_of_pairs(pairs, c);
+        },
+        qb, scale_log2e, kc, n_valid);
+}
+
+__global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
+{
+    constexpr int D = 128;
+    using C = GqaCfg<D>;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, kc = lane >> 4;
+
+    // which (shard, split, sequence, kv head, head tile) this workgroup serves
+    int u = blockIdx.x, si = 0;
+    while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
+    const ShardDev& sh = a.shard[si];
+    u -= sh.unit_base;
+    const int split = u % sh.n_splits;
+    int rest = u / sh.n_splits;
+    const int ht = rest % a.head_tiles; rest /= a.head_tiles;
+    const int kh = rest % a.K;
+    const int b = rest / a.K;
+
+    const int len = sh.len[b];
+    const int t0 = split * a.split_tokens;
+    const int t1 = min(t0 + a.split_tokens, len);
+    const int h0 = kh * a.g + ht * 16;
+    const int nh = min(16, a.g - ht * 16);
+    const size_t rec = ((size_t)(sh.split_base + split) * a.B + b) * a.Q + h0;
+
+    if (t0 >= len) {              // nothing to attend to: an empty record
+        if (tid < nh) { a.ws_m[rec + tid] = -INFINITY; a.ws_l[rec + tid] = 0.f; }
+        return;
+    }
+
+    // element index of the split's first token row; codes sit at index / 2, scales at index / 32
+    const int64_t tok0 = (sh.tok_off ? sh.tok_off[b] : 0) + t0;
+    const int64_t ke = (int64_t)b * sh.k_sb + (int64_t)kh * sh.k_sh + tok0 * sh.k_st;
+    const int64_t ve = (int64_t)b * sh.v_sb + (int64_t)kh * sh.v_sh + tok0 * sh.v_st;
+    const char* kbase = reinterpret_cast<const char*>(sh.k) + ke / 2;
+    const char* vbase = reinterpret_cast<const char*>(sh.v) + ve / 2;
+    const char* ksbase = reinterpret_cast<const char*>(sh.k_mx) + ke / 32;
+    const char* vsbase = reinterpret_cast<const char*>(sh.v_mx) + ve / 32;
+    const uint32_t k_row_bytes = (uint32_t)sh.k_st / 2u, v_row_bytes = (uint32_t)sh.v_st / 2u;   // scale rows: a 16th of that
+
+    GqaState<D> st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int c = 0; c < C::CPL; c++) st.o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int n_tok = t1 - t0;
+    const int n_full = n_tok / C::TB;
+    const int n_blk = (n_tok + C::TB - 1) / C::TB;
+    const int nw = n_full > wave ? (n_full - wave + 3) / 4 : 0;       // this wave's full blocks: wave, wave+4, ...
+
+    // block i of this wave; the index is clamped, so a prefetch past the end re-reads the last block
+    auto load = [&](Mx4Raw& raw, int i) {
+        const size_t blk = (size_t)(wave + 4 * min(i, nw - 1)) * C::TB;
+        mx4_load_block<false>(raw, kbase + blk * k_row_bytes, vbase + blk * v_row_bytes, ksbase + blk * (k_row_bytes / 16u),
+                              vsbase + blk * (v_row_bytes / 16u), k_row_bytes, v_row_bytes, r, kc, C::TB);
+    };
+    Mx4Raw r0, r1;
+    if (nw > 0) load(r0, 0);
+
+    // Q as the score MFMA's B operand, in the dim order of the K operand: lane (r,kc) holds head r,
+    // dims 32kc + 8s .. +8 for k-step s
+    bf16x8 qb[C::KS];
+    {
+        const uint16_t* qrow = a.q + ((size_t)b * a.Q + h0 + min(r, nh - 1)) * D + kc * 32;
+#pragma unroll
+        for (int s = 0; s < C::KS; s++) {
+            u32x4 w = *reinterpret_cast<const u32x4*>(qrow + s * 8);
+            if (r >= nh) w = u32x4{0, 0, 0, 0};
+            qb[s] = __builtin_bit_cast(bf16x8, w);
+        }
+    }
+
+    if (nw > 0) {
+        int i = 0;
+        for (; i + 2 <= nw; i += 2) {
+            load(r1, i + 1);
+            mx4_compute_block<false>(st, r0, qb, a.scale_log2e, r, kc, C::TB);
+            load(r0, i + 2);
+            mx4_compute_block<false>(st, r1, qb, a.scale_log2e, r, kc, C::TB);
+        }
+        if (i < nw) mx4_compute_block<false>(st, r0, qb, a.scale_log2e, r, kc, C::TB);
+    }
+    // the ragged last block, if any, belongs to wave (n_full % 4)
+    if (n_blk > n_full && (n_full & 3) == wave) {
+        const int nv = n_tok - n_full * C::TB;
+        const size_t blk0 = (size_t)n_full * C::TB;
+        mx4_load_block<true>(r0, kbase + blk0 * k_row_bytes, vbase + blk0 * v_row_bytes, ksbase + blk0 * (k_row_bytes / 16u),
+                             vsbase + blk0 * (v_row_bytes / 16u), k_row_bytes, v_row_bytes, r, kc, nv);
+        mx4_compute_block<true>(st, r0, qb, a.scale_log2e, r, kc, nv);
+    }
+
+    gqa_emit_record<D>(st, a, rec, nh, tid, wave, r, kc);
+}
+
+}  // namespace helix

@@ -11,6 +11,7 @@
 
 #include "common.hpp"
 #include "gqa_decode.hpp"
+#include "gqa_mxfp4.hpp"
 #include "merge_combine.hpp"
 #include "mla_decode.hpp"
 
@@ -18,7 +19,7 @@ namespace {
 
 using namespace helix;
 
-enum class Path { Gqa64, Gqa128, Mla };
+enum class Path { Gqa64, Gqa128, GqaMx128, Mla };
 
 struct Plan {
     Path path;
@@ -32,6 +33,7 @@ struct Plan {
 
 constexpr int64_t kTargetWorkgroups = 256;   // CUs of an MI355X
 constexpr int64_t kMinSplitTokens = 512;
+constexpr int64_t kTargetWorkgroupsMx = 768;    // MXFP4 streams 3.8x fewer bytes per token: three workgroups resident per CU
 constexpr int64_t kTargetWorkgroupsMla = 4096;   // upper end: keeps the split records of a call near 1 GB at most
 constexpr int64_t kMinSplitTokensMla = 4096;
 
@@ -45,7 +47,7 @@ int check_problem(const helix_problem* p, Path* path)
     if (p->q_heads % p->kv_heads != 0) return HELIX_ERR_SHAPE;
     if (!(p->scale > 0.f) || !std::isfinite(p->scale)) return HELIX_ERR_SHAPE;
     if (p->split_tokens < 0) return HELIX_ERR_SHAPE;
-    if (p->kv_dtype != HELIX_KV_BF16 && p->kv_dtype != HELIX_KV_FP8_E4M3) return HELIX_ERR_UNSUPPORTED;
+    if (p->kv_dtype != HELIX_KV_BF16 && p->kv_dtype != HELIX_KV_FP8_E4M3 && p->kv_dtype != HELIX_KV_MXFP4) return HELIX_ERR_UNSUPPORTED;
     if (p->v_aliases_k != 0 && p->v_aliases_k != 1) return HELIX_ERR_SHAPE;
     if (p->v_aliases_k && p->dv > p->dk) return HELIX_ERR_SHAPE;
     if ((int64_t)p->batch * p->q_heads > (int64_t)1 << 24) return HELIX_ERR_SHAPE;
@@ -53,7 +55,11 @@ int check_problem(const helix_problem* p, Path* path)
         *path = p->dk == 64 ? Path::Gqa64 : Path::Gqa128;
         return HELIX_OK;
     }
-    if (p->v_aliases_k && p->dk == 576 && p->dv == 512 && p->kv_heads == 1) {
+    if (!p->v_aliases_k && p->kv_dtype == HELIX_KV_MXFP4 && p->dk == 128 && p->dv == 128) {
+        *path = Path::GqaMx128;
+        return HELIX_OK;
+    }
+    if (p->v_aliases_k && p->kv_dtype != HELIX_KV_MXFP4 && p->dk == 576 && p->dv == 512 && p->kv_heads == 1) {
         *path = Path::Mla;
         return HELIX_OK;
     }
@@ -87,7 +93,7 @@ int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_
         // Measured: the ragged e4m3 workload takes 4.7 ms with 4096-token runs, 5.2 with 8192, 6.7 with
         // one run per (shard, sequence); the uniform bf16 share loses 3 % against its best (8192).  The
         // 256 KB record of a run is 5-11 % of the latent bytes it reads.
-        const int64_t target = path == Path::Mla ? kTargetWorkgroupsMla : kTargetWorkgroups;
+        const int64_t target = path == Path::Mla ? kTargetWorkgroupsMla : path == Path::GqaMx128 ? kTargetWorkgroupsMx : kTargetWorkgroups;
         const int64_t floor_tokens = path == Path::Mla ? kMinSplitTokensMla : kMinSplitTokens;
         split = ceil_div(ceil_div(rows * total, target), plan->granule) * plan->granule;
         split = std::max<int64_t>(split, floor_tokens);
@@ -132,6 +138,16 @@ int check_shard(const helix_problem* p, const helix_kv_shard* s)
     const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
     if (fp8 ? s->kv_scale == nullptr : false) return HELIX_ERR_NULL;
     if (s->max_len < 0) return HELIX_ERR_SHAPE;
+    if (p->kv_dtype == HELIX_KV_MXFP4) {
+        // strides count elements; a row is dk/2 code bytes and dk/32 scale bytes, token rows dense
+        if (!s->k_scale_mx || !s->v_scale_mx) return HELIX_ERR_NULL;
+        if (s->k_stride_b < 0 || s->k_stride_h < 0 || s->v_stride_b < 0 || s->v_stride_h < 0) return HELIX_ERR_SHAPE;
+        if (s->k_stride_b % 128 || s->k_stride_h % 128 || s->v_stride_b % 128 || s->v_stride_h % 128) return HELIX_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(s->k) % 16 || reinterpret_cast<uintptr_t>(s->v) % 16) return HELIX_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(s->k_scale_mx) % 4 || reinterpret_cast<uintptr_t>(s->v_scale_mx) % 4) return HELIX_ERR_SHAPE;
+        if (s->k_stride_t != p->dk || s->v_stride_t != p->dv) return HELIX_ERR_UNSUPPORTED;
+        return HELIX_OK;
+    }
     const int64_t esz = fp8 ? 1 : 2, mult = 16 / esz;
     if (s->k_stride_t < p->dk || s->k_stride_t > ((int64_t)1 << 24) || s->k_stride_b < 0 || s->k_stride_h < 0) return HELIX_ERR_SHAPE;
     if (s->k_stride_t % mult || s->k_stride_b % mult || s->k_stride_h % mult) return HELIX_ERR_SHAPE;
@@ -206,6 +222,7 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             d.k_sb = s.k_stride_b; d.k_sh = s.k_stride_h; d.k_st = s.k_stride_t;
             d.v_sb = s.v_stride_b; d.v_sh = s.v_stride_h; d.v_st = s.v_stride_t;
             d.s_sb = s.s_stride_b; d.s_sh = s.s_stride_h;
+            d.k_mx = s.k_scale_mx; d.v_mx = s.v_scale_mx;
             d.n_splits = (int32_t)std::max<int64_t>(1, ceil_div(s.max_len, plan.split_tokens));
             d.split_base = split_base;
             d.unit_base = (int32_t)units;
@@ -222,6 +239,9 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
                 break;
             case Path::Gqa128:
                 hipLaunchKernelGGL((gqa_decode_kernel<128>), dim3((unsigned)units), dim3(256), 0, stream, a);
+                break;
+            case Path::GqaMx128:
+                hipLaunchKernelGGL(gqa_mxfp4_kernel, dim3((unsigned)units), dim3(256), 0, stream, a);
                 break;
             case Path::Mla: {
                 const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
@@ -389,34 +409,61 @@ int32_t helix_kv_append_owner(int64_t decode_index, int32_t n_shards)
     return (int32_t)((decode_index / HELIX_APPEND_BLOCK) % n_shards);
 }
 
-int helix_kv_append(const helix_problem* problem, const helix_kv_shard* shards, int32_t n_shards,
-                    int64_t decode_index, const void* k_new, const void* v_new, const float* scale_new,
-                    int32_t capacity, int32_t* overflow, void* hip_stream)
+namespace {
+int append_common(const helix_problem* problem, const helix_kv_shard* shards, int32_t n_shards, int64_t decode_index,
+                  const void* k_new, const void* v_new, const float* scale_new, const uint8_t* k_mx_new, const uint8_t* v_mx_new,
+                  int32_t capacity, int32_t* overflow, void* hip_stream)
 {
-    Path path;
-    if (int rc = check_problem(problem, &path)) return rc;
-    if (!shards || !k_new) return HELIX_ERR_NULL;
-    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS || decode_index < 0 || capacity < 0) return HELIX_ERR_SHAPE;
     const helix_kv_shard& s = shards[helix_kv_append_owner(decode_index, n_shards)];
     if (int rc = check_shard(problem, &s)) return rc;
-    const bool fp8 = problem->kv_dtype == HELIX_KV_FP8_E4M3;
-    if (problem->v_aliases_k ? v_new != nullptr : v_new == nullptr) return problem->v_aliases_k ? HELIX_ERR_SHAPE : HELIX_ERR_NULL;
-    if (fp8 ? scale_new == nullptr : scale_new != nullptr) return fp8 ? HELIX_ERR_NULL : HELIX_ERR_SHAPE;
+    const bool fp8 = problem->kv_dtype == HELIX_KV_FP8_E4M3, fp4 = problem->kv_dtype == HELIX_KV_MXFP4;
     AppendArgs a;
     std::memset(&a, 0, sizeof a);
     a.sh.k = s.k; a.sh.v = s.v; a.sh.kv_scale = s.kv_scale; a.sh.tok_off = s.tok_off; a.sh.len = s.len;
     a.sh.k_sb = s.k_stride_b; a.sh.k_sh = s.k_stride_h; a.sh.k_st = s.k_stride_t;
     a.sh.v_sb = s.v_stride_b; a.sh.v_sh = s.v_stride_h; a.sh.v_st = s.v_stride_t;
     a.sh.s_sb = s.s_stride_b; a.sh.s_sh = s.s_stride_h;
+    a.sh.k_mx = s.k_scale_mx; a.sh.v_mx = s.v_scale_mx;
     a.k_new = static_cast<const uint8_t*>(k_new);
     a.v_new = static_cast<const uint8_t*>(v_new);
     a.scale_new = scale_new;
+    a.k_mx_new = k_mx_new; a.v_mx_new = v_mx_new;
     a.len = const_cast<int32_t*>(s.len);
     a.overflow = overflow;
-    a.K = problem->kv_heads; a.dk = problem->dk; a.dv = problem->dv; a.esz = fp8 ? 1 : 2; a.capacity = capacity;
+    a.K = problem->kv_heads; a.dk = problem->dk; a.dv = problem->dv; a.capacity = capacity;
+    a.num = fp4 || fp8 ? 1 : 2; a.den = fp4 ? 2 : 1;
     hipLaunchKernelGGL(helix::kv_append_kernel, dim3((unsigned)problem->batch), dim3(256), 0,
                        static_cast<hipStream_t>(hip_stream), a);
     return launch_status();
+}
+}  // namespace
+
+int helix_kv_append(const helix_problem* problem, const helix_kv_shard* shards, int32_t n_shards,
+                    int64_t decode_index, const void* k_new, const void* v_new, const float* scale_new,
+                    int32_t capacity, int32_t* overflow, void* hip_stream)
+{
+    Path path;
+    if (int rc = check_problem(problem, &path)) return rc;
+    if (problem->kv_dtype == HELIX_KV_MXFP4) return HELIX_ERR_UNSUPPORTED;      // helix_kv_append_mxfp4 carries the block scales
+    if (!shards || !k_new) return HELIX_ERR_NULL;
+    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS || decode_index < 0 || capacity < 0) return HELIX_ERR_SHAPE;
+    const bool fp8 = problem->kv_dtype == HELIX_KV_FP8_E4M3;
+    if (problem->v_aliases_k ? v_new != nullptr : v_new == nullptr) return problem->v_aliases_k ? HELIX_ERR_SHAPE : HELIX_ERR_NULL;
+    if (fp8 ? scale_new == nullptr : scale_new != nullptr) return fp8 ? HELIX_ERR_NULL : HELIX_ERR_SHAPE;
+    return append_common(problem, shards, n_shards, decode_index, k_new, v_new, scale_new, nullptr, nullptr, capacity, overflow, hip_stream);
+}
+
+int helix_kv_append_mxfp4(const helix_problem* problem, const helix_kv_shard* shards, int32_t n_shards,
+                          int64_t decode_index, const void* k_codes, const void* v_codes,
+                          const uint8_t* k_scales, const uint8_t* v_scales,
+                          int32_t capacity, int32_t* overflow, void* hip_stream)
+{
+    Path path;
+    if (int rc = check_problem(problem, &path)) return rc;
+    if (problem->kv_dtype != HELIX_KV_MXFP4) return HELIX_ERR_UNSUPPORTED;
+    if (!shards || !k_codes || !v_codes || !k_scales || !v_scales) return HELIX_ERR_NULL;
+    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS || decode_index < 0 || capacity < 0) return HELIX_ERR_SHAPE;
+    return append_common(problem, shards, n_shards, decode_index, k_codes, v_codes, nullptr, k_scales, v_scales, capacity, overflow, hip_stream);
 }
 
 int helix_shard_layout(const int32_t* seq_len, const int64_t* seq_base, int32_t batch, int32_t n_shards,

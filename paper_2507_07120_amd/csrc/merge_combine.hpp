@@ -229,16 +229,19 @@ __global__ void shard_layout_kernel(const int32_t* __restrict__ seq_len, const i
 }
 
 // Staggered KV append (Sec. 2.3): one workgroup per sequence copies the new token's row of every KV
-// head into the owner shard at position len[b] and bumps len[b].  Pure byte copies: esz bytes per
-// element, rows of dk (and dv) elements.
+// head into the owner shard at position len[b] and bumps len[b].  Pure byte copies: an element is
+// num/den bytes (bf16 2/1, e4m3 1/1, MXFP4 1/2), rows of dk (and dv) elements; MXFP4 rows carry
+// dk/32 (dv/32) block-scale bytes in separate arrays.
 struct AppendArgs {
     ShardDev sh;          // the owner shard
-    const uint8_t* k_new; // [B][K][dk]
-    const uint8_t* v_new; // [B][K][dv] or NULL
+    const uint8_t* k_new; // [B][K][dk elements]
+    const uint8_t* v_new; // [B][K][dv elements] or NULL
     const float* scale_new;
+    const uint8_t* k_mx_new; // MXFP4: [B][K][dk/32]
+    const uint8_t* v_mx_new; // MXFP4: [B][K][dv/32]
     int32_t* len;         // the owner's len array (writable alias of sh.len)
     int32_t* overflow;
-    int32_t K, dk, dv, esz, capacity;
+    int32_t K, dk, dv, num, den, capacity;
 };
 
 __global__ __launch_bounds__(256) void kv_append_kernel(const AppendArgs a)
@@ -256,19 +259,32 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendArgs a)
     uint8_t* kdst = const_cast<uint8_t*>(static_cast<const uint8_t*>(a.sh.k));
     uint8_t* vdst = const_cast<uint8_t*>(static_cast<const uint8_t*>(a.sh.v));
     float* sdst = const_cast<float*>(a.sh.kv_scale);
-    const int krow = a.dk * a.esz, vrow = a.dv * a.esz;
+    const int krow = a.dk * a.num / a.den, vrow = a.dv * a.num / a.den;
     for (int i = tid; i < a.K * krow; i += 256) {
         const int kh = i / krow, x = i % krow;
-        kdst[((int64_t)b * a.sh.k_sb + (int64_t)kh * a.sh.k_sh + tok * a.sh.k_st) * a.esz + x] = a.k_new[((int64_t)b * a.K + kh) * krow + x];
+        kdst[((int64_t)b * a.sh.k_sb + (int64_t)kh * a.sh.k_sh + tok * a.sh.k_st) * a.num / a.den + x] = a.k_new[((int64_t)b * a.K + kh) * krow + x];
     }
     if (a.v_new)
         for (int i = tid; i < a.K * vrow; i += 256) {
             const int kh = i / vrow, x = i % vrow;
-            vdst[((int64_t)b * a.sh.v_sb + (int64_t)kh * a.sh.v_sh + tok * a.sh.v_st) * a.esz + x] = a.v_new[((int64_t)b * a.K + kh) * vrow + x];
+            vdst[((int64_t)b * a.sh.v_sb + (int64_t)kh * a.sh.v_sh + tok * a.sh.v_st) * a.num / a.den + x] = a.v_new[((int64_t)b * a.K + kh) * vrow + x];
         }
     if (a.scale_new)
         for (int kh = tid; kh < a.K; kh += 256)
             sdst[(int64_t)b * a.sh.s_sb + (int64_t)kh * a.sh.s_sh + tok] = a.scale_new[(int64_t)b * a.K + kh];
+    if (a.k_mx_new) {
+        uint8_t* kmx = const_cast<uint8_t*>(a.sh.k_mx);
+        uint8_t* vmx = const_cast<uint8_t*>(a.sh.v_mx);
+        const int kr = a.dk / 32, vr = a.dv / 32;
+        for (int i = tid; i < a.K * kr; i += 256) {
+            const int kh = i / kr, x = i % kr;
+            kmx[((int64_t)b * a.sh.k_sb + (int64_t)kh * a.sh.k_sh + tok * a.sh.k_st) / 32 + x] = a.k_mx_new[((int64_t)b * a.K + kh) * kr + x];
+        }
+        for (int i = tid; i < a.K * vr; i += 256) {
+            const int kh = i / vr, x = i % vr;
+            vmx[((int64_t)b * a.sh.v_sb + (int64_t)kh * a.sh.v_sh + tok * a.sh.v_st) / 32 + x] = a.v_mx_new[((int64_t)b * a.K + kh) * vr + x];
+        }
+    }
     if (tid == 0) a.len[b] = len + 1;     // every thread took its copy of the old length before the barrier
 }
 

@@ -11,7 +11,8 @@ from . import binding as hx
 def problem_for(w, split_tokens: int = 0) -> hx.Problem:
     """helix_problem of a synth.Workload-like object (B, Q, K, dk, dv, scale, mla, fp8)."""
     return hx.Problem(batch=w.B, q_heads=w.Q, kv_heads=w.K, dk=w.dk, dv=w.dv, scale=float(w.scale),
-                      v_aliases_k=bool(w.mla), kv_dtype=hx.KV_FP8_E4M3 if w.fp8 else hx.KV_BF16,
+                      v_aliases_k=bool(w.mla),
+                      kv_dtype=hx.KV_MXFP4 if getattr(w, "fp4", False) else hx.KV_FP8_E4M3 if w.fp8 else hx.KV_BF16,
                       split_tokens=split_tokens)
 
 
@@ -26,12 +27,14 @@ class ShardSet:
 
 
 def make_shards(k: torch.Tensor, v: Optional[torch.Tensor], lens_dev: torch.Tensor, n_shards: int,
-                kv_scale: Optional[torch.Tensor] = None, seq_base: Optional[torch.Tensor] = None) -> ShardSet:
+                kv_scale: Optional[torch.Tensor] = None, seq_base: Optional[torch.Tensor] = None,
+                mx=None) -> ShardSet:
     """Cuts every sequence into ``n_shards`` KVP slices with the library's layout kernel and wraps
     each slice as a view (tok_off) into the unsharded tensors.
 
     Padded storage: k [B,K,S,dk], v [B,K,S,dv] or None (MLA), kv_scale [B,K,S].
     Packed storage: k [rows,dk], seq_base int64 [B] = first row of each sequence, kv_scale [rows].
+    MXFP4: k, v uint8 codes [B,K,S,d/2] and mx = (k_mx, v_mx) uint8 block scales [B,K,S,d/32].
     """
     B = lens_dev.numel()
     dev = lens_dev.device
@@ -41,7 +44,9 @@ def make_shards(k: torch.Tensor, v: Optional[torch.Tensor], lens_dev: torch.Tens
     max_lens = shard_len.max(dim=1).values.cpu().tolist()      # harness-side sync, not in the library
     shards = []
     for i in range(n_shards):
-        if k.dim() == 2:
+        if mx is not None:
+            s = hx.KVShard.from_mxfp4(k, v, mx[0], mx[1], shard_len[i], max_lens[i], tok_off=shard_off[i])
+        elif k.dim() == 2:
             s = hx.KVShard.from_packed(k, shard_len[i], max_lens[i], shard_off[i], kv_scale=kv_scale)
         else:
             s = hx.KVShard.from_padded(k, v, shard_len[i], max_lens[i], tok_off=shard_off[i], kv_scale=kv_scale)

@@ -25,7 +25,8 @@ def decode(hx, w, inp, n_shards, want_parts=False):
     dev = "cuda"
     prob = harness.problem_for(w)
     seq_base = inp.seq_off[:-1].to(dev) if inp.seq_off is not None else None
-    ss = harness.make_shards(inp.k, inp.v, inp.lens.to(dev), n_shards, kv_scale=inp.kv_scale, seq_base=seq_base)
+    ss = harness.make_shards(inp.k, inp.v, inp.lens.to(dev), n_shards, kv_scale=inp.kv_scale, seq_base=seq_base,
+                             mx=None if inp.k_mx is None else (inp.k_mx, inp.v_mx))
     ws = harness.workspace_for(prob, n_shards, max(ss.max_lens), dev)
     o = torch.full((w.B, w.Q, w.dv), float("nan"), device=dev)
     lse = torch.full((w.B, w.Q), float("nan"), device=dev)
@@ -56,7 +57,8 @@ def oracle_rows(oracle, w, inp, rows):
             v = synth.bits(inp.v[b:b + 1, kh:kh + 1]) if inp.v is not None else None
             # a one-KV-head problem holding exactly this row's group: head index within the group
             qg = np.ascontiguousarray(q[:, kh * g:(kh + 1) * g])
-            o, l = oracle.attention(qg, k, v, inp.lens[b:b + 1].numpy(), w.scale, kv_heads=1, dv=w.dv, rows=[(0, h - kh * g)])
+            mx = None if inp.k_mx is None else (inp.k_mx[b:b + 1, kh:kh + 1].cpu().numpy(), inp.v_mx[b:b + 1, kh:kh + 1].cpu().numpy())
+            o, l = oracle.attention(qg, k, v, inp.lens[b:b + 1].numpy(), w.scale, kv_heads=1, dv=w.dv, rows=[(0, h - kh * g)], mx=mx)
         out_o.append(o[0])
         out_l.append(l[0])
     return np.stack(out_o), np.array(out_l)
@@ -137,3 +139,19 @@ def test_mla_fp8_ragged_full(hx, oracle):
     rows = [(b_short, 3), (b_long, 100), (7, 64)]
     o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
     check_rows(o8, lse8, o_ref, lse_ref, rows, "mla_fp8_ragged sharded")
+
+
+def test_gqa_share_mxfp4_full(hx, oracle):
+    """The MXFP4-KV share (4M-token context at KVP=8): sampled rows against the oracle, and the same
+    cache cut into 4 shards against the unsharded run."""
+    w = synth.WORKLOADS["gqa_share_mxfp4"]
+    inp = synth.make_inputs(w, "cuda")
+    o, lse, _, _, _ = decode(hx, w, inp, 1)
+    assert torch.isfinite(o).all() and torch.isfinite(lse).all()
+    rows = [(0, 0), (5, 9), (15, 15)]
+    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    check_rows(o, lse, o_ref, lse_ref, rows, "gqa_share_mxfp4")
+    o4, lse4, _, _, _ = decode(hx, w, inp, 4)
+    d = (o4 - o).abs().max().item()
+    print(f"gqa_share_mxfp4: 4 shards vs unsharded max-abs {d:.3e}")
+    assert d <= SHARD_VS_UNSHARDED and (lse4 - lse).abs().max().item() <= 1e-5
