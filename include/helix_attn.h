@@ -184,6 +184,17 @@ int helix_kv_append_mxfp4(const helix_problem *problem, const helix_kv_shard *sh
                           const uint8_t *k_scales, const uint8_t *v_scales,
                           int32_t capacity, int32_t *overflow, void *hip_stream);
 
+/* Appendix A: DRAM-read time of one layer's KV cache, the quantity the KVP width of this library's
+ * shards divides: B * 2 * ceil(K/TPA) * Hsz * (S/KVP) * bytes_per_param / mem_bw.  Host arithmetic in
+ * double; returns NaN for non-positive sizes.  mem_bw in bytes per second (8.0e12 for an MI355X). */
+double helix_kv_read_seconds(int64_t B, int64_t K, int64_t Hsz, double S, double bytes_per_param,
+                             double mem_bw, int64_t TPA, int64_t KVP);
+
+/* Appendix A: DRAM-read time of one layer's weights (QKV + output projection + SwiGLU FFN):
+ * (2*H*(Q/TPA)*Hsz + 2*H*ceil(K/TPA)*Hsz + 3*H*F/TPF) * bytes_per_param / mem_bw. */
+double helix_weight_read_seconds(int64_t H, int64_t Q, int64_t K, int64_t Hsz, int64_t F,
+                                 double bytes_per_param, double mem_bw, int64_t TPA, int64_t TPF);
+
 /* How the library would cut the work: tokens per workgroup and workgroups of the attention launch
  * for the given shards' max_len (host array [N]).  For benchmarks and tests; launches nothing. */
 int helix_attn_plan(const helix_problem *problem, const int32_t *max_lens, int32_t n_shards,

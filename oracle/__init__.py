@@ -243,3 +243,9 @@ def kv_read_seconds(B, K, Hsz, S, bytes_param, mem_bw, TPA=1, KVP=1):
     """Appendix A, first formula: time to read one layer's KV cache,
     B * 2 * ceil(K/TPA) * Hsz * (S/KVP) * bytes_param / MemBW."""
     return B * 2 * math.ceil(K / TPA) * Hsz * (S / KVP) * bytes_param / mem_bw
+
+
+def weight_read_seconds(H, Q, K, Hsz, F, bytes_param, mem_bw, TPA=1, TPF=1):
+    """Appendix A, second formula: time to read one layer's weights (SwiGLU FFN),
+    (2*H*(Q/TPA)*Hsz + 2*H*ceil(K/TPA)*Hsz + 3*H*F/TPF) * bytes_param / MemBW."""
+    return (2 * H * (Q / TPA) * Hsz + 2 * H * math.ceil(K / TPA) * Hsz + 3 * (H * F / TPF)) * bytes_param / mem_bw

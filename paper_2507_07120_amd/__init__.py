@@ -21,8 +21,10 @@ from .binding import (  # noqa: F401
     helix_kv_append,
     helix_kv_append_mxfp4,
     helix_kv_append_owner,
+    helix_kv_read_seconds,
     helix_shard_layout,
     helix_status_string,
+    helix_weight_read_seconds,
     library_path,
     load_library,
 )

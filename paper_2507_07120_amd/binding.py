@@ -84,6 +84,11 @@ def load_library():
     lib.helix_kv_append.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(_CShard), i32, i64, vp, vp, vp, i32, vp, vp]
     lib.helix_kv_append_mxfp4.restype = ctypes.c_int
     lib.helix_kv_append_mxfp4.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(_CShard), i32, i64, vp, vp, vp, vp, i32, vp, vp]
+    f64 = ctypes.c_double
+    lib.helix_kv_read_seconds.restype = f64
+    lib.helix_kv_read_seconds.argtypes = [i64, i64, i64, f64, f64, f64, i64, i64]
+    lib.helix_weight_read_seconds.restype = f64
+    lib.helix_weight_read_seconds.argtypes = [i64, i64, i64, i64, i64, f64, f64, i64, i64]
     lib.helix_attn_set_profile_events.restype = ctypes.c_int
     lib.helix_attn_set_profile_events.argtypes = [vp, vp]
     _lib = lib
@@ -327,3 +332,15 @@ def helix_kv_append_mxfp4(problem: Problem, shards: Sequence[KVShard], decode_in
                                                 int(capacity), None if overflow is None else overflow.data_ptr(),
                                                 _stream_ptr(stream)),
            "helix_kv_append_mxfp4")
+
+
+def helix_kv_read_seconds(B: int, K: int, Hsz: int, S: float, bytes_per_param: float, mem_bw: float,
+                          TPA: int = 1, KVP: int = 1) -> float:
+    """Appendix A: DRAM-read time of one layer's KV cache (host arithmetic in the library)."""
+    return float(load_library().helix_kv_read_seconds(B, K, Hsz, float(S), float(bytes_per_param), float(mem_bw), TPA, KVP))
+
+
+def helix_weight_read_seconds(H: int, Q: int, K: int, Hsz: int, F: int, bytes_per_param: float, mem_bw: float,
+                              TPA: int = 1, TPF: int = 1) -> float:
+    """Appendix A: DRAM-read time of one layer's weights (host arithmetic in the library)."""
+    return float(load_library().helix_weight_read_seconds(H, Q, K, Hsz, F, float(bytes_per_param), float(mem_bw), TPA, TPF))

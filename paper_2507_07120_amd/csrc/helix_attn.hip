@@ -466,6 +466,24 @@ int helix_kv_append_mxfp4(const helix_problem* problem, const helix_kv_shard* sh
     return append_common(problem, shards, n_shards, decode_index, k_codes, v_codes, nullptr, k_scales, v_scales, capacity, overflow, hip_stream);
 }
 
+double helix_kv_read_seconds(int64_t B, int64_t K, int64_t Hsz, double S, double bytes_per_param,
+                             double mem_bw, int64_t TPA, int64_t KVP)
+{
+    if (B < 1 || K < 1 || Hsz < 1 || !(S >= 0) || !(bytes_per_param > 0) || !(mem_bw > 0) || TPA < 1 || KVP < 1) return NAN;
+    const double heads = (double)ceil_div(K, TPA);         // a KV head is never split: TPA > K duplicates it
+    return (double)B * 2.0 * heads * (double)Hsz * (S / (double)KVP) * bytes_per_param / mem_bw;
+}
+
+double helix_weight_read_seconds(int64_t H, int64_t Q, int64_t K, int64_t Hsz, int64_t F,
+                                 double bytes_per_param, double mem_bw, int64_t TPA, int64_t TPF)
+{
+    if (H < 1 || Q < 1 || K < 1 || Hsz < 1 || F < 1 || !(bytes_per_param > 0) || !(mem_bw > 0) || TPA < 1 || TPF < 1) return NAN;
+    const double q_and_out = 2.0 * (double)H * ((double)Q / (double)TPA) * (double)Hsz;
+    const double kv = 2.0 * (double)H * (double)ceil_div(K, TPA) * (double)Hsz;
+    const double ffn = 3.0 * ((double)H * (double)F / (double)TPF);
+    return (q_and_out + kv + ffn) * bytes_per_param / mem_bw;
+}
+
 int helix_shard_layout(const int32_t* seq_len, const int64_t* seq_base, int32_t batch, int32_t n_shards,
                        int64_t* shard_off, int32_t* shard_len, void* hip_stream)
 {

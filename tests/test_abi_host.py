@@ -110,3 +110,23 @@ def test_append_owner_matches_the_oracle_rule(hx, oracle):
         for t in list(range(0, 300)) + [10 ** 6, 2 ** 40 + 17]:
             assert hx.helix_kv_append_owner(t, n) == oracle.round_robin_owner(t, n)
     assert hx.helix_kv_append_owner(-1, 4) == -1 and hx.helix_kv_append_owner(3, 0) == -1
+
+
+def test_appendix_a_calculator_matches_the_oracle(hx, oracle):
+    """Host arithmetic of the library against the oracle's closed forms (Appendix A), over the Fig. 1
+    parameter set and MI355X parameters, plus the plateau beyond TP = K."""
+    for TPA in (1, 2, 4, 8, 16, 64):
+        for KVP in (1, 2, 8, 32):
+            for S in (4096, 1 << 20, 3.5e6):
+                for bp, bw in ((0.5, 8.0e12), (2.0, 8.0e12), (0.53125, 8.0e12)):
+                    a = hx.helix_kv_read_seconds(8, 8, 128, S, bp, bw, TPA, KVP)
+                    b = oracle.kv_read_seconds(8, 8, 128, S, bp, bw, TPA, KVP)
+                    assert abs(a - b) <= 1e-15 * max(1.0, abs(b))
+    for TPA, TPF in ((1, 1), (8, 8), (16, 16), (8, 64)):
+        a = hx.helix_weight_read_seconds(16384, 128, 8, 128, 65536, 0.5, 8.0e12, TPA, TPF)
+        b = oracle.weight_read_seconds(16384, 128, 8, 128, 65536, 0.5, 8.0e12, TPA, TPF)
+        assert abs(a - b) <= 1e-18 + 1e-15 * abs(b)
+    assert hx.helix_kv_read_seconds(8, 8, 128, 1 << 20, 0.5, 8.0e12, 8, 1) == hx.helix_kv_read_seconds(8, 8, 128, 1 << 20, 0.5, 8.0e12, 64, 1)
+    import math
+    assert math.isnan(hx.helix_kv_read_seconds(0, 8, 128, 1.0, 0.5, 8.0e12, 1, 1))
+    assert math.isnan(hx.helix_weight_read_seconds(1, 1, 1, 1, 1, 0.5, 0.0, 1, 1))

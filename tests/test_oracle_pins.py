@@ -447,6 +447,24 @@ def test_appendix_a_kv_read_time(oracle):
             assert abs(got - float(sec)) <= 1e-15
 
 
+def test_appendix_a_weight_read_time(oracle):
+    with open(os.path.join(GOLDEN, "appendix_a_weight_read.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            H, Q, K, Hsz, F, bp, bw, TPA, TPF, sec = line.split()
+            got = oracle.weight_read_seconds(int(H), int(Q), int(K), int(Hsz), int(F), float(bp), float(bw), int(TPA), int(TPF))
+            assert abs(got - float(sec)) <= 1e-15
+
+
+def test_appendix_a_trends_of_fig_1(oracle):
+    """The three trends Fig. 1 shows for KV reads: flat in TP width beyond TP = K, linear in S, 1/KVP."""
+    kv = lambda **kw: oracle.kv_read_seconds(8, 8, 128, kw.get("S", 1 << 20), 0.5, 8.0e12, kw.get("TPA", 1), kw.get("KVP", 1))
+    assert kv(TPA=8) == kv(TPA=16) == kv(TPA=64) and kv(TPA=4) == 2 * kv(TPA=8)
+    assert kv(S=1 << 22) == 4 * kv(S=1 << 20)
+    assert kv(KVP=32) == kv() / 32
+
+
 # ---------------------------------------------------------------- P13 MXFP4 storage (FP4 of the paper's evaluation, Sec. 3)
 def test_mxfp4_tables_against_format_definition(oracle):
     with open(os.path.join(GOLDEN, "mxfp4_values.txt")) as f:
