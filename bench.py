@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--workload", default="gqa_share")
     ap.add_argument("--split-tokens", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hopb", type=int, default=0, metavar="G",
+                    help="also time the batch cut into G request groups whose exchange + combine run on a second "
+                         "stream under the next group's attention (Sec. 2.1.3), against the same call on one stream")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) before the timed loop, so that a "
                          "rocprofv3 --pmc run holds a kernel of known traffic to scale the counters by")
@@ -222,6 +225,25 @@ def main():
                    "split_tokens": split_tokens, "workgroups": workgroups},
         "roofline": roof,
     }
+    if args.hopb > 0:
+        mx = None if inp.k_mx is None else (inp.k_mx, inp.v_mx)
+        nbytes = hx.helix_attn_hopb_workspace_bytes(prob, N, max(ss.max_lens), args.hopb)
+        ws_h = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        bufs = hx.HopbBuffers(prob, N, args.hopb, dev)
+        cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
+
+        def timed(exchange_stream):
+            for _ in range(args.warmup):
+                hx.helix_attn_decode_hopb(prob, inp.q, ss.shards, o, ws_h, bufs, cs, exchange_stream, lse_out=lse)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(args.steps):
+                hx.helix_attn_decode_hopb(prob, inp.q, ss.shards, o, ws_h, bufs, cs, exchange_stream, lse_out=lse)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / args.steps * 1e6
+        out["hopb"] = {"groups": args.hopb, "us_per_step_two_streams": timed(xs), "us_per_step_one_stream": timed(cs),
+                       "note": "per-shard attention + device copy of the fragments (stand-in for the All-to-All) + combine; "
+                               "no shard_layout call in these steps"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out))

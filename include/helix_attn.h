@@ -184,6 +184,40 @@ int helix_kv_append_mxfp4(const helix_problem *problem, const helix_kv_shard *sh
                           const uint8_t *k_scales, const uint8_t *v_scales,
                           int32_t capacity, int32_t *overflow, void *hip_stream);
 
+/* Sec. 2.1.3 (HOP-B, batch-wise overlap of the KVP exchange with attention) on one GPU.  The batch is
+ * cut into n_groups groups of consecutive sequences (the first groups hold ceil(B / n_groups)).  Group
+ * g's per-shard attention runs on `compute_stream`; as soon as it is done its fragments are handed
+ * over on `exchange_stream` -- a device copy send -> recv stands in for the All-to-All, which is the
+ * identity when all N ranks are one GPU -- and combined there, while group g+1's attention is already
+ * running on `compute_stream`.
+ *   send_o, recv_o      fp32 [N*B*Q*dv] each, group-major: group g (sequences b0..b0+nb-1) owns the
+ *                       contiguous block [N, nb, Q, dv] starting at element N*b0*Q*dv
+ *   send_lse, recv_lse  fp32 [N*B*Q] each, same scheme
+ *   o, lse_out          fp32 [B,Q,dv], [B,Q] (lse_out may be NULL): complete once exchange_stream has
+ *                       drained
+ *   workspace           at least helix_attn_hopb_workspace_bytes
+ *   events              host array of n_groups + 1 hipEvent_t created by the caller: events[g] marks
+ *                       group g's fragments ready, events[n_groups] the end of the call's exchange
+ *                       work; the next call on the same buffers waits for it before it overwrites
+ *                       send_o / send_lse, so calls may be issued back to back
+ * compute_stream == exchange_stream is allowed and runs everything in order (HOP-B off). */
+int helix_attn_decode_hopb(const helix_problem *problem, const void *q,
+                           const helix_kv_shard *shards, int32_t n_shards, int32_t n_groups,
+                           float *o, float *lse_out,
+                           float *send_o, float *send_lse, float *recv_o, float *recv_lse,
+                           void *workspace, size_t workspace_bytes,
+                           void *compute_stream, void *exchange_stream, void *const *events);
+
+/* Workspace bytes helix_attn_decode_hopb needs (the largest group's); 0 if invalid. */
+size_t helix_attn_hopb_workspace_bytes(const helix_problem *problem, int32_t n_shards, int32_t max_len,
+                                       int32_t n_groups);
+
+/* Fig. 3's timeline as arithmetic: n_requests requests, each t_attn of attention followed by t_comm
+ * of exchange.  pipelined == 0: all attention, then all exchange (n*t_attn + n*t_comm); otherwise a
+ * two-stage pipeline in which request i's exchange runs under request i+1's attention:
+ * t_attn + (n-1)*max(t_attn, t_comm) + t_comm.  Host arithmetic; NaN for n < 1 or negative times. */
+double helix_hopb_span(int32_t n_requests, double t_attn, double t_comm, int32_t pipelined);
+
 /* Appendix A: DRAM-read time of one layer's KV cache, the quantity the KVP width of this library's
  * shards divides: B * 2 * ceil(K/TPA) * Hsz * (S/KVP) * bytes_per_param / mem_bw.  Host arithmetic in
  * double; returns NaN for non-positive sizes.  mem_bw in bytes per second (8.0e12 for an MI355X). */

@@ -245,6 +245,16 @@ def kv_read_seconds(B, K, Hsz, S, bytes_param, mem_bw, TPA=1, KVP=1):
     return B * 2 * math.ceil(K / TPA) * Hsz * (S / KVP) * bytes_param / mem_bw
 
 
+def hopb_span(n_requests, t_attn, t_comm, pipelined):
+    """Fig. 3's timeline.  Without HOP-B all requests finish attention, then all exchange:
+    n*t_attn + n*t_comm.  With HOP-B request i's exchange runs under request i+1's attention, a
+    two-stage pipeline: the first attention, then n-1 steps bounded by the slower stage, then the
+    last exchange."""
+    if not pipelined:
+        return n_requests * t_attn + n_requests * t_comm
+    return t_attn + (n_requests - 1) * max(t_attn, t_comm) + t_comm
+
+
 def weight_read_seconds(H, Q, K, Hsz, F, bytes_param, mem_bw, TPA=1, TPF=1):
     """Appendix A, second formula: time to read one layer's weights (SwiGLU FFN),
     (2*H*(Q/TPA)*Hsz + 2*H*ceil(K/TPA)*Hsz + 3*H*F/TPF) * bytes_param / MemBW."""

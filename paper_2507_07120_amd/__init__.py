@@ -7,6 +7,7 @@ raises.
 """
 from .binding import (  # noqa: F401
     HelixError,
+    HopbBuffers,
     KV_BF16,
     KV_FP8_E4M3,
     KV_MXFP4,
@@ -14,10 +15,13 @@ from .binding import (  # noqa: F401
     Problem,
     helix_attn_combine,
     helix_attn_decode,
+    helix_attn_decode_hopb,
+    helix_attn_hopb_workspace_bytes,
     helix_attn_partial,
     helix_attn_plan,
     helix_attn_set_profile_events,
     helix_attn_workspace_bytes,
+    helix_hopb_span,
     helix_kv_append,
     helix_kv_append_mxfp4,
     helix_kv_append_owner,

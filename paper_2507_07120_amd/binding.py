@@ -85,6 +85,13 @@ def load_library():
     lib.helix_kv_append_mxfp4.restype = ctypes.c_int
     lib.helix_kv_append_mxfp4.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(_CShard), i32, i64, vp, vp, vp, vp, i32, vp, vp]
     f64 = ctypes.c_double
+    lib.helix_attn_decode_hopb.restype = ctypes.c_int
+    lib.helix_attn_decode_hopb.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), i32, i32, vp, vp,
+                                           vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, ctypes.POINTER(vp)]
+    lib.helix_attn_hopb_workspace_bytes.restype = ctypes.c_size_t
+    lib.helix_attn_hopb_workspace_bytes.argtypes = [ctypes.POINTER(_CProblem), i32, i32, i32]
+    lib.helix_hopb_span.restype = f64
+    lib.helix_hopb_span.argtypes = [i32, f64, f64, i32]
     lib.helix_kv_read_seconds.restype = f64
     lib.helix_kv_read_seconds.argtypes = [i64, i64, i64, f64, f64, f64, i64, i64]
     lib.helix_weight_read_seconds.restype = f64
@@ -344,3 +351,48 @@ def helix_weight_read_seconds(H: int, Q: int, K: int, Hsz: int, F: int, bytes_pe
                               TPA: int = 1, TPF: int = 1) -> float:
     """Appendix A: DRAM-read time of one layer's weights (host arithmetic in the library)."""
     return float(load_library().helix_weight_read_seconds(H, Q, K, Hsz, F, float(bytes_per_param), float(mem_bw), TPA, TPF))
+
+
+def helix_hopb_span(n_requests: int, t_attn: float, t_comm: float, pipelined: bool) -> float:
+    """Fig. 3's timeline model (host arithmetic in the library)."""
+    return float(load_library().helix_hopb_span(int(n_requests), float(t_attn), float(t_comm), int(bool(pipelined))))
+
+
+def helix_attn_hopb_workspace_bytes(problem: Problem, n_shards: int, max_len: int, n_groups: int) -> int:
+    p = problem.c()
+    return int(load_library().helix_attn_hopb_workspace_bytes(ctypes.byref(p), n_shards, max_len, n_groups))
+
+
+class HopbBuffers:
+    """Send / receive fragment buffers and the events of helix_attn_decode_hopb, owned by the caller."""
+
+    def __init__(self, problem: Problem, n_shards: int, n_groups: int, device="cuda"):
+        n_o = n_shards * problem.batch * problem.q_heads * problem.dv
+        n_l = n_shards * problem.batch * problem.q_heads
+        self.send_o, self.recv_o = (torch.empty(n_o, dtype=torch.float32, device=device) for _ in range(2))
+        self.send_lse, self.recv_lse = (torch.empty(n_l, dtype=torch.float32, device=device) for _ in range(2))
+        self.events = [torch.cuda.Event() for _ in range(n_groups + 1)]
+        for e in self.events:                   # torch creates the hipEvent_t lazily, on the first record
+            e.record()
+        self.n_groups = n_groups
+
+
+def helix_attn_decode_hopb(problem: Problem, q: torch.Tensor, shards: Sequence[KVShard], o: torch.Tensor,
+                           workspace: torch.Tensor, buffers: HopbBuffers, compute_stream, exchange_stream,
+                           lse_out: Optional[torch.Tensor] = None) -> None:
+    """Sec. 2.1.3 on one GPU: group g's fragments are exchanged and combined on ``exchange_stream`` while
+    group g+1's attention runs on ``compute_stream``."""
+    n = len(shards)
+    assert q.dtype == torch.bfloat16 and q.is_contiguous()
+    _f32(o, (problem.batch, problem.q_heads, problem.dv), "o")
+    if lse_out is not None:
+        _f32(lse_out, (problem.batch, problem.q_heads), "lse_out")
+    p = problem.c()
+    arr = (_CShard * n)(*[s.c() for s in shards])
+    ev = (ctypes.c_void_p * (buffers.n_groups + 1))(*[e.cuda_event for e in buffers.events])
+    _check(load_library().helix_attn_decode_hopb(
+        ctypes.byref(p), q.data_ptr(), arr, n, buffers.n_groups, o.data_ptr(),
+        None if lse_out is None else lse_out.data_ptr(),
+        buffers.send_o.data_ptr(), buffers.send_lse.data_ptr(), buffers.recv_o.data_ptr(), buffers.recv_lse.data_ptr(),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+        _stream_ptr(compute_stream), _stream_ptr(exchange_stream), ev), "helix_attn_decode_hopb")

@@ -403,6 +403,95 @@ int helix_attn_decode(const helix_problem* problem, const void* q, const helix_k
     return combine_any(problem->dv, po, pl, o, lse_out, nullptr, n_shards, rows, stream);
 }
 
+namespace {
+// The descriptors of sequences b0 .. of a shard: every base pointer advanced by b0 batch strides.
+helix_kv_shard shard_of_group(const helix_problem* p, const helix_kv_shard& s, int32_t b0)
+{
+    helix_kv_shard g = s;
+    const int64_t num = p->kv_dtype == HELIX_KV_BF16 ? 2 : 1, den = p->kv_dtype == HELIX_KV_MXFP4 ? 2 : 1;
+    g.k = static_cast<const char*>(s.k) + b0 * s.k_stride_b * num / den;
+    if (s.v) g.v = static_cast<const char*>(s.v) + b0 * s.v_stride_b * num / den;
+    if (s.kv_scale) g.kv_scale = s.kv_scale + b0 * s.s_stride_b;
+    if (s.k_scale_mx) g.k_scale_mx = s.k_scale_mx + b0 * s.k_stride_b / 32;
+    if (s.v_scale_mx) g.v_scale_mx = s.v_scale_mx + b0 * s.v_stride_b / 32;
+    if (s.tok_off) g.tok_off = s.tok_off + b0;
+    g.len = s.len + b0;
+    return g;
+}
+}  // namespace
+
+size_t helix_attn_hopb_workspace_bytes(const helix_problem* problem, int32_t n_shards, int32_t max_len, int32_t n_groups)
+{
+    if (!problem || n_groups < 1 || n_groups > problem->batch) return 0;
+    helix_problem sub = *problem;
+    sub.batch = (int32_t)ceil_div(problem->batch, n_groups);
+    const size_t a = helix_attn_workspace_bytes(&sub, n_shards, max_len);
+    sub.batch = problem->batch - (n_groups - 1) * sub.batch > 0 ? problem->batch - (n_groups - 1) * sub.batch : sub.batch;
+    const size_t b = helix_attn_workspace_bytes(&sub, n_shards, max_len);
+    return a == 0 || b == 0 ? 0 : std::max(a, b);
+}
+
+int helix_attn_decode_hopb(const helix_problem* problem, const void* q, const helix_kv_shard* shards, int32_t n_shards,
+                           int32_t n_groups, float* o, float* lse_out,
+                           float* send_o, float* send_lse, float* recv_o, float* recv_lse,
+                           void* workspace, size_t workspace_bytes,
+                           void* compute_stream, void* exchange_stream, void* const* events)
+{
+    Path path;
+    if (int rc = check_problem(problem, &path)) return rc;
+    if (!q || !o || !shards || !send_o || !send_lse || !recv_o || !recv_lse || !events) return HELIX_ERR_NULL;
+    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS || n_groups < 1 || n_groups > problem->batch) return HELIX_ERR_SHAPE;
+    for (int g = 0; g <= n_groups; g++)
+        if (!events[g]) return HELIX_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(q) % 16 || reinterpret_cast<uintptr_t>(o) % 16 || reinterpret_cast<uintptr_t>(send_o) % 16 ||
+        reinterpret_cast<uintptr_t>(recv_o) % 16) return HELIX_ERR_SHAPE;
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream), xs = static_cast<hipStream_t>(exchange_stream);
+    const int32_t B = problem->batch, Q = problem->q_heads, dv = problem->dv, N = n_shards;
+    const int32_t per = (int32_t)ceil_div(B, n_groups);
+    // validate everything before the first launch: an error return means no kernel ran
+    helix_kv_shard sub[HELIX_MAX_SHARDS];                  // on the stack: the library allocates nothing
+    for (int32_t b0 = 0; b0 < B; b0 += per) {
+        helix_problem sp = *problem;
+        sp.batch = std::min(per, B - b0);
+        for (int32_t i = 0; i < N; i++) sub[i] = shard_of_group(problem, shards[i], b0);
+        Plan plan;
+        Workspace ws;
+        if (int rc = prepare(&sp, sub, N, workspace, workspace_bytes, &plan, &ws)) return rc;
+    }
+    // the previous call's exchange may still be reading the send buffers
+    if (hipStreamWaitEvent(cs, static_cast<hipEvent_t>(events[n_groups]), 0) != hipSuccess) return HELIX_ERR_LAUNCH;
+    int g = 0;
+    for (int32_t b0 = 0; b0 < B; b0 += per, g++) {
+        helix_problem sp = *problem;
+        sp.batch = std::min(per, B - b0);
+        for (int32_t i = 0; i < N; i++) sub[i] = shard_of_group(problem, shards[i], b0);
+        Plan plan;
+        Workspace ws;
+        if (int rc = prepare(&sp, sub, N, workspace, workspace_bytes, &plan, &ws)) return rc;
+        const size_t off_o = (size_t)N * b0 * Q * dv, off_l = (size_t)N * b0 * Q;
+        const size_t n_o = (size_t)N * sp.batch * Q * dv, n_l = (size_t)N * sp.batch * Q;
+        const char* qg = static_cast<const char*>(q) + (size_t)b0 * Q * problem->dk * 2;
+        if (int rc = run_partials(&sp, plan, qg, sub, N, ws, send_o + off_o, send_lse + off_l, cs)) return rc;
+        hipEvent_t ready = static_cast<hipEvent_t>(events[g]);
+        if (hipEventRecord(ready, cs) != hipSuccess || hipStreamWaitEvent(xs, ready, 0) != hipSuccess) return HELIX_ERR_LAUNCH;
+        if (hipMemcpyAsync(recv_o + off_o, send_o + off_o, n_o * 4, hipMemcpyDeviceToDevice, xs) != hipSuccess ||
+            hipMemcpyAsync(recv_lse + off_l, send_lse + off_l, n_l * 4, hipMemcpyDeviceToDevice, xs) != hipSuccess)
+            return HELIX_ERR_LAUNCH;
+        if (int rc = combine_any(dv, recv_o + off_o, recv_lse + off_l, o + (size_t)b0 * Q * dv,
+                                 lse_out ? lse_out + (size_t)b0 * Q : nullptr, nullptr, N, (int64_t)sp.batch * Q, xs))
+            return rc;
+    }
+    if (hipEventRecord(static_cast<hipEvent_t>(events[n_groups]), xs) != hipSuccess) return HELIX_ERR_LAUNCH;
+    return HELIX_OK;
+}
+
+double helix_hopb_span(int32_t n_requests, double t_attn, double t_comm, int32_t pipelined)
+{
+    if (n_requests < 1 || !(t_attn >= 0) || !(t_comm >= 0)) return NAN;
+    if (!pipelined) return n_requests * t_attn + n_requests * t_comm;
+    return t_attn + (n_requests - 1) * std::max(t_attn, t_comm) + t_comm;
+}
+
 int32_t helix_kv_append_owner(int64_t decode_index, int32_t n_shards)
 {
     if (n_shards < 1 || decode_index < 0) return -1;

@@ -130,3 +130,14 @@ def test_appendix_a_calculator_matches_the_oracle(hx, oracle):
     import math
     assert math.isnan(hx.helix_kv_read_seconds(0, 8, 128, 1.0, 0.5, 8.0e12, 1, 1))
     assert math.isnan(hx.helix_weight_read_seconds(1, 1, 1, 1, 1, 0.5, 0.0, 1, 1))
+
+
+def test_hopb_timeline_model_matches_the_oracle(hx, oracle):
+    """Fig. 3 as arithmetic, library against oracle; 8 requests of 2 + 1.2 units: 25.6 without overlap."""
+    import math
+    assert hx.helix_hopb_span(8, 2.0, 1.2, False) == 25.6
+    for n in (1, 2, 8, 33):
+        for ta, tc in ((2.0, 1.2), (0.5, 3.0), (1.0, 1.0), (0.0, 1.0)):
+            for pipe in (False, True):
+                assert hx.helix_hopb_span(n, ta, tc, pipe) == oracle.hopb_span(n, ta, tc, pipe)
+    assert math.isnan(hx.helix_hopb_span(0, 1.0, 1.0, True)) and math.isnan(hx.helix_hopb_span(3, -1.0, 1.0, True))

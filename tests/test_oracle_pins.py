@@ -465,6 +465,32 @@ def test_appendix_a_trends_of_fig_1(oracle):
     assert kv(KVP=32) == kv() / 32
 
 
+def test_hopb_timeline_of_fig_3(oracle):
+    with open(os.path.join(GOLDEN, "fig3_hopb_timeline.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            n, ta, tc, pipe, span, tol = line.split()
+            assert abs(oracle.hopb_span(int(n), float(ta), float(tc), int(pipe)) - float(span)) <= float(tol)
+    # structure: one request cannot overlap with anything; a slow exchange becomes the bottleneck stage;
+    # the pipelined span never exceeds the sequential one and never undercuts either stage's total
+    assert oracle.hopb_span(1, 2.0, 1.2, 1) == oracle.hopb_span(1, 2.0, 1.2, 0) == 3.2
+    assert oracle.hopb_span(8, 2.0, 1.2, 1) == 8 * 2.0 + 1.2
+    assert oracle.hopb_span(8, 1.0, 3.0, 1) == 1.0 + 8 * 3.0
+    for n, ta, tc in [(2, 1.0, 1.0), (5, 0.3, 2.0), (7, 2.0, 0.1)]:
+        p_, s_ = oracle.hopb_span(n, ta, tc, 1), oracle.hopb_span(n, ta, tc, 0)
+        assert max(n * ta, n * tc) <= p_ <= s_
+    # brute force: simulate the two resources event by event
+    def simulate(n, ta, tc):
+        attn_free = comm_free = 0.0
+        for _ in range(n):
+            attn_free += ta                       # attention unit is busy back to back
+            comm_free = max(comm_free, attn_free) + tc
+        return comm_free
+    for n, ta, tc in [(8, 2.0, 1.2), (3, 1.0, 4.0), (6, 0.5, 0.5)]:
+        assert abs(simulate(n, ta, tc) - oracle.hopb_span(n, ta, tc, 1)) <= 1e-12
+
+
 # ---------------------------------------------------------------- P13 MXFP4 storage (FP4 of the paper's evaluation, Sec. 3)
 def test_mxfp4_tables_against_format_definition(oracle):
     with open(os.path.join(GOLDEN, "mxfp4_values.txt")) as f:
