@@ -153,8 +153,9 @@ __device__ __forceinline__ void gqa_compute_core(GqaState<D>& st, KOp&& kop, VOp
         const uint32_t lo = pack_bf16_rne(r0, r1);
         phi[e >> 1] = h;
         plo[e >> 1] = lo;
-        // l sums exactly what the MFMAs will see, so O/l carries no bias from the split
-        lsum += (as_f32(h << 16) + as_f32(lo << 16)) + (as_f32(h & 0xffff0000u) + as_f32(lo & 0xffff0000u));
+        // l sums the unsplit weights: hi + lo differs from p by at most 2^-17 p, far below the bars,
+        // and re-adding the split would cost three more VALU instructions per weight pair
+        lsum += p0 + p1;
     }
     st.l += lsum;
     const bf16x8 bhi = __builtin_bit_cast(bf16x8, u32x4{phi[0], phi[1], phi[2], phi[3]});
