@@ -141,3 +141,23 @@ def test_hopb_timeline_model_matches_the_oracle(hx, oracle):
             for pipe in (False, True):
                 assert hx.helix_hopb_span(n, ta, tc, pipe) == oracle.hopb_span(n, ta, tc, pipe)
     assert math.isnan(hx.helix_hopb_span(0, 1.0, 1.0, True)) and math.isnan(hx.helix_hopb_span(3, -1.0, 1.0, True))
+
+
+def test_mxfp4_and_hopb_argument_errors_without_gpu(hx):
+    """The newer entry points validate on the host as well: status codes, nothing launched."""
+    lib = hx.load_library()
+    mx = hx.Problem(2, 16, 1, 128, 128, 0.088, kv_dtype=hx.KV_MXFP4)
+    assert hx.helix_attn_workspace_bytes(mx, 1, 4096) > 0
+    assert hx.helix_attn_workspace_bytes(hx.Problem(2, 16, 1, 64, 64, 0.125, kv_dtype=hx.KV_MXFP4), 1, 4096) == 0
+    assert hx.helix_attn_workspace_bytes(hx.Problem(2, 128, 1, 576, 512, 0.07, v_aliases_k=True, kv_dtype=hx.KV_MXFP4), 1, 4096) == 0
+    p = mx.c()
+    # helix_kv_append refuses an MXFP4 cache (3 = unsupported); the MXFP4 variant refuses a bf16 one and NULLs
+    assert lib.helix_kv_append(ctypes.byref(p), None, 1, 0, None, None, None, 16, None, None) == 3
+    pb = hx.Problem(2, 16, 1, 128, 128, 0.088).c()
+    assert lib.helix_kv_append_mxfp4(ctypes.byref(pb), None, 1, 0, None, None, None, None, 16, None, None) == 3
+    assert lib.helix_kv_append_mxfp4(ctypes.byref(p), None, 1, 0, None, None, None, None, 16, None, None) == 1
+    # pipelined decode: NULL buffers, more groups than sequences
+    assert lib.helix_attn_decode_hopb(ctypes.byref(pb), None, None, 1, 2, None, None, None, None, None, None,
+                                      None, 0, None, None, None) == 1
+    assert hx.helix_attn_hopb_workspace_bytes(hx.Problem(2, 16, 1, 128, 128, 0.088), 1, 4096, 2) > 0
+    assert hx.helix_attn_hopb_workspace_bytes(hx.Problem(2, 16, 1, 128, 128, 0.088), 1, 4096, 3) == 0
