@@ -115,6 +115,21 @@ def test_gqa_shapes_against_oracle(hx, oracle, B, Q, K, D, S, N, lens, split):
     assert (o_n - o_1).abs().max().item() <= SHARD_VS_UNSHARDED
 
 
+def test_maximum_shard_count(hx, oracle):
+    """HELIX_MAX_SHARDS = 1024 slices of one cache (64 launches of 16 descriptors each, then the
+    stand-alone combine over 1024 fragments): layout bit-exact, combined result and argmax against the oracle."""
+    w = synth.Workload("max_shards", B=2, Q=16, K=1, dk=128, dv=128, n_shards=1024, scale=1 / math.sqrt(128), seed=88, seq_len=20000)
+    inp = synth.make_inputs(w, "cuda")
+    inp.lens = torch.tensor([20000, 9000], dtype=torch.int32)
+    o_n, lse_n = run_sharded(hx, oracle, w, inp, 1024, check_partials=False)
+    o_1, lse_1 = run_sharded(hx, oracle, w, inp, 1, check_partials=False)
+    assert (o_n - o_1).abs().max().item() <= SHARD_VS_UNSHARDED
+    from paper_2507_07120_amd import harness
+    with pytest.raises(hx.HelixError):                      # one more than the limit is refused before any launch
+        hx.helix_shard_layout(inp.lens.cuda(), 1025, torch.empty((1025, 2), dtype=torch.int64, device="cuda"),
+                              torch.empty((1025, 2), dtype=torch.int32, device="cuda"))
+
+
 def test_peaked_softmax_sharded_vs_unsharded(hx, oracle):
     """The sharp-peak recipe of the 16-shard configuration (1% of keys x8) at a reduced length."""
     w = synth.scaled(synth.WORKLOADS["gqa_full"], B=2, seq_len=16384)
