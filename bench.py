@@ -116,11 +116,14 @@ def read_traffic(workload: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gqa_share")
     ap.add_argument("--split-tokens", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-call", action="store_true",
+                    help="time the step as helix_shard_layout + helix_attn_decode (two entry points, one more "
+                         "launch) instead of helix_attn_decode_kvp, which cuts the slices inside the kernel")
     ap.add_argument("--hopb", type=int, default=0, metavar="G",
                     help="also time the batch cut into G request groups whose exchange + combine run on a second "
                          "stream under the next group's attention (Sec. 2.1.3), against the same call on one stream")
@@ -156,9 +159,23 @@ def main():
     lse = torch.empty((w.B, w.Q), device=dev)
     split_tokens, workgroups = hx.helix_attn_plan(prob, ss.max_lens)
 
-    def step():
-        hx.helix_shard_layout(lens_dev, N, shard_off, shard_len, seq_base=seq_base)
-        hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+    max_len = int(inp.lens.max())
+    if inp.k_mx is not None:
+        cache = hx.KVShard.from_mxfp4(inp.k, inp.v, inp.k_mx, inp.v_mx, lens_dev, max_len)
+    elif inp.k.dim() == 2:
+        cache = hx.KVShard.from_packed(inp.k, lens_dev, max_len, seq_base, kv_scale=inp.kv_scale)
+    else:
+        cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, max_len, kv_scale=inp.kv_scale)
+
+    # one step = the whole path over one batch: the KVP cut of every sequence (integer metadata, written
+    # out), the per-slice attention fragments, and their combine
+    if args.two_call:
+        def step():
+            hx.helix_shard_layout(lens_dev, N, shard_off, shard_len, seq_base=seq_base)
+            hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+    else:
+        def step():
+            hx.helix_attn_decode_kvp(prob, inp.q, cache, N, o, ws, lse_out=lse, shard_off=shard_off, shard_len=shard_len)
 
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
@@ -222,7 +239,8 @@ def main():
         "config": {"workload": w.name, "B": w.B, "q_heads": w.Q, "kv_heads": w.K, "dk": w.dk, "dv": w.dv,
                    "n_shards": N, "tokens_per_step": int(sum(inp.lens.tolist())) * w.K,
                    "kv_dtype": "e4m3+fp32 scale" if w.fp8 else "mxfp4 (e2m1 + e8m0 per 32)" if getattr(w, "fp4", False) else "bf16",
-                   "split_tokens": split_tokens, "workgroups": workgroups},
+                   "split_tokens": split_tokens, "workgroups": workgroups,
+                   "entry": "helix_shard_layout + helix_attn_decode" if args.two_call else "helix_attn_decode_kvp"},
         "roofline": roof,
     }
     if args.hopb > 0:

@@ -142,6 +142,18 @@ int helix_attn_decode(const helix_problem *problem, const void *q,
                       float *o, float *lse_out, float *o_partials, float *lses,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* helix_shard_layout and helix_attn_decode in one call: `cache` describes the UNSHARDED cache (len =
+ * the sequences' full lengths, tok_off = their first rows or NULL, max_len = an upper bound of the
+ * lengths) and the N slices of Sec. 2.1.1 are cut inside the attention kernel, with the integers
+ * helix_shard_layout would produce.  One launch less per decode step.
+ *   shard_off, shard_len   int64 / int32 [N,B] or both NULL: the cut, written by the kernel
+ *   everything else as in helix_attn_decode; size the workspace with helix_attn_workspace_bytes(
+ *   problem, n_shards, max_len). */
+int helix_attn_decode_kvp(const helix_problem *problem, const void *q, const helix_kv_shard *cache,
+                          int32_t n_shards, float *o, float *lse_out, float *o_partials, float *lses,
+                          int64_t *shard_off, int32_t *shard_len,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Sec. 2.1.1: the contiguous KVP cut of every sequence into N slices, as device-side integer
  * bookkeeping.  Slice width c_b = 16 * ceil(ceil(L_b / N) / 16) tokens (whole 16-token blocks, the
  * append granule of Sec. 2.3); shard i of sequence b = [min(i*c_b, L_b), min((i+1)*c_b, L_b)).

@@ -76,6 +76,9 @@ def load_library():
     lib.helix_attn_decode.restype = ctypes.c_int
     lib.helix_attn_decode.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), i32,
                                       vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.helix_attn_decode_kvp.restype = ctypes.c_int
+    lib.helix_attn_decode_kvp.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), i32,
+                                          vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.helix_shard_layout.restype = ctypes.c_int
     lib.helix_shard_layout.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.helix_kv_append_owner.restype = ctypes.c_int32
@@ -396,3 +399,29 @@ def helix_attn_decode_hopb(problem: Problem, q: torch.Tensor, shards: Sequence[K
         buffers.send_o.data_ptr(), buffers.send_lse.data_ptr(), buffers.recv_o.data_ptr(), buffers.recv_lse.data_ptr(),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(),
         _stream_ptr(compute_stream), _stream_ptr(exchange_stream), ev), "helix_attn_decode_hopb")
+
+
+def helix_attn_decode_kvp(problem: Problem, q: torch.Tensor, cache: KVShard, n_shards: int, o: torch.Tensor,
+                          workspace: torch.Tensor, lse_out: Optional[torch.Tensor] = None,
+                          o_partials: Optional[torch.Tensor] = None, lses: Optional[torch.Tensor] = None,
+                          shard_off: Optional[torch.Tensor] = None, shard_len: Optional[torch.Tensor] = None,
+                          stream=None) -> None:
+    """Layout + decode in one call: ``cache`` describes the unsharded cache, the KVP cut happens in the kernel."""
+    assert q.dtype == torch.bfloat16 and q.is_contiguous()
+    _f32(o, (problem.batch, problem.q_heads, problem.dv), "o")
+    if lse_out is not None:
+        _f32(lse_out, (problem.batch, problem.q_heads), "lse_out")
+    if o_partials is not None:
+        _f32(o_partials, (n_shards, problem.batch, problem.q_heads, problem.dv), "o_partials")
+        _f32(lses, (n_shards, problem.batch, problem.q_heads), "lses")
+    if shard_off is not None:
+        assert shard_off.dtype == torch.int64 and shard_off.is_contiguous() and tuple(shard_off.shape) == (n_shards, problem.batch)
+        assert shard_len.dtype == torch.int32 and shard_len.is_contiguous() and tuple(shard_len.shape) == (n_shards, problem.batch)
+    p, c = problem.c(), cache.c()
+
+    def ptr(t):
+        return None if t is None else t.data_ptr()
+    _check(load_library().helix_attn_decode_kvp(ctypes.byref(p), q.data_ptr(), ctypes.byref(c), int(n_shards), o.data_ptr(),
+                                                ptr(lse_out), ptr(o_partials), ptr(lses), ptr(shard_off), ptr(shard_len),
+                                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                _stream_ptr(stream)), "helix_attn_decode_kvp")

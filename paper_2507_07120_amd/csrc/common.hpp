@@ -31,7 +31,11 @@ struct ShardDev {
     int32_t split_base;   // index of this shard's first split among all splits of the call
     int32_t n_splits;     // ceil(max_len / split_tokens)
     int32_t unit_base;    // first workgroup of this shard in the launch
+    int32_t kvp_n;        // 0: tok_off / len describe this shard.  N > 0: they describe the WHOLE cache and
+    int32_t kvp_i;        //    this descriptor is KVP slice kvp_i of N, cut inside the kernel (shard_range)
     int32_t pad;
+    int64_t* out_off;     // kvp_n > 0: where slice kvp_i's offsets / lengths of all sequences are recorded, or NULL
+    int32_t* out_len;
     const uint8_t* k_mx;  // MXFP4 only: E8M0 block scales, index = element index / 32
     const uint8_t* v_mx;
 };
@@ -49,6 +53,29 @@ struct AttnArgs {
     int32_t n_shards;
     ShardDev shard[kMaxLaunchShards];
 };
+
+// Tokens of sequence b this shard holds and the row of the first one.  With kvp_n > 0 the contiguous
+// KVP cut of Sec. 2.1.1 is made here: slice width c = 16 * ceil(ceil(L / N) / 16) tokens (whole blocks of
+// the append granule of Sec. 2.3), slice i = [min(i c, L), min((i+1) c, L)) -- the same integers the
+// stand-alone layout kernel produces.
+__device__ __forceinline__ void shard_range(const ShardDev& sh, int b, int& len, int64_t& first_row)
+{
+    const int64_t base = sh.tok_off ? sh.tok_off[b] : 0;
+    const int64_t L = sh.len[b];
+    if (sh.kvp_n == 0) {
+        len = (int)L;
+        first_row = base;
+        return;
+    }
+    // 32-bit unsigned arithmetic for the division (L < 2^31, N <= 1024, so L + N - 1 and c fit); only
+    // the product i * c needs 64 bits
+    const uint32_t n = (uint32_t)sh.kvp_n;
+    const uint32_t per = ((uint32_t)L + n - 1u) / n;
+    const uint32_t c = ((per + 15u) >> 4) << 4;
+    const int64_t lo = min((int64_t)sh.kvp_i * c, L), hi = min((int64_t)(sh.kvp_i + 1) * c, L);
+    len = (int)(hi - lo);
+    first_row = base + lo;
+}
 
 __device__ __forceinline__ uint32_t as_u32(float x) { return __builtin_bit_cast(uint32_t, x); }
 __device__ __forceinline__ float as_f32(uint32_t x) { return __builtin_bit_cast(float, x); }

@@ -263,7 +263,10 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
     const int kh = rest % a.K;
     const int b = rest / a.K;
 
-    const int len = sh.len[b];
+    int len;
+    int64_t first_row;
+    shard_range(sh, b, len, first_row);
+    if (sh.out_off && split == 0 && ht == 0 && kh == 0 && threadIdx.x == 0) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
     const int t0 = split * a.split_tokens;
     const int t1 = min(t0 + a.split_tokens, len);
     const int h0 = kh * a.g + ht * 16;
@@ -275,7 +278,7 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
         return;
     }
 
-    const int64_t tok0 = (sh.tok_off ? sh.tok_off[b] : 0) + t0;
+    const int64_t tok0 = first_row + t0;
     const char* kbase = reinterpret_cast<const char*>(sh.k) + 2 * ((int64_t)b * sh.k_sb + (int64_t)kh * sh.k_sh + tok0 * sh.k_st);
     const char* vbase = reinterpret_cast<const char*>(sh.v) + 2 * ((int64_t)b * sh.v_sb + (int64_t)kh * sh.v_sh + tok0 * sh.v_st);
     const uint32_t k_row_bytes = (uint32_t)sh.k_st * 2u, v_row_bytes = (uint32_t)sh.v_st * 2u;

@@ -192,9 +192,17 @@ int combine_any(int32_t dv, const float* o_parts, const float* lses, float* o, f
 // Attention over `n` shards into per-shard partials (o_part [n,B,Q,dv], lse_part [n,B,Q]).
 // With `o` non-NULL and n <= kMaxLaunchShards the merge and the combine run fused (finish_kernel)
 // and *finished is set; otherwise the caller still has to combine.
+// kvp_n > 0: every descriptor in `shards` describes the whole cache and shard i is cut inside the kernels
+// as slice i of kvp_n; kvp_off / kvp_len ([kvp_n, B], may be NULL) receive the cut.
+struct KvpCut {
+    int32_t n = 0;
+    int64_t* off = nullptr;
+    int32_t* len = nullptr;
+};
+
 int run_partials(const helix_problem* p, const Plan& plan, const void* q, const helix_kv_shard* shards, int32_t n,
                  const Workspace& ws, float* o_part, float* lse_part, hipStream_t stream,
-                 float* o = nullptr, float* lse_out = nullptr, bool* finished = nullptr)
+                 float* o = nullptr, float* lse_out = nullptr, bool* finished = nullptr, KvpCut cut = KvpCut())
 {
     const bool fuse = o != nullptr && n <= kMaxLaunchShards;
     if (finished) *finished = fuse;
@@ -223,6 +231,9 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             d.v_sb = s.v_stride_b; d.v_sh = s.v_stride_h; d.v_st = s.v_stride_t;
             d.s_sb = s.s_stride_b; d.s_sh = s.s_stride_h;
             d.k_mx = s.k_scale_mx; d.v_mx = s.v_scale_mx;
+            d.kvp_n = cut.n; d.kvp_i = s0 + i;
+            d.out_off = cut.off ? cut.off + (int64_t)(s0 + i) * p->batch : nullptr;
+            d.out_len = cut.len ? cut.len + (int64_t)(s0 + i) * p->batch : nullptr;
             d.n_splits = (int32_t)std::max<int64_t>(1, ceil_div(s.max_len, plan.split_tokens));
             d.split_base = split_base;
             d.unit_base = (int32_t)units;
@@ -490,6 +501,40 @@ double helix_hopb_span(int32_t n_requests, double t_attn, double t_comm, int32_t
     if (n_requests < 1 || !(t_attn >= 0) || !(t_comm >= 0)) return NAN;
     if (!pipelined) return n_requests * t_attn + n_requests * t_comm;
     return t_attn + (n_requests - 1) * std::max(t_attn, t_comm) + t_comm;
+}
+
+int helix_attn_decode_kvp(const helix_problem* problem, const void* q, const helix_kv_shard* cache, int32_t n_shards,
+                          float* o, float* lse_out, float* o_partials, float* lses,
+                          int64_t* shard_off, int32_t* shard_len,
+                          void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!q || !o || !cache) return HELIX_ERR_NULL;
+    if ((o_partials == nullptr) != (lses == nullptr) || (shard_off == nullptr) != (shard_len == nullptr)) return HELIX_ERR_NULL;
+    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(q) % 16 || reinterpret_cast<uintptr_t>(o) % 16 ||
+        reinterpret_cast<uintptr_t>(o_partials) % 16) return HELIX_ERR_SHAPE;
+    if (cache->max_len < 0) return HELIX_ERR_SHAPE;
+    // every slice is at most c = 16 * ceil(ceil(max_len / N) / 16) tokens long
+    helix_kv_shard slices[HELIX_MAX_SHARDS];               // on the stack: the library allocates nothing
+    const int64_t per = ceil_div(cache->max_len, n_shards);
+    const int32_t c = (int32_t)std::min<int64_t>(16 * ceil_div(per, 16), cache->max_len);
+    for (int32_t i = 0; i < n_shards; i++) {
+        slices[i] = *cache;
+        slices[i].max_len = c;
+    }
+    Plan plan;
+    Workspace ws;
+    if (int rc = prepare(problem, slices, n_shards, workspace, workspace_bytes, &plan, &ws)) return rc;
+    float* po = o_partials ? o_partials : ws.part_o;
+    float* pl = lses ? lses : ws.part_lse;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    KvpCut cut;
+    cut.n = n_shards; cut.off = shard_off; cut.len = shard_len;
+    bool finished = false;
+    if (int rc = run_partials(problem, plan, q, slices, n_shards, ws, po, pl, stream, o, lse_out, &finished, cut)) return rc;
+    if (finished) return HELIX_OK;
+    const int64_t rows = (int64_t)problem->batch * problem->q_heads;
+    return combine_any(problem->dv, po, pl, o, lse_out, nullptr, n_shards, rows, stream);
 }
 
 int32_t helix_kv_append_owner(int64_t decode_index, int32_t n_shards)

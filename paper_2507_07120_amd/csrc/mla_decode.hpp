@@ -314,7 +314,10 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     const int split = logical / a.B;
     const int b = (logical % a.B + 3 * split) % a.B;
 
-    const int len = sh.len[b];
+    int len;
+    int64_t first_row;
+    shard_range(sh, b, len, first_row);
+    if (sh.out_off && split == 0 && htw == 0 && threadIdx.x == 0) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
     const int t0 = split * a.split_tokens;
     const int t1 = min(t0 + a.split_tokens, len);
     const int h0 = htw * C::HPW;                      // first head of this workgroup
@@ -341,7 +344,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     }
 
     const int esz = FP8 ? 1 : 2;
-    const int64_t tok0 = (sh.tok_off ? sh.tok_off[b] : 0) + t0;
+    const int64_t tok0 = first_row + t0;
     const char* kbase = reinterpret_cast<const char*>(sh.k) + (int64_t)esz * ((int64_t)b * sh.k_sb + tok0 * sh.k_st);
     const float* sbase = FP8 ? sh.kv_scale + (int64_t)b * sh.s_sb + tok0 : nullptr;
     const uint32_t row_bytes = (uint32_t)sh.k_st * esz;

@@ -159,5 +159,7 @@ def test_mxfp4_and_hopb_argument_errors_without_gpu(hx):
     # pipelined decode: NULL buffers, more groups than sequences
     assert lib.helix_attn_decode_hopb(ctypes.byref(pb), None, None, 1, 2, None, None, None, None, None, None,
                                       None, 0, None, None, None) == 1
+    # decode with the cut inside the kernel: NULL buffers, a shard count out of range
+    assert lib.helix_attn_decode_kvp(ctypes.byref(pb), None, None, 2, None, None, None, None, None, None, None, 0, None) == 1
     assert hx.helix_attn_hopb_workspace_bytes(hx.Problem(2, 16, 1, 128, 128, 0.088), 1, 4096, 2) > 0
     assert hx.helix_attn_hopb_workspace_bytes(hx.Problem(2, 16, 1, 128, 128, 0.088), 1, 4096, 3) == 0
