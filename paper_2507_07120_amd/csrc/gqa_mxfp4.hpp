@@ -51,14 +51,14 @@ __device__ __forceinline__ void mx4_load_block(Mx4Raw& raw, const char* kblk, co
     for (int a = 0; a < 2; a++) {
         int tok = a * 16 + r;
         if (TAIL) tok = min(tok, n_valid - 1);
-        raw.k[a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kblk + (uint32_t)tok * k_row_bytes + (uint32_t)kc * 16u));
+        raw.k[a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kblk + (uint32_t)((uint32_t)tok * k_row_bytes + (uint32_t)kc * 16u)));
         raw.ks[a] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(ksc + (uint32_t)tok * (k_row_bytes / 16u)));
     }
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         int tok = (j >> 2) * 16 + kc * 4 + (j & 3);
         if (TAIL) tok = min(tok, n_valid - 1);
-        raw.v[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(vblk + (uint32_t)tok * v_row_bytes + (uint32_t)r * 4u));
+        raw.v[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(vblk + (uint32_t)((uint32_t)tok * v_row_bytes + (uint32_t)r * 4u)));
     }
     if (TAIL) {
 #pragma unroll
@@ -128,7 +128,9 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
     constexpr int D = 128;
     using C = GqaCfg<D>;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    // the wave index as a scalar: block addresses then stay in scalar registers and the loads take a
+    // scalar base plus a 32-bit lane offset instead of 64-bit vector arithmetic per load
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, kc = lane >> 4;
 
     // which (shard, split, sequence, kv head, head tile) this workgroup serves
