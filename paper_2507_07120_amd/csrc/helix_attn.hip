@@ -37,6 +37,11 @@ constexpr int64_t kTargetWorkgroupsMx = 768;    // MXFP4 streams 3.8x fewer byte
 constexpr int64_t kTargetWorkgroupsMla = 4096;   // upper end: keeps the split records of a call near 1 GB at most
 constexpr int64_t kMinSplitTokensMla = 4096;
 
+inline int64_t target_workgroups(Path path)
+{
+    return path == Path::Mla ? kTargetWorkgroupsMla : path == Path::GqaMx128 ? kTargetWorkgroupsMx : kTargetWorkgroups;
+}
+
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -93,7 +98,7 @@ int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_
         // Measured: the ragged e4m3 workload takes 4.7 ms with 4096-token runs, 5.2 with 8192, 6.7 with
         // one run per (shard, sequence); the uniform bf16 share loses 3 % against its best (8192).  The
         // 256 KB record of a run is 5-11 % of the latent bytes it reads.
-        const int64_t target = path == Path::Mla ? kTargetWorkgroupsMla : path == Path::GqaMx128 ? kTargetWorkgroupsMx : kTargetWorkgroups;
+        const int64_t target = target_workgroups(path);
         const int64_t floor_tokens = path == Path::Mla ? kMinSplitTokensMla : kMinSplitTokens;
         split = ceil_div(ceil_div(rows * total, target), plan->granule) * plan->granule;
         split = std::max<int64_t>(split, floor_tokens);
@@ -189,17 +194,17 @@ int combine_any(int32_t dv, const float* o_parts, const float* lses, float* o, f
     }
 }
 
-// Attention over `n` shards into per-shard partials (o_part [n,B,Q,dv], lse_part [n,B,Q]).
-// With `o` non-NULL and n <= kMaxLaunchShards the merge and the combine run fused (finish_kernel)
-// and *finished is set; otherwise the caller still has to combine.
-// kvp_n > 0: every descriptor in `shards` describes the whole cache and shard i is cut inside the kernels
-// as slice i of kvp_n; kvp_off / kvp_len ([kvp_n, B], may be NULL) receive the cut.
+// n > 0: every descriptor handed to run_partials describes the whole cache and shard i is cut inside
+// the kernels as slice i of n (Sec. 2.1.1); off / len ([n, B], may be NULL) receive the cut.
 struct KvpCut {
     int32_t n = 0;
     int64_t* off = nullptr;
     int32_t* len = nullptr;
 };
 
+// Attention over `n` shards into per-shard partials (o_part [n,B,Q,dv], lse_part [n,B,Q]).
+// With `o` non-NULL and n <= kMaxLaunchShards the merge and the combine run fused (finish_kernel)
+// and *finished is set; otherwise the caller still has to combine.
 int run_partials(const helix_problem* p, const Plan& plan, const void* q, const helix_kv_shard* shards, int32_t n,
                  const Workspace& ws, float* o_part, float* lse_part, hipStream_t stream,
                  float* o = nullptr, float* lse_out = nullptr, bool* finished = nullptr, KvpCut cut = KvpCut())
@@ -367,7 +372,7 @@ size_t helix_attn_workspace_bytes(const helix_problem* problem, int32_t n_shards
     const int64_t rows = (int64_t)problem->batch * problem->kv_heads * plan.head_tiles;
     int64_t worst = plan.total_splits;
     if (problem->split_tokens == 0)
-        worst = std::max<int64_t>(worst, ceil_div(path == Path::Mla ? kTargetWorkgroupsMla : kTargetWorkgroups, rows) + n_shards);
+        worst = std::max<int64_t>(worst, ceil_div(target_workgroups(path), rows) + n_shards);
     return carve(problem, worst, n_shards, nullptr).bytes;
 }
 

@@ -58,13 +58,16 @@ def test_workspace_bound_covers_shorter_shards(hx):
     """The sizing call must cover any set of shards no longer than max_len."""
     lib = hx.load_library()
     for prob in [hx.Problem(16, 16, 1, 128, 128, 0.088), hx.Problem(4, 64, 8, 128, 128, 0.088),
-                 hx.Problem(1, 8, 2, 64, 64, 0.125), hx.Problem(2, 40, 2, 64, 64, 0.125, split_tokens=256)]:
+                 hx.Problem(1, 8, 2, 64, 64, 0.125), hx.Problem(2, 40, 2, 64, 64, 0.125, split_tokens=256),
+                 hx.Problem(16, 16, 1, 128, 128, 0.088, kv_dtype=hx.KV_MXFP4), hx.Problem(2, 32, 2, 128, 128, 0.088, kv_dtype=hx.KV_MXFP4),
+                 hx.Problem(4, 128, 1, 576, 512, 0.07, v_aliases_k=True), hx.Problem(2, 160, 1, 576, 512, 0.07, v_aliases_k=True)]:
         for n, max_len in [(1, 131072), (16, 65536), (4, 1024), (8, 100)]:
             bound = hx.helix_attn_workspace_bytes(prob, n, max_len)
             for lens in [[max_len] * n, [max_len // 3] * n, [1] * n, [0] * n, [max_len] + [7] * (n - 1)]:
                 split, wgs = hx.helix_attn_plan(prob, lens)
                 g = prob.q_heads // prob.kv_heads
-                rows = prob.batch * prob.kv_heads * ((g + 15) // 16)
+                hpw = 128 if prob.v_aliases_k else 16           # query heads one workgroup serves
+                rows = prob.batch * prob.kv_heads * ((g + hpw - 1) // hpw)
                 splits = wgs // rows
                 need = splits * prob.batch * prob.q_heads * (prob.dv + 2) * 4
                 assert need <= bound, (prob, n, max_len, lens)
