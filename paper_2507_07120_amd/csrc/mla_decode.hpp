@@ -72,7 +72,7 @@ struct MlaCfg {
     // LDS map
     static constexpr int OFF_K = 0;
     static constexpr int OFF_P = NBUF * TILE_BYTES;               // [pair][hi, lo]
-    static constexpr int OFF_FLAG = OFF_P + (WAVES / 2) * 2 * P_BYTES;   // int: a wave saw a score beyond the limit
+    static constexpr int OFF_FLAG = OFF_P + (WAVES / 2) * 2 * P_BYTES;   // int: a wave saw a score beyond the limit; + 4, + 8: maxima of the e4m3 set-up
     static constexpr int OFF_SCALE = OFF_FLAG + 16;               // [NBUF][32] fp32 per-token scales
     static constexpr int OFF_DMA = OFF_SCALE + NBUF * T * 4;      // [THREADS][8] u32: per-lane source offsets of the tile DMA (5 used)
     static constexpr int OFF_STAGE = OFF_DMA + THREADS * 32;      // [WAVES][4 rows][576] e4m3 codes on their way in
@@ -80,6 +80,25 @@ struct MlaCfg {
     static constexpr float kHeadroom = 32.f, kLimit = 64.f;
 };
 static_assert(MlaCfg::LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+// The 16x16x32 MFMA on 16-bit operands handed over as raw bits: fp16 for the e4m3 latent (whose tile in
+// LDS is widened to fp16), bf16 otherwise.  Same operand and result layout for both.
+template <bool F16>
+__device__ __forceinline__ f32x4 mla_mfma(const u32x4& a, const u32x4& b, const f32x4& c)
+{
+    if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// Two fp32 -> packed fp16 pair, round to nearest even (one v_cvt_pk_f16_f32).
+__device__ __forceinline__ uint32_t pack_f16_rne(float lo, float hi)
+{
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
+}
 
 typedef __attribute__((address_space(3))) uint8_t lds_byte;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -276,8 +295,8 @@ struct MlaDmaFp8 {
             for (int d = 0; d < 4; d++) {
                 const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[d], false);
                 const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[d], true);
-                o[2 * d] = pack_bf16_rne(lo.x, lo.y);
-                o[2 * d + 1] = pack_bf16_rne(hi.x, hi.y);
+                o[2 * d] = pack_f16_rne(lo.x, lo.y);            // exact: every e4m3 value is an fp16 value
+                o[2 * d + 1] = pack_f16_rne(hi.x, hi.y);
             }
             *reinterpret_cast<lds_u32x4*>(tile + mla_swz(row, 2 * cc)) = u32x4{o[0], o[1], o[2], o[3]};
             *reinterpret_cast<lds_u32x4*>(tile + mla_swz(row, 2 * cc + 1)) = u32x4{o[4], o[5], o[6], o[7]};
@@ -332,14 +351,42 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     // Q slice of this wave as the score MFMA's B operand: lane (r,kc) holds head 16*wave + r of the
     // workgroup, dims 32*ks + 8*kc .. +8
     const int hl = wave * 16 + r;                     // this lane's head within the workgroup
-    bf16x8 qb[C::KS];
+    u32x4 qb[C::KS];
+    float q_mul = a.scale_log2e;                      // raw MFMA score -> exponent (base 2) of the weight
     {
         const uint16_t* qrow = a.q + ((size_t)b * a.Q + h0 + min(hl, nh - 1)) * C::DK + kc * 8;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ks++) {
             u32x4 w = *reinterpret_cast<const u32x4*>(qrow + ks * 32);
             if (hl >= nh) w = u32x4{0, 0, 0, 0};
-            qb[ks] = __builtin_bit_cast(bf16x8, w);
+            qb[ks] = w;
+        }
+        if constexpr (FP8) {
+            // The e4m3 path contracts in fp16: the workgroup's query rows are scaled by the power of two
+            // that puts their largest magnitude in [2^14, 2^15) and converted (exact for every entry within
+            // 2^-28 of the largest, the rest is off by less than 2^-39 of it); the scores get the inverse.
+            // One factor for the whole workgroup, so that it lives in a scalar register.
+            uint32_t mx = 0;
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ks++)
+#pragma unroll
+                for (int j = 0; j < 4; j++) mx = max(mx, max(qb[ks][j] & 0x7fffu, (qb[ks][j] >> 16) & 0x7fffu));
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o));
+            uint32_t* cell = reinterpret_cast<uint32_t*>(smem_raw + C::OFF_FLAG);
+            if (tid == 0) cell[1] = 0;
+            __syncthreads();
+            if (lane == 0) atomicMax(&cell[1], mx);
+            __syncthreads();
+            mx = __builtin_amdgcn_readfirstlane(cell[1]);
+            const uint32_t e = min(max(mx >> 7, 15u), 254u);            // biased exponent of the largest |q|
+            const float up = as_f32((268u - e) << 23);                   // 2^(14 - (e - 127))
+            q_mul *= as_f32((e - 14u) << 23);                            // 2^((e - 127) - 14)
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ks++)
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    qb[ks][j] = pack_f16_rne(as_f32(qb[ks][j] << 16) * up, as_f32(qb[ks][j] & 0xffff0000u) * up);
         }
     }
 
@@ -355,6 +402,8 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     float m_ref = -INFINITY;                          // reference exponent of head hl (integer-valued)
     float m_floor = -INFINITY;                        // lower bound for it in a repeated run
     float l_run = 0.f;                                // this lane's share of sum p (tokens 4kc+i, 16+4kc+i of every tile)
+    float w_scale = 1.f;                              // e4m3: 2^-E, the power of two that brings p_t * f_t into fp16 range (uniform)
+    float w_max = 0.f;                                // e4m3: largest weight this lane handed to the P.V MFMAs in the run
     f32x4 acc[C::DVT][C::NHT];                        // O^T[256half + 16d + 4kc + i][32pair + 16h + r]
 
     auto ktile_of = [&](int slot) { return smem + C::OFF_K + slot * C::TILE_BYTES; };      // slot = tile index mod NBUF
@@ -367,14 +416,14 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     // per-lane base, +-64 bytes, immediates for ks and the half.  Reads run PD k-steps ahead.
     auto scores = [&](const lds_byte* ktile, f32x4& s0, f32x4& s1) {
         constexpr int PD = 3;
-        bf16x8 k0[C::KS], k1[C::KS];
+        u32x4 k0[C::KS], k1[C::KS];
         const int l = mla_opaque(lane), r = l & 15, kc = l >> 4;
         const int f = r & 7;
         const lds_byte* kp = ktile + r * C::ROW + ((kc ^ (f & 3)) << 4);
         const int flip = (f & 4) << 4;
         auto rd = [&](int ks, int half) {
             const lds_byte* q = ((ks & 1) ? kp - flip : kp + flip) + half * 16 * C::ROW;
-            return __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(q + ks * 64));
+            return *reinterpret_cast<const lds_u32x4*>(q + ks * 64);
         };
         s0 = f32x4{0.f, 0.f, 0.f, 0.f};
         s1 = s0;
@@ -382,8 +431,8 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         for (int o = 0; o < PD; o++) { k0[o] = rd(o, 0); k1[o] = rd(o, 1); }
 #pragma unroll
         for (int o = 0; o < C::KS; o++) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0[o], qb[o], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[o], qb[o], s1, 0, 0, 0);
+            s0 = mla_mfma<FP8>(k0[o], qb[o], s0);
+            s1 = mla_mfma<FP8>(k1[o], qb[o], s1);
             if (o + PD < C::KS) { k0[o + PD] = rd(o + PD, 0); k1[o + PD] = rd(o + PD, 1); }
             __builtin_amdgcn_sched_barrier(0);        // keep the reads PD k-steps ahead
         }
@@ -401,11 +450,12 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             for (int i = 0; i < 4; i++) { fs[i] = f0[i]; fs[4 + i] = f1[i]; }
         }
         float bmax = -INFINITY;
+        const int tok = (mla_opaque(lane) >> 4) * 4;      // recomputed here: eight hoisted token indices would not fit
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            float x = (i < 4 ? s0[i] : s1[i - 4]) * a.scale_log2e;
+            float x = (i < 4 ? s0[i] : s1[i - 4]) * q_mul;
             if (FP8) x *= fs[i];
-            if ((i >> 2) * 16 + kc * 4 + (i & 3) >= n_valid) x = -INFINITY;
+            if (tok >= n_valid - ((i >> 2) * 16 + (i & 3))) x = -INFINITY;
             t[i] = x;
             bmax = fmaxf(bmax, x);
         }
@@ -419,6 +469,28 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     // limit, a ballot turns that into the workgroup's redo flag.
     auto softmax = [&](const f32x4& s0, const f32x4& s1, int kb, int n_valid) {
         float t[8], fs[8], p[8];
+        if constexpr (FP8) {
+            // One fp16 weight per token, w_t = p_t * f_t * 2^-E (11 significant bits: relative L2 error of
+            // O about 2e-4); the normaliser sums the plain p_t in fp32.  Range is checked once per run.
+            exponents(s0, s1, kb, n_valid, t, fs);
+            float lsum = 0.f, wm = w_max;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const float pi = exp2_rel(fmaxf(t[i], m_ref - 200.f), m_ref);
+                lsum += pi;
+                p[i] = pi * (fs[i] * w_scale);
+                wm = fmaxf(wm, p[i]);
+            }
+            l_run += lsum;
+            w_max = wm;
+            u32x4 w;
+#pragma unroll
+            for (int j = 0; j < 4; j++) w[j] = pack_f16_rne(p[2 * j], p[2 * j + 1]);
+            const int l = mla_opaque(lane);
+            lds_byte* pw = smem + C::OFF_P + pair * 2 * C::P_BYTES + (half * 16 + (l & 15)) * (C::T * 2) + (l >> 4) * 16;
+            *reinterpret_cast<lds_u32x4*>(pw) = w;
+            return;
+        }
         const float top = __builtin_ceilf(exponents(s0, s1, kb, n_valid, t, fs));
         const bool over = top > m_ref + C::kLimit;
         if (over) m_floor = fmaxf(m_floor, top + C::kHeadroom);
@@ -453,11 +525,11 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     auto pv = [&](const lds_byte* ktile, auto&& between) {
         const int l = mla_opaque(lane), r = l & 15, kc = l >> 4;
         const lds_byte* pp = smem + C::OFF_P + pair * 2 * C::P_BYTES + r * (C::T * 2) + kc * 16;
-        bf16x8 bh[C::NHT], bl[C::NHT];
+        u32x4 bh[C::NHT], bl[C::NHT];
 #pragma unroll
         for (int h = 0; h < C::NHT; h++) {
-            bh[h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(pp + h * 16 * (C::T * 2)));
-            bl[h] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const lds_u32x4*>(pp + h * 16 * (C::T * 2) + C::P_BYTES));
+            bh[h] = *reinterpret_cast<const lds_u32x4*>(pp + h * 16 * (C::T * 2));
+            if constexpr (!FP8) bl[h] = *reinterpret_cast<const lds_u32x4*>(pp + h * 16 * (C::T * 2) + C::P_BYTES);
         }
         const int vrow = 4 * kc + (r >> 2), vf = vrow & 7, cb = (r & 3) >> 1;
         const lds_byte* vb = ktile + vrow * C::ROW + ((r & 1) << 3) + half * 512;
@@ -467,18 +539,20 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         auto rd = [&](int d) {
             const lds_byte* p0 = ve[d & 3] + (d >> 2) * 128;
             const u32x2 v0 = lds_read_tr16(p0), v1 = lds_read_tr16(p0 + 16 * C::ROW);
-            return __builtin_bit_cast(bf16x8, u32x4{v0.x, v0.y, v1.x, v1.y});
+            return u32x4{v0.x, v0.y, v1.x, v1.y};
         };
         constexpr int PD = 3;
-        bf16x8 va[C::DVT];
+        u32x4 va[C::DVT];
 #pragma unroll
         for (int d = 0; d < PD; d++) va[d] = rd(d);
 #pragma unroll
         for (int d = 0; d < C::DVT; d++) {
 #pragma unroll
-            for (int h = 0; h < C::NHT; h++) acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[d], bh[h], acc[d][h], 0, 0, 0);
+            for (int h = 0; h < C::NHT; h++) acc[d][h] = mla_mfma<FP8>(va[d], bh[h], acc[d][h]);
+            if constexpr (!FP8) {
 #pragma unroll
-            for (int h = 0; h < C::NHT; h++) acc[d][h] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[d], bl[h], acc[d][h], 0, 0, 0);
+                for (int h = 0; h < C::NHT; h++) acc[d][h] = mla_mfma<false>(va[d], bl[h], acc[d][h]);
+            }
             if (d + PD < C::DVT) va[d + PD] = rd(d + PD);
             if (d % 3 == 1) between(d / 3);
             __builtin_amdgcn_sched_barrier(0);
@@ -521,13 +595,18 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     };
 
     // The outer loop runs once unless the reference exponent turned out too low.
+    bool redo = false;                                // e4m3: second pass, references already adjusted
     for (;;) {
         l_run = 0.f;
+        w_max = 0.f;
 #pragma unroll
         for (int d = 0; d < C::DVT; d++)
 #pragma unroll
             for (int h = 0; h < C::NHT; h++) acc[d][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (tid == 0) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 0;
+        if (tid == 0) {
+            *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 0;
+            if (FP8) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG + 8) = 0;     // largest first-tile weight
+        }
 
         // ---- first tiles on their way; tile 0 fixes the reference exponent of every head ----
         if constexpr (FP8) {
@@ -547,7 +626,27 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             f32x4 s0, s1;
             scores(ktile_of(0), s0, s1);
             const float top = wave_xor_max_16_32(exponents(s0, s1, 0, valid_of(0), t, fs));
-            m_ref = fmaxf(__builtin_ceilf(top) + C::kHeadroom, m_floor);          // finite: token 0 is valid
+            if constexpr (FP8) {
+                if (!redo) {
+                    // fp16 weights: a head's reference sits 4 octaves BELOW its largest exponent of the first
+                    // tile, and E (one for the workgroup: a scalar) puts the largest first-tile weight
+                    // p_t * f_t * 2^-E of any head into [2^4, 2^5) -- ten octaves of headroom to the fp16
+                    // maximum, eighteen down to the smallest normal number
+                    m_ref = __builtin_ceilf(top) - 4.f;
+                    float wm = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 8; i++) wm = fmaxf(wm, exp2_rel(fmaxf(t[i], m_ref - 200.f), m_ref) * fs[i]);
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) wm = fmaxf(wm, __shfl_xor(wm, o));
+                    uint32_t* cell = reinterpret_cast<uint32_t*>(smem_raw + C::OFF_FLAG);
+                    if (lane == 0) atomicMax(&cell[2], as_u32(wm));        // non-negative floats order like their bits
+                    mla_barrier();
+                    const float wg = as_f32(__builtin_amdgcn_readfirstlane(cell[2]));
+                    w_scale = wg > 0.f ? __builtin_ldexpf(1.f, 5 - __builtin_amdgcn_frexp_expf(wg)) : 1.f;
+                }
+            } else {
+                m_ref = fmaxf(__builtin_ceilf(top) + C::kHeadroom, m_floor);      // finite: token 0 is valid
+            }
         }
 
         // ---- the tile loop ----
@@ -569,6 +668,18 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             slot = slot1;
         }
 
+        if constexpr (FP8) {
+            // The run's largest weight per head decides: at or beyond 2^15 an fp16 weight may have
+            // overflowed, below 2^-6 too much of the softmax sat in fp16's denormal range.  Either way the
+            // reference moves so that this largest weight lands in [2^4, 2^5) and the run is repeated once
+            // (weights are exact powers of two apart between the passes, so the second pass always fits).
+            const float wh = wave_xor_max_16_32(w_max);
+            const bool bad = !redo && (wh >= 32768.f || (wh > 0.f && wh < 0.015625f));
+            if (bad) m_ref += (float)(__builtin_amdgcn_frexp_expf(wh) - 5);
+            if (__any(bad)) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 1;
+            mla_barrier();
+            redo = true;
+        }
         if (__builtin_expect(*reinterpret_cast<const lds_i32*>(smem + C::OFF_FLAG) == 0, 1)) break;
         // Some score went beyond the limit: run again with references above everything seen
         // (the four lanes of a head saw different tokens).
@@ -580,8 +691,14 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     {
         const float l = wave_xor_sum_16_32(l_run);
         if (kc == 0 && hl < nh) {
-            a.ws_m[rec + hl] = m_ref;
-            a.ws_l[rec + hl] = l;
+            if constexpr (FP8) {
+                // acc holds sum w_t v_t with w_t = p_t f_t 2^-E: the record's exponent takes the E
+                a.ws_m[rec + hl] = m_ref - (float)(__builtin_amdgcn_frexp_expf(w_scale) - 1);
+                a.ws_l[rec + hl] = l * w_scale;
+            } else {
+                a.ws_m[rec + hl] = m_ref;
+                a.ws_l[rec + hl] = l;
+            }
         }
     }
 #pragma unroll

@@ -23,11 +23,11 @@ def hx():
     return hx_
 
 
-def check_o(got, ref, what):
+def check_o(got, ref, what, max_abs=O_MAX_ABS):
     got = np.asarray(got, dtype=np.float64)
     err = np.abs(got - ref).max()
     rel = np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-300)
-    assert err <= O_MAX_ABS and rel <= O_REL_L2, f"{what}: max-abs {err:.3e} rel-L2 {rel:.3e}"
+    assert err <= max_abs and rel <= O_REL_L2, f"{what}: max-abs {err:.3e} rel-L2 {rel:.3e}"
     return err, rel
 
 
