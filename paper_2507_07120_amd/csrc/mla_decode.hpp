@@ -32,7 +32,7 @@
 //   S phase  scores S^T[token, head] = K . Q^T: wave w owns heads 16w..16w+15 and both token halves
 //            (two independent MFMA chains); its Q slice (16 x 576 bf16 = 72 registers) never moves,
 //            the K operands come from LDS.  Softmax stays inside the wave, with an integer reference
-//            exponent that is FIXED for the whole run (32 octaves above the first tile's maximum): no
+//            exponent that is FIXED for the whole run (bf16: 32 octaves above the first tile's maximum): no
 //            rescale of accumulators, no cross-lane maximum in the loop.  A tile that exceeds the
 //            reference by more than 64 octaves raises a flag; the workgroup then redoes the run with
 //            a reference raised above everything it saw (never on real logits, exercised by a test).
@@ -46,10 +46,14 @@
 // Each wave copies 4 rows of every tile and awaits only its own share before the barrier that
 // publishes it.
 //
-// e4m3 latent: the raw codes are DMA-ed into a per-wave staging area and widened to bf16 (exact) by
-// the wave that requested them when the tile is due; the per-token scale f_t multiplies the score
-// (s_t = f_t * q.k8_t) and the weight that meets the values (p_t * f_t), while the normaliser sums the
-// plain p_t.
+// e4m3 latent: the raw codes are DMA-ed into a per-wave staging area and widened to fp16 (exact) by
+// the wave that requested them when the tile is due, and both contractions run on the fp16 MFMA (same
+// rate as bf16, 11 significant bits): the query rows are scaled into fp16 range by a power of two, and
+// ONE fp16 weight w_t = p_t * f_t * 2^-E per token replaces the bf16 hi/lo pair -- half the P.V MFMAs.
+// The per-token scale f_t multiplies the score (s_t = f_t * q.k8_t) and the weight; the normaliser sums
+// the plain p_t in fp32.  fp16's range is narrow: a head's reference sits 4 octaves below its first-tile
+// maximum, E is chosen from the first tile, and a run whose largest weight of some head left
+// [2^-6, 2^15) is repeated once with that head's reference moved.
 #pragma once
 #include "common.hpp"
 
@@ -77,7 +81,7 @@ struct MlaCfg {
     static constexpr int OFF_DMA = OFF_SCALE + NBUF * T * 4;      // [THREADS][8] u32: per-lane source offsets of the tile DMA (5 used)
     static constexpr int OFF_STAGE = OFF_DMA + THREADS * 32;      // [WAVES][4 rows][576] e4m3 codes on their way in
     static constexpr int LDS_BYTES = OFF_STAGE + T * DK;
-    static constexpr float kHeadroom = 32.f, kLimit = 64.f;
+    static constexpr float kHeadroom = 32.f, kLimit = 64.f;   // bf16 latent: reference above the first tile's maximum, redo beyond this
 };
 static_assert(MlaCfg::LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 
@@ -233,7 +237,7 @@ struct MlaDma {
 
 // e4m3 latent tiles: wave w DMAs the raw codes of rows 4w..4w+3 (2304 bytes = 2.25 wave
 // instructions) into its own staging area plus the four per-token scales straight into the scale
-// slot, and later widens its rows to bf16 (exact: e4m3 has 3 mantissa bits and a 4-bit exponent)
+// slot, and later widens its rows to fp16 (exact: e4m3 has 3 mantissa bits and a 4-bit exponent)
 // into the swizzled tile.  Staging is private to the wave: no barrier between request and conversion.
 struct MlaDmaFp8 {
     static constexpr int ROWS = MlaDma::ROWS;
