@@ -55,6 +55,8 @@
 // maximum, E is chosen from the first tile, and a run whose largest weight of some head left
 // [2^-6, 2^15) is repeated once with that head's reference moved.
 #pragma once
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace helix {
@@ -258,6 +260,14 @@ struct MlaDmaFp8 {
             o[j] = (uint32_t)row * row_bytes + (uint32_t)(cpos << 4);
         }
         *reinterpret_cast<lds_u32x4*>(table + tid * 32) = u32x4{o[0], o[1], o[2], 0};
+        // where convert() puts the lane's chunk j of codes: (row, 16-byte chunk 2cc) of the widened tile
+        uint32_t t[INSTRS];
+#pragma unroll
+        for (int j = 0; j < INSTRS; j++) {
+            const int q = min(j * 64 + lane, CHUNKS - 1), row = row_of(wave, q), cc = q - (row - wave * ROWS) * CHUNKS_PER_ROW;
+            t[j] = (uint32_t)mla_swz(row, 2 * cc);
+        }
+        *reinterpret_cast<lds_u32x4*>(table + tid * 32 + 16) = u32x4{t[0], t[1], t[2], 0};
     }
 
     // part j < INSTRS: codes; part INSTRS: scales.  `stage`, `scale_dst` = LDS byte addresses of the
@@ -282,32 +292,36 @@ struct MlaDmaFp8 {
         }
     }
 
-    // After the wave's DMA has landed: widen its rows into the tile; rows the tile does not have
-    // become zeros with scale zero.
-    static __device__ __forceinline__ void convert(int n_valid, const lds_byte* stage, lds_byte* tile, lds_byte* scale_slot, int wave, int lane)
+    // After the wave's DMA has landed: widen its rows into the tile (v_cvt_scalef32_pk_f16_fp8 with scale 1:
+    // two codes -> two fp16, exact for all 256 codes -- checked on the device); rows the tile does not
+    // have become zeros with scale zero.  The destination offsets come from the table init() wrote.
+    static __device__ __forceinline__ void convert(int n_valid, const lds_byte* stage, lds_byte* tile, lds_byte* scale_slot,
+                                                   const lds_byte* table, int wave, int lane, int tid)
     {
         lane = mla_opaque(lane);                          // addresses recomputed here, not carried through the tile loop
+        const u32x4 dst = *reinterpret_cast<const lds_u32x4*>(table + mla_opaque(tid) * 32 + 16);
+        const lds_byte* sp = stage + lane * 16;
+        const bool ragged = n_valid != MlaCfg::T;
 #pragma unroll
         for (int j = 0; j < INSTRS; j++) {
-            const int q = j * 64 + lane;
-            if (q >= CHUNKS) continue;
-            const int row = row_of(wave, q), cc = q - (row - wave * ROWS) * CHUNKS_PER_ROW;
-            u32x4 w = {0, 0, 0, 0};
-            if (row < n_valid) w = *reinterpret_cast<const lds_u32x4*>(stage + q * 16);
+            if (j * 64 + 63 >= CHUNKS && lane >= CHUNKS - j * 64) continue;
+            u32x4 w = *reinterpret_cast<const lds_u32x4*>(sp + j * 1024);
+            if (ragged && row_of(wave, j * 64 + lane) >= n_valid) w = u32x4{0, 0, 0, 0};
             uint32_t o[8];
 #pragma unroll
             for (int d = 0; d < 4; d++) {
-                const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[d], false);
-                const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[d], true);
-                o[2 * d] = pack_f16_rne(lo.x, lo.y);            // exact: every e4m3 value is an fp16 value
-                o[2 * d + 1] = pack_f16_rne(hi.x, hi.y);
+                o[2 * d] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[d], 1.0f, false));
+                o[2 * d + 1] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[d], 1.0f, true));
             }
-            *reinterpret_cast<lds_u32x4*>(tile + mla_swz(row, 2 * cc)) = u32x4{o[0], o[1], o[2], o[3]};
-            *reinterpret_cast<lds_u32x4*>(tile + mla_swz(row, 2 * cc + 1)) = u32x4{o[4], o[5], o[6], o[7]};
+            // chunks 2cc and 2cc + 1 of a row swap places under the XOR swizzle: the tile base and the row
+            // pitch are multiples of 32 bytes, so that is bit 4 of the offset
+            *reinterpret_cast<lds_u32x4*>(tile + dst[j]) = u32x4{o[0], o[1], o[2], o[3]};
+            *reinterpret_cast<lds_u32x4*>(tile + (dst[j] ^ 16u)) = u32x4{o[4], o[5], o[6], o[7]};
         }
-        if (lane < ROWS && wave * ROWS + lane >= n_valid) *reinterpret_cast<lds_f32*>(scale_slot + (wave * ROWS + lane) * 4) = 0.f;
+        if (ragged && lane < ROWS && wave * ROWS + lane >= n_valid) *reinterpret_cast<lds_f32*>(scale_slot + (wave * ROWS + lane) * 4) = 0.f;
     }
 };
+static_assert(MlaCfg::OFF_K % 32 == 0 && MlaCfg::TILE_BYTES % 32 == 0 && MlaCfg::ROW % 32 == 0, "convert() flips bit 4 of a tile offset");
 
 template <bool FP8>
 __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const AttnArgs a)
@@ -445,7 +459,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
 
     // exponents (base 2) of the lane's 8 scores, masked beyond the ragged end of the tile; returns
     // their maximum (-inf if none is valid)
-    auto exponents = [&](const f32x4& s0, const f32x4& s1, int kb, int n_valid, float (&t)[8], float (&fs)[8]) {
+    auto exponents = [&](auto masked, const f32x4& s0, const f32x4& s1, int kb, int n_valid, float (&t)[8], float (&fs)[8]) {
         if (FP8) {
             const auto* sc = reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(smem + C::OFF_SCALE + kb * C::T * 4);
             const int kq = mla_opaque(lane) >> 4;
@@ -454,12 +468,15 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             for (int i = 0; i < 4; i++) { fs[i] = f0[i]; fs[4 + i] = f1[i]; }
         }
         float bmax = -INFINITY;
-        const int tok = (mla_opaque(lane) >> 4) * 4;      // recomputed here: eight hoisted token indices would not fit
+        int tok = 0;
+        if constexpr (decltype(masked)::value) tok = (mla_opaque(lane) >> 4) * 4;   // recomputed here: eight hoisted token indices would not fit
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             float x = (i < 4 ? s0[i] : s1[i - 4]) * q_mul;
             if (FP8) x *= fs[i];
-            if (tok >= n_valid - ((i >> 2) * 16 + (i & 3))) x = -INFINITY;
+            if constexpr (decltype(masked)::value) {
+                if (tok >= n_valid - ((i >> 2) * 16 + (i & 3))) x = -INFINITY;
+            }
             t[i] = x;
             bmax = fmaxf(bmax, x);
         }
@@ -471,16 +488,20 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     // e >= 4 token 16 + 4kc + e - 4 -- the V^T operand is read to match.  The reference is fixed, so
     // no maximum has to be agreed on across lanes: every lane checks its own scores against the
     // limit, a ballot turns that into the workgroup's redo flag.
-    auto softmax = [&](const f32x4& s0, const f32x4& s1, int kb, int n_valid) {
+    // `masked`: the tile is the ragged last one of the run -- tokens beyond n_valid get exponent -inf,
+    // clamped 200 octaves below the reference where the weight is exactly 0.  Full tiles skip both.
+    auto softmax_tile = [&](auto masked, const f32x4& s0, const f32x4& s1, int kb, int n_valid) {
+        constexpr bool M = decltype(masked)::value;
+        auto floor_of = [&](float x) { return M ? fmaxf(x, m_ref - 200.f) : x; };
         float t[8], fs[8], p[8];
         if constexpr (FP8) {
             // One fp16 weight per token, w_t = p_t * f_t * 2^-E (11 significant bits: relative L2 error of
             // O about 2e-4); the normaliser sums the plain p_t in fp32.  Range is checked once per run.
-            exponents(s0, s1, kb, n_valid, t, fs);
+            exponents(masked, s0, s1, kb, n_valid, t, fs);
             float lsum = 0.f, wm = w_max;
 #pragma unroll
             for (int i = 0; i < 8; i++) {
-                const float pi = exp2_rel(fmaxf(t[i], m_ref - 200.f), m_ref);
+                const float pi = exp2_rel(floor_of(t[i]), m_ref);
                 lsum += pi;
                 p[i] = pi * (fs[i] * w_scale);
                 wm = fmaxf(wm, p[i]);
@@ -495,14 +516,14 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             *reinterpret_cast<lds_u32x4*>(pw) = w;
             return;
         }
-        const float top = __builtin_ceilf(exponents(s0, s1, kb, n_valid, t, fs));
+        const float top = __builtin_ceilf(exponents(masked, s0, s1, kb, n_valid, t, fs));
         const bool over = top > m_ref + C::kLimit;
         if (over) m_floor = fmaxf(m_floor, top + C::kHeadroom);
         if (__any(over)) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 1;
         float lsum = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            p[i] = exp2_rel(fmaxf(t[i], m_ref - 200.f), m_ref);   // masked (-inf) scores land 200 octaves down: exactly 0
+            p[i] = exp2_rel(floor_of(t[i]), m_ref);
             lsum += p[i];
             if (FP8) p[i] *= fs[i];
         }
@@ -517,6 +538,10 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         lds_byte* pw = smem + C::OFF_P + pair * 2 * C::P_BYTES + (half * 16 + (l & 15)) * (C::T * 2) + (l >> 4) * 16;
         *reinterpret_cast<lds_u32x4*>(pw) = hi;
         *reinterpret_cast<lds_u32x4*>(pw + C::P_BYTES) = lo;
+    };
+    auto softmax = [&](const f32x4& s0, const f32x4& s1, int kb, int n_valid) {
+        if (n_valid == C::T) softmax_tile(std::false_type{}, s0, s1, kb, n_valid);
+        else softmax_tile(std::true_type{}, s0, s1, kb, n_valid);
     };
 
     // O^T[value columns of this wave, 32 heads of the pair] += V^T . P^T for one tile.  The weights
@@ -590,7 +615,8 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     auto stage_commit = [&](int it, int slot, int newer) {
         if constexpr (FP8) {
             mla_wait_vm<0>();
-            MlaDmaFp8::convert(valid_of(it), smem + C::OFF_STAGE + wave * MlaDmaFp8::SHARE_BYTES, ktile_of(slot), smem + C::OFF_SCALE + slot * C::T * 4, wave, lane);
+            MlaDmaFp8::convert(valid_of(it), smem + C::OFF_STAGE + wave * MlaDmaFp8::SHARE_BYTES, ktile_of(slot), smem + C::OFF_SCALE + slot * C::T * 4,
+                               smem + C::OFF_DMA, wave, lane, tid);
         } else {
             MlaDma::zero_fill(valid_of(it), ktile_of(slot), wave, lane);
             if (newer == 1) mla_wait_vm<MlaDma::INSTRS>();
@@ -629,7 +655,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             float t[8], fs[8];
             f32x4 s0, s1;
             scores(ktile_of(0), s0, s1);
-            const float top = wave_xor_max_16_32(exponents(s0, s1, 0, valid_of(0), t, fs));
+            const float top = wave_xor_max_16_32(exponents(std::true_type{}, s0, s1, 0, valid_of(0), t, fs));
             if constexpr (FP8) {
                 if (!redo) {
                     // fp16 weights: a head's reference sits 4 octaves BELOW its largest exponent of the first
