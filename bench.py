@@ -120,6 +120,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="gqa_share")
     ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--settle-seconds", type=float, default=1.0,
+                    help="untimed: repeat the step for this long before the warmup steps, so that the part's memory "
+                         "and fabric clocks have left their idle state (a fresh process otherwise measures the ramp)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-call", action="store_true",
                     help="time the step as helix_shard_layout + helix_attn_decode (two entry points, one more "
@@ -184,6 +187,11 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < args.settle_seconds:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -199,3 +199,19 @@ def test_mla_fp8_head_far_below_the_shared_weight_scale(hx, oracle):
     o, lse = run_mla(hx, oracle, w, inp, 1)
     assert torch.isfinite(o).all() and torch.isfinite(lse).all()
     run_mla(hx, oracle, w, inp, 2)
+
+
+def test_mla_fp8_query_magnitudes_far_apart(hx, oracle):
+    """The e4m3 path rounds the workgroup's query rows to fp16 after ONE power-of-two scaling for all 128
+    heads.  A zero head, a head 2^-40 of the others and a head with one entry 2^20 above everything must still
+    come out right: the tiny heads' scores vanish either way (O = the plain mean of the values), the big
+    entry sets the scale and the ordinary entries, now 2^-6 in fp16 units, keep their significant bits."""
+    w, inp = _mla_fp8_padded(81, [257, 64], 257)
+    inp.q[0, 3] = 0
+    inp.q[0, 9] = (inp.q[0, 9].float() * 2.0 ** -40).to(torch.bfloat16)
+    inp.q[1, 17, 0] = 2.0 ** 20                  # sets the scale of sequence 1's workgroup ...
+    inp.k[1, 0, :, 0] = 0                        # ... without touching any logit: that latent column is zero
+    o, lse = run_mla(hx, oracle, w, inp, 2)
+    mean_v = (inp.k[0, 0, :257, :512].view(torch.float8_e4m3fn).float() * inp.kv_scale[0, 0, :257, None]).mean(dim=0)
+    # 257 equal weights, each rounded to fp16 (2^-12 relative): about 1e-5 rms per output, 3.5 sigma over 512 columns
+    assert (o[0, 3] - mean_v).abs().max().item() <= 1e-4
