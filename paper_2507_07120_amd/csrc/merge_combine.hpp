@@ -44,8 +44,8 @@ __device__ __forceinline__ float lse_of(float M, float L)
 // Folds the split records of one (shard, b, h) row: M = max_j m_j, L = sum_j l_j 2^(m_j - M),
 // O = sum_j O_j 2^(m_j - M) / L.  Records carry an integer reference exponent m (a float holding an
 // integer, or -inf for "no tokens"), so every rescale is an exact power of two and the running
-// maximum below changes no bit of the result.  One pass: all three loads of a record are issued
-// together (an empty record's O was never written and is discarded after the load).
+// maximum below changes no bit of the result.  One pass; the O row of an empty record (ragged
+// sequences leave many) is not fetched.
 // Returns the normalised O (valid in threads tid < TPR, 4 columns each); M and L in all threads.
 template <int DV>
 __device__ __forceinline__ f32x4 merge_row(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
@@ -61,8 +61,8 @@ __device__ __forceinline__ f32x4 merge_row(const float* __restrict__ ws_o, const
         const size_t rec = (size_t)(sb + j) * bq + rem;
         const float mj = ws_m[rec];
         const float lj = ws_l[rec];
+        if (mj == -INFINITY) continue;         // an empty record's O was never written: not fetched either
         const f32x4 oj = *reinterpret_cast<const f32x4*>(ws_o + rec * DV + c4);
-        if (mj == -INFINITY) continue;
         if (mj > Mt) {
             const float f = __builtin_amdgcn_exp2f(Mt - mj);   // 0 from -inf
             acc *= f;
