@@ -22,7 +22,9 @@
 //       exponent field (codes 1..254).
 // A block is only 4.3 KB per wave, so three waves per SIMD are kept resident (at most 168 registers,
 // two raw blocks of 26 registers each); loads are never issued under a condition of their own (the
-// index is clamped instead), which keeps the compiler's wait counts exact.
+// index is clamped instead), which keeps the compiler's wait counts exact.  The kernel is bound by
+// vector-ALU issue, not by HBM, so full blocks are fetched with buffer loads whose addresses cost no
+// vector instruction (Mx4Streams).
 #pragma once
 #include "gqa_decode.hpp"
 
@@ -73,6 +75,50 @@ __device__ __forceinline__ void mx4_load_block(Mx4Raw& raw, const char* kblk, co
             raw.vs[a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(vsc + (uint32_t)(a * 16 + kc * 4) * (v_row_bytes / 16u)));
     }
 }
+
+// Full blocks are fetched with buffer loads: address = 64-bit base of the split (a descriptor in scalar
+// registers) + a scalar offset (block, token row inside the block) + one loop-invariant 32-bit lane
+// offset per stream -- no vector address arithmetic in the block loop.  The descriptors carry no usable
+// range (the host has checked the shapes); offsets stay below 2^32 because a split is at most 2^25 tokens.
+struct Mx4Streams {
+    __amdgpu_buffer_rsrc_t k, v, ks, vs;
+    uint32_t lane_k, lane_ks, lane_v, lane_vs;
+    uint32_t k_row_bytes, v_row_bytes;
+
+    __device__ __forceinline__ void init(const char* kbase, const char* vbase, const char* ksbase, const char* vsbase,
+                                         uint32_t krb, uint32_t vrb, int r, int kc)
+    {
+        constexpr int kRaw32 = 0x00020000;                // dword 3 of a raw buffer descriptor: 32-bit data format
+        k = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(kbase), 0, -1, kRaw32);
+        v = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vbase), 0, -1, kRaw32);
+        ks = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(ksbase), 0, -1, kRaw32);
+        vs = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(vsbase), 0, -1, kRaw32);
+        k_row_bytes = krb;
+        v_row_bytes = vrb;
+        lane_k = (uint32_t)r * krb + (uint32_t)kc * 16u;
+        lane_ks = (uint32_t)r * (krb / 16u);
+        lane_v = (uint32_t)kc * 4u * vrb + (uint32_t)r * 4u;
+        lane_vs = (uint32_t)kc * 4u * (vrb / 16u);
+    }
+
+    // the full block of 32 tokens that starts `tok` rows into the split (uniform)
+    __device__ __forceinline__ void load(Mx4Raw& raw, uint32_t tok) const
+    {
+        constexpr int NT = 2;                             // non-temporal: every byte is used once
+        const uint32_t sk = tok * k_row_bytes, sv = tok * v_row_bytes, sks = tok * (k_row_bytes / 16u), svs = tok * (v_row_bytes / 16u);
+#pragma unroll
+        for (int a = 0; a < 2; a++) {
+            raw.k[a] = __builtin_amdgcn_raw_buffer_load_b128(k, lane_k, sk + a * 16 * k_row_bytes, NT);
+            raw.ks[a] = __builtin_amdgcn_raw_buffer_load_b32(ks, lane_ks, sks + a * (k_row_bytes), NT);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+            raw.v[j] = __builtin_amdgcn_raw_buffer_load_b32(v, lane_v, sv + ((j >> 2) * 16 + (j & 3)) * v_row_bytes, NT);
+        // rows of a value block that are contiguous in memory have contiguous scale rows
+#pragma unroll
+        for (int a = 0; a < 2; a++) raw.vs[a] = __builtin_amdgcn_raw_buffer_load_b128(vs, lane_vs, svs + a * v_row_bytes, NT);
+    }
+};
 
 // 2^(code - 127) of byte `which` of a dword of E8M0 scales, for codes 1..254: the code is the
 // exponent field of the float.  Rotating right by 8*which + 9 moves the byte to bits 23..30.
@@ -181,11 +227,9 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
     const int nw = n_full > wave ? (n_full - wave + 3) / 4 : 0;       // this wave's full blocks: wave, wave+4, ...
 
     // block i of this wave; the index is clamped, so a prefetch past the end re-reads the last block
-    auto load = [&](Mx4Raw& raw, int i) {
-        const size_t blk = (size_t)(wave + 4 * min(i, nw - 1)) * C::TB;
-        mx4_load_block<false>(raw, kbase + blk * k_row_bytes, vbase + blk * v_row_bytes, ksbase + blk * (k_row_bytes / 16u),
-                              vsbase + blk * (v_row_bytes / 16u), k_row_bytes, v_row_bytes, r, kc, C::TB);
-    };
+    Mx4Streams in;
+    in.init(kbase, vbase, ksbase, vsbase, k_row_bytes, v_row_bytes, r, kc);
+    auto load = [&](Mx4Raw& raw, int i) { in.load(raw, (uint32_t)(wave + 4 * min(i, nw - 1)) * C::TB); };
     Mx4Raw r0, r1;
     if (nw > 0) load(r0, 0);
 

@@ -103,6 +103,7 @@ int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_
         split = ceil_div(ceil_div(rows * total, target), plan->granule) * plan->granule;
         split = std::max<int64_t>(split, floor_tokens);
     }
+    if (path == Path::GqaMx128) split = std::min<int64_t>(split, (int64_t)1 << 25);   // 32-bit byte offsets inside a split
     plan->split_tokens = (int32_t)split;
     plan->total_splits = 0;
     for (int i = 0; i < n; i++) plan->total_splits += std::max<int64_t>(1, ceil_div(max_lens[i], split));
