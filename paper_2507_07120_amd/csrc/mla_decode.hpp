@@ -625,7 +625,8 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     };
 
     // The outer loop runs once unless the reference exponent turned out too low.
-    bool redo = false;                                // e4m3: second pass, references already adjusted
+    bool redo = false;                                // e4m3: not the first pass, references already adjusted
+    int repeats_left = 11;                            // e4m3: see the end-of-run check
     for (;;) {
         l_run = 0.f;
         w_max = 0.f;
@@ -704,14 +705,18 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         if constexpr (FP8) {
             // The run's largest weight per head decides: at or beyond 2^15 an fp16 weight may have
             // overflowed, below 2^-6 too much of the softmax sat in fp16's denormal range.  Either way the
-            // reference moves so that this largest weight lands in [2^4, 2^5) and the run is repeated once
-            // (weights are exact powers of two apart between the passes, so the second pass always fits).
+            // reference moves so that this largest weight lands in [2^4, 2^5) and the run is repeated
+            // (weights are exact powers of two apart between the passes, so the next pass fits).
             const float wh = wave_xor_max_16_32(w_max);
-            const bool bad = !redo && (wh >= 32768.f || (wh > 0.f && wh < 0.015625f));
-            if (bad) m_ref += (float)(__builtin_amdgcn_frexp_expf(wh) - 5);
+            // !(wh < 2^15) also catches a weight that overflowed fp32: that takes an exponent at least 128
+            // octaves above the reference, so moving the reference by 120 cannot overshoot; further
+            // passes follow until the weight is finite and the exact move is known.
+            const bool bad = repeats_left > 0 && (!(wh < 32768.f) || (wh > 0.f && wh < 0.015625f));
+            if (bad) m_ref += wh < INFINITY ? (float)(__builtin_amdgcn_frexp_expf(wh) - 5) : 120.f;
             if (__any(bad)) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 1;
             mla_barrier();
             redo = true;
+            repeats_left--;
         }
         if (__builtin_expect(*reinterpret_cast<const lds_i32*>(smem + C::OFF_FLAG) == 0, 1)) break;
         // Some score went beyond the limit: run again with references above everything seen

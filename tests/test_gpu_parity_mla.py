@@ -168,6 +168,19 @@ def test_mla_fp8_weight_beyond_fp16_range_restarts(hx, oracle):
     run_mla(hx, oracle, w, inp, 3, check_partials=True)
 
 
+def test_mla_fp8_weight_beyond_fp32_range_restarts(hx, oracle):
+    """As above with a key three times as long: its weight relative to the first tile's reference is ~2^360,
+    infinite in fp32.  The kernel still knows the exponent and repeats the run from there (a third pass
+    then settles the fp16 range exactly)."""
+    w, inp = _mla_fp8_padded(82, [400], 400)
+    codes, sc = synth.quantize_e4m3_per_token(inp.q[0, 77].float() * 6.0)
+    inp.k[0, 0, 300] = codes
+    inp.kv_scale[0, 0, 300] = sc
+    vmax = (inp.k[0, 0, :, :512].view(torch.float8_e4m3fn).float().abs().amax(dim=-1) * inp.kv_scale[0, 0]).max().item()
+    o, lse = run_mla(hx, oracle, w, inp, 1, max_abs=max(O_MAX_ABS, 2.0 ** -11 * vmax))
+    assert torch.isfinite(o).all() and torch.isfinite(lse).all()
+
+
 def test_mla_fp8_token_scales_spread_over_octaves(hx, oracle):
     """Per-token scales between 1/8 and 8 times their natural size (the scores move with them, the softmax
     becomes peaked on rows with values up to ~36).  The e4m3 path rounds each weight to fp16 (half an ulp =
