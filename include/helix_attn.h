@@ -34,6 +34,13 @@
  *     scale (the MLA path).  q is always bf16.
  *   - Alignment: q, k, v rows must start on 16-byte boundaries: base pointers 16-byte aligned and
  *     all strides multiples of 16 bytes.
+ *   - Arithmetic: scores are exact products of the stored values accumulated in fp32; softmax weights
+ *     are computed in fp32 relative to an integer power-of-two reference, so results do not depend on
+ *     how a sequence is cut into shards beyond fp32 summation order (1e-5 on O(1) outputs).  The bf16
+ *     and MXFP4 paths hand each weight to the matrix cores as a bf16 hi + lo pair (relative error
+ *     2^-17); the e4m3 MLA path contracts in fp16 with ONE fp16 weight per token (relative error up to
+ *     2^-12 that the normaliser does not share: |error of O| <= 2^-12 * max |v| for a peaked softmax,
+ *     about 2e-4 relative L2 otherwise).  LSE always comes from the unrounded fp32 sums.
  */
 #ifndef HELIX_ATTN_H
 #define HELIX_ATTN_H
