@@ -70,3 +70,28 @@ def test_mla_padded_row_pitch(hx, fp8):
         sc[:, :, :500] = inp.kv_scale
     o, lse = decode(hx, w, inp.q, kp[:, :, :, :576], None, lens, 2, kv_scale=sc)
     assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+
+
+def test_calls_on_a_side_stream(hx):
+    """Every entry point enqueues on the stream it is given: work issued on a side stream (default priority)
+    while the default stream is busy with something else gives the same bits as on the default stream."""
+    w = synth.Workload("side_stream", B=2, Q=16, K=1, dk=128, dv=128, n_shards=2, scale=1 / math.sqrt(128), seed=920, seq_len=2000)
+    inp = synth.make_inputs(w, "cuda")
+    lens = torch.tensor([2000, 1234], dtype=torch.int32, device="cuda")
+    o_ref, lse_ref = decode(hx, w, inp.q, inp.k, inp.v, lens, 2)
+    from paper_2507_07120_amd import harness
+    prob = harness.problem_for(w)
+    cache = hx.KVShard.from_padded(inp.k, inp.v, lens, 2000)
+    ws = harness.workspace_for(prob, 2, 2000, "cuda")
+    o = torch.full((2, 16, 128), float("nan"), device="cuda")
+    lse = torch.full((2, 16), float("nan"), device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    busy = torch.empty(1 << 26, device="cuda")
+    for _ in range(4):
+        busy.normal_()                                 # keeps the default stream occupied
+    with torch.cuda.stream(side):
+        hx.helix_attn_decode_kvp(prob, inp.q, cache, 2, o, ws, lse_out=lse, stream=side)
+    side.synchronize()
+    assert torch.equal(o, o_ref) and torch.equal(lse, lse_ref)
+    torch.cuda.synchronize()
