@@ -130,6 +130,9 @@ def main():
     ap.add_argument("--hopb", type=int, default=0, metavar="G",
                     help="also time the batch cut into G request groups whose exchange + combine run on a second "
                          "stream under the next group's attention (Sec. 2.1.3), against the same call on one stream")
+    ap.add_argument("--graph", type=int, default=0, metavar="G",
+                    help="also capture G consecutive steps into one HIP graph and time its replays (launch-bound "
+                         "configurations: the library only enqueues kernels, so a step is capturable as it is)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) before the timed loop, so that a "
                          "rocprofv3 --pmc run holds a kernel of known traffic to scale the counters by")
@@ -252,6 +255,21 @@ def main():
                    "entry": "helix_shard_layout + helix_attn_decode" if args.two_call else "helix_attn_decode_kvp"},
         "roofline": roof,
     }
+    if args.graph > 0:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(args.graph):
+                step()
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // args.graph)
+        tg = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        out["graph"] = {"steps_per_graph": args.graph, "replays": reps,
+                        "us_per_step": (time.perf_counter() - tg) / (reps * args.graph) * 1e6}
     if args.hopb > 0:
         mx = None if inp.k_mx is None else (inp.k_mx, inp.v_mx)
         nbytes = hx.helix_attn_hopb_workspace_bytes(prob, N, max(ss.max_lens), args.hopb)

@@ -263,10 +263,17 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             case Path::Mla: {
                 const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
                 auto kern = fp8 ? mla_decode_kernel<true> : mla_decode_kernel<false>;
-                // more than the default 64 KB of LDS per workgroup has to be asked for
-                if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        MlaCfg::LDS_BYTES) != hipSuccess)
-                    return HELIX_ERR_LAUNCH;
+                // more than the default 64 KB of LDS per workgroup has to be asked for: once per device and
+                // kernel, so that later calls consist of launches only (and can be captured into a HIP graph)
+                static bool asked[2][64];
+                int dev = 0;
+                if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return HELIX_ERR_LAUNCH;
+                if (!asked[fp8][dev]) {
+                    if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            MlaCfg::LDS_BYTES) != hipSuccess)
+                        return HELIX_ERR_LAUNCH;
+                    asked[fp8][dev] = true;
+                }
                 hipLaunchKernelGGL(kern, dim3((unsigned)units), dim3(MlaCfg::THREADS), MlaCfg::LDS_BYTES, stream, a);
                 break;
             }
