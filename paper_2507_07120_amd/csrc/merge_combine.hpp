@@ -57,21 +57,42 @@ __device__ __forceinline__ f32x4 merge_row(const float* __restrict__ ws_o, const
     const int sl = tid / S::TPR, c4 = (tid % S::TPR) * 4;
     float Mt = -INFINITY, Lt = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int j = sl; j < nsp; j += S::SL) {
-        const size_t rec = (size_t)(sb + j) * bq + rem;
-        const float mj = ws_m[rec];
-        const float lj = ws_l[rec];
-        if (mj == -INFINITY) continue;         // an empty record's O was never written: not fetched either
-        const f32x4 oj = *reinterpret_cast<const f32x4*>(ws_o + rec * DV + c4);
-        if (mj > Mt) {
-            const float f = __builtin_amdgcn_exp2f(Mt - mj);   // 0 from -inf
-            acc *= f;
-            Lt *= f;
-            Mt = mj;
+    // Four records in flight per thread: first their (m, l), then the O rows of those that are not empty.
+    // One record at a time would make the loop a chain of dependent HBM round trips.
+    constexpr int U = 4;
+    for (int j0 = sl; j0 < nsp; j0 += S::SL * U) {
+        float mj[U], lj[U];
+        f32x4 oj[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int j = j0 + u * S::SL;
+            mj[u] = -INFINITY;
+            lj[u] = 0.f;
+            if (j < nsp) {
+                const size_t rec = (size_t)(sb + j) * bq + rem;
+                mj[u] = ws_m[rec];
+                lj[u] = ws_l[rec];
+            }
         }
-        const float g = __builtin_amdgcn_exp2f(mj - Mt);
-        acc += oj * g;
-        Lt += lj * g;
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            oj[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (mj[u] != -INFINITY)                // an empty record's O was never written: not fetched either
+                oj[u] = *reinterpret_cast<const f32x4*>(ws_o + ((size_t)(sb + j0 + u * S::SL) * bq + rem) * DV + c4);
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            if (mj[u] == -INFINITY) continue;
+            if (mj[u] > Mt) {
+                const float f = __builtin_amdgcn_exp2f(Mt - mj[u]);   // 0 from -inf
+                acc *= f;
+                Lt *= f;
+                Mt = mj[u];
+            }
+            const float g = __builtin_amdgcn_exp2f(mj[u] - Mt);
+            acc += oj[u] * g;
+            Lt += lj[u] * g;
+        }
     }
     __syncthreads();                       // previous users of sm are done
     *reinterpret_cast<f32x4*>(&sm.o[sl][c4]) = acc;
