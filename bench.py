@@ -29,7 +29,9 @@ def kv_bytes_per_step(w, lens) -> int:
     latent row serves as key and value and counts once; fp8 rows carry one fp32 scale, MXFP4 rows
     half a byte per element plus one scale byte per 32 elements."""
     tokens = int(sum(int(x) for x in lens))
-    if w.mla:
+    if w.mla and getattr(w, "fp4", False):
+        per_token = w.dk // 2 + w.dk // 32
+    elif w.mla:
         per_token = w.dk * (1 if w.fp8 else 2) + (4 if w.fp8 else 0)
     elif getattr(w, "fp4", False):
         per_token = (w.dk + w.dv) // 2 + (w.dk + w.dv) // 32
@@ -92,7 +94,7 @@ def cpu_baseline(w, inp, budget_macs=1.5e11):
         if inp.kv_scale is not None:
             kw["kv_scale"] = inp.kv_scale[:nb].cpu().numpy()
         if inp.k_mx is not None:
-            kw["mx"] = (inp.k_mx[:nb].cpu().numpy(), inp.v_mx[:nb].cpu().numpy())
+            kw["mx"] = (inp.k_mx[:nb].cpu().numpy(), None if inp.v_mx is None else inp.v_mx[:nb].cpu().numpy())
     t0 = time.perf_counter()
     oracle.attention(q, k, v, lens[:nb], w.scale, **kw)
     dt = time.perf_counter() - t0
@@ -247,7 +249,7 @@ def main():
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         # arithmetic type of the contractions: the e4m3 latent is widened to fp16 (same MFMA rate as bf16)
-        "dtype": "f16" if (w.mla and w.fp8) else "bf16", "data": "synthetic",
+        "dtype": "f16" if (w.mla and (w.fp8 or getattr(w, "fp4", False))) else "bf16", "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "q_heads": w.Q, "kv_heads": w.K, "dk": w.dk, "dv": w.dv,
                    "n_shards": N, "tokens_per_step": int(sum(inp.lens.tolist())) * w.K,
                    "kv_dtype": "e4m3+fp32 scale" if w.fp8 else "mxfp4 (e2m1 + e8m0 per 32)" if getattr(w, "fp4", False) else "bf16",

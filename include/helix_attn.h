@@ -30,17 +30,20 @@
  *     is launched, so an error return means no kernel ran.
  *   - Supported shapes: (dk,dv) = (64,64) or (128,128) with bf16 K/V and any Q/K group size
  *     (the GQA path), (128,128) with MXFP4 K/V (the FP4 of the paper's evaluation, Sec. 3), and
- *     (dk,dv) = (576,512) with v_aliases_k = 1, kv_heads = 1, bf16 or e4m3 + per-token fp32
- *     scale (the MLA path).  q is always bf16.
+ *     (dk,dv) = (576,512) with v_aliases_k = 1, kv_heads = 1, bf16, e4m3 + per-token fp32
+ *     scale, or MXFP4 (the MLA path).  q is always bf16.
  *   - Alignment: q, k, v rows must start on 16-byte boundaries: base pointers 16-byte aligned and
  *     all strides multiples of 16 bytes.
  *   - Arithmetic: scores are exact products of the stored values accumulated in fp32; softmax weights
  *     are computed in fp32 relative to an integer power-of-two reference, so results do not depend on
  *     how a sequence is cut into shards beyond fp32 summation order (1e-5 on O(1) outputs).  The bf16
  *     and MXFP4 paths hand each weight to the matrix cores as a bf16 hi + lo pair (relative error
- *     2^-17); the e4m3 MLA path contracts in fp16 with ONE fp16 weight per token (relative error up to
- *     2^-12 that the normaliser does not share: |error of O| <= 2^-12 * max |v| for a peaked softmax,
- *     about 2e-4 relative L2 otherwise).  LSE always comes from the unrounded fp32 sums.
+ *     2^-17); the e4m3 and MXFP4 MLA paths contract in fp16 with ONE fp16 weight per token (relative
+ *     error up to 2^-12 that the normaliser does not share: |error of O| <= 2^-12 * max |v| for a peaked
+ *     softmax, about 2e-4 relative L2 otherwise).  An MXFP4 latent row is held as fp16 entries times a
+ *     power of two taken from its largest block scale: exact for blocks within 21 octaves of that scale,
+ *     smaller ones are off by at most 2^-24 of the row's largest magnitude; the largest scale code of a
+ *     row must be at least 10.  LSE always comes from the unrounded fp32 sums.
  */
 #ifndef HELIX_ATTN_H
 #define HELIX_ATTN_H
@@ -94,7 +97,8 @@ typedef struct helix_problem {
  * MXFP4: strides still count ELEMENTS (two per byte); the code of element index e sits in byte e/2
  * of k (v), its block scale in byte e/32 of k_scale_mx (v_scale_mx).  Token rows must be dense
  * (k_stride_t == dk, v_stride_t == dv), the other strides multiples of 128, the scale arrays
- * 4-byte aligned. */
+ * 4-byte aligned.  An MXFP4 MLA latent (v_aliases_k) has v == NULL and v_scale_mx == NULL: the value is
+ * the first dv entries of the key row, block scales included. */
 typedef struct helix_kv_shard {
     const void *k;          /* bf16 or e4m3 */
     const void *v;          /* same dtype; must be NULL iff v_aliases_k */
@@ -197,7 +201,8 @@ int helix_kv_append(const helix_problem *problem, const helix_kv_shard *shards, 
 
 /* The same for an MXFP4 cache (helix_kv_append returns HELIX_ERR_UNSUPPORTED for it):
  *   k_codes, v_codes    device uint8 [B,K,dk/2], [B,K,dv/2]: the new rows' E2M1 codes
- *   k_scales, v_scales  device uint8 [B,K,dk/32], [B,K,dv/32]: their E8M0 block scales */
+ *   k_scales, v_scales  device uint8 [B,K,dk/32], [B,K,dv/32]: their E8M0 block scales
+ * v_codes and v_scales must be NULL iff v_aliases_k. */
 int helix_kv_append_mxfp4(const helix_problem *problem, const helix_kv_shard *shards, int32_t n_shards,
                           int64_t decode_index, const void *k_codes, const void *v_codes,
                           const uint8_t *k_scales, const uint8_t *v_scales,

@@ -159,16 +159,21 @@ class KVShard:
         return KVShard(k, v, lens, int(max_len), (k.stride(0), k.stride(1), k.stride(2)), vs, kv_scale, ss, tok_off)
 
     @staticmethod
-    def from_mxfp4(k: torch.Tensor, v: torch.Tensor, k_mx: torch.Tensor, v_mx: torch.Tensor, lens: torch.Tensor,
+    def from_mxfp4(k: torch.Tensor, v: Optional[torch.Tensor], k_mx: torch.Tensor, v_mx: Optional[torch.Tensor], lens: torch.Tensor,
                    max_len: int, tok_off: Optional[torch.Tensor] = None) -> "KVShard":
         """k [B,K,S,dk/2], v [B,K,S,dv/2] uint8 codes, k_mx [B,K,S,dk/32], v_mx [B,K,S,dv/32] uint8 scales,
-        all contiguous in their last two axes; strides are handed over in elements."""
+        all contiguous in their last two axes; strides are handed over in elements.  v and v_mx are None
+        for an MLA latent (the value is the first dv entries of the key row)."""
+        assert (v is None) == (v_mx is None)
         for t, m in ((k, k_mx), (v, v_mx)):
+            if t is None:
+                continue
             assert t.dtype == torch.uint8 and m.dtype == torch.uint8 and t.dim() == 4 and m.dim() == 4
             assert t.stride(3) == 1 and m.is_contiguous() and t.is_contiguous()
             assert m.shape[:3] == t.shape[:3] and m.shape[3] * 16 == t.shape[3]
+        v_strides = (0, 0, 0) if v is None else tuple(2 * x for x in (v.stride(0), v.stride(1), v.stride(2)))
         return KVShard(k, v, lens, int(max_len), tuple(2 * x for x in (k.stride(0), k.stride(1), k.stride(2))),
-                       tuple(2 * x for x in (v.stride(0), v.stride(1), v.stride(2))), None, (0, 0), tok_off, k_mx, v_mx)
+                       v_strides, None, (0, 0), tok_off, k_mx, v_mx)
 
     @staticmethod
     def from_packed(k: torch.Tensor, lens: torch.Tensor, max_len: int, tok_off: torch.Tensor,
@@ -325,22 +330,25 @@ def helix_kv_append(problem: Problem, shards: Sequence[KVShard], decode_index: i
 
 
 def helix_kv_append_mxfp4(problem: Problem, shards: Sequence[KVShard], decode_index: int, k_codes: torch.Tensor,
-                          v_codes: torch.Tensor, k_scales: torch.Tensor, v_scales: torch.Tensor, capacity: int,
+                          v_codes: Optional[torch.Tensor], k_scales: torch.Tensor, v_scales: Optional[torch.Tensor], capacity: int,
                           overflow: Optional[torch.Tensor] = None, stream=None) -> None:
-    """helix_kv_append for an MXFP4 cache: code rows [B,K,d/2] and their block scales [B,K,d/32] (uint8)."""
+    """helix_kv_append for an MXFP4 cache: code rows [B,K,d/2] and their block scales [B,K,d/32] (uint8);
+    v_codes and v_scales are None for an MLA latent."""
     n = len(shards)
     B, K = problem.batch, problem.kv_heads
     for t, shape in ((k_codes, (B, K, problem.dk // 2)), (v_codes, (B, K, problem.dv // 2)),
                      (k_scales, (B, K, problem.dk // 32)), (v_scales, (B, K, problem.dv // 32))):
-        assert t.dtype == torch.uint8 and t.is_contiguous() and tuple(t.shape) == shape
+        assert t is None or (t.dtype == torch.uint8 and t.is_contiguous() and tuple(t.shape) == shape)
     if overflow is not None:
         assert overflow.dtype == torch.int32 and overflow.numel() == 1
     p = problem.c()
     arr = (_CShard * n)(*[s.c() for s in shards])
-    _check(load_library().helix_kv_append_mxfp4(ctypes.byref(p), arr, n, int(decode_index), k_codes.data_ptr(),
-                                                v_codes.data_ptr(), k_scales.data_ptr(), v_scales.data_ptr(),
-                                                int(capacity), None if overflow is None else overflow.data_ptr(),
-                                                _stream_ptr(stream)),
+
+    def ptr(t):
+        return None if t is None else t.data_ptr()
+    _check(load_library().helix_kv_append_mxfp4(ctypes.byref(p), arr, n, int(decode_index), ptr(k_codes),
+                                                ptr(v_codes), ptr(k_scales), ptr(v_scales),
+                                                int(capacity), ptr(overflow), _stream_ptr(stream)),
            "helix_kv_append_mxfp4")
 
 

@@ -64,7 +64,7 @@ int check_problem(const helix_problem* p, Path* path)
         *path = Path::GqaMx128;
         return HELIX_OK;
     }
-    if (p->v_aliases_k && p->kv_dtype != HELIX_KV_MXFP4 && p->dk == 576 && p->dv == 512 && p->kv_heads == 1) {
+    if (p->v_aliases_k && p->dk == 576 && p->dv == 512 && p->kv_heads == 1) {
         *path = Path::Mla;
         return HELIX_OK;
     }
@@ -146,12 +146,15 @@ int check_shard(const helix_problem* p, const helix_kv_shard* s)
     if (s->max_len < 0) return HELIX_ERR_SHAPE;
     if (p->kv_dtype == HELIX_KV_MXFP4) {
         // strides count elements; a row is dk/2 code bytes and dk/32 scale bytes, token rows dense
-        if (!s->k_scale_mx || !s->v_scale_mx) return HELIX_ERR_NULL;
-        if (s->k_stride_b < 0 || s->k_stride_h < 0 || s->v_stride_b < 0 || s->v_stride_h < 0) return HELIX_ERR_SHAPE;
-        if (s->k_stride_b % 128 || s->k_stride_h % 128 || s->v_stride_b % 128 || s->v_stride_h % 128) return HELIX_ERR_SHAPE;
-        if (reinterpret_cast<uintptr_t>(s->k) % 16 || reinterpret_cast<uintptr_t>(s->v) % 16) return HELIX_ERR_SHAPE;
-        if (reinterpret_cast<uintptr_t>(s->k_scale_mx) % 4 || reinterpret_cast<uintptr_t>(s->v_scale_mx) % 4) return HELIX_ERR_SHAPE;
-        if (s->k_stride_t != p->dk || s->v_stride_t != p->dv) return HELIX_ERR_UNSUPPORTED;
+        if (!s->k_scale_mx) return HELIX_ERR_NULL;
+        if (s->k_stride_b < 0 || s->k_stride_h < 0 || s->k_stride_b % 128 || s->k_stride_h % 128) return HELIX_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(s->k) % 16 || reinterpret_cast<uintptr_t>(s->k_scale_mx) % 4) return HELIX_ERR_SHAPE;
+        if (s->k_stride_t != p->dk) return HELIX_ERR_UNSUPPORTED;
+        if (p->v_aliases_k) return s->v_scale_mx ? HELIX_ERR_SHAPE : HELIX_OK;      // the latent's scales serve key and value
+        if (!s->v_scale_mx) return HELIX_ERR_NULL;
+        if (s->v_stride_b < 0 || s->v_stride_h < 0 || s->v_stride_b % 128 || s->v_stride_h % 128) return HELIX_ERR_SHAPE;
+        if (reinterpret_cast<uintptr_t>(s->v) % 16 || reinterpret_cast<uintptr_t>(s->v_scale_mx) % 4) return HELIX_ERR_SHAPE;
+        if (s->v_stride_t != p->dv) return HELIX_ERR_UNSUPPORTED;
         return HELIX_OK;
     }
     const int64_t esz = fp8 ? 1 : 2, mult = 16 / esz;
@@ -261,18 +264,18 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
                 hipLaunchKernelGGL(gqa_mxfp4_kernel, dim3((unsigned)units), dim3(256), 0, stream, a);
                 break;
             case Path::Mla: {
-                const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
-                auto kern = fp8 ? mla_decode_kernel<true> : mla_decode_kernel<false>;
+                const int kind = p->kv_dtype == HELIX_KV_FP8_E4M3 ? 1 : p->kv_dtype == HELIX_KV_MXFP4 ? 2 : 0;
+                auto kern = kind == 2 ? mla_decode_kernel<true, true> : kind == 1 ? mla_decode_kernel<true> : mla_decode_kernel<false>;
                 // more than the default 64 KB of LDS per workgroup has to be asked for: once per device and
                 // kernel, so that later calls consist of launches only (and can be captured into a HIP graph)
-                static bool asked[2][64];
+                static bool asked[3][64];
                 int dev = 0;
                 if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return HELIX_ERR_LAUNCH;
-                if (!asked[fp8][dev]) {
+                if (!asked[kind][dev]) {
                     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                             MlaCfg::LDS_BYTES) != hipSuccess)
                         return HELIX_ERR_LAUNCH;
-                    asked[fp8][dev] = true;
+                    asked[kind][dev] = true;
                 }
                 hipLaunchKernelGGL(kern, dim3((unsigned)units), dim3(MlaCfg::THREADS), MlaCfg::LDS_BYTES, stream, a);
                 break;
@@ -608,7 +611,8 @@ int helix_kv_append_mxfp4(const helix_problem* problem, const helix_kv_shard* sh
     Path path;
     if (int rc = check_problem(problem, &path)) return rc;
     if (problem->kv_dtype != HELIX_KV_MXFP4) return HELIX_ERR_UNSUPPORTED;
-    if (!shards || !k_codes || !v_codes || !k_scales || !v_scales) return HELIX_ERR_NULL;
+    if (!shards || !k_codes || !k_scales) return HELIX_ERR_NULL;
+    if (problem->v_aliases_k ? (v_codes || v_scales) : (!v_codes || !v_scales)) return problem->v_aliases_k ? HELIX_ERR_SHAPE : HELIX_ERR_NULL;
     if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS || decode_index < 0 || capacity < 0) return HELIX_ERR_SHAPE;
     return append_common(problem, shards, n_shards, decode_index, k_codes, v_codes, nullptr, k_scales, v_scales, capacity, overflow, hip_stream);
 }

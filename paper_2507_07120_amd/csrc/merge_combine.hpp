@@ -301,7 +301,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const AppendArgs a)
             const int kh = i / kr, x = i % kr;
             kmx[((int64_t)b * a.sh.k_sb + (int64_t)kh * a.sh.k_sh + tok * a.sh.k_st) / 32 + x] = a.k_mx_new[((int64_t)b * a.K + kh) * kr + x];
         }
-        for (int i = tid; i < a.K * vr; i += 256) {
+        for (int i = tid; a.v_mx_new && i < a.K * vr; i += 256) {
             const int kh = i / vr, x = i % vr;
             vmx[((int64_t)b * a.sh.v_sb + (int64_t)kh * a.sh.v_sh + tok * a.sh.v_st) / 32 + x] = a.v_mx_new[((int64_t)b * a.K + kh) * vr + x];
         }

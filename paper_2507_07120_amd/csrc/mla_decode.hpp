@@ -323,9 +323,132 @@ struct MlaDmaFp8 {
 };
 static_assert(MlaCfg::OFF_K % 32 == 0 && MlaCfg::TILE_BYTES % 32 == 0 && MlaCfg::ROW % 32 == 0, "convert() flips bit 4 of a tile offset");
 
-template <bool FP8>
+// MXFP4 latent tiles (E2M1 codes, blocks of 32 along the row sharing an E8M0 scale; rows dense: 288 code
+// bytes and 18 scale bytes per token): wave w DMAs the codes of rows 4w..4w+3 (1152 contiguous bytes =
+// 1.125 wave instructions) and their 72 scale bytes (18 or 19 dwords from the 4-byte boundary below
+// them: a token row's scales start on an even address, not always on a multiple of 4) into its own
+// staging area.  Conversion turns the tile into exactly what the e4m3 path produces -- fp16 entries
+// plus one fp32 scale per token -- so everything downstream is shared: the token scale is
+// f_t = 2^(top_t - 127 - UP) with top_t the largest scale code of the row, and the entries of block j
+// become code * 2^(X_j - top_t + UP) in fp16 (v_cvt_scalef32_pk_f16_fp4: two codes of a byte, low
+// nibble first, times a float scale).  That is exact while X_j >= top_t - 21 (normal fp16 numbers);
+// blocks further below the row's largest lose at most 2^-24 of the row's largest magnitude.
+struct MlaDmaFp4 {
+    static constexpr int ROWS = MlaDma::ROWS;
+    static constexpr int CODE_ROW = MlaCfg::DK / 2;                         // 288
+    static constexpr int SCALE_ROW = MlaCfg::DK / 32;                       // 18
+    static constexpr int CHUNKS = ROWS * CODE_ROW / 16;                     // 72
+    static constexpr int INSTRS = (CHUNKS + 63) / 64;                       // 2 for the codes, one more for the scales
+    static constexpr int PARTS = INSTRS + 1;
+    static constexpr int UNITS = ROWS * CODE_ROW / 8;                       // 144 eight-byte units = 16 codes = two chunks of the tile
+    static constexpr int PASSES = (UNITS + 63) / 64;                        // 3
+    static constexpr int OFF_SC = ROWS * CODE_ROW;                          // staging: the scale dwords ...
+    static constexpr int OFF_TOP = OFF_SC + 80;                             // ... and the largest scale code of each row (int)
+    static constexpr int SHARE_BYTES = 1280;
+    static constexpr int UP = 8;
+    static_assert(OFF_TOP + ROWS * 4 <= SHARE_BYTES && MlaCfg::WAVES * SHARE_BYTES <= MlaCfg::T * MlaCfg::DK, "staging area");
+    static_assert(PASSES == 3 && INSTRS == 2, "layout of the offset table");
+
+    static __device__ __forceinline__ int row_of_chunk(int q) { return (q * 3641) >> 16; }      // q / 18 for q < 72
+    static __device__ __forceinline__ int row_of_unit(int q) { return (q * 1821) >> 16; }       // q / 36 for q < 192
+
+    // `shift` = the run's first scale byte address modulo 4 (0 or 2; the same for every wave and tile,
+    // because 4 rows are 72 bytes)
+    static __device__ __forceinline__ void init(lds_byte* table, int wave, int lane, int tid, int shift)
+    {
+        // [0], [1]: the lane's chunk of the wave's 1152 code bytes; [3]: where the set-up step of convert()
+        // finds scale (lane & 15) of row (lane >> 4) in the staging area
+        *reinterpret_cast<lds_u32x4*>(table + tid * 32) =
+            u32x4{(uint32_t)lane * 16u, 1024u + (uint32_t)lane * 16u, 0u, (uint32_t)(OFF_SC + shift + (lane >> 4) * SCALE_ROW + (lane & 15))};
+        // [4..6]: unit q = 64 pass + lane of convert(): tile offset of its first chunk | staging offset of its
+        // block's scale (from OFF_SC) << 20 | row << 28
+        uint32_t t[PASSES];
+#pragma unroll
+        for (int j = 0; j < PASSES; j++) {
+            const int q = min(j * 64 + lane, UNITS - 1), row = row_of_unit(q), uu = q - row * (CODE_ROW / 8);
+            t[j] = (uint32_t)mla_swz(wave * ROWS + row, 2 * uu) | (uint32_t)(shift + row * SCALE_ROW + (uu >> 1)) << 20 | (uint32_t)row << 28;
+        }
+        static_assert(MlaCfg::TILE_BYTES <= (1 << 20) && 3 + ROWS * SCALE_ROW <= 256, "packing of the table entries");
+        *reinterpret_cast<lds_u32x4*>(table + tid * 32 + 16) = u32x4{t[0], t[1], t[2], 0};
+    }
+
+    // part j < INSTRS: codes; part INSTRS: scales.  `codes` = the wave's rows of the tile in global memory,
+    // `scales` = the 4-byte boundary at or below their scale bytes; `stage` = LDS byte address of the wave's
+    // staging area.  Only dwords that hold a byte of a row the tile has are requested.
+    static __device__ __forceinline__ void issue_part(int j, const MlaDma::Offsets& f, const char* codes, const char* scales, int n_valid,
+                                                      uint32_t stage, int wave, int lane, int shift)
+    {
+        if (j < INSTRS) {
+            bool live = j * 64 + 63 < CHUNKS || lane < CHUNKS - j * 64;
+            if (n_valid != MlaCfg::T) {
+                int l = lane;
+                asm volatile("" : "+v"(l));
+                live = live && wave * ROWS + row_of_chunk(j * 64 + l) < n_valid;
+            }
+            if (live)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                             :: "s"(stage + j * 1024), "v"(f.a[j]), "s"(codes) : "memory");
+        } else {
+            const int rows = min(ROWS, n_valid - wave * ROWS);
+            if (rows > 0 && lane < ((shift + rows * SCALE_ROW + 3) >> 2))
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                             :: "s"(stage + OFF_SC), "v"((uint32_t)lane * 4u), "s"(scales) : "memory");
+        }
+    }
+
+    template <int BYTE>
+    static __device__ __forceinline__ uint32_t pair(uint32_t codes, float scale)
+    {
+        return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, scale, BYTE));
+    }
+
+    // After the wave's DMA has landed.  Set-up: lane (row = lane / 16, j = lane % 16) looks at scales j and
+    // 16 + j of its row; the row's largest code goes to the staging area, the token scale to the tile's
+    // scale slot (zero for rows the tile does not have, whose entries become zeros as well).  Then three
+    // passes over the 144 units.
+    static __device__ __forceinline__ void convert(int n_valid, lds_byte* stage, lds_byte* tile, lds_byte* scale_slot,
+                                                   const lds_byte* table, int wave, int lane, int tid)
+    {
+        typedef __attribute__((address_space(3))) uint32_t lds_u32;
+        lane = mla_opaque(lane);
+        const lds_byte* mine = table + mla_opaque(tid) * 32;
+        {
+            const uint32_t at = *reinterpret_cast<const lds_u32*>(mine + 12);
+            const int j = lane & 15, row = lane >> 4;
+            int x = stage[at];
+            if (j < SCALE_ROW - 16) x = max(x, (int)stage[at + 16]);
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) x = max(x, __shfl_xor(x, o));
+            if (j == 0) {
+                *reinterpret_cast<lds_i32*>(stage + OFF_TOP + row * 4) = x;
+                *reinterpret_cast<lds_f32*>(scale_slot + (wave * ROWS + row) * 4) =
+                    wave * ROWS + row < n_valid ? __builtin_ldexpf(1.f, x - (127 + UP)) : 0.f;
+            }
+        }
+        const u32x4 dst = *reinterpret_cast<const lds_u32x4*>(mine + 16);
+        const bool ragged = n_valid != MlaCfg::T;
+#pragma unroll
+        for (int j = 0; j < PASSES; j++) {
+            if (j * 64 + 63 >= UNITS && lane >= UNITS - j * 64) continue;
+            u32x2 w = *reinterpret_cast<const lds_u32x2*>(stage + lane * 8 + j * 512);
+            const uint32_t meta = dst[j];
+            const int row = (int)(meta >> 28);
+            const int e = (int)stage[OFF_SC + ((meta >> 20) & 0xffu)] - *reinterpret_cast<const lds_i32*>(stage + OFF_TOP + row * 4) + (127 + UP);
+            const float scale = as_f32((uint32_t)max(e, 0) << 23);        // 2^(X - top + UP); more than 135 octaves down: zero
+            if (ragged && wave * ROWS + row >= n_valid) w = u32x2{0, 0};
+            const uint32_t to = meta & 0xfffffu;
+            *reinterpret_cast<lds_u32x4*>(tile + to) = u32x4{pair<0>(w.x, scale), pair<1>(w.x, scale), pair<2>(w.x, scale), pair<3>(w.x, scale)};
+            *reinterpret_cast<lds_u32x4*>(tile + (to ^ 16u)) = u32x4{pair<0>(w.y, scale), pair<1>(w.y, scale), pair<2>(w.y, scale), pair<3>(w.y, scale)};
+        }
+    }
+};
+
+// FP8: the latent is not bf16 and the contractions run in fp16 -- e4m3 codes with a scale per token, or,
+// with MX, MXFP4 codes with block scales (widened to the same tile and token scales).
+template <bool FP8, bool MX = false>
 __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const AttnArgs a)
 {
+    static_assert(FP8 || !MX, "the MXFP4 latent takes the fp16 pipeline");
     using C = MlaCfg;
     extern __shared__ __align__(16) uint8_t smem_raw[];
     lds_byte* smem = (lds_byte*)smem_raw;
@@ -410,9 +533,18 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
 
     const int esz = FP8 ? 1 : 2;
     const int64_t tok0 = first_row + t0;
-    const char* kbase = reinterpret_cast<const char*>(sh.k) + (int64_t)esz * ((int64_t)b * sh.k_sb + tok0 * sh.k_st);
-    const float* sbase = FP8 ? sh.kv_scale + (int64_t)b * sh.s_sb + tok0 : nullptr;
-    const uint32_t row_bytes = (uint32_t)sh.k_st * esz;
+    const int64_t first_elem = (int64_t)b * sh.k_sb + tok0 * sh.k_st;
+    const char* kbase = reinterpret_cast<const char*>(sh.k) + (MX ? first_elem / 2 : esz * first_elem);
+    const float* sbase = FP8 && !MX ? sh.kv_scale + (int64_t)b * sh.s_sb + tok0 : nullptr;
+    const uint32_t row_bytes = MX ? (uint32_t)MlaDmaFp4::CODE_ROW : (uint32_t)sh.k_st * esz;
+    // MXFP4: the run's block scales, from the 4-byte boundary at or below them
+    const char* xbase = nullptr;
+    int xshift = 0;
+    if constexpr (MX) {
+        xbase = reinterpret_cast<const char*>(sh.k_mx) + first_elem / 32;
+        xshift = (int)(reinterpret_cast<uintptr_t>(xbase) & 3);
+        xbase -= xshift;
+    }
 
     const int n_tok = t1 - t0;
     const int n_tiles = (n_tok + C::T - 1) / C::T;
@@ -592,15 +724,20 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     // stage_issue_part() requests one part, stage_commit() completes the tile as far as this wave
     // is concerned (its own requests have landed; e4m3 rows are widened); a barrier then publishes it.
     constexpr int AHEAD = C::AHEAD;
-    constexpr int PARTS = FP8 ? MlaDmaFp8::PARTS : MlaDma::INSTRS;
+    constexpr int PARTS = MX ? MlaDmaFp4::PARTS : FP8 ? MlaDmaFp8::PARTS : MlaDma::INSTRS;
     static_assert(AHEAD == 2 && C::NBUF == 3, "ring arithmetic: tile it+2 goes where tile it-1 was");
-    if constexpr (FP8) MlaDmaFp8::init(smem + C::OFF_DMA, row_bytes, wave, lane, tid);
+    if constexpr (MX) MlaDmaFp4::init(smem + C::OFF_DMA, wave, lane, tid, xshift);
+    else if constexpr (FP8) MlaDmaFp8::init(smem + C::OFF_DMA, row_bytes, wave, lane, tid);
     else MlaDma::init(smem + C::OFF_DMA, row_bytes, wave, lane, tid);
     MlaDma::Offsets dma_off;                              // valid from stage_begin() to the last part of that phase
     auto stage_begin = [&]() { dma_off = MlaDma::fetch(smem + C::OFF_DMA, tid); };
     auto stage_issue_part = [&](int it, int slot, int j) {
         const char* src = kbase + (size_t)it * C::T * row_bytes;
-        if constexpr (FP8)
+        if constexpr (MX)
+            MlaDmaFp4::issue_part(j, dma_off, src + wave * MlaDmaFp4::ROWS * MlaDmaFp4::CODE_ROW,
+                                  xbase + ((size_t)it * C::T + wave * MlaDmaFp4::ROWS) * MlaDmaFp4::SCALE_ROW, valid_of(it),
+                                  (uint32_t)(uintptr_t)(smem + C::OFF_STAGE) + wave * MlaDmaFp4::SHARE_BYTES, wave, lane, xshift);
+        else if constexpr (FP8)
             MlaDmaFp8::issue_part(j, dma_off, src, sbase + it * C::T, valid_of(it), (uint32_t)(uintptr_t)(smem + C::OFF_STAGE) + wave * MlaDmaFp8::SHARE_BYTES,
                                   (uint32_t)(uintptr_t)(smem + C::OFF_SCALE) + slot * C::T * 4, wave, lane);
         else
@@ -613,7 +750,11 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     };
     // `newer` = whole tiles (5 instructions per wave) requested after this one, which may stay in flight
     auto stage_commit = [&](int it, int slot, int newer) {
-        if constexpr (FP8) {
+        if constexpr (MX) {
+            mla_wait_vm<0>();
+            MlaDmaFp4::convert(valid_of(it), smem + C::OFF_STAGE + wave * MlaDmaFp4::SHARE_BYTES, ktile_of(slot), smem + C::OFF_SCALE + slot * C::T * 4,
+                               smem + C::OFF_DMA, wave, lane, tid);
+        } else if constexpr (FP8) {
             mla_wait_vm<0>();
             MlaDmaFp8::convert(valid_of(it), smem + C::OFF_STAGE + wave * MlaDmaFp8::SHARE_BYTES, ktile_of(slot), smem + C::OFF_SCALE + slot * C::T * 4,
                                smem + C::OFF_DMA, wave, lane, tid);

@@ -203,6 +203,9 @@ WORKLOADS = {
     # 4x longer context, which keeps the cache near 1 GiB: KVP=8 of a 4M-token context
     "gqa_share_mxfp4": Workload("gqa_share_mxfp4", B=16, Q=16, K=1, dk=128, dv=128, n_shards=1,
                                 scale=1 / math.sqrt(128), seed=1006, seq_len=524288, fp4=True),
+    # the MLA share with the latent in MXFP4 (DeepSeek-R1 with FP4 KV states is the paper's second model, Sec. 3)
+    "mla_share_mxfp4": Workload("mla_share_mxfp4", B=32, Q=128, K=1, dk=576, dv=512, n_shards=1,
+                                scale=1 / math.sqrt(192), seed=1007, seq_len=131072, mla=True, fp4=True),
 }
 
 
@@ -244,8 +247,13 @@ def make_inputs(w: Workload, device="cpu") -> Inputs:
     S = w.seq_len
     lens = torch.full((w.B,), S, dtype=torch.int32)
     kv_scale = None
+    if w.fp4 and w.mla:
+        # one MXFP4 latent per token: 576 codes (288 bytes) + 18 block scales; the value aliases its first 512 entries
+        assert not w.fp8 and w.K == 1
+        kc, ks = normal_mxfp4_rows(w.seed, TAG_K, w.B * S, w.dk, device)
+        return Inputs(w, q, kc.view(w.B, 1, S, w.dk // 2), None, None, lens, None, ks.view(w.B, 1, S, w.dk // 32), None)
     if w.fp4:
-        assert not w.mla and not w.fp8
+        assert not w.fp8
         kc, ks = normal_mxfp4_rows(w.seed, TAG_K, w.B * w.K * S, w.dk, device)
         vc, vs = normal_mxfp4_rows(w.seed, TAG_V, w.B * w.K * S, w.dv, device)
         return Inputs(w, q, kc.view(w.B, w.K, S, w.dk // 2), vc.view(w.B, w.K, S, w.dv // 2), None, lens, None,

@@ -60,7 +60,8 @@ def test_workspace_bound_covers_shorter_shards(hx):
     for prob in [hx.Problem(16, 16, 1, 128, 128, 0.088), hx.Problem(4, 64, 8, 128, 128, 0.088),
                  hx.Problem(1, 8, 2, 64, 64, 0.125), hx.Problem(2, 40, 2, 64, 64, 0.125, split_tokens=256),
                  hx.Problem(16, 16, 1, 128, 128, 0.088, kv_dtype=hx.KV_MXFP4), hx.Problem(2, 32, 2, 128, 128, 0.088, kv_dtype=hx.KV_MXFP4),
-                 hx.Problem(4, 128, 1, 576, 512, 0.07, v_aliases_k=True), hx.Problem(2, 160, 1, 576, 512, 0.07, v_aliases_k=True)]:
+                 hx.Problem(4, 128, 1, 576, 512, 0.07, v_aliases_k=True), hx.Problem(2, 160, 1, 576, 512, 0.07, v_aliases_k=True),
+                 hx.Problem(4, 128, 1, 576, 512, 0.07, v_aliases_k=True, kv_dtype=hx.KV_MXFP4)]:
         for n, max_len in [(1, 131072), (16, 65536), (4, 1024), (8, 100)]:
             bound = hx.helix_attn_workspace_bytes(prob, n, max_len)
             for lens in [[max_len] * n, [max_len // 3] * n, [1] * n, [0] * n, [max_len] + [7] * (n - 1)]:
@@ -152,7 +153,15 @@ def test_mxfp4_and_hopb_argument_errors_without_gpu(hx):
     mx = hx.Problem(2, 16, 1, 128, 128, 0.088, kv_dtype=hx.KV_MXFP4)
     assert hx.helix_attn_workspace_bytes(mx, 1, 4096) > 0
     assert hx.helix_attn_workspace_bytes(hx.Problem(2, 16, 1, 64, 64, 0.125, kv_dtype=hx.KV_MXFP4), 1, 4096) == 0
-    assert hx.helix_attn_workspace_bytes(hx.Problem(2, 128, 1, 576, 512, 0.07, v_aliases_k=True, kv_dtype=hx.KV_MXFP4), 1, 4096) == 0
+    mla_mx = hx.Problem(2, 128, 1, 576, 512, 0.07, v_aliases_k=True, kv_dtype=hx.KV_MXFP4)
+    assert hx.helix_attn_workspace_bytes(mla_mx, 1, 4096) > 0                 # an MXFP4 latent is served by the MLA path
+    assert hx.helix_attn_workspace_bytes(hx.Problem(2, 128, 1, 576, 512, 0.07, kv_dtype=hx.KV_MXFP4), 1, 4096) == 0
+    # ... and appended to without value rows: value codes or scales given for a latent are a shape error
+    pm = mla_mx.c()
+    from paper_2507_07120_amd import binding
+    dummy, no_shard = ctypes.c_void_p(64), (binding._CShard * 1)()            # never dereferenced: both calls fail first
+    assert lib.helix_kv_append_mxfp4(ctypes.byref(pm), no_shard, 1, 0, dummy, dummy, dummy, None, 16, None, None) == 2
+    assert lib.helix_kv_append_mxfp4(ctypes.byref(pm), no_shard, 1, 0, dummy, None, None, None, 16, None, None) == 1
     p = mx.c()
     # helix_kv_append refuses an MXFP4 cache (3 = unsupported); the MXFP4 variant refuses a bf16 one and NULLs
     assert lib.helix_kv_append(ctypes.byref(p), None, 1, 0, None, None, None, 16, None, None) == 3

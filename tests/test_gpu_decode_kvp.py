@@ -75,8 +75,8 @@ def run_both(hx, oracle, w, inp, N, split_tokens=0):
     qb = synth.bits(inp.q)
     lens = inp.lens.numpy()
     if mx is not None:
-        o_ref, lse_ref = oracle.attention(qb, inp.k.cpu().numpy(), inp.v.cpu().numpy(), lens, w.scale, kv_heads=w.K,
-                                          mx=(inp.k_mx.cpu().numpy(), inp.v_mx.cpu().numpy()))
+        o_ref, lse_ref = oracle.attention(qb, inp.k.cpu().numpy(), None if w.mla else inp.v.cpu().numpy(), lens, w.scale, kv_heads=w.K,
+                                          dv=w.dv, mx=(inp.k_mx.cpu().numpy(), None if w.mla else inp.v_mx.cpu().numpy()))
     else:
         sc = None if inp.kv_scale is None else inp.kv_scale.cpu().numpy()
         o_ref, lse_ref = oracle.attention(qb, synth.bits(inp.k), None if w.mla else synth.bits(inp.v), lens, w.scale,

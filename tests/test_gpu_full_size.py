@@ -57,7 +57,8 @@ def oracle_rows(oracle, w, inp, rows):
             v = synth.bits(inp.v[b:b + 1, kh:kh + 1]) if inp.v is not None else None
             # a one-KV-head problem holding exactly this row's group: head index within the group
             qg = np.ascontiguousarray(q[:, kh * g:(kh + 1) * g])
-            mx = None if inp.k_mx is None else (inp.k_mx[b:b + 1, kh:kh + 1].cpu().numpy(), inp.v_mx[b:b + 1, kh:kh + 1].cpu().numpy())
+            mx = None if inp.k_mx is None else (inp.k_mx[b:b + 1, kh:kh + 1].cpu().numpy(),
+                                                None if inp.v_mx is None else inp.v_mx[b:b + 1, kh:kh + 1].cpu().numpy())
             o, l = oracle.attention(qg, k, v, inp.lens[b:b + 1].numpy(), w.scale, kv_heads=1, dv=w.dv, rows=[(0, h - kh * g)], mx=mx)
         out_o.append(o[0])
         out_l.append(l[0])
@@ -155,3 +156,19 @@ def test_gqa_share_mxfp4_full(hx, oracle):
     d = (o4 - o).abs().max().item()
     print(f"gqa_share_mxfp4: 4 shards vs unsharded max-abs {d:.3e}")
     assert d <= SHARD_VS_UNSHARDED and (lse4 - lse).abs().max().item() <= 1e-5
+
+
+def test_mla_share_mxfp4_full(hx, oracle):
+    """The MXFP4 latent share: sampled rows against the oracle, and the same cache cut into 8 shards
+    against the unsharded run."""
+    w = synth.WORKLOADS["mla_share_mxfp4"]
+    inp = synth.make_inputs(w, "cuda")
+    o, lse, _, _, _ = decode(hx, w, inp, 1)
+    assert torch.isfinite(o).all() and torch.isfinite(lse).all()
+    rows = [(0, 0), (11, 77), (31, 127)]
+    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    check_rows(o, lse, o_ref, lse_ref, rows, "mla_share_mxfp4")
+    o8, lse8, _, _, _ = decode(hx, w, inp, 8)
+    d = (o8 - o).abs().max().item()
+    print(f"mla_share_mxfp4: 8 shards vs unsharded max-abs {d:.3e}")
+    assert d <= SHARD_VS_UNSHARDED and (lse8 - lse).abs().max().item() <= 1e-5

@@ -541,6 +541,29 @@ def test_mxfp4_attention_equals_the_same_values_given_as_bf16(oracle):
     assert np.array_equal(o4s, o16s) and np.array_equal(l4s, l16s)
 
 
+def test_mxfp4_latent_equals_the_same_values_given_as_bf16(oracle):
+    """The MLA case of the MXFP4 read path: the value is the first dv entries of the key row, block scales
+    included.  Identical element values given as a bf16 latent must give identical results, bit for bit --
+    and a value that took its scales from anywhere else would not."""
+    rng = np.random.default_rng(18)
+    B, Q, D, DV, S = 2, 5, 96, 64, 29
+    q, _ = bf16_bits(rng.standard_normal((B, Q, D)))
+    kc, ks, kv = _mxfp4_random(rng, (B, 1, S), D)
+    kb, kf = bf16_bits(kv)
+    assert np.array_equal(kf, kv)
+    lens = np.array([S, S - 6], np.int32)
+    o4, l4 = oracle.attention(q, kc, None, lens, 0.2, kv_heads=1, dv=DV, mx=(ks, None))
+    o16, l16 = oracle.attention(q, kb, None, lens, 0.2, kv_heads=1, dv=DV)
+    assert o4.shape == (B, Q, DV) and np.array_equal(o4, o16) and np.array_equal(l4, l16)
+    t_lo, t_hi = np.array([3, 0], np.int64), np.array([20, 7], np.int64)
+    o4s, l4s = oracle.attention(q, kc, None, lens, 0.2, kv_heads=1, dv=DV, mx=(ks, None), t_lo=t_lo, t_hi=t_hi)
+    o16s, l16s = oracle.attention(q, kb, None, lens, 0.2, kv_heads=1, dv=DV, t_lo=t_lo, t_hi=t_hi)
+    assert np.array_equal(o4s, o16s) and np.array_equal(l4s, l16s)
+    # one token: O is that token's decoded row, cut to dv
+    o1, _ = oracle.attention(q, kc, None, np.array([1, 1], np.int32), 0.2, kv_heads=1, dv=DV, mx=(ks, None))
+    assert np.array_equal(o1, np.broadcast_to(kv[:, 0, 0:1, :DV], (B, Q, DV)))
+
+
 def test_mxfp4_single_token_returns_the_decoded_value_row(oracle):
     """S = 1: the output is the value row itself -- element j of the row must come from nibble j%2 of
     byte j/2 and scale j/32 (a transposed nibble or a shifted scale index fails here)."""
