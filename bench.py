@@ -86,6 +86,8 @@ def cpu_baseline(w, inp, budget_macs=1.5e11):
         hi = int(inp.seq_off[nb])
         k, v = synth.bits(inp.k[:hi]), None
         kw["tok_off"] = inp.seq_off[:nb].numpy()
+        if inp.k_mx is not None:
+            kw["mx"] = (inp.k_mx[:hi].cpu().numpy(), None)
         if inp.kv_scale is not None:
             kw["kv_scale"] = inp.kv_scale[:hi].cpu().numpy()
     else:
@@ -169,7 +171,7 @@ def main():
 
     max_len = int(inp.lens.max())
     if inp.k_mx is not None:
-        cache = hx.KVShard.from_mxfp4(inp.k, inp.v, inp.k_mx, inp.v_mx, lens_dev, max_len)
+        cache = hx.KVShard.from_mxfp4(inp.k, inp.v, inp.k_mx, inp.v_mx, lens_dev, max_len, tok_off=seq_base)
     elif inp.k.dim() == 2:
         cache = hx.KVShard.from_packed(inp.k, lens_dev, max_len, seq_base, kv_scale=inp.kv_scale)
     else:

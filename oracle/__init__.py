@@ -92,7 +92,8 @@ def attention(q, k, v, lens, scale, *, kv_heads, dv=None, kv_scale=None, tok_off
     """Exact softmax attention of one decode query per sequence.
 
     q         uint16 [B,Q,dk]   bf16 bits
-    k         uint16/uint8 [B,K,T,dk] (or [T,dk] rows addressed through tok_off with B-stride 0)
+    k         uint16/uint8 [B,K,T,dk] (or [T,dk] rows addressed through tok_off with B-stride 0; MXFP4
+              codes: half as many bytes in the last axis)
     v         same layout with dv columns, or None: the value is the first ``dv`` entries of the
               key row (MLA latent)
     lens      int32 [B]  tokens of sequence b
@@ -116,8 +117,8 @@ def attention(q, k, v, lens, scale, *, kv_heads, dv=None, kv_scale=None, tok_off
     packed = k.ndim == 2
     epb = 2 if fp4 else 1                                  # elements per stored unit
     if packed:
-        assert tok_off is not None and K == 1 and not fp4
-        k_sb, k_sh, k_st = 0, 0, k.shape[1]
+        assert tok_off is not None and K == 1 and k.shape[1] * epb == dk
+        k_sb, k_sh, k_st = 0, 0, dk
     else:
         assert k.ndim == 4 and k.shape[0] == B and k.shape[1] == K and k.shape[3] * epb == dk
         k_sb, k_sh, k_st = K * k.shape[2] * dk, k.shape[2] * dk, dk
@@ -148,9 +149,9 @@ def attention(q, k, v, lens, scale, *, kv_heads, dv=None, kv_scale=None, tok_off
     if fp4:
         assert k.dtype == np.uint8 and dk % 32 == 0 and dv % 32 == 0
         k_mx, v_mx = mx
-        assert k_mx.dtype == np.uint8 and k_mx.flags.c_contiguous and k_mx.shape == k.shape[:3] + (dk // 32,)
+        assert k_mx.dtype == np.uint8 and k_mx.flags.c_contiguous and k_mx.shape == k.shape[:-1] + (dk // 32,)
         if not alias:
-            assert v_mx.dtype == np.uint8 and v_mx.flags.c_contiguous and v_mx.shape == v.shape[:3] + (dv // 32,)
+            assert v_mx.dtype == np.uint8 and v_mx.flags.c_contiguous and v_mx.shape == v.shape[:-1] + (dv // 32,)
 
     p = _Problem(B, Q, K, dk, dv, int(alias), KV_MXFP4 if fp4 else KV_FP8_E4M3 if fp8 else KV_BF16, float(scale),
                  _ptr(q), _ptr(k), _ptr(v), k_sb, k_sh, k_st, v_sb, v_sh, v_st,

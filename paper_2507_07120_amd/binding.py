@@ -163,14 +163,19 @@ class KVShard:
                    max_len: int, tok_off: Optional[torch.Tensor] = None) -> "KVShard":
         """k [B,K,S,dk/2], v [B,K,S,dv/2] uint8 codes, k_mx [B,K,S,dk/32], v_mx [B,K,S,dv/32] uint8 scales,
         all contiguous in their last two axes; strides are handed over in elements.  v and v_mx are None
-        for an MLA latent (the value is the first dv entries of the key row)."""
+        for an MLA latent (the value is the first dv entries of the key row), which may also be packed:
+        k [rows, dk/2], k_mx [rows, dk/32], sequence b starting at row tok_off[b]."""
         assert (v is None) == (v_mx is None)
         for t, m in ((k, k_mx), (v, v_mx)):
             if t is None:
                 continue
-            assert t.dtype == torch.uint8 and m.dtype == torch.uint8 and t.dim() == 4 and m.dim() == 4
-            assert t.stride(3) == 1 and m.is_contiguous() and t.is_contiguous()
-            assert m.shape[:3] == t.shape[:3] and m.shape[3] * 16 == t.shape[3]
+            assert t.dtype == torch.uint8 and m.dtype == torch.uint8 and t.dim() == m.dim()
+            assert m.is_contiguous() and t.is_contiguous()
+            assert m.shape[:-1] == t.shape[:-1] and m.shape[-1] * 16 == t.shape[-1]
+        if k.dim() == 2:
+            assert v is None and tok_off is not None
+            return KVShard(k, None, lens, int(max_len), (0, 0, 2 * k.stride(0)), (0, 0, 0), None, (0, 0), tok_off, k_mx, None)
+        assert k.dim() == 4
         v_strides = (0, 0, 0) if v is None else tuple(2 * x for x in (v.stride(0), v.stride(1), v.stride(2)))
         return KVShard(k, v, lens, int(max_len), tuple(2 * x for x in (k.stride(0), k.stride(1), k.stride(2))),
                        v_strides, None, (0, 0), tok_off, k_mx, v_mx)

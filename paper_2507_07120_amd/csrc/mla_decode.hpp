@@ -342,11 +342,10 @@ struct MlaDmaFp4 {
     static constexpr int PARTS = INSTRS + 1;
     static constexpr int UNITS = ROWS * CODE_ROW / 8;                       // 144 eight-byte units = 16 codes = two chunks of the tile
     static constexpr int PASSES = (UNITS + 63) / 64;                        // 3
-    static constexpr int OFF_SC = ROWS * CODE_ROW;                          // staging: the scale dwords ...
-    static constexpr int OFF_TOP = OFF_SC + 80;                             // ... and the largest scale code of each row (int)
+    static constexpr int OFF_SC = ROWS * CODE_ROW;                          // staging: the scale dwords behind the codes
     static constexpr int SHARE_BYTES = 1280;
     static constexpr int UP = 8;
-    static_assert(OFF_TOP + ROWS * 4 <= SHARE_BYTES && MlaCfg::WAVES * SHARE_BYTES <= MlaCfg::T * MlaCfg::DK, "staging area");
+    static_assert(OFF_SC + 3 + ROWS * SCALE_ROW + 16 <= SHARE_BYTES && MlaCfg::WAVES * SHARE_BYTES <= MlaCfg::T * MlaCfg::DK, "staging area");
     static_assert(PASSES == 3 && INSTRS == 2, "layout of the offset table");
 
     static __device__ __forceinline__ int row_of_chunk(int q) { return (q * 3641) >> 16; }      // q / 18 for q < 72
@@ -402,43 +401,62 @@ struct MlaDmaFp4 {
         return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp4(codes, scale, BYTE));
     }
 
-    // After the wave's DMA has landed.  Set-up: lane (row = lane / 16, j = lane % 16) looks at scales j and
-    // 16 + j of its row; the row's largest code goes to the staging area, the token scale to the tile's
-    // scale slot (zero for rows the tile does not have, whose entries become zeros as well).  Then three
-    // passes over the 144 units.
+    // max over each group of 16 lanes, by DPP (no LDS round trips): lane ^ 1, lane ^ 2, mirror within 8, mirror within 16
+    static __device__ __forceinline__ int max16(int x)
+    {
+        x = max(x, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, true));      // quad_perm [1,0,3,2]
+        x = max(x, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, true));      // quad_perm [2,3,0,1]
+        x = max(x, __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true));     // row_half_mirror
+        x = max(x, __builtin_amdgcn_mov_dpp(x, 0x140, 0xf, 0xf, true));     // row_mirror
+        return x;
+    }
+
+    // After the wave's DMA has landed.  Every LDS read is issued up front (the conversion sits at the start
+    // of a phase: a chain of dependent LDS round trips there delays the wave's first MFMA).  Lane
+    // (row = lane / 16, j = lane % 16) looks at scales j and 16 + j of its row; the rows' largest codes end up
+    // in four scalar registers, the token scales in the tile's scale slot (zero for rows the tile does not
+    // have, whose entries become zeros as well).  Then three passes over the 144 units; which rows a pass's
+    // lanes work on is fixed: units 0..35 are row 0, 36..71 row 1, ...
     static __device__ __forceinline__ void convert(int n_valid, lds_byte* stage, lds_byte* tile, lds_byte* scale_slot,
                                                    const lds_byte* table, int wave, int lane, int tid)
     {
         typedef __attribute__((address_space(3))) uint32_t lds_u32;
+        static_assert(CODE_ROW / 8 == 36 && ROWS == 4, "row boundaries of the passes below");
         lane = mla_opaque(lane);
         const lds_byte* mine = table + mla_opaque(tid) * 32;
-        {
-            const uint32_t at = *reinterpret_cast<const lds_u32*>(mine + 12);
-            const int j = lane & 15, row = lane >> 4;
-            int x = stage[at];
-            if (j < SCALE_ROW - 16) x = max(x, (int)stage[at + 16]);
-#pragma unroll
-            for (int o = 1; o < 16; o <<= 1) x = max(x, __shfl_xor(x, o));
-            if (j == 0) {
-                *reinterpret_cast<lds_i32*>(stage + OFF_TOP + row * 4) = x;
-                *reinterpret_cast<lds_f32*>(scale_slot + (wave * ROWS + row) * 4) =
-                    wave * ROWS + row < n_valid ? __builtin_ldexpf(1.f, x - (127 + UP)) : 0.f;
-            }
-        }
+        const uint32_t at = *reinterpret_cast<const lds_u32*>(mine + 12);
         const u32x4 dst = *reinterpret_cast<const lds_u32x4*>(mine + 16);
+        const int j = lane & 15, row = lane >> 4;
+        int x = stage[at];
+        const int x2 = stage[at + 16];                                      // inside the staging area for every lane
+        u32x2 w[PASSES];
+        int xb[PASSES];
+#pragma unroll
+        for (int p = 0; p < PASSES; p++) {
+            if (p * 64 + 63 >= UNITS && lane >= UNITS - p * 64) continue;
+            w[p] = *reinterpret_cast<const lds_u32x2*>(stage + lane * 8 + p * 512);
+            xb[p] = stage[OFF_SC + ((dst[p] >> 20) & 0xffu)];
+        }
+        if (j < SCALE_ROW - 16) x = max(x, x2);
+        x = max16(x);
+        const int t0 = __builtin_amdgcn_readlane(x, 0), t1 = __builtin_amdgcn_readlane(x, 16);
+        const int t2 = __builtin_amdgcn_readlane(x, 32), t3 = __builtin_amdgcn_readlane(x, 48);
+        if (j == 0)
+            *reinterpret_cast<lds_f32*>(scale_slot + (wave * ROWS + row) * 4) =
+                wave * ROWS + row < n_valid ? __builtin_ldexpf(1.f, x - (127 + UP)) : 0.f;
         const bool ragged = n_valid != MlaCfg::T;
 #pragma unroll
-        for (int j = 0; j < PASSES; j++) {
-            if (j * 64 + 63 >= UNITS && lane >= UNITS - j * 64) continue;
-            u32x2 w = *reinterpret_cast<const lds_u32x2*>(stage + lane * 8 + j * 512);
-            const uint32_t meta = dst[j];
-            const int row = (int)(meta >> 28);
-            const int e = (int)stage[OFF_SC + ((meta >> 20) & 0xffu)] - *reinterpret_cast<const lds_i32*>(stage + OFF_TOP + row * 4) + (127 + UP);
+        for (int p = 0; p < PASSES; p++) {
+            if (p * 64 + 63 >= UNITS && lane >= UNITS - p * 64) continue;
+            const uint32_t meta = dst[p];
+            const int top = p == 0 ? (lane < 36 ? t0 : t1) : p == 1 ? (lane < 8 ? t1 : lane < 44 ? t2 : t3) : t3;
+            const int e = xb[p] - top + (127 + UP);
             const float scale = as_f32((uint32_t)max(e, 0) << 23);        // 2^(X - top + UP); more than 135 octaves down: zero
-            if (ragged && wave * ROWS + row >= n_valid) w = u32x2{0, 0};
+            u32x2 cw = w[p];
+            if (ragged && wave * ROWS + (int)(meta >> 28) >= n_valid) cw = u32x2{0, 0};
             const uint32_t to = meta & 0xfffffu;
-            *reinterpret_cast<lds_u32x4*>(tile + to) = u32x4{pair<0>(w.x, scale), pair<1>(w.x, scale), pair<2>(w.x, scale), pair<3>(w.x, scale)};
-            *reinterpret_cast<lds_u32x4*>(tile + (to ^ 16u)) = u32x4{pair<0>(w.y, scale), pair<1>(w.y, scale), pair<2>(w.y, scale), pair<3>(w.y, scale)};
+            *reinterpret_cast<lds_u32x4*>(tile + to) = u32x4{pair<0>(cw.x, scale), pair<1>(cw.x, scale), pair<2>(cw.x, scale), pair<3>(cw.x, scale)};
+            *reinterpret_cast<lds_u32x4*>(tile + (to ^ 16u)) = u32x4{pair<0>(cw.y, scale), pair<1>(cw.y, scale), pair<2>(cw.y, scale), pair<3>(cw.y, scale)};
         }
     }
 };

@@ -206,6 +206,10 @@ WORKLOADS = {
     # the MLA share with the latent in MXFP4 (DeepSeek-R1 with FP4 KV states is the paper's second model, Sec. 3)
     "mla_share_mxfp4": Workload("mla_share_mxfp4", B=32, Q=128, K=1, dk=576, dv=512, n_shards=1,
                                 scale=1 / math.sqrt(192), seed=1007, seq_len=131072, mla=True, fp4=True),
+    # the ragged MLA configuration (same seed: same lengths, same rows before quantisation) with the latent in MXFP4
+    "mla_mxfp4_ragged": Workload("mla_mxfp4_ragged", B=64, Q=128, K=1, dk=576, dv=512, n_shards=8,
+                                 scale=1 / math.sqrt(192), seed=1005, len_range=(16384, 262144),
+                                 mla=True, fp4=True),
 }
 
 
@@ -219,7 +223,8 @@ def scaled(w: Workload, **kw) -> Workload:
 @dataclass
 class Inputs:
     """Tensors of one workload.  Padded layout: k [B,K,S,dk], v [B,K,S,dv] (None for MLA).
-    Ragged layout (len_range): k [sum L_b, dk] packed, seq_off int64 [B+1]; kv_scale [sum L_b]."""
+    Ragged layout (len_range): k [sum L_b, dk] packed, seq_off int64 [B+1]; kv_scale [sum L_b]
+    (MXFP4: k [sum L_b, dk/2] codes, k_mx [sum L_b, dk/32])."""
     w: Workload
     q: torch.Tensor
     k: torch.Tensor
@@ -239,6 +244,10 @@ def make_inputs(w: Workload, device="cpu") -> Inputs:
         seq_off[1:] = torch.cumsum(lens.to(torch.int64), 0)
         rows = int(seq_off[-1])
         assert w.K == 1 and w.mla, "ragged packed storage is defined for the single-latent case"
+        if w.fp4:
+            assert not w.fp8
+            kc, ks = normal_mxfp4_rows(w.seed, TAG_K, rows, w.dk, device)
+            return Inputs(w, q, kc, None, None, lens, seq_off, ks, None)
         if w.fp8:
             k, kv_scale = normal_e4m3_rows(w.seed, TAG_K, rows, w.dk, device)
         else:

@@ -25,7 +25,7 @@ def hx():
 def whole_cache(hx, w, inp, lens_dev, seq_base):
     max_len = int(inp.lens.max())
     if getattr(w, "fp4", False):
-        return hx.KVShard.from_mxfp4(inp.k, inp.v, inp.k_mx, inp.v_mx, lens_dev, max_len)
+        return hx.KVShard.from_mxfp4(inp.k, inp.v, inp.k_mx, inp.v_mx, lens_dev, max_len, tok_off=seq_base)
     if inp.k.dim() == 2:
         return hx.KVShard.from_packed(inp.k, lens_dev, max_len, seq_base, kv_scale=inp.kv_scale)
     return hx.KVShard.from_padded(inp.k, inp.v, lens_dev, max_len, kv_scale=inp.kv_scale)
@@ -76,7 +76,8 @@ def run_both(hx, oracle, w, inp, N, split_tokens=0):
     lens = inp.lens.numpy()
     if mx is not None:
         o_ref, lse_ref = oracle.attention(qb, inp.k.cpu().numpy(), None if w.mla else inp.v.cpu().numpy(), lens, w.scale, kv_heads=w.K,
-                                          dv=w.dv, mx=(inp.k_mx.cpu().numpy(), None if w.mla else inp.v_mx.cpu().numpy()))
+                                          dv=w.dv, mx=(inp.k_mx.cpu().numpy(), None if w.mla else inp.v_mx.cpu().numpy()),
+                                          tok_off=inp.seq_off[:-1].numpy() if packed else None)
     else:
         sc = None if inp.kv_scale is None else inp.kv_scale.cpu().numpy()
         o_ref, lse_ref = oracle.attention(qb, synth.bits(inp.k), None if w.mla else synth.bits(inp.v), lens, w.scale,

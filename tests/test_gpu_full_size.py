@@ -48,8 +48,9 @@ def oracle_rows(oracle, w, inp, rows):
             lo, hi = int(inp.seq_off[b]), int(inp.seq_off[b + 1])
             k = synth.bits(inp.k[lo:hi])
             sc = inp.kv_scale[lo:hi].cpu().numpy() if inp.kv_scale is not None else None
+            mx = None if inp.k_mx is None else (inp.k_mx[lo:hi].cpu().numpy(), None)
             o, l = oracle.attention(q, k, None, np.array([hi - lo], np.int32), w.scale, kv_heads=1, dv=w.dv,
-                                    kv_scale=sc, tok_off=np.zeros(1, np.int64), rows=[(0, h)])
+                                    kv_scale=sc, tok_off=np.zeros(1, np.int64), rows=[(0, h)], mx=mx)
         else:
             g = w.Q // w.K
             kh = h // g
@@ -172,3 +173,23 @@ def test_mla_share_mxfp4_full(hx, oracle):
     d = (o8 - o).abs().max().item()
     print(f"mla_share_mxfp4: 8 shards vs unsharded max-abs {d:.3e}")
     assert d <= SHARD_VS_UNSHARDED and (lse8 - lse).abs().max().item() <= 1e-5
+
+
+def test_mla_mxfp4_ragged_full(hx, oracle):
+    """The ragged MLA configuration with the latent in MXFP4: packed rows (odd and even first rows), 8 shards."""
+    w = synth.WORKLOADS["mla_mxfp4_ragged"]
+    inp = synth.make_inputs(w, "cuda")
+    lens = inp.lens.numpy()
+    o8, lse8, _, _, ss = decode(hx, w, inp, 8)
+    off_ref, len_ref = oracle.shard_layout(lens, 8)
+    assert np.array_equal(ss.shard_off.cpu().numpy(), off_ref + inp.seq_off[:-1].numpy()[None, :])
+    assert np.array_equal(ss.shard_len.cpu().numpy(), len_ref)
+    assert torch.isfinite(o8).all() and torch.isfinite(lse8).all()
+    o1, lse1, _, _, _ = decode(hx, w, inp, 1)
+    d = (o8 - o1).abs().max().item()
+    print(f"mla_mxfp4_ragged: sharded(8) vs unsharded max-abs {d:.3e}")
+    assert d <= SHARD_VS_UNSHARDED
+    odd = [b for b in range(w.B) if int(inp.seq_off[b]) % 2 == 1]
+    rows = [(int(lens.argmin()), 3), (odd[0] if odd else 1, 100)]
+    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    check_rows(o8, lse8, o_ref, lse_ref, rows, "mla_mxfp4_ragged sharded")

@@ -111,6 +111,19 @@ def test_mla_mxfp4_views_that_start_on_any_row(hx, oracle, first):
     check_lse(lse.cpu().numpy(), lse_ref, f"views from rows {first} LSE")
 
 
+@pytest.mark.parametrize("B,lo,hi,N,split", [
+    (4, 40, 900, 8, 0),                        # ragged packed rows, sequences starting on odd and even rows
+    (3, 1, 70, 2, 0),
+    (2, 1500, 3000, 3, 256),
+])
+def test_mla_mxfp4_ragged_packed_against_oracle(hx, oracle, B, lo, hi, N, split):
+    from test_gpu_decode_kvp import run_both
+    w = synth.scaled(synth.WORKLOADS["mla_mxfp4_ragged"], B=B, len_range=(lo, hi), n_shards=N, seed=900 + hi)
+    inp = synth.make_inputs(w, "cuda")
+    assert inp.k.dim() == 2 and inp.k_mx.shape == (inp.k.shape[0], 18)
+    run_both(hx, oracle, w, inp, N, split_tokens=split)
+
+
 def test_mla_mxfp4_block_scales_spread(hx, oracle):
     """Block scales that differ inside a row (up to 6 octaves) and between rows (14 more): every entry stays
     exact in the widened tile, the per-token powers of two spread the weights over fp16's range; the

@@ -564,6 +564,30 @@ def test_mxfp4_latent_equals_the_same_values_given_as_bf16(oracle):
     assert np.array_equal(o1, np.broadcast_to(kv[:, 0, 0:1, :DV], (B, Q, DV)))
 
 
+def test_mxfp4_latent_packed_rows_equal_padded(oracle):
+    """Ragged packed storage of an MXFP4 latent (rows of all sequences back to back, odd first rows
+    included) addresses the same codes and block scales as the padded layout."""
+    rng = np.random.default_rng(19)
+    B, Q, D, DV = 3, 4, 64, 32
+    lens = np.array([7, 12, 5], np.int32)
+    q, _ = bf16_bits(rng.standard_normal((B, Q, D)))
+    kc, ks, _ = _mxfp4_random(rng, (int(lens.sum()),), D)
+    off = np.concatenate([[0], np.cumsum(lens)[:-1]]).astype(np.int64)
+    S = int(lens.max())
+    pc = np.zeros((B, 1, S, D // 2), np.uint8)
+    ps = np.full((B, 1, S, D // 32), 127, np.uint8)
+    for b in range(B):
+        pc[b, 0, :lens[b]] = kc[off[b]:off[b] + lens[b]]
+        ps[b, 0, :lens[b]] = ks[off[b]:off[b] + lens[b]]
+    o_p, l_p = oracle.attention(q, kc, None, lens, 0.25, kv_heads=1, dv=DV, mx=(ks, None), tok_off=off)
+    o_d, l_d = oracle.attention(q, pc, None, lens, 0.25, kv_heads=1, dv=DV, mx=(ps, None))
+    assert np.array_equal(o_p, o_d) and np.array_equal(l_p, l_d)
+    t_lo, t_hi = np.array([2, 0, 1], np.int64), np.array([7, 5, 1], np.int64)
+    o_p, l_p = oracle.attention(q, kc, None, lens, 0.25, kv_heads=1, dv=DV, mx=(ks, None), tok_off=off, t_lo=t_lo, t_hi=t_hi)
+    o_d, l_d = oracle.attention(q, pc, None, lens, 0.25, kv_heads=1, dv=DV, mx=(ps, None), t_lo=t_lo, t_hi=t_hi)
+    assert np.array_equal(o_p, o_d) and np.array_equal(l_p, l_d)
+
+
 def test_mxfp4_single_token_returns_the_decoded_value_row(oracle):
     """S = 1: the output is the value row itself -- element j of the row must come from nibble j%2 of
     byte j/2 and scale j/32 (a transposed nibble or a shifted scale index fails here)."""
