@@ -51,6 +51,7 @@ struct AttnArgs {
     int32_t split_tokens; // tokens of a shard one workgroup streams
     float scale_log2e;    // softmax scale * log2(e)
     int32_t n_shards;
+    const uint2* units;   // MLA: which (shard << 24 | sequence, split) each workgroup serves, written by mla_order_kernel; NULL: by id
     ShardDev shard[kMaxLaunchShards];
 };
 

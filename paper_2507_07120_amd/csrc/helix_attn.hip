@@ -118,6 +118,7 @@ struct Workspace {
     float* ws_l;
     float* part_o;
     float* part_lse;
+    uint2* units;           // MLA: the run each workgroup serves (mla_order_kernel), one entry per split record row
     size_t bytes;
 };
 
@@ -133,6 +134,7 @@ Workspace carve(const helix_problem* p, int64_t total_splits, int32_t n, void* b
     w.ws_l = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * 4, 256);
     w.part_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * p->dv * 4, 256);
     w.part_lse = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * 4, 256);
+    w.units = reinterpret_cast<uint2*>(c + off); off = align_up(off + (size_t)total_splits * p->batch * sizeof(uint2), 256);
     w.bytes = off;
     return w;
 }
@@ -249,8 +251,15 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             m.split_base[i] = split_base;
             m.n_splits[i] = d.n_splits;
             split_base += d.n_splits;
-            units += plan.path == Path::Mla ? mla_units_of_shard(d.n_splits, p->batch, plan.head_tiles)
-                                            : (int64_t)d.n_splits * rows;
+            units += plan.path == Path::Mla && plan.head_tiles > 1 ? mla_units_of_shard(d.n_splits, p->batch, plan.head_tiles)
+                                                                   : (int64_t)d.n_splits * rows;
+        }
+        // MLA with one head tile: the runs are handed to the workgroups in the order mla_order_kernel
+        // writes -- full runs first, then partial ones, then empty ones (see there)
+        if (plan.path == Path::Mla && plan.head_tiles == 1) {
+            hipLaunchKernelGGL(helix::mla_order_kernel, dim3(1), dim3(helix::kOrderThreads), 0, stream, a, ws.units, (int)units);
+            if (int rc = launch_status()) return rc;
+            a.units = ws.units;
         }
         if (g_prof_start && g_prof_stop && s0 == 0) (void)hipEventRecord(g_prof_start, stream);
         switch (plan.path) {

@@ -461,6 +461,72 @@ struct MlaDmaFp4 {
     }
 };
 
+// The order in which the workgroups of an MLA launch take their runs.  Workgroup ids are dealt
+// round-robin to the 8 XCDs for good, and a workgroup needs a whole CU whatever it finds to do.  With
+// ragged lengths the runs of a launch are full (split_tokens rows), partial (the last of a sequence's
+// slice) or empty (the grid is sized for the longest sequence), and with the plain id -> (split, sequence)
+// map the XCDs whose ids happen to hold less work idle at the end (measured: 15 % of the ragged
+// configuration).  This kernel (one workgroup) writes the map instead: all full runs first -- equal
+// cost, so every XCD gets the same share -- then the partial ones by descending length (16 classes),
+// then the empty ones, which only write their empty record.  Entry i: x = shard << 24 | sequence,
+// y = split index.  Which workgroup serves which run has no influence on any result.
+constexpr int kOrderThreads = 1024, kOrderClasses = 16;
+
+__global__ __launch_bounds__(kOrderThreads) void mla_order_kernel(const AttnArgs a, uint2* units, int n_units)
+{
+    __shared__ int count[kOrderClasses + 2];              // runs per segment: [0] full, [1 + c] partial of class c, [last] empty
+    __shared__ int cursor[kOrderClasses + 2];
+    const int tid = threadIdx.x;
+    const int pairs = a.n_shards * a.B;
+    if (tid < kOrderClasses + 2) count[tid] = 0;
+    __syncthreads();
+    // what one (shard, sequence) pair contributes: nf full runs, one partial run of class cls (or none: -1)
+    auto runs_of = [&](int p, int& si, int& b, int& nf, int& cls, int& n) {
+        si = p / a.B;
+        b = p - si * a.B;
+        const ShardDev& sh = a.shard[si];
+        int len;
+        int64_t first_row;
+        shard_range(sh, b, len, first_row);
+        n = sh.n_splits;
+        nf = min(len / a.split_tokens, n);
+        const int rem = len - nf * a.split_tokens;
+        cls = nf < n && rem > 0 ? kOrderClasses - 1 - min(kOrderClasses - 1, (int)((int64_t)rem * kOrderClasses / a.split_tokens)) : -1;
+    };
+    for (int p = tid; p < pairs; p += kOrderThreads) {
+        int si, b, nf, cls, n;
+        runs_of(p, si, b, nf, cls, n);
+        if (nf) atomicAdd(&count[0], nf);
+        if (cls >= 0) atomicAdd(&count[1 + cls], 1);
+        if (n - nf - (cls >= 0)) atomicAdd(&count[kOrderClasses + 1], n - nf - (cls >= 0));
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int at = 0;
+        for (int j = 0; j < kOrderClasses + 2; j++) { cursor[j] = at; at += count[j]; }
+    }
+    __syncthreads();
+    for (int p = tid; p < pairs; p += kOrderThreads) {
+        int si, b, nf, cls, n;
+        runs_of(p, si, b, nf, cls, n);
+        const uint32_t who = (uint32_t)si << 24 | (uint32_t)b;
+        int s = 0;
+        if (nf) {
+            const int at = atomicAdd(&cursor[0], nf);
+            for (; s < nf; s++) if (at + s < n_units) units[at + s] = uint2{who, (uint32_t)s};
+        }
+        if (cls >= 0) {
+            const int at = atomicAdd(&cursor[1 + cls], 1);
+            if (at < n_units) units[at] = uint2{who, (uint32_t)s};
+            s++;
+        }
+        if (s < n) {
+            const int at = atomicAdd(&cursor[kOrderClasses + 1], n - s) - s;
+            for (; s < n; s++) if (at + s < n_units) units[at + s] = uint2{who, (uint32_t)s};
+        }
+    }
+}
+
 // FP8: the latent is not bf16 and the contractions run in fp16 -- e4m3 codes with a scale per token, or,
 // with MX, MXFP4 codes with block scales (widened to the same tile and token scales).
 template <bool FP8, bool MX = false>
@@ -476,21 +542,27 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     const int r = lane & 15, kc = lane >> 4;
     const int pair = wave >> 1, half = wave & 1;                  // waves 2p, 2p+1 share heads 32p..32p+31
 
-    // which (shard, split, sequence, head tile of HPW heads) this workgroup serves
-    int u = blockIdx.x, si = 0;
-    while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
+    // which (shard, split, sequence, head tile of HPW heads) this workgroup serves: from the map
+    // mla_order_kernel wrote (one head tile), else from its id
+    int u = blockIdx.x, si = 0, split, b, htw = 0;
+    if (a.units) {
+        const uint2 e = a.units[u];
+        si = __builtin_amdgcn_readfirstlane((int)(e.x >> 24));
+        b = __builtin_amdgcn_readfirstlane((int)(e.x & 0xffffffu));
+        split = __builtin_amdgcn_readfirstlane((int)e.y);
+    } else {
+        while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
+        u -= a.shard[si].unit_base;
+        const int ug = u / (8 * a.head_tiles), j8 = u % (8 * a.head_tiles);
+        const int logical = ug * 8 + (j8 & 7);
+        htw = j8 >> 3;
+        if (logical >= a.shard[si].n_splits * a.B) return;         // padding workgroup
+        // Split index slow, sequence fast, and the sequence rotated by 3 per split: consecutive workgroup
+        // ids go to different XCDs, so every XCD sees every split index and a mix of sequences.
+        split = logical / a.B;
+        b = (logical % a.B + 3 * split) % a.B;
+    }
     const ShardDev& sh = a.shard[si];
-    u -= sh.unit_base;
-    const int ug = u / (8 * a.head_tiles), j8 = u % (8 * a.head_tiles);
-    const int logical = ug * 8 + (j8 & 7);
-    const int htw = j8 >> 3;
-    if (logical >= sh.n_splits * a.B) return;         // padding workgroup
-    // Split index slow, sequence fast, and the sequence rotated by 3 per split: consecutive workgroup
-    // ids go to different XCDs, so every XCD sees every split index and a mix of sequences.  With
-    // ragged lengths the high split indices are mostly empty; were they tied to fixed XCDs (split =
-    // id mod n_splits), those XCDs would idle while the ones serving split 0 do all the work.
-    const int split = logical / a.B;
-    const int b = (logical % a.B + 3 * split) % a.B;
 
     int len;
     int64_t first_row;
