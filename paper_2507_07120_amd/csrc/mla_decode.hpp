@@ -493,9 +493,12 @@ __global__ __launch_bounds__(kOrderThreads) void mla_order_kernel(const AttnArgs
         const int rem = len - nf * a.split_tokens;
         cls = nf < n && rem > 0 ? kOrderClasses - 1 - min(kOrderClasses - 1, (int)((int64_t)rem * kOrderClasses / a.split_tokens)) : -1;
     };
+    // a thread's first pair is looked up once (the usual launch has fewer pairs than threads)
+    int si0 = 0, b0 = 0, nf0 = 0, cls0 = -1, n0 = 0;
+    if (tid < pairs) runs_of(tid, si0, b0, nf0, cls0, n0);
     for (int p = tid; p < pairs; p += kOrderThreads) {
-        int si, b, nf, cls, n;
-        runs_of(p, si, b, nf, cls, n);
+        int si = si0, b = b0, nf = nf0, cls = cls0, n = n0;
+        if (p != tid) runs_of(p, si, b, nf, cls, n);
         if (nf) atomicAdd(&count[0], nf);
         if (cls >= 0) atomicAdd(&count[1 + cls], 1);
         if (n - nf - (cls >= 0)) atomicAdd(&count[kOrderClasses + 1], n - nf - (cls >= 0));
@@ -507,8 +510,8 @@ __global__ __launch_bounds__(kOrderThreads) void mla_order_kernel(const AttnArgs
     }
     __syncthreads();
     for (int p = tid; p < pairs; p += kOrderThreads) {
-        int si, b, nf, cls, n;
-        runs_of(p, si, b, nf, cls, n);
+        int si = si0, b = b0, nf = nf0, cls = cls0, n = n0;
+        if (p != tid) runs_of(p, si, b, nf, cls, n);
         const uint32_t who = (uint32_t)si << 24 | (uint32_t)b;
         int s = 0;
         if (nf) {
