@@ -90,6 +90,34 @@ def test_mla_bf16_against_oracle(hx, oracle, B, Q, S, N, lens, split):
     assert (o_n - o_1).abs().max().item() <= SHARD_VS_UNSHARDED
 
 
+def test_mla_many_short_sequences_run_order(hx, oracle):
+    """More (shard, sequence) pairs than the run-ordering kernel has threads (1200 > 1024), lengths from 0 to
+    three runs of 64 tokens: every run -- full, partial or empty -- must be served exactly once, whatever
+    workgroup it lands on (an unserved one leaves the NaN the records were filled with)."""
+    from paper_2507_07120_amd import harness
+    B, N = 300, 4
+    w = synth.Workload("mla_many", B=B, Q=16, K=1, dk=576, dv=512, n_shards=N, scale=1 / math.sqrt(192), seed=404,
+                       seq_len=640, mla=True)
+    inp = synth.make_inputs(w, "cuda")
+    lens = synth.uniform_lengths(11, 7, B, 0, 640)
+    lens[:3] = torch.tensor([0, 640, 1], dtype=torch.int32)
+    inp.lens = lens
+    prob = harness.problem_for(w, 64)
+    ss = harness.make_shards(inp.k, None, inp.lens.cuda(), N)
+    ws = harness.workspace_for(prob, N, max(ss.max_lens), "cuda")
+    ws.view(torch.float32)[: ws.numel() // 4].fill_(float("nan"))
+    o = torch.full((B, 16, 512), float("nan"), device="cuda")
+    lse = torch.full((B, 16), float("nan"), device="cuda")
+    hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+    torch.cuda.synchronize()
+    ln = inp.lens.numpy()
+    o_ref, lse_ref = oracle.attention(synth.bits(inp.q), synth.bits(inp.k), None, ln, w.scale, kv_heads=1, dv=512)
+    has = ln > 0
+    check_o(o.cpu().numpy()[has], o_ref[has], "1200 pairs O")
+    check_lse(lse.cpu().numpy(), lse_ref, "1200 pairs LSE")
+    assert np.all(o.cpu().numpy()[~has] == 0)
+
+
 def run_mla_allow_empty(hx, oracle, w, inp, n_shards, split):
     from paper_2507_07120_amd import harness
     prob = harness.problem_for(w, split)
