@@ -162,12 +162,13 @@ def main():
     N = w.n_shards
     shard_off = torch.empty((N, w.B), dtype=torch.int64, device=dev)
     shard_len = torch.empty((N, w.B), dtype=torch.int32, device=dev)
+    # the host knows the lengths it generated: it declares their sum (only a ragged batch is planned differently)
     ss = harness.make_shards(inp.k, inp.v, lens_dev, N, kv_scale=inp.kv_scale, seq_base=seq_base,
-                             mx=None if inp.k_mx is None else (inp.k_mx, inp.v_mx))
+                             mx=None if inp.k_mx is None else (inp.k_mx, inp.v_mx), declare_sums=True)
     ws = harness.workspace_for(prob, N, max(ss.max_lens), dev)
     o = torch.empty((w.B, w.Q, w.dv), device=dev)
     lse = torch.empty((w.B, w.Q), device=dev)
-    split_tokens, workgroups = hx.helix_attn_plan(prob, ss.max_lens)
+    split_tokens, workgroups = hx.helix_attn_plan(prob, ss.max_lens, [s.sum_len for s in ss.shards])
 
     max_len = int(inp.lens.max())
     if inp.k_mx is not None:
@@ -176,6 +177,7 @@ def main():
         cache = hx.KVShard.from_packed(inp.k, lens_dev, max_len, seq_base, kv_scale=inp.kv_scale)
     else:
         cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, max_len, kv_scale=inp.kv_scale)
+    cache.sum_len = int(inp.lens.sum())
 
     # one step = the whole path over one batch: the KVP cut of every sequence (integer metadata, written
     # out), the per-slice attention fragments, and their combine

@@ -51,7 +51,7 @@ struct AttnArgs {
     int32_t split_tokens; // tokens of a shard one workgroup streams
     float scale_log2e;    // softmax scale * log2(e)
     int32_t n_shards;
-    const uint2* units;   // MLA: which (shard << 24 | sequence, split) each workgroup serves, written by mla_order_kernel; NULL: by id
+    const uint2* units;   // which (shard << 24 | row, split) each workgroup serves, written by run_order_kernel; NULL: by id
     ShardDev shard[kMaxLaunchShards];
 };
 
@@ -113,5 +113,78 @@ __device__ __forceinline__ float wave_xor_sum_16_32(float x)
     x += __shfl_xor(x, 32);
     return x;
 }
+
+// The order in which the workgroups of an attention launch take their runs.  Workgroup ids are dealt
+// round-robin to the 8 XCDs (and on to their CUs) for good; an MLA workgroup needs a whole CU whatever it
+// finds to do.  With ragged lengths the runs of a launch are full (split_tokens rows), partial (the last
+// of a sequence's slice) or empty (the grid is sized for the longest sequence), and with a plain
+// id -> (split, row) map the XCDs whose ids happen to hold less work idle at the end (measured: 15 % of
+// the ragged MLA configuration).  This kernel (one workgroup) writes the map instead: all full runs
+// first -- equal cost, so every XCD gets the same share -- then the partial ones by descending length
+// (16 classes), then the empty ones, which only write their empty record.  A row is a (sequence, kv
+// head, head tile): row = (b * K + kv head) * head_tiles + head tile.  Entry i: x = shard << 24 | row,
+// y = split index.  Which workgroup serves which run has no influence on any result.
+constexpr int kOrderThreads = 1024, kOrderClasses = 16;
+
+__global__ __launch_bounds__(kOrderThreads) void run_order_kernel(const AttnArgs a, uint2* units, int n_units)
+{
+    __shared__ int count[kOrderClasses + 2];              // runs per segment: [0] full, [1 + c] partial of class c, [last] empty
+    __shared__ int cursor[kOrderClasses + 2];
+    const int tid = threadIdx.x;
+    const int rows = a.B * a.K * a.head_tiles;
+    const int pairs = a.n_shards * rows;
+    if (tid < kOrderClasses + 2) count[tid] = 0;
+    __syncthreads();
+    // what one (shard, row) pair contributes: nf full runs, one partial run of class cls (or none: -1)
+    auto runs_of = [&](int p, int& si, int& row, int& nf, int& cls, int& n) {
+        si = p / rows;
+        row = p - si * rows;
+        const int b = row / (a.K * a.head_tiles);
+        const ShardDev& sh = a.shard[si];
+        int len;
+        int64_t first_row;
+        shard_range(sh, b, len, first_row);
+        n = sh.n_splits;
+        nf = min(len / a.split_tokens, n);
+        const int rem = len - nf * a.split_tokens;
+        cls = nf < n && rem > 0 ? kOrderClasses - 1 - min(kOrderClasses - 1, (int)((int64_t)rem * kOrderClasses / a.split_tokens)) : -1;
+    };
+    // a thread's first pair is looked up once (the usual launch has fewer pairs than threads)
+    int si0 = 0, row0 = 0, nf0 = 0, cls0 = -1, n0 = 0;
+    if (tid < pairs) runs_of(tid, si0, row0, nf0, cls0, n0);
+    for (int p = tid; p < pairs; p += kOrderThreads) {
+        int si = si0, row = row0, nf = nf0, cls = cls0, n = n0;
+        if (p != tid) runs_of(p, si, row, nf, cls, n);
+        if (nf) atomicAdd(&count[0], nf);
+        if (cls >= 0) atomicAdd(&count[1 + cls], 1);
+        if (n - nf - (cls >= 0)) atomicAdd(&count[kOrderClasses + 1], n - nf - (cls >= 0));
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int at = 0;
+        for (int j = 0; j < kOrderClasses + 2; j++) { cursor[j] = at; at += count[j]; }
+    }
+    __syncthreads();
+    for (int p = tid; p < pairs; p += kOrderThreads) {
+        int si = si0, row = row0, nf = nf0, cls = cls0, n = n0;
+        if (p != tid) runs_of(p, si, row, nf, cls, n);
+        const uint32_t who = (uint32_t)si << 24 | (uint32_t)row;
+        int s = 0;
+        if (nf) {
+            const int at = atomicAdd(&cursor[0], nf);
+            for (; s < nf; s++) if (at + s < n_units) units[at + s] = uint2{who, (uint32_t)s};
+        }
+        if (cls >= 0) {
+            const int at = atomicAdd(&cursor[1 + cls], 1);
+            if (at < n_units) units[at] = uint2{who, (uint32_t)s};
+            s++;
+        }
+        if (s < n) {
+            const int at = atomicAdd(&cursor[kOrderClasses + 1], n - s) - s;
+            for (; s < n; s++) if (at + s < n_units) units[at + s] = uint2{who, (uint32_t)s};
+        }
+    }
+}
+
 
 }  // namespace helix

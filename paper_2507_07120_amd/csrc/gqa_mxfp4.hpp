@@ -180,12 +180,19 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
     const int r = lane & 15, kc = lane >> 4;
 
     // which (shard, split, sequence, kv head, head tile) this workgroup serves
-    int u = blockIdx.x, si = 0;
-    while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
+    int u = blockIdx.x, si = 0, split, rest;
+    if (a.units) {                // a batch declared ragged: the map run_order_kernel wrote (non-empty runs first)
+        const uint2 e = a.units[u];
+        si = __builtin_amdgcn_readfirstlane((int)(e.x >> 24));
+        rest = __builtin_amdgcn_readfirstlane((int)(e.x & 0xffffffu));
+        split = __builtin_amdgcn_readfirstlane((int)e.y);
+    } else {
+        while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
+        u -= a.shard[si].unit_base;
+        split = u % a.shard[si].n_splits;
+        rest = u / a.shard[si].n_splits;
+    }
     const ShardDev& sh = a.shard[si];
-    u -= sh.unit_base;
-    const int split = u % sh.n_splits;
-    int rest = u / sh.n_splits;
     const int ht = rest % a.head_tiles; rest /= a.head_tiles;
     const int kh = rest % a.K;
     const int b = rest / a.K;

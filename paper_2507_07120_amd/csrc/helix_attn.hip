@@ -29,6 +29,7 @@ struct Plan {
     int32_t split_tokens;
     int64_t total_splits;   // over all shards
     int64_t workgroups;
+    bool ordered;           // the workgroups take their runs from a map written on the device (run_order_kernel)
 };
 
 constexpr int64_t kTargetWorkgroups = 256;   // CUs of an MI355X
@@ -76,7 +77,14 @@ int check_problem(const helix_problem* p, Path* path)
 // streams: 6.8 TB/s at 256 workgroups, 6.5 at 512, 6.2 at 1024 on the 1 GiB GQA share), so the
 // target is one workgroup per CU, never less than one per (shard, sequence, kv head, head tile) row,
 // with split records that stay small next to the KV bytes a workgroup streams.
-int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_t n, Plan* plan)
+// Split records a GQA plan may use per (sequence, kv head, head tile) row when a ragged batch asks for
+// runs shorter than its longest sequence needs at one workgroup per CU; the sizing call covers it.
+inline int64_t ragged_split_cap(Path path, int64_t rows, int32_t n)
+{
+    return ceil_div(4 * target_workgroups(path), rows) + n;
+}
+
+int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, const int64_t* sum_lens, int32_t n, Plan* plan)
 {
     plan->path = path;
     plan->heads_per_wg = path == Path::Mla ? MlaCfg::HPW : 16;
@@ -84,11 +92,20 @@ int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_
     const int g = p->q_heads / p->kv_heads;
     plan->head_tiles = (int32_t)ceil_div(g, plan->heads_per_wg);
     const int64_t rows = (int64_t)p->batch * p->kv_heads * plan->head_tiles;
-    int64_t total = 0;
+    int64_t total = 0;       // tokens of a row if every sequence had max_len
+    int64_t tokens = 0;      // tokens of all sequences, as far as the caller has told
+    bool ragged = false;
     for (int i = 0; i < n; i++) {
-        if (max_lens[i] < 0) return HELIX_ERR_SHAPE;
+        if (max_lens[i] < 0 || (sum_lens && sum_lens[i] < 0)) return HELIX_ERR_SHAPE;
         total += max_lens[i];
+        const int64_t full = (int64_t)p->batch * max_lens[i];
+        const bool told = sum_lens && sum_lens[i] > 0 && sum_lens[i] < full;
+        tokens += told ? sum_lens[i] : full;
+        ragged = ragged || told;
     }
+    // MLA launches always take their runs from the map (one head tile); the streaming kernels do so for
+    // a batch that is declared ragged -- the map costs a launch of its own
+    plan->ordered = path == Path::Mla ? plan->head_tiles == 1 : ragged;
     int64_t split;
     if (p->split_tokens > 0) {
         split = ceil_div(p->split_tokens, plan->granule) * plan->granule;
@@ -100,8 +117,14 @@ int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_
         // 256 KB record of a run is 5-11 % of the latent bytes it reads.
         const int64_t target = target_workgroups(path);
         const int64_t floor_tokens = path == Path::Mla ? kMinSplitTokensMla : kMinSplitTokens;
-        split = ceil_div(ceil_div(rows * total, target), plan->granule) * plan->granule;
+        const int64_t work = path == Path::Mla ? rows * total : rows / p->batch * tokens;   // token rows to stream
+        split = ceil_div(ceil_div(work, target), plan->granule) * plan->granule;
         split = std::max<int64_t>(split, floor_tokens);
+        if (path != Path::Mla && ragged) {
+            // the longest sequence decides how many records a row needs: keep them within the sizing call's bound
+            const int64_t cap = ragged_split_cap(path, rows, n) - n;
+            split = std::max<int64_t>(split, ceil_div(ceil_div(total, cap), plan->granule) * plan->granule);
+        }
     }
     if (path == Path::GqaMx128) split = std::min<int64_t>(split, (int64_t)1 << 25);   // 32-bit byte offsets inside a split
     plan->split_tokens = (int32_t)split;
@@ -118,12 +141,12 @@ struct Workspace {
     float* ws_l;
     float* part_o;
     float* part_lse;
-    uint2* units;           // MLA: the run each workgroup serves (mla_order_kernel), one entry per split record row
+    uint2* units;           // MLA: the run each workgroup serves (run_order_kernel), one entry per split record row
     size_t bytes;
 };
 
 // Carves a workspace for `total_splits` records and `n` shard partials.  base may be NULL (sizing).
-Workspace carve(const helix_problem* p, int64_t total_splits, int32_t n, void* base)
+Workspace carve(const helix_problem* p, int64_t total_splits, int64_t rows, int32_t n, void* base)
 {
     const size_t bq = (size_t)p->batch * p->q_heads;
     char* c = static_cast<char*>(base);
@@ -134,7 +157,7 @@ Workspace carve(const helix_problem* p, int64_t total_splits, int32_t n, void* b
     w.ws_l = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * 4, 256);
     w.part_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * p->dv * 4, 256);
     w.part_lse = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * 4, 256);
-    w.units = reinterpret_cast<uint2*>(c + off); off = align_up(off + (size_t)total_splits * p->batch * sizeof(uint2), 256);
+    w.units = reinterpret_cast<uint2*>(c + off); off = align_up(off + (size_t)total_splits * rows * sizeof(uint2), 256);
     w.bytes = off;
     return w;
 }
@@ -145,7 +168,7 @@ int check_shard(const helix_problem* p, const helix_kv_shard* s)
     if (p->v_aliases_k ? s->v != nullptr : s->v == nullptr) return p->v_aliases_k ? HELIX_ERR_SHAPE : HELIX_ERR_NULL;
     const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
     if (fp8 ? s->kv_scale == nullptr : false) return HELIX_ERR_NULL;
-    if (s->max_len < 0) return HELIX_ERR_SHAPE;
+    if (s->max_len < 0 || s->sum_len < 0) return HELIX_ERR_SHAPE;
     if (p->kv_dtype == HELIX_KV_MXFP4) {
         // strides count elements; a row is dk/2 code bytes and dk/32 scale bytes, token rows dense
         if (!s->k_scale_mx) return HELIX_ERR_NULL;
@@ -251,13 +274,13 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             m.split_base[i] = split_base;
             m.n_splits[i] = d.n_splits;
             split_base += d.n_splits;
-            units += plan.path == Path::Mla && plan.head_tiles > 1 ? mla_units_of_shard(d.n_splits, p->batch, plan.head_tiles)
+            units += plan.path == Path::Mla && !plan.ordered ? mla_units_of_shard(d.n_splits, p->batch, plan.head_tiles)
                                                                    : (int64_t)d.n_splits * rows;
         }
-        // MLA with one head tile: the runs are handed to the workgroups in the order mla_order_kernel
+        // MLA with one head tile: the runs are handed to the workgroups in the order run_order_kernel
         // writes -- full runs first, then partial ones, then empty ones (see there)
-        if (plan.path == Path::Mla && plan.head_tiles == 1) {
-            hipLaunchKernelGGL(helix::mla_order_kernel, dim3(1), dim3(helix::kOrderThreads), 0, stream, a, ws.units, (int)units);
+        if (plan.ordered) {
+            hipLaunchKernelGGL(helix::run_order_kernel, dim3(1), dim3(helix::kOrderThreads), 0, stream, a, ws.units, (int)units);
             if (int rc = launch_status()) return rc;
             a.units = ws.units;
         }
@@ -329,12 +352,14 @@ int prepare(const helix_problem* p, const helix_kv_shard* shards, int32_t n, voi
     if (!shards) return HELIX_ERR_NULL;
     if (n < 1 || n > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
     int32_t max_lens[HELIX_MAX_SHARDS];
+    int64_t sum_lens[HELIX_MAX_SHARDS];
     for (int32_t i = 0; i < n; i++) {
         if (int rc = check_shard(p, &shards[i])) return rc;
         max_lens[i] = shards[i].max_len;
+        sum_lens[i] = shards[i].sum_len;
     }
-    if (int rc = make_plan(p, path, max_lens, n, plan)) return rc;
-    *ws = carve(p, plan->total_splits, n, workspace);
+    if (int rc = make_plan(p, path, max_lens, sum_lens, n, plan)) return rc;
+    *ws = carve(p, plan->total_splits, (int64_t)p->batch * p->kv_heads * plan->head_tiles, n, workspace);
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || ws->bytes > workspace_bytes) return HELIX_ERR_WORKSPACE;
     return HELIX_OK;
 }
@@ -364,7 +389,7 @@ int helix_attn_set_profile_events(void* start_event, void* stop_event)
     return HELIX_OK;
 }
 
-int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, int32_t n_shards,
+int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, const int64_t* sum_lens, int32_t n_shards,
                     int32_t* split_tokens, int64_t* workgroups)
 {
     Path path;
@@ -372,7 +397,7 @@ int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, int32
     if (!max_lens) return HELIX_ERR_NULL;
     if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
     Plan plan;
-    if (int rc = make_plan(problem, path, max_lens, n_shards, &plan)) return rc;
+    if (int rc = make_plan(problem, path, max_lens, sum_lens, n_shards, &plan)) return rc;
     if (split_tokens) *split_tokens = plan.split_tokens;
     if (workgroups) *workgroups = plan.workgroups;
     return HELIX_OK;
@@ -388,12 +413,14 @@ size_t helix_attn_workspace_bytes(const helix_problem* problem, int32_t n_shards
     int32_t lens[HELIX_MAX_SHARDS];
     for (int i = 0; i < n_shards; i++) lens[i] = max_len;
     Plan plan;
-    if (make_plan(problem, path, lens, n_shards, &plan) != HELIX_OK) return 0;
+    if (make_plan(problem, path, lens, nullptr, n_shards, &plan) != HELIX_OK) return 0;
     const int64_t rows = (int64_t)problem->batch * problem->kv_heads * plan.head_tiles;
     int64_t worst = plan.total_splits;
-    if (problem->split_tokens == 0)
+    if (problem->split_tokens == 0) {
         worst = std::max<int64_t>(worst, ceil_div(target_workgroups(path), rows) + n_shards);
-    return carve(problem, worst, n_shards, nullptr).bytes;
+        if (path != Path::Mla) worst = std::max<int64_t>(worst, ragged_split_cap(path, rows, n_shards));   // a batch declared ragged
+    }
+    return carve(problem, worst, rows, n_shards, nullptr).bytes;
 }
 
 int helix_attn_partial(const helix_problem* problem, const void* q, const helix_kv_shard* shard,
@@ -546,6 +573,8 @@ int helix_attn_decode_kvp(const helix_problem* problem, const void* q, const hel
     for (int32_t i = 0; i < n_shards; i++) {
         slices[i] = *cache;
         slices[i].max_len = c;
+        // a slice holds a N-th of every sequence, rounded up to whole 16-token blocks
+        if (cache->sum_len > 0) slices[i].sum_len = std::min<int64_t>(ceil_div(cache->sum_len, n_shards) + 16 * (int64_t)problem->batch, (int64_t)problem->batch * c);
     }
     Plan plan;
     Workspace ws;

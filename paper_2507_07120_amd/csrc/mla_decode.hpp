@@ -461,75 +461,6 @@ struct MlaDmaFp4 {
     }
 };
 
-// The order in which the workgroups of an MLA launch take their runs.  Workgroup ids are dealt
-// round-robin to the 8 XCDs for good, and a workgroup needs a whole CU whatever it finds to do.  With
-// ragged lengths the runs of a launch are full (split_tokens rows), partial (the last of a sequence's
-// slice) or empty (the grid is sized for the longest sequence), and with the plain id -> (split, sequence)
-// map the XCDs whose ids happen to hold less work idle at the end (measured: 15 % of the ragged
-// configuration).  This kernel (one workgroup) writes the map instead: all full runs first -- equal
-// cost, so every XCD gets the same share -- then the partial ones by descending length (16 classes),
-// then the empty ones, which only write their empty record.  Entry i: x = shard << 24 | sequence,
-// y = split index.  Which workgroup serves which run has no influence on any result.
-constexpr int kOrderThreads = 1024, kOrderClasses = 16;
-
-__global__ __launch_bounds__(kOrderThreads) void mla_order_kernel(const AttnArgs a, uint2* units, int n_units)
-{
-    __shared__ int count[kOrderClasses + 2];              // runs per segment: [0] full, [1 + c] partial of class c, [last] empty
-    __shared__ int cursor[kOrderClasses + 2];
-    const int tid = threadIdx.x;
-    const int pairs = a.n_shards * a.B;
-    if (tid < kOrderClasses + 2) count[tid] = 0;
-    __syncthreads();
-    // what one (shard, sequence) pair contributes: nf full runs, one partial run of class cls (or none: -1)
-    auto runs_of = [&](int p, int& si, int& b, int& nf, int& cls, int& n) {
-        si = p / a.B;
-        b = p - si * a.B;
-        const ShardDev& sh = a.shard[si];
-        int len;
-        int64_t first_row;
-        shard_range(sh, b, len, first_row);
-        n = sh.n_splits;
-        nf = min(len / a.split_tokens, n);
-        const int rem = len - nf * a.split_tokens;
-        cls = nf < n && rem > 0 ? kOrderClasses - 1 - min(kOrderClasses - 1, (int)((int64_t)rem * kOrderClasses / a.split_tokens)) : -1;
-    };
-    // a thread's first pair is looked up once (the usual launch has fewer pairs than threads)
-    int si0 = 0, b0 = 0, nf0 = 0, cls0 = -1, n0 = 0;
-    if (tid < pairs) runs_of(tid, si0, b0, nf0, cls0, n0);
-    for (int p = tid; p < pairs; p += kOrderThreads) {
-        int si = si0, b = b0, nf = nf0, cls = cls0, n = n0;
-        if (p != tid) runs_of(p, si, b, nf, cls, n);
-        if (nf) atomicAdd(&count[0], nf);
-        if (cls >= 0) atomicAdd(&count[1 + cls], 1);
-        if (n - nf - (cls >= 0)) atomicAdd(&count[kOrderClasses + 1], n - nf - (cls >= 0));
-    }
-    __syncthreads();
-    if (tid == 0) {
-        int at = 0;
-        for (int j = 0; j < kOrderClasses + 2; j++) { cursor[j] = at; at += count[j]; }
-    }
-    __syncthreads();
-    for (int p = tid; p < pairs; p += kOrderThreads) {
-        int si = si0, b = b0, nf = nf0, cls = cls0, n = n0;
-        if (p != tid) runs_of(p, si, b, nf, cls, n);
-        const uint32_t who = (uint32_t)si << 24 | (uint32_t)b;
-        int s = 0;
-        if (nf) {
-            const int at = atomicAdd(&cursor[0], nf);
-            for (; s < nf; s++) if (at + s < n_units) units[at + s] = uint2{who, (uint32_t)s};
-        }
-        if (cls >= 0) {
-            const int at = atomicAdd(&cursor[1 + cls], 1);
-            if (at < n_units) units[at] = uint2{who, (uint32_t)s};
-            s++;
-        }
-        if (s < n) {
-            const int at = atomicAdd(&cursor[kOrderClasses + 1], n - s) - s;
-            for (; s < n; s++) if (at + s < n_units) units[at + s] = uint2{who, (uint32_t)s};
-        }
-    }
-}
-
 // FP8: the latent is not bf16 and the contractions run in fp16 -- e4m3 codes with a scale per token, or,
 // with MX, MXFP4 codes with block scales (widened to the same tile and token scales).
 template <bool FP8, bool MX = false>
@@ -546,7 +477,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     const int pair = wave >> 1, half = wave & 1;                  // waves 2p, 2p+1 share heads 32p..32p+31
 
     // which (shard, split, sequence, head tile of HPW heads) this workgroup serves: from the map
-    // mla_order_kernel wrote (one head tile), else from its id
+    // run_order_kernel wrote (one head tile), else from its id
     int u = blockIdx.x, si = 0, split, b, htw = 0;
     if (a.units) {
         const uint2 e = a.units[u];

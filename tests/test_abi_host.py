@@ -147,6 +147,35 @@ def test_hopb_timeline_model_matches_the_oracle(hx, oracle):
     assert math.isnan(hx.helix_hopb_span(0, 1.0, 1.0, True)) and math.isnan(hx.helix_hopb_span(3, -1.0, 1.0, True))
 
 
+def test_plans_of_batches_declared_ragged(hx):
+    """A shard may state the sum of its lengths.  A sum below batch * max_len makes the streaming paths cut
+    shorter runs (the tokens that exist, not batch * max_len, are spread over the CUs) within the records
+    the sizing call covers; a sum that says nothing new changes nothing; the MLA path keeps its run length."""
+    gqa = hx.Problem(16, 16, 1, 128, 128, 0.088)
+    full, _ = hx.helix_attn_plan(gqa, [131072])
+    assert hx.helix_attn_plan(gqa, [131072], [0]) == hx.helix_attn_plan(gqa, [131072])
+    assert hx.helix_attn_plan(gqa, [131072], [16 * 131072]) == hx.helix_attn_plan(gqa, [131072])
+    assert hx.helix_attn_plan(gqa, [131072], [17 * 131072]) == hx.helix_attn_plan(gqa, [131072])
+    half, wgs = hx.helix_attn_plan(gqa, [131072], [8 * 131072])
+    assert half == full // 2 and wgs == 2 * 256
+    with pytest.raises(hx.HelixError):
+        hx.helix_attn_plan(gqa, [131072], [-1])
+    for prob in [gqa, hx.Problem(4, 64, 8, 128, 128, 0.088), hx.Problem(2, 40, 2, 64, 64, 0.125),
+                 hx.Problem(16, 16, 1, 128, 128, 0.088, kv_dtype=hx.KV_MXFP4)]:
+        for n, max_len in [(1, 131072), (8, 65536), (3, 1000)]:
+            bound = hx.helix_attn_workspace_bytes(prob, n, max_len)
+            g = prob.q_heads // prob.kv_heads
+            rows = prob.batch * prob.kv_heads * ((g + 15) // 16)
+            for sums in [[max_len + prob.batch - 1] * n, [max_len * prob.batch // 3] * n, [1] * n, [max_len] + [5] * (n - 1)]:
+                for lens in [[max_len] * n, [max_len] + [max_len // 5] * (n - 1)]:
+                    split, wgs = hx.helix_attn_plan(prob, lens, sums)
+                    assert split % 128 == 0 and split >= 512
+                    need = (wgs // rows) * prob.batch * prob.q_heads * (prob.dv + 2) * 4 + wgs * 8
+                    assert need <= bound, (prob, n, max_len, sums, lens)
+    mla = hx.Problem(64, 128, 1, 576, 512, 0.07, v_aliases_k=True, kv_dtype=hx.KV_FP8_E4M3)
+    assert hx.helix_attn_plan(mla, [32768] * 8, [32768 * 20] * 8) == hx.helix_attn_plan(mla, [32768] * 8)
+
+
 def test_mxfp4_and_hopb_argument_errors_without_gpu(hx):
     """The newer entry points validate on the host as well: status codes, nothing launched."""
     lib = hx.load_library()

@@ -145,3 +145,31 @@ def test_mxfp4_fused_cut(hx, oracle):
     inp = synth.make_inputs(w, "cuda")
     inp.lens = torch.tensor([1000, 517, 33], dtype=torch.int32)
     run_both(hx, oracle, w, inp, 3)
+
+
+def test_fused_cut_of_a_batch_declared_ragged(hx, oracle):
+    """helix_attn_decode_kvp on a cache that states the sum of its lengths: every slice is planned for its
+    share of it; the cut and the results are those of the oracle."""
+    from paper_2507_07120_amd import harness
+    lens = [50000, 1000, 0, 333, 20000, 4096, 77, 15000]
+    w = synth.Workload("kvp_ragged_hint", B=8, Q=16, K=1, dk=128, dv=128, n_shards=4, scale=1 / math.sqrt(128), seed=71, seq_len=50000)
+    inp = synth.make_inputs(w, "cuda")
+    inp.lens = torch.tensor(lens, dtype=torch.int32)
+    prob = harness.problem_for(w)
+    lens_dev = inp.lens.cuda()
+    cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, 50000)
+    cache.sum_len = int(sum(lens))
+    ws = harness.workspace_for(prob, 4, 50000, "cuda")
+    o = torch.full((8, 16, 128), float("nan"), device="cuda")
+    lse = torch.full((8, 16), float("nan"), device="cuda")
+    off = torch.full((4, 8), -7, dtype=torch.int64, device="cuda")
+    ln = torch.full((4, 8), -7, dtype=torch.int32, device="cuda")
+    hx.helix_attn_decode_kvp(prob, inp.q, cache, 4, o, ws, lse_out=lse, shard_off=off, shard_len=ln)
+    torch.cuda.synchronize()
+    off_ref, len_ref = oracle.shard_layout(inp.lens.numpy(), 4)
+    assert np.array_equal(off.cpu().numpy(), off_ref) and np.array_equal(ln.cpu().numpy(), len_ref)
+    o_ref, lse_ref = oracle.attention(synth.bits(inp.q), synth.bits(inp.k), synth.bits(inp.v), inp.lens.numpy(), w.scale, kv_heads=1, dv=128)
+    has = np.array(lens) > 0
+    check_o(o.cpu().numpy()[has], o_ref[has], "fused cut, declared ragged O")
+    check_lse(lse.cpu().numpy(), lse_ref, "fused cut, declared ragged LSE")
+    assert np.all(o.cpu().numpy()[~has] == 0)

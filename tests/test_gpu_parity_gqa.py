@@ -39,13 +39,13 @@ def check_lse(got, ref, what):
     assert err <= LSE_MAX_ABS, f"{what}: lse max-abs {err:.3e}"
 
 
-def run_sharded(hx, oracle, w, inp, n_shards, split_tokens=0, check_partials=True):
+def run_sharded(hx, oracle, w, inp, n_shards, split_tokens=0, check_partials=True, declare_sums=False):
     """decode over n_shards on the GPU, compared with the oracle; returns the GPU output."""
     from paper_2507_07120_amd import harness
     dev = "cuda"
     prob = harness.problem_for(w, split_tokens)
     lens_dev = inp.lens.to(dev)
-    ss = harness.make_shards(inp.k, inp.v, lens_dev, n_shards, kv_scale=inp.kv_scale)
+    ss = harness.make_shards(inp.k, inp.v, lens_dev, n_shards, kv_scale=inp.kv_scale, declare_sums=declare_sums)
     # integer metadata: bit-exact against the oracle's layout
     off_ref, len_ref = oracle.shard_layout(inp.lens.numpy(), n_shards)
     assert np.array_equal(ss.shard_off.cpu().numpy(), off_ref)
@@ -84,6 +84,30 @@ def run_sharded(hx, oracle, w, inp, n_shards, split_tokens=0, check_partials=Tru
     assert torch.equal(o2, o) and torch.equal(lse2, lse)
     assert np.array_equal(amax.cpu().numpy(), oracle.argmax_f32(lses.cpu().numpy()))
     return o, lse
+
+
+@pytest.mark.parametrize("B,Q,K,D,S,N,lens", [
+    (8, 16, 1, 128, 40000, 1, [40000, 3000, 17, 0, 9000, 128, 20000, 511], ),     # runs sized for 72k tokens, not 320k
+    (8, 16, 1, 128, 40000, 3, [40000, 3000, 17, 0, 9000, 128, 20000, 511], ),
+    (5, 40, 2, 64, 9000, 2, [9000, 100, 4000, 1, 2500]),                           # two head tiles, d=64
+])
+def test_gqa_batch_declared_ragged(hx, oracle, B, Q, K, D, S, N, lens):
+    """A batch whose shards state the sum of their lengths: shorter runs, workgroups that take the non-empty
+    runs first through the map written on the device -- and the same results as without the statement."""
+    from paper_2507_07120_amd import harness
+    w = synth.Workload("ragged_hint", B=B, Q=Q, K=K, dk=D, dv=D, n_shards=N, scale=1 / math.sqrt(D), seed=55 + N, seq_len=S)
+    inp = synth.make_inputs(w, "cuda")
+    inp.lens = torch.tensor(lens, dtype=torch.int32)
+    ss = harness.make_shards(inp.k, inp.v, inp.lens.cuda(), N, declare_sums=True)
+    prob = harness.problem_for(w)
+    told, _ = hx.helix_attn_plan(prob, ss.max_lens, [s.sum_len for s in ss.shards])
+    plain, _ = hx.helix_attn_plan(prob, ss.max_lens)
+    assert told < plain
+    o_t, lse_t = run_sharded(hx, oracle, w, inp, N, declare_sums=True)
+    o_p, lse_p = run_sharded(hx, oracle, w, inp, N, check_partials=False)
+    has = np.array(lens) > 0
+    assert (o_t - o_p).abs().cpu().numpy()[has].max() <= SHARD_VS_UNSHARDED
+    assert (lse_t - lse_p).abs().cpu().numpy()[has].max() <= 1e-5
 
 
 def test_tiny_gqa_config(hx, oracle):
