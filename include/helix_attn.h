@@ -98,7 +98,8 @@ typedef struct helix_problem {
  * of k (v), its block scale in byte e/32 of k_scale_mx (v_scale_mx).  Token rows must be dense
  * (k_stride_t == dk, v_stride_t == dv), the other strides multiples of 128, the scale arrays
  * 4-byte aligned.  An MXFP4 MLA latent (v_aliases_k) has v == NULL and v_scale_mx == NULL: the value is
- * the first dv entries of the key row, block scales included. */
+ * the first dv entries of the key row, block scales included; its scale bytes are fetched as aligned
+ * 4-byte words, so the array must be readable up to the next 4-byte boundary after its last row. */
 typedef struct helix_kv_shard {
     const void *k;          /* bf16 or e4m3 */
     const void *v;          /* same dtype; must be NULL iff v_aliases_k */

@@ -144,6 +144,7 @@ __global__ __launch_bounds__(kOrderThreads) void run_order_kernel(const AttnArgs
         int len;
         int64_t first_row;
         shard_range(sh, b, len, first_row);
+        len = max(len, 0);                                // a negative length is an empty sequence, as in the attention kernels
         n = sh.n_splits;
         nf = min(len / a.split_tokens, n);
         const int rem = len - nf * a.split_tokens;
