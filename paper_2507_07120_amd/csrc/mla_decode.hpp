@@ -51,7 +51,7 @@
 // rate as bf16, 11 significant bits): the query rows are scaled into fp16 range by a power of two, and
 // ONE fp16 weight w_t = p_t * f_t * 2^-E per token replaces the bf16 hi/lo pair -- half the P.V MFMAs.
 // The per-token scale f_t multiplies the score (s_t = f_t * q.k8_t) and the weight; the normaliser sums
-// the plain p_t in fp32.  fp16's range is narrow: a head's reference sits 4 octaves below its first-tile
+// the unrounded p_t (times 2^-E, exactly) in fp32.  fp16's range is narrow: a head's reference sits 4 octaves below its first-tile
 // maximum, E is chosen from the first tile, and a run whose largest weight of some head left
 // [2^-6, 2^15) is repeated once with that head's reference moved.
 #pragma once
@@ -661,7 +661,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         float t[8], fs[8], p[8];
         if constexpr (FP8) {
             // One fp16 weight per token, w_t = p_t * f_t * 2^-E (11 significant bits: relative L2 error of
-            // O about 2e-4); the normaliser sums the plain p_t in fp32.  Range is checked once per run.
+            // O about 2e-4); the normaliser sums the unrounded p_t * 2^-E in fp32.  Range is checked once per run.
             // p_t * 2^-E comes straight out of the exponent: the reference used here is m_ref + E, and the
             // normaliser sums the scaled terms (the record wants l * 2^-E anyway)
             exponents(masked, s0, s1, kb, n_valid, t, fs);
