@@ -100,6 +100,16 @@ __device__ __forceinline__ float exp2_rel(float t, float m)
     return __builtin_ldexpf(e, (int)(fl - m));
 }
 
+// 2^(t - m) for an integer m, the fractional and the integer part of t taken by one instruction each
+// (v_fract_f32, v_cvt_flr_i32_f32): the same bits as exp2_rel(t, (float)m) in five instructions instead of six
+// (for |t| below 2^31 octaves; the conversion saturates beyond).
+__device__ __forceinline__ float exp2_rel_int(float t, int m)
+{
+    int n;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(n) : "v"(t));
+    return __builtin_ldexpf(__builtin_amdgcn_exp2f(__builtin_amdgcn_fractf(t)), n - m);
+}
+
 __device__ __forceinline__ float wave_xor_max_16_32(float x)
 {
     x = fmaxf(x, __shfl_xor(x, 16));

@@ -137,15 +137,16 @@ __device__ __forceinline__ void gqa_compute_core(GqaState<D>& st, KOp&& kop, VOp
     // weights and their bf16 hi/lo split, packed as the MFMA's B operand (8 tokens of head r)
     uint32_t phi[4], plo[4];
     float lsum = 0.f;
+    const int mi = (int)m_new;                            // finite: the block has a valid token
 #pragma unroll
     for (int e = 0; e < 8; e += 2) {
         float p0, p1;
         if (TAIL) {
-            p0 = valid[e] ? exp2_rel(t[e], m_new) : 0.f;
-            p1 = valid[e + 1] ? exp2_rel(t[e + 1], m_new) : 0.f;
+            p0 = valid[e] ? exp2_rel_int(t[e], mi) : 0.f;
+            p1 = valid[e + 1] ? exp2_rel_int(t[e + 1], mi) : 0.f;
         } else {
-            p0 = exp2_rel(t[e], m_new);
-            p1 = exp2_rel(t[e + 1], m_new);
+            p0 = exp2_rel_int(t[e], mi);
+            p1 = exp2_rel_int(t[e + 1], mi);
         }
         const uint32_t h = pack_bf16_rne(p0, p1);
         const float r0 = p0 - as_f32(h << 16);

@@ -106,15 +106,6 @@ __device__ __forceinline__ uint32_t pack_f16_rne(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 
-// 2^(t - m) for an integer m, the fractional and the integer part of t taken by one instruction each
-// (v_fract_f32, v_cvt_flr_i32_f32): the same bits as exp2_rel(t, (float)m) in five instructions instead of six.
-__device__ __forceinline__ float mla_exp2_rel(float t, int m)
-{
-    int n;
-    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(n) : "v"(t));
-    return __builtin_ldexpf(__builtin_amdgcn_exp2f(__builtin_amdgcn_fractf(t)), n - m);
-}
-
 typedef __attribute__((address_space(3))) uint8_t lds_byte;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -669,7 +660,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             float lsum = 0.f, wm = w_max;
 #pragma unroll
             for (int i = 0; i < 8; i++) {
-                const float pi = mla_exp2_rel(floor_of(t[i]), mi);
+                const float pi = exp2_rel_int(floor_of(t[i]), mi);
                 lsum += pi;
                 p[i] = pi * fs[i];
                 wm = fmaxf(wm, p[i]);
