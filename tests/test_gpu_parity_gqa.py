@@ -90,6 +90,7 @@ def run_sharded(hx, oracle, w, inp, n_shards, split_tokens=0, check_partials=Tru
     (8, 16, 1, 128, 40000, 1, [40000, 3000, 17, 0, 9000, 128, 20000, 511], ),     # runs sized for 72k tokens, not 320k
     (8, 16, 1, 128, 40000, 3, [40000, 3000, 17, 0, 9000, 128, 20000, 511], ),
     (5, 40, 2, 64, 9000, 2, [9000, 100, 4000, 1, 2500]),                           # two head tiles, d=64
+    (3, 16, 2, 128, 20000, 20, [20000, 700, 5000]),                                # more shards than one launch carries
 ])
 def test_gqa_batch_declared_ragged(hx, oracle, B, Q, K, D, S, N, lens):
     """A batch whose shards state the sum of their lengths: shorter runs, workgroups that take the non-empty
@@ -102,7 +103,7 @@ def test_gqa_batch_declared_ragged(hx, oracle, B, Q, K, D, S, N, lens):
     prob = harness.problem_for(w)
     told, _ = hx.helix_attn_plan(prob, ss.max_lens, [s.sum_len for s in ss.shards])
     plain, _ = hx.helix_attn_plan(prob, ss.max_lens)
-    assert told < plain
+    assert told <= plain and (N > 3 or told < plain)         # short slices sit at the smallest run length either way
     o_t, lse_t = run_sharded(hx, oracle, w, inp, N, declare_sums=True)
     o_p, lse_p = run_sharded(hx, oracle, w, inp, N, check_partials=False)
     has = np.array(lens) > 0

@@ -74,6 +74,7 @@ def run_mla(hx, oracle, w, inp, n_shards, split_tokens=0, check_partials=True, m
     (2, 64, 97, 1, [97, 1], 0),               # 64 heads (padded head tile), a 1-token sequence
     (1, 160, 400, 4, [400], 0),               # 160 heads -> two head tiles, the second padded
     (3, 128, 64, 8, [64, 0, 33], 0),          # empty sequence, empty shards
+    (2, 128, 1500, 20, [1500, 640], 0),       # more shards than one launch carries: two run maps in a row
 ])
 def test_mla_bf16_against_oracle(hx, oracle, B, Q, S, N, lens, split):
     w = synth.Workload("mla_case", B=B, Q=Q, K=1, dk=576, dv=512, n_shards=N, scale=1 / math.sqrt(192), seed=300 + S,
