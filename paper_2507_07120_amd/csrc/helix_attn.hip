@@ -33,7 +33,7 @@ struct Plan {
 };
 
 constexpr int64_t kTargetWorkgroups = 256;   // CUs of an MI355X
-constexpr int64_t kMinSplitTokens = 512;
+constexpr int64_t kMinSplitTokens = 128;        // one block per wave: a launch too small to fill the CUs is latency-bound, shorter runs end sooner
 constexpr int64_t kTargetWorkgroupsMx = 768;    // MXFP4 streams 3.8x fewer bytes per token: three workgroups resident per CU
 constexpr int64_t kTargetWorkgroupsMla = 4096;   // upper end: keeps the split records of a call near 1 GB at most
 constexpr int64_t kMinSplitTokensMla = 4096;
