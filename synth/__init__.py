@@ -11,6 +11,8 @@ heads on one latent) at >=1M-token KV lengths in a simulator (Sec. 3): attention
 shapes only, so i.i.d. N(0,1) tensors of those shapes stand in for real caches.
 """
 import math
+import os
+import sys
 from dataclasses import dataclass, field
 from typing import Optional
 
@@ -63,6 +65,14 @@ def uniform_f32(seed: int, tag: int, start: int, count: int, device) -> torch.Te
 _CHUNK = 1 << 26
 
 
+def _progress(what: str, done: int, total: int) -> None:
+    """With HELIX_SYNTH_PROGRESS set, one line per generated chunk on stderr: under a counter-collecting
+    profiler the generation of a multi-GB workload takes minutes, and a run that shows no sign of life
+    for that long is taken for hung."""
+    if os.environ.get("HELIX_SYNTH_PROGRESS"):
+        print(f"synth: {what} {done}/{total}", file=sys.stderr, flush=True)
+
+
 def normal_bf16(seed: int, tag: int, shape, device="cpu") -> torch.Tensor:
     """N(0,1) rounded to nearest-even bf16, shape ``shape``."""
     n = math.prod(shape)
@@ -70,6 +80,7 @@ def normal_bf16(seed: int, tag: int, shape, device="cpu") -> torch.Tensor:
     for s in range(0, n, _CHUNK):
         c = min(_CHUNK, n - s)
         out[s:s + c] = normal_f32(seed, tag, s, c, device).to(torch.bfloat16)
+        _progress("bf16 elements", s + c, n)
     return out.view(*shape)
 
 
@@ -116,6 +127,7 @@ def normal_e4m3_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", row
         c = min(row_chunk, rows - r)
         x = normal_f32(seed, tag, r * dim, c * dim, device).view(c, dim)
         codes[r:r + c], scale[r:r + c] = quantize_e4m3_per_token(x)
+        _progress("e4m3 rows", r + c, rows)
     return codes, scale
 
 
@@ -152,6 +164,7 @@ def normal_mxfp4_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", ro
         c = min(row_chunk, rows - r)
         x = normal_f32(seed, tag, r * dim, c * dim, device).view(c, dim)
         codes[r:r + c], scales[r:r + c] = quantize_mxfp4(x)
+        _progress("MXFP4 rows", r + c, rows)
     return codes, scales
 
 
