@@ -1,7 +1,8 @@
-"""The benchmark configurations at FULL size, in the launch configuration bench.py times (automatic
-work split): sampled (b, h) rows against the CPU oracle, integer metadata bit-exact, and the GPU's
-sharded-then-combined output against its own unsharded output (max-abs 1e-5) where the
-configuration has several shards."""
+"""The benchmark configurations at FULL size, in the launch configurations bench.py times (automatic
+work split; the two-call path helix_shard_layout + helix_attn_decode and the default one,
+helix_attn_decode_kvp with the sum of the lengths declared): sampled (b, h) rows against the CPU
+oracle, integer metadata bit-exact, both paths against each other, and the GPU's sharded-then-combined
+output against its own unsharded output (max-abs 1e-5) where the configuration has several shards."""
 import numpy as np
 import pytest
 import torch
@@ -37,6 +38,43 @@ def decode(hx, w, inp, n_shards, want_parts=False):
     hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse, o_partials=parts, lses=lses)
     torch.cuda.synchronize()
     return o, lse, parts, lses, ss
+
+
+def decode_as_bench(hx, w, inp, n_shards):
+    """The step bench.py times: helix_attn_decode_kvp on the whole cache, the sum of the lengths declared."""
+    from paper_2507_07120_amd import harness
+    dev = "cuda"
+    prob = harness.problem_for(w)
+    lens_dev = inp.lens.to(dev)
+    seq_base = inp.seq_off[:-1].to(dev) if inp.seq_off is not None else None
+    max_len = int(inp.lens.max())
+    if inp.k_mx is not None:
+        cache = hx.KVShard.from_mxfp4(inp.k, inp.v, inp.k_mx, inp.v_mx, lens_dev, max_len, tok_off=seq_base)
+    elif inp.k.dim() == 2:
+        cache = hx.KVShard.from_packed(inp.k, lens_dev, max_len, seq_base, kv_scale=inp.kv_scale)
+    else:
+        cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, max_len, kv_scale=inp.kv_scale)
+    cache.sum_len = int(inp.lens.sum())
+    ws = harness.workspace_for(prob, n_shards, max_len, dev)
+    o = torch.full((w.B, w.Q, w.dv), float("nan"), device=dev)
+    lse = torch.full((w.B, w.Q), float("nan"), device=dev)
+    off = torch.empty((n_shards, w.B), dtype=torch.int64, device=dev)
+    ln = torch.empty((n_shards, w.B), dtype=torch.int32, device=dev)
+    hx.helix_attn_decode_kvp(prob, inp.q, cache, n_shards, o, ws, lse_out=lse, shard_off=off, shard_len=ln)
+    torch.cuda.synchronize()
+    return o, lse, off, ln
+
+
+def check_as_bench(hx, oracle, w, inp, n_shards, o_two_call, lse_two_call, o_ref, lse_ref, rows, what):
+    """The bench's entry point at full size: the cut bit-exact, sampled rows against the oracle, and the whole
+    output against the two-call path (split plans may differ: fp32 summation order only)."""
+    o, lse, off, ln = decode_as_bench(hx, w, inp, n_shards)
+    off_ref, len_ref = oracle.shard_layout(inp.lens.numpy(), n_shards)
+    base = inp.seq_off[:-1].numpy()[None, :] if inp.seq_off is not None else 0
+    assert np.array_equal(off.cpu().numpy(), off_ref + base) and np.array_equal(ln.cpu().numpy(), len_ref)
+    check_rows(o, lse, o_ref, lse_ref, rows, what + " (helix_attn_decode_kvp)")
+    assert (o - o_two_call).abs().max().item() <= SHARD_VS_UNSHARDED
+    assert (lse - lse_two_call).abs().max().item() <= 1e-5
 
 
 def oracle_rows(oracle, w, inp, rows):
@@ -84,6 +122,7 @@ def test_gqa_share_full(hx, oracle):
     rows = [(0, 0), (3, 7), (9, 15), (15, 4)]
     o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
     check_rows(o, lse, o_ref, lse_ref, rows, "gqa_share full size")
+    check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "gqa_share full size")
 
 
 def test_mla_share_full(hx, oracle):
@@ -94,6 +133,7 @@ def test_mla_share_full(hx, oracle):
     rows = [(0, 0), (0, 77), (17, 127), (31, 64)]
     o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
     check_rows(o, lse, o_ref, lse_ref, rows, "mla_share full size")
+    check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "mla_share full size")
 
 
 def test_gqa_full_sharded_vs_unsharded_and_oracle(hx, oracle):
@@ -120,6 +160,7 @@ def test_gqa_full_sharded_vs_unsharded_and_oracle(hx, oracle):
     o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
     check_rows(o16, lse16, o_ref, lse_ref, rows, "gqa_full sharded")
     check_rows(o1, lse1, o_ref, lse_ref, rows, "gqa_full unsharded")
+    check_as_bench(hx, oracle, w, inp, 16, o16, lse16, o_ref, lse_ref, rows, "gqa_full sharded")
 
 
 def test_mla_fp8_ragged_full(hx, oracle):
@@ -141,6 +182,7 @@ def test_mla_fp8_ragged_full(hx, oracle):
     rows = [(b_short, 3), (b_long, 100), (7, 64)]
     o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
     check_rows(o8, lse8, o_ref, lse_ref, rows, "mla_fp8_ragged sharded")
+    check_as_bench(hx, oracle, w, inp, 8, o8, lse8, o_ref, lse_ref, rows, "mla_fp8_ragged sharded")
 
 
 def test_gqa_share_mxfp4_full(hx, oracle):
@@ -153,6 +195,7 @@ def test_gqa_share_mxfp4_full(hx, oracle):
     rows = [(0, 0), (5, 9), (15, 15)]
     o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
     check_rows(o, lse, o_ref, lse_ref, rows, "gqa_share_mxfp4")
+    check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "gqa_share_mxfp4")
     o4, lse4, _, _, _ = decode(hx, w, inp, 4)
     d = (o4 - o).abs().max().item()
     print(f"gqa_share_mxfp4: 4 shards vs unsharded max-abs {d:.3e}")
@@ -169,6 +212,7 @@ def test_mla_share_mxfp4_full(hx, oracle):
     rows = [(0, 0), (11, 77), (31, 127)]
     o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
     check_rows(o, lse, o_ref, lse_ref, rows, "mla_share_mxfp4")
+    check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "mla_share_mxfp4")
     o8, lse8, _, _, _ = decode(hx, w, inp, 8)
     d = (o8 - o).abs().max().item()
     print(f"mla_share_mxfp4: 8 shards vs unsharded max-abs {d:.3e}")
@@ -193,3 +237,4 @@ def test_mla_mxfp4_ragged_full(hx, oracle):
     rows = [(int(lens.argmin()), 3), (odd[0] if odd else 1, 100)]
     o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
     check_rows(o8, lse8, o_ref, lse_ref, rows, "mla_mxfp4_ragged sharded")
+    check_as_bench(hx, oracle, w, inp, 8, o8, lse8, o_ref, lse_ref, rows, "mla_mxfp4_ragged sharded")
