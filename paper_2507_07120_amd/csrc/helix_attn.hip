@@ -112,9 +112,9 @@ int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, const 
     } else {
         // MLA is compute-bound, one workgroup per CU at a time, and sequence lengths may be ragged (the
         // host only knows the longest): short runs of 4096 tokens let the dispatcher balance the CUs.
-        // Measured: the ragged e4m3 workload takes 4.7 ms with 4096-token runs, 5.2 with 8192, 6.7 with
-        // one run per (shard, sequence); the uniform bf16 share loses 3 % against its best (8192).  The
-        // 256 KB record of a run is 5-11 % of the latent bytes it reads.
+        // Measured (runs ordered by run_order_kernel): the ragged e4m3 workload takes 2.81 ms with 4096-token
+        // runs, 2.90 with 3072 or 8192, 3.00 with 2048; the uniform bf16 share loses 1 % (3 % of the whole
+        // step) against its best (8192).  The 256 KB record of a run is 5-11 % of the latent bytes it reads.
         const int64_t target = target_workgroups(path);
         const int64_t floor_tokens = path == Path::Mla ? kMinSplitTokensMla : kMinSplitTokens;
         const int64_t work = path == Path::Mla ? rows * total : rows / p->batch * tokens;   // token rows to stream
