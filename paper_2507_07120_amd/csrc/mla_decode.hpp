@@ -589,7 +589,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     // f = row & 7 = r & 7: the low two bits of f permute kc, bit 2 swaps k-steps 2j and 2j+1 -> one
     // per-lane base, +-64 bytes, immediates for ks and the half.  Reads run PD k-steps ahead.
     auto scores = [&](const lds_byte* ktile, f32x4& s0, f32x4& s1) {
-        constexpr int PD = 3;
+        constexpr int PD = MX ? 2 : 3;           // measured: MXFP4 2.3 % faster with 2, e4m3 1 % slower, bf16 unchanged
         u32x4 k0[C::KS], k1[C::KS];
         const int l = mla_opaque(lane), r = l & 15, kc = l >> 4;
         const int f = r & 7;
