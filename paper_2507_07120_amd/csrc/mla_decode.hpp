@@ -855,13 +855,15 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
                 f32x4 s0, s1;
                 scores(ktile_of(slot), s0, s1);
                 softmax(s0, s1, slot, valid_of(it));
-                if (!FP8 && it + 1 < n_tiles) stage_commit(it + 1, slot1, 0);
+                // the next tile is completed here (bf16: its DMA awaited; MXFP4: widened -- measured 1.6-2 %
+                // faster here than at the start of the P phase, the e4m3 widening 1 % slower)
+                if ((!FP8 || MX) && it + 1 < n_tiles) stage_commit(it + 1, slot1, 0);
             }
             mla_barrier();
             {   // P phase
                 // e4m3: the next tile is widened here rather than in the S phase, which is the longer one
                 // and the one that loads LDS most; its staging area is free again for the request below
-                if (FP8 && it + 1 < n_tiles) stage_commit(it + 1, slot1, 0);
+                if (FP8 && !MX && it + 1 < n_tiles) stage_commit(it + 1, slot1, 0);
                 const bool more = it + AHEAD < n_tiles;
                 if (more) stage_begin();
                 pv(ktile_of(slot), [&](int j) { if (more && j < PARTS) stage_issue_part(it + AHEAD, slot2, j); });
