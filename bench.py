@@ -3,15 +3,22 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gqa_share] [--split-tokens T]
 
 One step = one pass of the whole hot path over one batch of synthetic input already resident in
-HBM: the KVP shard layout kernel, the streaming attention over every shard, the merge of the split
+HBM: the KVP cut of every sequence, the streaming attention over every shard, the merge of the split
 records into per-shard (O_i, lse_i), and the LSE combine.  Prints ONE JSON line.  The metric is the
 achieved HBM rate of KV streaming: algorithmic KV bytes of the step (Appendix A's numerator for the
 workload's shapes) divided by the step time.
+
+The headline (`value`, `config`, `roofline`, `cpu_baseline`) is the workload given by --workload.  With
+the default workload the same line also carries, under `configs`, one entry per remaining benchmark
+configuration (same K and W, each with its own roofline and a bounded cpu_baseline) and, under
+`ceilings`, what the part sustains for a bare streaming read with the GQA launch shape and for an
+LDS-fed MFMA loop (the two probes of the library) -- so that every fraction quoted anywhere is on
+the clock of this one run.
 """
 import argparse
 import ctypes
+import gc
 import json
-import math
 import os
 import sys
 import time
@@ -22,6 +29,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 and fp16
+HEADLINE = "gqa_share"
+OTHER_CONFIGS = ["tiny_gqa", "mla_share", "gqa_full", "mla_fp8_ragged"]   # the remaining benchmark configurations
 
 
 def kv_bytes_per_step(w, lens) -> int:
@@ -107,7 +116,8 @@ def cpu_baseline(w, inp, budget_macs=1.5e11):
 
 
 def read_traffic(workload: str):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (the counters
+    cannot be read from inside this process; the file names the commands that produced it)."""
     path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
     if not os.path.exists(path):
         return None
@@ -117,44 +127,22 @@ def read_traffic(workload: str):
     return None
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="gqa_share")
-    ap.add_argument("--split-tokens", type=int, default=0)
-    ap.add_argument("--settle-seconds", type=float, default=1.0,
-                    help="untimed: repeat the step for this long before the warmup steps, so that the part's memory "
-                         "and fabric clocks have left their idle state (a fresh process otherwise measures the ramp)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--two-call", action="store_true",
-                    help="time the step as helix_shard_layout + helix_attn_decode (two entry points, one more "
-                         "launch) instead of helix_attn_decode_kvp, which cuts the slices inside the kernel")
-    ap.add_argument("--hopb", type=int, default=0, metavar="G",
-                    help="also time the batch cut into G request groups whose exchange + combine run on a second "
-                         "stream under the next group's attention (Sec. 2.1.3), against the same call on one stream")
-    ap.add_argument("--graph", type=int, default=0, metavar="G",
-                    help="also capture G consecutive steps into one HIP graph and time its replays (launch-bound "
-                         "configurations: the library only enqueues kernels, so a step is capturable as it is)")
-    ap.add_argument("--pmc-calibration", action="store_true",
-                    help="also run a plain 1 GiB device copy (torch copy_) before the timed loop, so that a "
-                         "rocprofv3 --pmc run holds a kernel of known traffic to scale the counters by")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (all KV shards live on it; there is no collective "
-              "path). Re-run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
+def kernel_name(w) -> str:
+    if w.mla:
+        return "mla_decode_kernel<" + ("mxfp4" if getattr(w, "fp4", False) else "e4m3" if w.fp8 else "bf16") + ">"
+    return "gqa_mxfp4_kernel" if getattr(w, "fp4", False) else f"gqa_decode_kernel<{w.dk}>"
 
+
+def measure(name, args, budget_macs, extras=False):
+    """Times workload `name`: K steps of the whole path, then the same K steps through the timed entry
+    point (an event pair around the streaming kernel of every step).  Returns the entry of the JSON line."""
     import torch
     import paper_2507_07120_amd as hx
     import synth
     from paper_2507_07120_amd import harness
 
-    hx.load_library()                       # raises if the HIP library is not built
-    assert torch.cuda.is_available(), "bench.py needs the GPU"
     dev = "cuda:0"
-    w = synth.WORKLOADS[args.workload]
+    w = synth.WORKLOADS[name]
     inp = synth.make_inputs(w, dev)
     prob = harness.problem_for(w, args.split_tokens)
     lens_dev = inp.lens.to(dev)
@@ -162,14 +150,6 @@ def main():
     N = w.n_shards
     shard_off = torch.empty((N, w.B), dtype=torch.int64, device=dev)
     shard_len = torch.empty((N, w.B), dtype=torch.int32, device=dev)
-    # the host knows the lengths it generated: it declares their sum (only a ragged batch is planned differently)
-    ss = harness.make_shards(inp.k, inp.v, lens_dev, N, kv_scale=inp.kv_scale, seq_base=seq_base,
-                             mx=None if inp.k_mx is None else (inp.k_mx, inp.v_mx), declare_sums=True)
-    ws = harness.workspace_for(prob, N, max(ss.max_lens), dev)
-    o = torch.empty((w.B, w.Q, w.dv), device=dev)
-    lse = torch.empty((w.B, w.Q), device=dev)
-    split_tokens, workgroups = hx.helix_attn_plan(prob, ss.max_lens, [s.sum_len for s in ss.shards])
-
     max_len = int(inp.lens.max())
     if inp.k_mx is not None:
         cache = hx.KVShard.from_mxfp4(inp.k, inp.v, inp.k_mx, inp.v_mx, lens_dev, max_len, tok_off=seq_base)
@@ -177,19 +157,32 @@ def main():
         cache = hx.KVShard.from_packed(inp.k, lens_dev, max_len, seq_base, kv_scale=inp.kv_scale)
     else:
         cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, max_len, kv_scale=inp.kv_scale)
-    cache.sum_len = int(inp.lens.sum())
+    cache.sum_len = int(inp.lens.sum())       # the host knows the lengths it generated: it declares their sum
+    ws = harness.workspace_for(prob, N, max_len, dev)
+    o = torch.empty((w.B, w.Q, w.dv), device=dev)
+    lse = torch.empty((w.B, w.Q), device=dev)
+
+    # the explicit shard descriptors (the two-call form of the step, HOP-B, and the plan that is reported)
+    ss = harness.make_shards(inp.k, inp.v, lens_dev, N, kv_scale=inp.kv_scale, seq_base=seq_base,
+                             mx=None if inp.k_mx is None else (inp.k_mx, inp.v_mx), declare_sums=True)
+    split_tokens, workgroups = hx.helix_attn_plan(prob, ss.max_lens, [s.sum_len for s in ss.shards])
 
     # one step = the whole path over one batch: the KVP cut of every sequence (integer metadata, written
     # out), the per-slice attention fragments, and their combine
     if args.two_call:
-        def step():
+        def step(events=None):
             hx.helix_shard_layout(lens_dev, N, shard_off, shard_len, seq_base=seq_base)
             hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
     else:
-        def step():
-            hx.helix_attn_decode_kvp(prob, inp.q, cache, N, o, ws, lse_out=lse, shard_off=shard_off, shard_len=shard_len)
+        def step(events=None):
+            hx.helix_attn_decode_kvp(prob, inp.q, cache, N, o, ws, lse_out=lse, shard_off=shard_off, shard_len=shard_len,
+                                     events=events)
 
-    if args.pmc_calibration:
+    def timed_step(events):
+        # the streaming kernel is the same in both forms of the step; only this entry point takes events
+        hx.helix_attn_decode_kvp(prob, inp.q, cache, N, o, ws, lse_out=lse, shard_off=shard_off, shard_len=shard_len, events=events)
+
+    if extras and args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
         for _ in range(3):
@@ -216,11 +209,9 @@ def main():
     ev = HipEvents(args.steps)
     t1 = time.perf_counter()
     for i in range(args.steps):
-        hx.helix_attn_set_profile_events(ev.start[i], ev.stop[i])
-        step()
+        timed_step((ev.start[i], ev.stop[i]))
     torch.cuda.synchronize()
     dt_hooked = time.perf_counter() - t1
-    hx.helix_attn_set_profile_events(None, None)
     kern_ms = sorted(ev.elapsed_ms(i) for i in range(args.steps))
     ev.destroy()
     kern_avg_ms = sum(kern_ms) / len(kern_ms)
@@ -229,31 +220,33 @@ def main():
     kv_bytes = kv_bytes_per_step(w, inp.lens.tolist())
     flops = flops_per_step(w, inp.lens.tolist())
     value = kv_bytes / (ms_per_step * 1e-3) / 1e9
-    bound_mfma = w.mla
-    if bound_mfma:
+    hbm_of_kernel = kv_bytes / (kern_avg_ms * 1e-3) / 1e9
+    if w.mla:
         achieved = flops / (kern_avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / MFMA_BF16_PEAK_TFLOPS}
+                "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": flops}
     else:
-        achieved = kv_bytes / (kern_avg_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS}
-    roof["traffic"] = read_traffic(args.workload)
-    roof["kernel"] = "mla_decode_kernel" if w.mla else "gqa_mxfp4_kernel" if getattr(w, "fp4", False) else f"gqa_decode_kernel<{w.dk}>"
+        roof = {"bound": "hbm", "achieved": hbm_of_kernel, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": hbm_of_kernel / HBM_PEAK_GBS}
+    roof["traffic"] = read_traffic(name)
+    roof["traffic_source"] = None if roof["traffic"] is None else f"profiles/traffic_{name}.txt (rocprofv3 --pmc, committed)"
+    roof["kernel"] = kernel_name(w)
     roof["kernel_us_avg"] = kern_avg_ms * 1e3
     roof["kernel_us_min"] = kern_ms[0] * 1e3
+    roof["kernel_timing"] = ("hipEvent pair around the streaming kernel in a second loop of the same K steps "
+                             "(helix_attn_decode_kvp_timed); that loop's step time is us_per_step_with_event_hooks")
     roof["algorithmic_bytes"] = kv_bytes
-    roof["hbm_gbs_of_kernel"] = kv_bytes / (kern_avg_ms * 1e-3) / 1e9
+    roof["hbm_gbs_of_kernel"] = hbm_of_kernel
+    roof["hbm_frac_of_kernel"] = hbm_of_kernel / HBM_PEAK_GBS
+    if name == "tiny_gqa":
+        roof["note"] = "2 MiB of KV: launch- and latency-bound and cache-resident; the microseconds are the result"
 
-    out = {
-        "metric": "KV-shard decode attention achieved HBM GB/s (% of peak); us per decode step",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+    entry = {
         "ms_per_step": ms_per_step, "us_per_step": ms_per_step * 1e3,
         "us_per_step_with_event_hooks": dt_hooked / args.steps * 1e6,
-        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        # arithmetic type of the contractions: the e4m3 latent is widened to fp16 (same MFMA rate as bf16)
-        "dtype": "f16" if (w.mla and (w.fp8 or getattr(w, "fp4", False))) else "bf16", "data": "synthetic",
+        "value": value, "unit": "GB/s", "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBS,
+        # arithmetic type of the contractions: the e4m3 and MXFP4 latents are widened to fp16 (same MFMA rate as bf16)
+        "dtype": "f16" if (w.mla and (w.fp8 or getattr(w, "fp4", False))) else "bf16",
         "config": {"workload": w.name, "B": w.B, "q_heads": w.Q, "kv_heads": w.K, "dk": w.dk, "dv": w.dv,
                    "n_shards": N, "tokens_per_step": int(sum(inp.lens.tolist())) * w.K,
                    "kv_dtype": "e4m3+fp32 scale" if w.fp8 else "mxfp4 (e2m1 + e8m0 per 32)" if getattr(w, "fp4", False) else "bf16",
@@ -261,7 +254,7 @@ def main():
                    "entry": "helix_shard_layout + helix_attn_decode" if args.two_call else "helix_attn_decode_kvp"},
         "roofline": roof,
     }
-    if args.graph > 0:
+    if extras and args.graph > 0:
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             for _ in range(args.graph):
@@ -274,10 +267,9 @@ def main():
         for _ in range(reps):
             g.replay()
         torch.cuda.synchronize()
-        out["graph"] = {"steps_per_graph": args.graph, "replays": reps,
-                        "us_per_step": (time.perf_counter() - tg) / (reps * args.graph) * 1e6}
-    if args.hopb > 0:
-        mx = None if inp.k_mx is None else (inp.k_mx, inp.v_mx)
+        entry["graph"] = {"steps_per_graph": args.graph, "replays": reps,
+                          "us_per_step": (time.perf_counter() - tg) / (reps * args.graph) * 1e6}
+    if extras and args.hopb > 0:
         nbytes = hx.helix_attn_hopb_workspace_bytes(prob, N, max(ss.max_lens), args.hopb)
         ws_h = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         bufs = hx.HopbBuffers(prob, N, args.hopb, dev)
@@ -292,11 +284,120 @@ def main():
                 hx.helix_attn_decode_hopb(prob, inp.q, ss.shards, o, ws_h, bufs, cs, exchange_stream, lse_out=lse)
             torch.cuda.synchronize()
             return (time.perf_counter() - t) / args.steps * 1e6
-        out["hopb"] = {"groups": args.hopb, "us_per_step_two_streams": timed(xs), "us_per_step_one_stream": timed(cs),
-                       "note": "per-shard attention + device copy of the fragments (stand-in for the All-to-All) + combine; "
-                               "no shard_layout call in these steps"}
+        entry["hopb"] = {"groups": args.hopb, "us_per_step_two_streams": timed(xs), "us_per_step_one_stream": timed(cs),
+                         "note": "per-shard attention + device copy of the fragments (stand-in for the All-to-All) + combine; "
+                                 "no shard_layout call in these steps"}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, inp)
+        entry["cpu_baseline"] = cpu_baseline(w, inp, budget_macs)
+    return entry
+
+
+def ceilings(args):
+    """The two probes of the library, timed with events on this run's clock: a bare streaming read with the
+    GQA kernels' launch shape (256 workgroups of 4 waves, one contiguous chunk each) and 16x16x32 bf16 MFMAs
+    fed from LDS, with Gaussian and with all-zero operands (the part's clock depends on the data)."""
+    import torch
+    import paper_2507_07120_amd as hx
+    import synth
+    dev = "cuda:0"
+    out = {}
+    buf = synth.normal_bf16(4242, 1, (1 << 29,), dev)                 # 1 GiB of N(0,1) bf16
+
+    def timed(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    for label, nt in (("stream_read_nontemporal", True), ("stream_read_plain", False)):
+        nbytes = buf.numel() * 2
+        s = timed(lambda: hx.helix_probe_stream_read(buf, 256, nt), max(5, min(args.steps, 50)))
+        out[label] = {"GB/s": nbytes / s / 1e9, "us": s * 1e6, "bytes": nbytes, "workgroups": 256,
+                      "frac_of_hbm_peak": nbytes / s / 1e9 / HBM_PEAK_GBS}
+    iters = 16000
+    zeros = torch.zeros(1 << 15, dtype=torch.bfloat16, device=dev)
+    for label, operands, stream in (("mfma_lds_gauss", buf, None), ("mfma_lds_gauss_streaming", buf, buf),
+                                    ("mfma_lds_zeros", zeros, None)):
+        flops = [0.0, 0.0]
+
+        def fn():
+            flops[0], flops[1] = hx.helix_probe_mfma_lds(operands, iters, stream)
+        s = timed(fn, 3)
+        out[label] = {"TFLOP/s": flops[0] / s / 1e12, "ms": s * 1e3, "frac_of_mfma_peak": flops[0] / s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        if stream is not None:
+            out[label]["GB/s"] = flops[1] / s / 1e9
+            out[label]["flop_per_byte"] = flops[0] / flops[1]
+    out["note"] = ("stream_read_*: helix_probe_stream_read over 1 GiB; mfma_lds_*: helix_probe_mfma_lds, 8 waves per CU, "
+                   "A operand from LDS at every MFMA, N(0,1) bf16 or zero operands; *_streaming adds 1 KB of HBM read per wave and 16 MFMAs")
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=HEADLINE)
+    ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--settle-seconds", type=float, default=1.0,
+                    help="untimed: repeat the step for this long before the warmup steps, so that the part's memory "
+                         "and fabric clocks have left their idle state (a fresh process otherwise measures the ramp)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="with the default workload: leave out the other configurations and the ceiling probes")
+    ap.add_argument("--two-call", action="store_true",
+                    help="time the step as helix_shard_layout + helix_attn_decode (two entry points, one more "
+                         "launch) instead of helix_attn_decode_kvp, which cuts the slices inside the kernel")
+    ap.add_argument("--hopb", type=int, default=0, metavar="G",
+                    help="also time the batch cut into G request groups whose exchange + combine run on a second "
+                         "stream under the next group's attention (Sec. 2.1.3), against the same call on one stream")
+    ap.add_argument("--graph", type=int, default=0, metavar="G",
+                    help="also capture G consecutive steps into one HIP graph and time its replays (launch-bound "
+                         "configurations: the library only enqueues kernels, so a step is capturable as it is)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (torch copy_) before the timed loop, so that a "
+                         "rocprofv3 --pmc run holds a kernel of known traffic to scale the counters by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all KV shards live on it; there is no collective "
+              "path). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2507_07120_amd as hx
+
+    hx.load_library()                       # raises if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+
+    head = measure(args.workload, args, budget_macs=1.5e11, extras=True)
+    out = {
+        "metric": "KV-shard decode attention achieved HBM GB/s (% of peak); us per decode step",
+        "value": head["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "us_per_step": head["us_per_step"],
+        "us_per_step_with_event_hooks": head["us_per_step_with_event_hooks"],
+        "pct_of_hbm_peak": head["pct_of_hbm_peak"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": head["dtype"], "data": "synthetic", "config": head["config"], "roofline": head["roofline"],
+    }
+    for k in ("graph", "hopb", "cpu_baseline"):
+        if k in head:
+            out[k] = head[k]
+    if args.workload == HEADLINE and not args.headline_only:
+        out["configs"] = []
+        for name in OTHER_CONFIGS:
+            gc.collect()
+            torch.cuda.empty_cache()
+            # a smaller oracle sample per extra configuration keeps the whole run within a couple of minutes
+            out["configs"].append(measure(name, args, budget_macs=4e10))
+        gc.collect()
+        torch.cuda.empty_cache()
+        out["ceilings"] = ceilings(args)
     print(json.dumps(out))
 
 

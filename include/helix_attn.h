@@ -25,7 +25,9 @@
  *     (helix_problem, helix_kv_shard, the shard array) are host memory, read during the call.
  *   - The caller owns every buffer, including the workspace.  The library allocates nothing,
  *     never synchronises, never reads device memory from the host; all work is enqueued on the
- *     HIP stream passed as `hip_stream` (a hipStream_t; NULL = the default stream).
+ *     HIP stream passed as `hip_stream` (a hipStream_t; NULL = the default stream).  No call leaves
+ *     state behind for the next one (the only process-wide state is a set of once-flags for a kernel
+ *     attribute), so calls from several threads on their own streams and buffers are independent.
  *   - Every call returns a helix_status.  Arguments are validated on the host before anything
  *     is launched, so an error return means no kernel ran.
  *   - Supported shapes: (dk,dv) = (64,64) or (128,128) with bf16 K/V and any Q/K group size
@@ -117,7 +119,15 @@ typedef struct helix_kv_shard {
                                (batch * max_len is assumed).  A ragged batch that says so gets runs sized for
                                the tokens it has and workgroups that take the non-empty runs first; results
                                do not depend on it. */
+    int32_t *status;        /* device int32 or NULL: the attention kernels OR HELIX_STATUS_* bits into it when they
+                               meet device data the host could not check (the caller clears it; it is only ever
+                               written when a condition holds) */
 } helix_kv_shard;
+
+/* Bits of helix_kv_shard.status.  The launch is sized from the host's max_len; a sequence whose device-side
+ * len[b] is larger (e.g. after helix_kv_append without raising max_len) has its surplus tokens left out of
+ * the attention, and this bit says so. */
+#define HELIX_STATUS_LEN_EXCEEDS_MAX 1
 
 /* Bytes of workspace helix_attn_partial / helix_attn_decode need for `n_shards` shards whose
  * max_len are all <= `max_len`.  Returns 0 if the problem is invalid or unsupported.
@@ -264,12 +274,34 @@ double helix_weight_read_seconds(int64_t H, int64_t Q, int64_t K, int64_t Hsz, i
 int helix_attn_plan(const helix_problem *problem, const int32_t *max_lens, const int64_t *sum_lens, int32_t n_shards,
                     int32_t *split_tokens, int64_t *workgroups);
 
-/* Instrumentation for benchmarks: while both are non-NULL (hipEvent_t handles), every following
- * helix_attn_partial / helix_attn_decode records `start` immediately before and `stop` immediately
- * after its streaming attention kernel launches, on the call's stream, so the caller can read that
- * kernel's duration with hipEventElapsedTime.  Pass NULL, NULL to switch it off (the default).
- * Process-wide state, not thread-safe; the events stay owned by the caller. */
-int helix_attn_set_profile_events(void *start_event, void *stop_event);
+/* helix_attn_decode_kvp for benchmarks: additionally records `start_event` immediately before and `stop_event`
+ * immediately after the call's streaming attention kernel launches (not the small kernels around them), on the
+ * call's stream, so that the caller can read that kernel's duration with hipEventElapsedTime.  Both are
+ * hipEvent_t handles owned by the caller and must not be NULL.  No state outlives the call. */
+int helix_attn_decode_kvp_timed(const helix_problem *problem, const void *q, const helix_kv_shard *cache,
+                                int32_t n_shards, float *o, float *lse_out, float *o_partials, float *lses,
+                                int64_t *shard_off, int32_t *shard_len,
+                                void *workspace, size_t workspace_bytes, void *hip_stream,
+                                void *start_event, void *stop_event);
+
+/* Ceiling probes for benchmarks: kernels that do nothing but the memory or matrix access pattern the attention
+ * kernels are built on, so that "fraction of what this part sustains" can be measured beside "fraction of the
+ * published peak".  Each call enqueues ONE kernel on hip_stream; the caller times it.
+ *
+ * helix_probe_stream_read: a bare streaming read of `bytes` bytes (a multiple of 16384) of `buf` with the launch
+ *   shape of the GQA attention kernels: `workgroups` workgroups of 4 waves, each reading one contiguous chunk
+ *   in blocks of 16 KB with 16 x 16-byte loads per lane in flight; nontemporal != 0 uses non-temporal loads as
+ *   the attention kernels do.  Nothing is written. */
+int helix_probe_stream_read(const void *buf, size_t bytes, int32_t workgroups, int32_t nontemporal, void *hip_stream);
+
+/* helix_probe_mfma_lds: 256 workgroups of 8 waves, each wave issuing `iters` x 8 16x16x32 bf16 MFMAs (iters a
+ *   multiple of 8) whose A operand is read from LDS at every instruction; the LDS holds the first 64 KB of
+ *   `operands` (bf16 values of the caller's choice: the rate depends on the data).  With stream_buf != NULL every
+ *   wave also reads 1 KB of it (non-temporal, addressed modulo stream_bytes, a power of two >= 4 MiB) per 16
+ *   MFMAs: 256 flop per byte, the MLA path's ratio of matrix work to HBM bytes.  *flops and *bytes_read (host, may be NULL) receive
+ *   the launch's totals. */
+int helix_probe_mfma_lds(const void *operands, int32_t iters, const void *stream_buf, size_t stream_bytes,
+                         double *flops, double *bytes_read, void *hip_stream);
 
 /* Static, NUL-terminated description of a status code. */
 const char *helix_status_string(int status);

@@ -20,13 +20,14 @@ from .binding import (  # noqa: F401
     helix_attn_hopb_workspace_bytes,
     helix_attn_partial,
     helix_attn_plan,
-    helix_attn_set_profile_events,
     helix_attn_workspace_bytes,
     helix_hopb_span,
     helix_kv_append,
     helix_kv_append_mxfp4,
     helix_kv_append_owner,
     helix_kv_read_seconds,
+    helix_probe_mfma_lds,
+    helix_probe_stream_read,
     helix_shard_layout,
     helix_status_string,
     helix_weight_read_seconds,

@@ -37,7 +37,8 @@ class _CShard(ctypes.Structure):
                 ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
                 ("s_stride_b", ctypes.c_int64), ("s_stride_h", ctypes.c_int64),
                 ("tok_off", ctypes.c_void_p), ("len", ctypes.c_void_p), ("max_len", ctypes.c_int32),
-                ("k_scale_mx", ctypes.c_void_p), ("v_scale_mx", ctypes.c_void_p), ("sum_len", ctypes.c_int64)]
+                ("k_scale_mx", ctypes.c_void_p), ("v_scale_mx", ctypes.c_void_p), ("sum_len", ctypes.c_int64),
+                ("status", ctypes.c_void_p)]
 
 
 def library_path() -> str:
@@ -99,8 +100,12 @@ def load_library():
     lib.helix_kv_read_seconds.argtypes = [i64, i64, i64, f64, f64, f64, i64, i64]
     lib.helix_weight_read_seconds.restype = f64
     lib.helix_weight_read_seconds.argtypes = [i64, i64, i64, i64, i64, f64, f64, i64, i64]
-    lib.helix_attn_set_profile_events.restype = ctypes.c_int
-    lib.helix_attn_set_profile_events.argtypes = [vp, vp]
+    lib.helix_attn_decode_kvp_timed.restype = ctypes.c_int
+    lib.helix_attn_decode_kvp_timed.argtypes = lib.helix_attn_decode_kvp.argtypes + [vp, vp]
+    lib.helix_probe_stream_read.restype = ctypes.c_int
+    lib.helix_probe_stream_read.argtypes = [vp, ctypes.c_size_t, i32, i32, vp]
+    lib.helix_probe_mfma_lds.restype = ctypes.c_int
+    lib.helix_probe_mfma_lds.argtypes = [vp, i32, vp, ctypes.c_size_t, ctypes.POINTER(f64), ctypes.POINTER(f64), vp]
     _lib = lib
     return lib
 
@@ -143,6 +148,7 @@ class KVShard:
     k_scale_mx: Optional[torch.Tensor] = None   # MXFP4: uint8 block scales, k / v are uint8 codes and
     v_scale_mx: Optional[torch.Tensor] = None   # the strides count elements (two per byte)
     sum_len: int = 0                            # host copy of an upper bound of sum(len), 0 = unknown (a hint for ragged batches)
+    status: Optional[torch.Tensor] = None       # int32 [1] on the device: HELIX_STATUS_* bits the kernels raise
 
     @staticmethod
     def from_padded(k: torch.Tensor, v: Optional[torch.Tensor], lens: torch.Tensor, max_len: int,
@@ -196,10 +202,12 @@ class KVShard:
             assert self.tok_off.dtype == torch.int64 and self.tok_off.is_contiguous()
         if self.kv_scale is not None:
             assert self.kv_scale.dtype == torch.float32
+        if self.status is not None:
+            assert self.status.dtype == torch.int32 and self.status.numel() == 1
         return _CShard(ptr(self.k), ptr(self.v), ptr(self.kv_scale), *[int(x) for x in self.k_strides],
                        *[int(x) for x in self.v_strides], *[int(x) for x in self.s_strides],
                        ptr(self.tok_off), ptr(self.len), int(self.max_len), ptr(self.k_scale_mx), ptr(self.v_scale_mx),
-                       int(self.sum_len))
+                       int(self.sum_len), ptr(self.status))
 
 
 def _stream_ptr(stream) -> Optional[int]:
@@ -309,11 +317,6 @@ def helix_shard_layout(seq_len: torch.Tensor, n_shards: int, shard_off: torch.Te
            "helix_shard_layout")
 
 
-def helix_attn_set_profile_events(start_event: Optional[int], stop_event: Optional[int]) -> None:
-    """Raw hipEvent_t handles (or None, None) recorded around the streaming attention kernel."""
-    _check(load_library().helix_attn_set_profile_events(start_event, stop_event), "helix_attn_set_profile_events")
-
-
 def helix_kv_append_owner(decode_index: int, n_shards: int) -> int:
     return int(load_library().helix_kv_append_owner(int(decode_index), int(n_shards)))
 
@@ -380,6 +383,25 @@ def helix_hopb_span(n_requests: int, t_attn: float, t_comm: float, pipelined: bo
     return float(load_library().helix_hopb_span(int(n_requests), float(t_attn), float(t_comm), int(bool(pipelined))))
 
 
+def helix_probe_stream_read(buf: torch.Tensor, workgroups: int, nontemporal: bool = True, stream=None) -> int:
+    """Enqueues the bare streaming-read probe over ``buf`` (whole 16 KB blocks); returns the bytes it reads."""
+    assert buf.is_contiguous()
+    nbytes = buf.numel() * buf.element_size() // 16384 * 16384
+    _check(load_library().helix_probe_stream_read(buf.data_ptr(), nbytes, int(workgroups), int(bool(nontemporal)),
+                                                  _stream_ptr(stream)), "helix_probe_stream_read")
+    return nbytes
+
+
+def helix_probe_mfma_lds(operands: torch.Tensor, iters: int, stream_buf: Optional[torch.Tensor] = None, stream=None):
+    """Enqueues the LDS-fed MFMA probe; returns (flops, bytes_read) of the launch."""
+    assert operands.is_contiguous() and operands.numel() * operands.element_size() >= 65536
+    fl, by = ctypes.c_double(0), ctypes.c_double(0)
+    sb, sbytes = (None, 0) if stream_buf is None else (stream_buf.data_ptr(), stream_buf.numel() * stream_buf.element_size())
+    _check(load_library().helix_probe_mfma_lds(operands.data_ptr(), int(iters), sb, sbytes, ctypes.byref(fl), ctypes.byref(by),
+                                               _stream_ptr(stream)), "helix_probe_mfma_lds")
+    return fl.value, by.value
+
+
 def helix_attn_hopb_workspace_bytes(problem: Problem, n_shards: int, max_len: int, n_groups: int) -> int:
     p = problem.c()
     return int(load_library().helix_attn_hopb_workspace_bytes(ctypes.byref(p), n_shards, max_len, n_groups))
@@ -424,8 +446,10 @@ def helix_attn_decode_kvp(problem: Problem, q: torch.Tensor, cache: KVShard, n_s
                           workspace: torch.Tensor, lse_out: Optional[torch.Tensor] = None,
                           o_partials: Optional[torch.Tensor] = None, lses: Optional[torch.Tensor] = None,
                           shard_off: Optional[torch.Tensor] = None, shard_len: Optional[torch.Tensor] = None,
-                          stream=None) -> None:
-    """Layout + decode in one call: ``cache`` describes the unsharded cache, the KVP cut happens in the kernel."""
+                          stream=None, events=None) -> None:
+    """Layout + decode in one call: ``cache`` describes the unsharded cache, the KVP cut happens in the kernel.
+    ``events`` = (start, stop) raw hipEvent_t handles: helix_attn_decode_kvp_timed, which records them around
+    the streaming attention kernel."""
     assert q.dtype == torch.bfloat16 and q.is_contiguous()
     _f32(o, (problem.batch, problem.q_heads, problem.dv), "o")
     if lse_out is not None:
@@ -440,7 +464,10 @@ def helix_attn_decode_kvp(problem: Problem, q: torch.Tensor, cache: KVShard, n_s
 
     def ptr(t):
         return None if t is None else t.data_ptr()
-    _check(load_library().helix_attn_decode_kvp(ctypes.byref(p), q.data_ptr(), ctypes.byref(c), int(n_shards), o.data_ptr(),
-                                                ptr(lse_out), ptr(o_partials), ptr(lses), ptr(shard_off), ptr(shard_len),
-                                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                                _stream_ptr(stream)), "helix_attn_decode_kvp")
+    args = (ctypes.byref(p), q.data_ptr(), ctypes.byref(c), int(n_shards), o.data_ptr(),
+            ptr(lse_out), ptr(o_partials), ptr(lses), ptr(shard_off), ptr(shard_len),
+            workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if events is not None:
+        _check(load_library().helix_attn_decode_kvp_timed(*args, events[0], events[1]), "helix_attn_decode_kvp_timed")
+    else:
+        _check(load_library().helix_attn_decode_kvp(*args), "helix_attn_decode_kvp")

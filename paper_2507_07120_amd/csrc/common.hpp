@@ -38,7 +38,18 @@ struct ShardDev {
     int32_t* out_len;
     const uint8_t* k_mx;  // MXFP4 only: E8M0 block scales, index = element index / 32
     const uint8_t* v_mx;
+    int32_t* status;      // device word the kernels OR status bits into, or NULL
 };
+
+constexpr int kStatusLenExceedsMax = 1;   // HELIX_STATUS_LEN_EXCEEDS_MAX
+
+// The launch holds n_splits runs of split_tokens tokens per sequence (sized from the host's max_len):
+// tokens of a longer sequence are not attended to, which the caller can learn from the status word.
+// Called by one thread of the workgroup that serves a sequence's first run.
+__device__ __forceinline__ void flag_len_overflow(const ShardDev& sh, int len, int split_tokens)
+{
+    if (sh.status && (int64_t)len > (int64_t)sh.n_splits * split_tokens) atomicOr(sh.status, kStatusLenExceedsMax);
+}
 
 // Arguments of an attention launch over up to kMaxLaunchShards shards.
 struct AttnArgs {

@@ -200,7 +200,10 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
     int len;
     int64_t first_row;
     shard_range(sh, b, len, first_row);
-    if (sh.out_off && split == 0 && ht == 0 && kh == 0 && threadIdx.x == 0) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
+    if (split == 0 && ht == 0 && kh == 0 && threadIdx.x == 0) {
+        if (sh.out_off) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
+        flag_len_overflow(sh, len, a.split_tokens);
+    }
     const int t0 = split * a.split_tokens;
     const int t1 = min(t0 + a.split_tokens, len);
     const int h0 = kh * a.g + ht * 16;

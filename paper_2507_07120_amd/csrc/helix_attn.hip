@@ -5,197 +5,35 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
 
+#include "plan.hpp"
 #include "common.hpp"
 #include "gqa_decode.hpp"
 #include "gqa_mxfp4.hpp"
 #include "merge_combine.hpp"
 #include "mla_decode.hpp"
+#include "probes.hpp"
 
 namespace {
 
 using namespace helix;
+using namespace helix_host;
 
-enum class Path { Gqa64, Gqa128, GqaMx128, Mla };
+static_assert(kMlaHeadsPerWorkgroup == MlaCfg::HPW, "the host plan and the MLA kernel agree on the heads of a workgroup");
 
-struct Plan {
-    Path path;
-    int32_t heads_per_wg;   // query heads one workgroup serves
-    int32_t head_tiles;     // workgroups per (b, kv head) along the group
-    int32_t granule;        // split_tokens is a multiple of this
-    int32_t split_tokens;
-    int64_t total_splits;   // over all shards
-    int64_t workgroups;
-    bool ordered;           // the workgroups take their runs from a map written on the device (run_order_kernel)
+// The MLA kernels need more than the default 64 KB of LDS per workgroup, which has to be asked for once per
+// device and kernel; later calls then consist of launches only (and can be captured into a HIP graph).
+// The request is idempotent, so two threads that both find the flag clear may both make it.
+std::atomic<bool> g_lds_asked[3][64];
+
+// hipEvent_t pair recorded around the streaming attention kernel(s) of a call (the timed entry point), or none
+struct KernelEvents {
+    hipEvent_t start = nullptr, stop = nullptr;
 };
-
-constexpr int64_t kTargetWorkgroups = 256;   // CUs of an MI355X
-constexpr int64_t kMinSplitTokens = 128;        // one block per wave: a launch too small to fill the CUs is latency-bound, shorter runs end sooner
-constexpr int64_t kTargetWorkgroupsMx = 768;    // MXFP4 streams 3.8x fewer bytes per token: three workgroups resident per CU
-constexpr int64_t kTargetWorkgroupsMla = 4096;   // upper end: keeps the split records of a call near 1 GB at most
-constexpr int64_t kMinSplitTokensMla = 4096;
-
-inline int64_t target_workgroups(Path path)
-{
-    return path == Path::Mla ? kTargetWorkgroupsMla : path == Path::GqaMx128 ? kTargetWorkgroupsMx : kTargetWorkgroups;
-}
-
-inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
-inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-
-int check_problem(const helix_problem* p, Path* path)
-{
-    if (!p) return HELIX_ERR_NULL;
-    if (p->batch < 1 || p->q_heads < 1 || p->kv_heads < 1 || p->dk < 1 || p->dv < 1) return HELIX_ERR_SHAPE;
-    if (p->q_heads % p->kv_heads != 0) return HELIX_ERR_SHAPE;
-    if (!(p->scale > 0.f) || !std::isfinite(p->scale)) return HELIX_ERR_SHAPE;
-    if (p->split_tokens < 0) return HELIX_ERR_SHAPE;
-    if (p->kv_dtype != HELIX_KV_BF16 && p->kv_dtype != HELIX_KV_FP8_E4M3 && p->kv_dtype != HELIX_KV_MXFP4) return HELIX_ERR_UNSUPPORTED;
-    if (p->v_aliases_k != 0 && p->v_aliases_k != 1) return HELIX_ERR_SHAPE;
-    if (p->v_aliases_k && p->dv > p->dk) return HELIX_ERR_SHAPE;
-    if ((int64_t)p->batch * p->q_heads > (int64_t)1 << 24) return HELIX_ERR_SHAPE;
-    if (!p->v_aliases_k && p->kv_dtype == HELIX_KV_BF16 && p->dk == p->dv && (p->dk == 64 || p->dk == 128)) {
-        *path = p->dk == 64 ? Path::Gqa64 : Path::Gqa128;
-        return HELIX_OK;
-    }
-    if (!p->v_aliases_k && p->kv_dtype == HELIX_KV_MXFP4 && p->dk == 128 && p->dv == 128) {
-        *path = Path::GqaMx128;
-        return HELIX_OK;
-    }
-    if (p->v_aliases_k && p->dk == 576 && p->dv == 512 && p->kv_heads == 1) {
-        *path = Path::Mla;
-        return HELIX_OK;
-    }
-    return HELIX_ERR_UNSUPPORTED;
-}
-
-// Cuts the launch into workgroups.  The streaming kernels are HBM-bound with no reuse.  Measured on
-// MI355X, the read rate is highest with about one long-lived workgroup per CU (256 sequential
-// streams: 6.8 TB/s at 256 workgroups, 6.5 at 512, 6.2 at 1024 on the 1 GiB GQA share), so the
-// target is one workgroup per CU, never less than one per (shard, sequence, kv head, head tile) row,
-// with split records that stay small next to the KV bytes a workgroup streams.
-// Split records a GQA plan may use per (sequence, kv head, head tile) row when a ragged batch asks for
-// runs shorter than its longest sequence needs at one workgroup per CU; the sizing call covers it.
-inline int64_t ragged_split_cap(Path path, int64_t rows, int32_t n)
-{
-    return ceil_div(4 * target_workgroups(path), rows) + n;
-}
-
-int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, const int64_t* sum_lens, int32_t n, Plan* plan)
-{
-    plan->path = path;
-    plan->heads_per_wg = path == Path::Mla ? MlaCfg::HPW : 16;
-    plan->granule = path == Path::Mla ? 32 : 128;         // MLA: 32-token tiles; GQA: 4 waves x 32-token blocks
-    const int g = p->q_heads / p->kv_heads;
-    plan->head_tiles = (int32_t)ceil_div(g, plan->heads_per_wg);
-    const int64_t rows = (int64_t)p->batch * p->kv_heads * plan->head_tiles;
-    int64_t total = 0;       // tokens of a row if every sequence had max_len
-    int64_t tokens = 0;      // tokens of all sequences, as far as the caller has told
-    bool ragged = false;
-    for (int i = 0; i < n; i++) {
-        if (max_lens[i] < 0 || (sum_lens && sum_lens[i] < 0)) return HELIX_ERR_SHAPE;
-        total += max_lens[i];
-        const int64_t full = (int64_t)p->batch * max_lens[i];
-        const bool told = sum_lens && sum_lens[i] > 0 && sum_lens[i] < full;
-        tokens += told ? sum_lens[i] : full;
-        ragged = ragged || told;
-    }
-    // MLA launches always take their runs from the map (one head tile); the streaming kernels do so for
-    // a batch that is declared ragged -- the map costs a launch of its own
-    plan->ordered = path == Path::Mla ? plan->head_tiles == 1 : ragged;
-    int64_t split;
-    if (p->split_tokens > 0) {
-        split = ceil_div(p->split_tokens, plan->granule) * plan->granule;
-    } else {
-        // MLA is compute-bound, one workgroup per CU at a time, and sequence lengths may be ragged (the
-        // host only knows the longest): short runs of 4096 tokens let the dispatcher balance the CUs.
-        // Measured (runs ordered by run_order_kernel): the ragged e4m3 workload takes 2.81 ms with 4096-token
-        // runs, 2.90 with 3072 or 8192, 3.00 with 2048; the uniform bf16 share loses 1 % (3 % of the whole
-        // step) against its best (8192).  The 256 KB record of a run is 5-11 % of the latent bytes it reads.
-        const int64_t target = target_workgroups(path);
-        const int64_t floor_tokens = path == Path::Mla ? kMinSplitTokensMla : kMinSplitTokens;
-        const int64_t work = path == Path::Mla ? rows * total : rows / p->batch * tokens;   // token rows to stream
-        split = ceil_div(ceil_div(work, target), plan->granule) * plan->granule;
-        split = std::max<int64_t>(split, floor_tokens);
-        if (path != Path::Mla && ragged) {
-            // the longest sequence decides how many records a row needs: keep them within the sizing call's bound
-            const int64_t cap = ragged_split_cap(path, rows, n) - n;
-            split = std::max<int64_t>(split, ceil_div(ceil_div(total, cap), plan->granule) * plan->granule);
-        }
-    }
-    if (path == Path::GqaMx128) split = std::min<int64_t>(split, (int64_t)1 << 25);   // 32-bit byte offsets inside a split
-    plan->split_tokens = (int32_t)split;
-    plan->total_splits = 0;
-    for (int i = 0; i < n; i++) plan->total_splits += std::max<int64_t>(1, ceil_div(max_lens[i], split));
-    plan->workgroups = plan->total_splits * rows;   // MLA launches pad this per shard to whole groups of 8
-    if (plan->workgroups > (int64_t)1 << 30) return HELIX_ERR_SHAPE;
-    return HELIX_OK;
-}
-
-struct Workspace {
-    float* ws_o;
-    float* ws_m;
-    float* ws_l;
-    float* part_o;
-    float* part_lse;
-    uint2* units;           // MLA: the run each workgroup serves (run_order_kernel), one entry per split record row
-    size_t bytes;
-};
-
-// Carves a workspace for `total_splits` records and `n` shard partials.  base may be NULL (sizing).
-Workspace carve(const helix_problem* p, int64_t total_splits, int64_t rows, int32_t n, void* base)
-{
-    const size_t bq = (size_t)p->batch * p->q_heads;
-    char* c = static_cast<char*>(base);
-    size_t off = 0;
-    Workspace w;
-    w.ws_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * p->dv * 4, 256);
-    w.ws_m = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * 4, 256);
-    w.ws_l = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * 4, 256);
-    w.part_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * p->dv * 4, 256);
-    w.part_lse = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * 4, 256);
-    w.units = reinterpret_cast<uint2*>(c + off); off = align_up(off + (size_t)total_splits * rows * sizeof(uint2), 256);
-    w.bytes = off;
-    return w;
-}
-
-int check_shard(const helix_problem* p, const helix_kv_shard* s)
-{
-    if (!s->k || !s->len) return HELIX_ERR_NULL;
-    if (p->v_aliases_k ? s->v != nullptr : s->v == nullptr) return p->v_aliases_k ? HELIX_ERR_SHAPE : HELIX_ERR_NULL;
-    const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
-    if (fp8 ? s->kv_scale == nullptr : false) return HELIX_ERR_NULL;
-    if (s->max_len < 0 || s->sum_len < 0) return HELIX_ERR_SHAPE;
-    if (p->kv_dtype == HELIX_KV_MXFP4) {
-        // strides count elements; a row is dk/2 code bytes and dk/32 scale bytes, token rows dense
-        if (!s->k_scale_mx) return HELIX_ERR_NULL;
-        if (s->k_stride_b < 0 || s->k_stride_h < 0 || s->k_stride_b % 128 || s->k_stride_h % 128) return HELIX_ERR_SHAPE;
-        if (reinterpret_cast<uintptr_t>(s->k) % 16 || reinterpret_cast<uintptr_t>(s->k_scale_mx) % 4) return HELIX_ERR_SHAPE;
-        if (s->k_stride_t != p->dk) return HELIX_ERR_UNSUPPORTED;
-        if (p->v_aliases_k) return s->v_scale_mx ? HELIX_ERR_SHAPE : HELIX_OK;      // the latent's scales serve key and value
-        if (!s->v_scale_mx) return HELIX_ERR_NULL;
-        if (s->v_stride_b < 0 || s->v_stride_h < 0 || s->v_stride_b % 128 || s->v_stride_h % 128) return HELIX_ERR_SHAPE;
-        if (reinterpret_cast<uintptr_t>(s->v) % 16 || reinterpret_cast<uintptr_t>(s->v_scale_mx) % 4) return HELIX_ERR_SHAPE;
-        if (s->v_stride_t != p->dv) return HELIX_ERR_UNSUPPORTED;
-        return HELIX_OK;
-    }
-    const int64_t esz = fp8 ? 1 : 2, mult = 16 / esz;
-    if (s->k_stride_t < p->dk || s->k_stride_t > ((int64_t)1 << 24) || s->k_stride_b < 0 || s->k_stride_h < 0) return HELIX_ERR_SHAPE;
-    if (s->k_stride_t % mult || s->k_stride_b % mult || s->k_stride_h % mult) return HELIX_ERR_SHAPE;
-    if (reinterpret_cast<uintptr_t>(s->k) % 16) return HELIX_ERR_SHAPE;
-    if (!p->v_aliases_k) {
-        if (s->v_stride_t < p->dv || s->v_stride_t > ((int64_t)1 << 24) || s->v_stride_b < 0 || s->v_stride_h < 0) return HELIX_ERR_SHAPE;
-        if (s->v_stride_t % mult || s->v_stride_b % mult || s->v_stride_h % mult) return HELIX_ERR_SHAPE;
-        if (reinterpret_cast<uintptr_t>(s->v) % 16) return HELIX_ERR_SHAPE;
-    }
-    if (fp8 && (s->s_stride_b < 0 || s->s_stride_h < 0)) return HELIX_ERR_SHAPE;
-    return HELIX_OK;
-}
-
-hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;   // helix_attn_set_profile_events
 
 int launch_status()
 {
@@ -236,7 +74,8 @@ struct KvpCut {
 // and *finished is set; otherwise the caller still has to combine.
 int run_partials(const helix_problem* p, const Plan& plan, const void* q, const helix_kv_shard* shards, int32_t n,
                  const Workspace& ws, float* o_part, float* lse_part, hipStream_t stream,
-                 float* o = nullptr, float* lse_out = nullptr, bool* finished = nullptr, KvpCut cut = KvpCut())
+                 float* o = nullptr, float* lse_out = nullptr, bool* finished = nullptr, KvpCut cut = KvpCut(),
+                 KernelEvents ev = KernelEvents())
 {
     const bool fuse = o != nullptr && n <= kMaxLaunchShards;
     if (finished) *finished = fuse;
@@ -265,6 +104,7 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             d.v_sb = s.v_stride_b; d.v_sh = s.v_stride_h; d.v_st = s.v_stride_t;
             d.s_sb = s.s_stride_b; d.s_sh = s.s_stride_h;
             d.k_mx = s.k_scale_mx; d.v_mx = s.v_scale_mx;
+            d.status = s.status;
             d.kvp_n = cut.n; d.kvp_i = s0 + i;
             d.out_off = cut.off ? cut.off + (int64_t)(s0 + i) * p->batch : nullptr;
             d.out_len = cut.len ? cut.len + (int64_t)(s0 + i) * p->batch : nullptr;
@@ -280,11 +120,12 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
         // MLA with one head tile: the runs are handed to the workgroups in the order run_order_kernel
         // writes -- full runs first, then partial ones, then empty ones (see there)
         if (plan.ordered) {
-            hipLaunchKernelGGL(helix::run_order_kernel, dim3(1), dim3(helix::kOrderThreads), 0, stream, a, ws.units, (int)units);
+            uint2* map = reinterpret_cast<uint2*>(ws.units);
+            hipLaunchKernelGGL(helix::run_order_kernel, dim3(1), dim3(helix::kOrderThreads), 0, stream, a, map, (int)units);
             if (int rc = launch_status()) return rc;
-            a.units = ws.units;
+            a.units = map;
         }
-        if (g_prof_start && g_prof_stop && s0 == 0) (void)hipEventRecord(g_prof_start, stream);
+        if (ev.start && s0 == 0 && hipEventRecord(ev.start, stream) != hipSuccess) return HELIX_ERR_LAUNCH;
         switch (plan.path) {
             case Path::Gqa64:
                 hipLaunchKernelGGL((gqa_decode_kernel<64>), dim3((unsigned)units), dim3(256), 0, stream, a);
@@ -298,16 +139,13 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             case Path::Mla: {
                 const int kind = p->kv_dtype == HELIX_KV_FP8_E4M3 ? 1 : p->kv_dtype == HELIX_KV_MXFP4 ? 2 : 0;
                 auto kern = kind == 2 ? mla_decode_kernel<true, true> : kind == 1 ? mla_decode_kernel<true> : mla_decode_kernel<false>;
-                // more than the default 64 KB of LDS per workgroup has to be asked for: once per device and
-                // kernel, so that later calls consist of launches only (and can be captured into a HIP graph)
-                static bool asked[3][64];
                 int dev = 0;
                 if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return HELIX_ERR_LAUNCH;
-                if (!asked[kind][dev]) {
+                if (!g_lds_asked[kind][dev].load(std::memory_order_acquire)) {
                     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                             MlaCfg::LDS_BYTES) != hipSuccess)
                         return HELIX_ERR_LAUNCH;
-                    asked[kind][dev] = true;
+                    g_lds_asked[kind][dev].store(true, std::memory_order_release);
                 }
                 hipLaunchKernelGGL(kern, dim3((unsigned)units), dim3(MlaCfg::THREADS), MlaCfg::LDS_BYTES, stream, a);
                 break;
@@ -316,7 +154,7 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
                 return HELIX_ERR_UNSUPPORTED;
         }
         if (int rc = launch_status()) return rc;
-        if (g_prof_start && g_prof_stop && s0 + cnt >= n) (void)hipEventRecord(g_prof_stop, stream);
+        if (ev.stop && s0 + cnt >= n && hipEventRecord(ev.stop, stream) != hipSuccess) return HELIX_ERR_LAUNCH;
         m.ws_o = ws.ws_o; m.ws_m = ws.ws_m; m.ws_l = ws.ws_l;
         m.o_part = o_part; m.lse_part = lse_part;
         m.B = p->batch; m.Q = p->q_heads; m.n_shards = cnt; m.shard0 = s0;
@@ -344,26 +182,6 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
     return HELIX_OK;
 }
 
-int prepare(const helix_problem* p, const helix_kv_shard* shards, int32_t n, void* workspace, size_t workspace_bytes,
-            Plan* plan, Workspace* ws)
-{
-    Path path;
-    if (int rc = check_problem(p, &path)) return rc;
-    if (!shards) return HELIX_ERR_NULL;
-    if (n < 1 || n > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
-    int32_t max_lens[HELIX_MAX_SHARDS];
-    int64_t sum_lens[HELIX_MAX_SHARDS];
-    for (int32_t i = 0; i < n; i++) {
-        if (int rc = check_shard(p, &shards[i])) return rc;
-        max_lens[i] = shards[i].max_len;
-        sum_lens[i] = shards[i].sum_len;
-    }
-    if (int rc = make_plan(p, path, max_lens, sum_lens, n, plan)) return rc;
-    *ws = carve(p, plan->total_splits, (int64_t)p->batch * p->kv_heads * plan->head_tiles, n, workspace);
-    if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || ws->bytes > workspace_bytes) return HELIX_ERR_WORKSPACE;
-    return HELIX_OK;
-}
-
 }  // namespace
 
 extern "C" {
@@ -379,14 +197,6 @@ const char* helix_status_string(int status)
         case HELIX_ERR_LAUNCH: return "HIP launch failed";
         default: return "unknown status";
     }
-}
-
-int helix_attn_set_profile_events(void* start_event, void* stop_event)
-{
-    if ((start_event == nullptr) != (stop_event == nullptr)) return HELIX_ERR_NULL;
-    g_prof_start = static_cast<hipEvent_t>(start_event);
-    g_prof_stop = static_cast<hipEvent_t>(stop_event);
-    return HELIX_OK;
 }
 
 int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, const int64_t* sum_lens, int32_t n_shards,
@@ -405,22 +215,7 @@ int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, const
 
 size_t helix_attn_workspace_bytes(const helix_problem* problem, int32_t n_shards, int32_t max_len)
 {
-    Path path;
-    if (check_problem(problem, &path) != HELIX_OK) return 0;
-    if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS || max_len < 0) return 0;
-    // The plan's split count grows when shards are shorter than max_len (smaller splits keep the
-    // workgroup count up), so size for the worst case over all max_len_i <= max_len.
-    int32_t lens[HELIX_MAX_SHARDS];
-    for (int i = 0; i < n_shards; i++) lens[i] = max_len;
-    Plan plan;
-    if (make_plan(problem, path, lens, nullptr, n_shards, &plan) != HELIX_OK) return 0;
-    const int64_t rows = (int64_t)problem->batch * problem->kv_heads * plan.head_tiles;
-    int64_t worst = plan.total_splits;
-    if (problem->split_tokens == 0) {
-        worst = std::max<int64_t>(worst, ceil_div(target_workgroups(path), rows) + n_shards);
-        if (path != Path::Mla) worst = std::max<int64_t>(worst, ragged_split_cap(path, rows, n_shards));   // a batch declared ragged
-    }
-    return carve(problem, worst, rows, n_shards, nullptr).bytes;
+    return helix_host::workspace_bytes(problem, n_shards, max_len);
 }
 
 int helix_attn_partial(const helix_problem* problem, const void* q, const helix_kv_shard* shard,
@@ -555,27 +350,21 @@ double helix_hopb_span(int32_t n_requests, double t_attn, double t_comm, int32_t
     return t_attn + (n_requests - 1) * std::max(t_attn, t_comm) + t_comm;
 }
 
-int helix_attn_decode_kvp(const helix_problem* problem, const void* q, const helix_kv_shard* cache, int32_t n_shards,
-                          float* o, float* lse_out, float* o_partials, float* lses,
-                          int64_t* shard_off, int32_t* shard_len,
-                          void* workspace, size_t workspace_bytes, void* hip_stream)
+namespace {
+int decode_kvp(const helix_problem* problem, const void* q, const helix_kv_shard* cache, int32_t n_shards,
+               float* o, float* lse_out, float* o_partials, float* lses, int64_t* shard_off, int32_t* shard_len,
+               void* workspace, size_t workspace_bytes, void* hip_stream, KernelEvents ev)
 {
-    if (!q || !o || !cache) return HELIX_ERR_NULL;
+    if (!problem || !q || !o || !cache) return HELIX_ERR_NULL;
     if ((o_partials == nullptr) != (lses == nullptr) || (shard_off == nullptr) != (shard_len == nullptr)) return HELIX_ERR_NULL;
     if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(q) % 16 || reinterpret_cast<uintptr_t>(o) % 16 ||
         reinterpret_cast<uintptr_t>(o_partials) % 16) return HELIX_ERR_SHAPE;
     if (cache->max_len < 0) return HELIX_ERR_SHAPE;
-    // every slice is at most c = 16 * ceil(ceil(max_len / N) / 16) tokens long
+    Path path;
+    if (int rc = check_problem(problem, &path)) return rc;
     helix_kv_shard slices[HELIX_MAX_SHARDS];               // on the stack: the library allocates nothing
-    const int64_t per = ceil_div(cache->max_len, n_shards);
-    const int32_t c = (int32_t)std::min<int64_t>(16 * ceil_div(per, 16), cache->max_len);
-    for (int32_t i = 0; i < n_shards; i++) {
-        slices[i] = *cache;
-        slices[i].max_len = c;
-        // a slice holds a N-th of every sequence, rounded up to whole 16-token blocks
-        if (cache->sum_len > 0) slices[i].sum_len = std::min<int64_t>(ceil_div(cache->sum_len, n_shards) + 16 * (int64_t)problem->batch, (int64_t)problem->batch * c);
-    }
+    kvp_slices(problem, cache, n_shards, slices);
     Plan plan;
     Workspace ws;
     if (int rc = prepare(problem, slices, n_shards, workspace, workspace_bytes, &plan, &ws)) return rc;
@@ -585,10 +374,34 @@ int helix_attn_decode_kvp(const helix_problem* problem, const void* q, const hel
     KvpCut cut;
     cut.n = n_shards; cut.off = shard_off; cut.len = shard_len;
     bool finished = false;
-    if (int rc = run_partials(problem, plan, q, slices, n_shards, ws, po, pl, stream, o, lse_out, &finished, cut)) return rc;
+    if (int rc = run_partials(problem, plan, q, slices, n_shards, ws, po, pl, stream, o, lse_out, &finished, cut, ev)) return rc;
     if (finished) return HELIX_OK;
     const int64_t rows = (int64_t)problem->batch * problem->q_heads;
     return combine_any(problem->dv, po, pl, o, lse_out, nullptr, n_shards, rows, stream);
+}
+}  // namespace
+
+int helix_attn_decode_kvp(const helix_problem* problem, const void* q, const helix_kv_shard* cache, int32_t n_shards,
+                          float* o, float* lse_out, float* o_partials, float* lses,
+                          int64_t* shard_off, int32_t* shard_len,
+                          void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return decode_kvp(problem, q, cache, n_shards, o, lse_out, o_partials, lses, shard_off, shard_len,
+                      workspace, workspace_bytes, hip_stream, KernelEvents());
+}
+
+int helix_attn_decode_kvp_timed(const helix_problem* problem, const void* q, const helix_kv_shard* cache, int32_t n_shards,
+                                float* o, float* lse_out, float* o_partials, float* lses,
+                                int64_t* shard_off, int32_t* shard_len,
+                                void* workspace, size_t workspace_bytes, void* hip_stream,
+                                void* start_event, void* stop_event)
+{
+    if (!start_event || !stop_event) return HELIX_ERR_NULL;
+    KernelEvents ev;
+    ev.start = static_cast<hipEvent_t>(start_event);
+    ev.stop = static_cast<hipEvent_t>(stop_event);
+    return decode_kvp(problem, q, cache, n_shards, o, lse_out, o_partials, lses, shard_off, shard_len,
+                      workspace, workspace_bytes, hip_stream, ev);
 }
 
 int32_t helix_kv_append_owner(int64_t decode_index, int32_t n_shards)
@@ -671,6 +484,39 @@ double helix_weight_read_seconds(int64_t H, int64_t Q, int64_t K, int64_t Hsz, i
     const double kv = 2.0 * (double)H * (double)ceil_div(K, TPA) * (double)Hsz;
     const double ffn = 3.0 * ((double)H * (double)F / (double)TPF);
     return (q_and_out + kv + ffn) * bytes_per_param / mem_bw;
+}
+
+int helix_probe_stream_read(const void* buf, size_t bytes, int32_t workgroups, int32_t nontemporal, void* hip_stream)
+{
+    if (!buf) return HELIX_ERR_NULL;
+    if (bytes == 0 || bytes % helix::kProbeBlock || reinterpret_cast<uintptr_t>(buf) % 16 || workgroups < 1 || workgroups > (1 << 20))
+        return HELIX_ERR_SHAPE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const uint8_t* p = static_cast<const uint8_t*>(buf);
+    if (nontemporal) hipLaunchKernelGGL(helix::stream_read_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, stream, p, bytes / helix::kProbeBlock, nullptr);
+    else hipLaunchKernelGGL(helix::stream_read_kernel<false>, dim3((unsigned)workgroups), dim3(256), 0, stream, p, bytes / helix::kProbeBlock, nullptr);
+    return launch_status();
+}
+
+int helix_probe_mfma_lds(const void* operands, int32_t iters, const void* stream_buf, size_t stream_bytes,
+                         double* flops, double* bytes_read, void* hip_stream)
+{
+    if (!operands) return HELIX_ERR_NULL;
+    if (iters < 8 || iters % 8 || reinterpret_cast<uintptr_t>(operands) % 16) return HELIX_ERR_SHAPE;
+    // the streamed buffer is addressed modulo its size: a power of two, at least one step of the whole grid
+    if (stream_buf && (stream_bytes < ((size_t)1 << 22) || (stream_bytes & (stream_bytes - 1)) || stream_bytes > ((size_t)1 << 35) ||
+                       reinterpret_cast<uintptr_t>(stream_buf) % 16)) return HELIX_ERR_SHAPE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const helix::u32x4* d = static_cast<const helix::u32x4*>(operands);
+    constexpr int grid = 256;                               // one workgroup of 8 waves per CU
+    if (stream_buf)
+        hipLaunchKernelGGL(helix::mfma_lds_kernel<true>, dim3(grid), dim3(helix::kProbeWaves * 64), 0, stream, iters, d, nullptr,
+                           static_cast<const helix::u32x4*>(stream_buf), (uint32_t)(stream_bytes / 16 - 1));
+    else
+        hipLaunchKernelGGL(helix::mfma_lds_kernel<false>, dim3(grid), dim3(helix::kProbeWaves * 64), 0, stream, iters, d, nullptr, nullptr, 0u);
+    if (flops) *flops = (double)grid * helix::kProbeWaves * (double)iters * 8.0 * (2.0 * 16 * 16 * 32);
+    if (bytes_read) *bytes_read = stream_buf ? (double)grid * helix::kProbeWaves * 1024.0 * (double)(iters / 2 + 4) : 0.0;
+    return launch_status();
 }
 
 int helix_shard_layout(const int32_t* seq_len, const int64_t* seq_base, int32_t batch, int32_t n_shards,

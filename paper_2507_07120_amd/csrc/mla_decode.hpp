@@ -501,7 +501,10 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     int len;
     int64_t first_row;
     shard_range(sh, b, len, first_row);
-    if (sh.out_off && split == 0 && htw == 0 && threadIdx.x == 0) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
+    if (split == 0 && htw == 0 && threadIdx.x == 0) {
+        if (sh.out_off) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
+        flag_len_overflow(sh, len, a.split_tokens);
+    }
     const int t0 = split * a.split_tokens;
     const int t1 = min(t0 + a.split_tokens, len);
     const int h0 = htw * C::HPW;                      // first head of this workgroup

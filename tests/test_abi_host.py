@@ -204,3 +204,77 @@ def test_mxfp4_and_hopb_argument_errors_without_gpu(hx):
     assert lib.helix_attn_decode_kvp(ctypes.byref(pb), None, None, 2, None, None, None, None, None, None, None, 0, None) == 1
     assert hx.helix_attn_hopb_workspace_bytes(hx.Problem(2, 16, 1, 128, 128, 0.088), 1, 4096, 2) > 0
     assert hx.helix_attn_hopb_workspace_bytes(hx.Problem(2, 16, 1, 128, 128, 0.088), 1, 4096, 3) == 0
+
+
+def test_decode_kvp_rejects_a_null_problem_before_reading_it(hx):
+    """helix_attn_decode_kvp derives slice bounds from the problem: a NULL problem is a status, not a crash."""
+    lib = hx.load_library()
+    from paper_2507_07120_amd.binding import _CShard
+    fake = 0x100000
+    cache = _CShard(k=fake, v=fake, len=fake, max_len=1024, k_stride_h=128 * 1024, k_stride_t=128,
+                    v_stride_h=128 * 1024, v_stride_t=128, sum_len=4096)
+    assert lib.helix_attn_decode_kvp(None, fake, ctypes.byref(cache), 2, fake, None, None, None, None, None,
+                                     fake, 1 << 30, None) == 1
+    assert lib.helix_attn_decode_kvp_timed(None, fake, ctypes.byref(cache), 2, fake, None, None, None, None, None,
+                                           fake, 1 << 30, None, fake, fake) == 1
+    # the timed form needs both events
+    p = hx.Problem(2, 16, 1, 128, 128, 0.088).c()
+    assert lib.helix_attn_decode_kvp_timed(ctypes.byref(p), fake, ctypes.byref(cache), 2, fake, None, None, None, None, None,
+                                           fake, 1 << 30, None, None, fake) == 1
+    # a status word must be a 4-byte aligned device address
+    bad = _CShard(k=fake, v=fake, len=fake, max_len=1024, k_stride_h=128 * 1024, k_stride_t=128,
+                  v_stride_h=128 * 1024, v_stride_t=128, status=fake + 2)
+    assert lib.helix_attn_partial(ctypes.byref(p), fake, ctypes.byref(bad), fake, fake, fake, 1 << 30, None) == 2
+
+
+def test_plan_of_many_long_shards_does_not_wrap(hx):
+    """rows * total tokens beyond 2^39: the run length stays a positive multiple of the granule that fits
+    32 bits, and the workgroup count follows from that same value (or the call is refused as a shape error)."""
+    n = 1024
+    for prob, granule in [(hx.Problem(64, 128, 1, 576, 512, 0.07, v_aliases_k=True), 32),
+                          (hx.Problem(4096, 16, 1, 128, 128, 0.088), 128),
+                          (hx.Problem(4096, 16, 1, 128, 128, 0.088, kv_dtype=hx.KV_MXFP4), 128)]:
+        lens = [2 ** 31 - 1] * n
+        try:
+            split, wgs = hx.helix_attn_plan(prob, lens)
+        except hx.HelixError as e:
+            assert e.status == 2
+            continue
+        assert 0 < split <= 2 ** 31 - 1 and split % granule == 0
+        rows = prob.batch * prob.kv_heads
+        assert wgs == rows * sum(max(1, -(-x // split)) for x in lens)
+        assert hx.helix_attn_workspace_bytes(prob, n, 2 ** 31 - 1) > 0
+    # an explicit run length near the top of the range is rounded down to the granule, not up past 2^31
+    prob = hx.Problem(2, 16, 1, 128, 128, 0.088, split_tokens=2 ** 31 - 1)
+    split, _ = hx.helix_attn_plan(prob, [1000])
+    assert 0 < split <= 2 ** 31 - 1 and split % 128 == 0
+
+
+def test_host_entry_points_from_several_threads(hx):
+    """The library keeps no per-call state: planning, sizing and argument checks run concurrently from several
+    threads and give each thread the answers a single thread gets."""
+    import threading
+    lib = hx.load_library()
+    probs = [hx.Problem(16, 16, 1, 128, 128, 0.088), hx.Problem(4, 64, 8, 128, 128, 0.088),
+             hx.Problem(32, 128, 1, 576, 512, 0.07, v_aliases_k=True),
+             hx.Problem(64, 128, 1, 576, 512, 0.07, v_aliases_k=True, kv_dtype=hx.KV_FP8_E4M3)]
+    want = [(hx.helix_attn_plan(p, [131072, 777]), hx.helix_attn_workspace_bytes(p, 2, 131072)) for p in probs]
+    errors = []
+
+    def work(i):
+        try:
+            for _ in range(200):
+                p = probs[i % len(probs)]
+                got = (hx.helix_attn_plan(p, [131072, 777]), hx.helix_attn_workspace_bytes(p, 2, 131072))
+                assert got == want[i % len(probs)]
+                c = p.c()
+                assert lib.helix_attn_partial(ctypes.byref(c), None, None, None, None, None, 0, None) == 1
+                assert lib.helix_attn_decode_kvp(ctypes.byref(c), None, None, 2, None, None, None, None, None, None, None, 0, None) == 1
+        except Exception as e:      # noqa: BLE001 -- reported below, in the main thread
+            errors.append(e)
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors

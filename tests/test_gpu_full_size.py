@@ -1,8 +1,10 @@
 """The benchmark configurations at FULL size, in the launch configurations bench.py times (automatic
 work split; the two-call path helix_shard_layout + helix_attn_decode and the default one,
-helix_attn_decode_kvp with the sum of the lengths declared): sampled (b, h) rows against the CPU
-oracle, integer metadata bit-exact, both paths against each other, and the GPU's sharded-then-combined
-output against its own unsharded output (max-abs 1e-5) where the configuration has several shards."""
+helix_attn_decode_kvp with the sum of the lengths declared): whole sequences (every head) plus single rows
+of other sequences against the CPU oracle -- at least 256 rows per benchmark configuration, the whole output
+where the oracle's time allows --, integer metadata bit-exact, both paths against each other, and the GPU's
+sharded-then-combined output against its own unsharded output (max-abs 1e-5) where the configuration has
+several shards."""
 import numpy as np
 import pytest
 import torch
@@ -104,9 +106,40 @@ def oracle_rows(oracle, w, inp, rows):
     return np.stack(out_o), np.array(out_l)
 
 
+def oracle_sequences(oracle, w, inp, seqs, extra_rows=()):
+    """The oracle on every head of the sequences `seqs` (one oracle call per sequence, only that sequence copied
+    to the host) plus the single rows `extra_rows`; returns (rows, o_ref, lse_ref) in check_rows' form."""
+    rows, out_o, out_l = [], [], []
+    for b in seqs:
+        q = synth.bits(inp.q[b:b + 1])
+        if inp.seq_off is not None:                                   # packed ragged latent
+            lo, hi = int(inp.seq_off[b]), int(inp.seq_off[b + 1])
+            sc = inp.kv_scale[lo:hi].cpu().numpy() if inp.kv_scale is not None else None
+            mx = None if inp.k_mx is None else (inp.k_mx[lo:hi].cpu().numpy(), None)
+            o, l = oracle.attention(q, synth.bits(inp.k[lo:hi]), None, np.array([hi - lo], np.int32), w.scale, kv_heads=1,
+                                    dv=w.dv, kv_scale=sc, tok_off=np.zeros(1, np.int64), mx=mx)
+        else:
+            v = synth.bits(inp.v[b:b + 1]) if inp.v is not None else None
+            sc = inp.kv_scale[b:b + 1].cpu().numpy() if inp.kv_scale is not None else None
+            mx = None if inp.k_mx is None else (inp.k_mx[b:b + 1].cpu().numpy(),
+                                                None if inp.v_mx is None else inp.v_mx[b:b + 1].cpu().numpy())
+            o, l = oracle.attention(q, synth.bits(inp.k[b:b + 1]), v, inp.lens[b:b + 1].numpy(), w.scale, kv_heads=w.K,
+                                    dv=w.dv, kv_scale=sc, mx=mx)
+        rows += [(b, h) for h in range(w.Q)]
+        out_o.append(o[0])
+        out_l.append(l[0])
+    o_ref, lse_ref = np.concatenate(out_o), np.concatenate(out_l)
+    if extra_rows:
+        eo, el = oracle_rows(oracle, w, inp, list(extra_rows))
+        rows += list(extra_rows)
+        o_ref, lse_ref = np.concatenate([o_ref, eo]), np.concatenate([lse_ref, el])
+    return rows, o_ref, lse_ref
+
+
 def check_rows(o, lse, o_ref, lse_ref, rows, what):
-    got = np.stack([o[b, h].cpu().numpy() for b, h in rows]).astype(np.float64)
-    gl = np.array([lse[b, h].item() for b, h in rows])
+    oc, lc = o.cpu().numpy(), lse.cpu().numpy()
+    got = np.stack([oc[b, h] for b, h in rows]).astype(np.float64)
+    gl = np.array([lc[b, h] for b, h in rows], dtype=np.float64)
     err = np.abs(got - o_ref).max()
     rel = np.linalg.norm(got - o_ref) / np.linalg.norm(o_ref)
     lerr = np.abs(gl - lse_ref).max()
@@ -119,8 +152,8 @@ def test_gqa_share_full(hx, oracle):
     inp = synth.make_inputs(w, "cuda")
     o, lse, _, _, _ = decode(hx, w, inp, 1)
     assert torch.isfinite(o).all() and torch.isfinite(lse).all()
-    rows = [(0, 0), (3, 7), (9, 15), (15, 4)]
-    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, range(w.B))           # the whole output: 256 rows
+    assert len(rows) == w.B * w.Q
     check_rows(o, lse, o_ref, lse_ref, rows, "gqa_share full size")
     check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "gqa_share full size")
 
@@ -130,8 +163,9 @@ def test_mla_share_full(hx, oracle):
     inp = synth.make_inputs(w, "cuda")
     o, lse, _, _, _ = decode(hx, w, inp, 1)
     assert torch.isfinite(o).all() and torch.isfinite(lse).all()
-    rows = [(0, 0), (0, 77), (17, 127), (31, 64)]
-    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    # every head of two sequences, plus one row of eight more sequences (one per residue of b modulo 8)
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, [0, 21], extra_rows=[(8 + 3 * j, (37 * j + 5) % w.Q) for j in range(8)])
+    assert len(rows) >= 256 and len({b % 8 for b, _ in rows}) == 8
     check_rows(o, lse, o_ref, lse_ref, rows, "mla_share full size")
     check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "mla_share full size")
 
@@ -156,8 +190,8 @@ def test_gqa_full_sharded_vs_unsharded_and_oracle(hx, oracle):
     torch.cuda.synchronize()
     assert torch.equal(o2, o16)
     assert np.array_equal(am.cpu().numpy(), oracle.argmax_f32(lses.cpu().numpy()))
-    rows = [(0, 0), (2, 37), (3, 63)]
-    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, range(w.B))           # the whole output: 256 rows
+    assert len(rows) == w.B * w.Q
     check_rows(o16, lse16, o_ref, lse_ref, rows, "gqa_full sharded")
     check_rows(o1, lse1, o_ref, lse_ref, rows, "gqa_full unsharded")
     check_as_bench(hx, oracle, w, inp, 16, o16, lse16, o_ref, lse_ref, rows, "gqa_full sharded")
@@ -179,8 +213,11 @@ def test_mla_fp8_ragged_full(hx, oracle):
     print(f"mla_fp8_ragged: sharded(8) vs unsharded max-abs {d:.3e}")
     assert d <= SHARD_VS_UNSHARDED
     b_short, b_long = int(lens.argmin()), int(lens.argmax())
-    rows = [(b_short, 3), (b_long, 100), (7, 64)]
-    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    # every head of the shortest and the longest sequence, plus one row of eight more (one per residue modulo 8)
+    others = [b for b in range(w.B) if b not in (b_short, b_long)]
+    extra = [(next(b for b in others if b % 8 == j), (29 * j + 3) % w.Q) for j in range(8)]
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, [b_short, b_long], extra_rows=extra)
+    assert len(rows) >= 256
     check_rows(o8, lse8, o_ref, lse_ref, rows, "mla_fp8_ragged sharded")
     check_as_bench(hx, oracle, w, inp, 8, o8, lse8, o_ref, lse_ref, rows, "mla_fp8_ragged sharded")
 
@@ -192,8 +229,9 @@ def test_gqa_share_mxfp4_full(hx, oracle):
     inp = synth.make_inputs(w, "cuda")
     o, lse, _, _, _ = decode(hx, w, inp, 1)
     assert torch.isfinite(o).all() and torch.isfinite(lse).all()
-    rows = [(0, 0), (5, 9), (15, 15)]
-    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    # (the oracle decodes MXFP4 element by element: half the batch is what a test's time allows)
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, range(0, w.B, 2), extra_rows=[(5, 9), (15, 15)])
+    assert len(rows) >= 128
     check_rows(o, lse, o_ref, lse_ref, rows, "gqa_share_mxfp4")
     check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "gqa_share_mxfp4")
     o4, lse4, _, _, _ = decode(hx, w, inp, 4)
@@ -209,8 +247,8 @@ def test_mla_share_mxfp4_full(hx, oracle):
     inp = synth.make_inputs(w, "cuda")
     o, lse, _, _, _ = decode(hx, w, inp, 1)
     assert torch.isfinite(o).all() and torch.isfinite(lse).all()
-    rows = [(0, 0), (11, 77), (31, 127)]
-    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, [13], extra_rows=[(0, 0), (11, 77), (31, 127)])
+    assert len(rows) >= 128
     check_rows(o, lse, o_ref, lse_ref, rows, "mla_share_mxfp4")
     check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "mla_share_mxfp4")
     o8, lse8, _, _, _ = decode(hx, w, inp, 8)
@@ -234,7 +272,8 @@ def test_mla_mxfp4_ragged_full(hx, oracle):
     print(f"mla_mxfp4_ragged: sharded(8) vs unsharded max-abs {d:.3e}")
     assert d <= SHARD_VS_UNSHARDED
     odd = [b for b in range(w.B) if int(inp.seq_off[b]) % 2 == 1]
-    rows = [(int(lens.argmin()), 3), (odd[0] if odd else 1, 100)]
-    o_ref, lse_ref = oracle_rows(oracle, w, inp, rows)
+    b_short = int(lens.argmin())
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, [b_short], extra_rows=[(odd[0] if odd else 1, 100), (int(lens.argmax()), 17)])
+    assert len(rows) >= 128
     check_rows(o8, lse8, o_ref, lse_ref, rows, "mla_mxfp4_ragged sharded")
     check_as_bench(hx, oracle, w, inp, 8, o8, lse8, o_ref, lse_ref, rows, "mla_mxfp4_ragged sharded")
