@@ -168,6 +168,20 @@ int helix_attn_decode(const helix_problem *problem, const void *q,
                       float *o, float *lse_out, float *o_partials, float *lses,
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): helix_attn_decode with the split records and the
+ * per-shard fragments in a static device array of HELIX_STATIC_SCRATCH_BYTES inside the library instead of a
+ * caller's workspace.  Same kernels, same plan, same results as helix_attn_decode with o_partials == NULL.
+ * The call allocates nothing; its first use on a device looks up the array's address (hipGetSymbolAddress).
+ * A problem that needs more than HELIX_STATIC_SCRATCH_BYTES of workspace is refused with HELIX_ERR_WORKSPACE
+ * before anything is launched.  Every call on a GPU uses that GPU's one array (nothing in it has to be
+ * cleared: each launch writes every record it later reads): calls that overlap on one GPU -- from different
+ * streams or threads -- race on it; calls on one stream are ordered. */
+#define HELIX_STATIC_SCRATCH_BYTES (16u << 20)
+int helix_attn_decode_static(const helix_problem *problem, const void *q,
+                             const helix_kv_shard *shards, int32_t n_shards,
+                             float *o, float *lse_out, void *hip_stream);
+
 /* helix_shard_layout and helix_attn_decode in one call: `cache` describes the UNSHARDED cache (len =
  * the sequences' full lengths, tok_off = their first rows or NULL, max_len = an upper bound of the
  * lengths) and the N slices of Sec. 2.1.1 are cut inside the attention kernel, with the integers

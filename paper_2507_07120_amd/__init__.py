@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     helix_attn_decode,
     helix_attn_decode_hopb,
     helix_attn_decode_kvp,
+    helix_attn_decode_static,
     helix_attn_hopb_workspace_bytes,
     helix_attn_partial,
     helix_attn_plan,

@@ -77,6 +77,8 @@ def load_library():
     lib.helix_attn_decode.restype = ctypes.c_int
     lib.helix_attn_decode.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), i32,
                                       vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.helix_attn_decode_static.restype = ctypes.c_int
+    lib.helix_attn_decode_static.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), i32, vp, vp, vp]
     lib.helix_attn_decode_kvp.restype = ctypes.c_int
     lib.helix_attn_decode_kvp.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), i32,
                                           vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
@@ -301,6 +303,26 @@ def helix_attn_decode(problem: Problem, q: torch.Tensor, shards: Sequence[KVShar
                                             workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                             _stream_ptr(stream)),
            "helix_attn_decode")
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def helix_attn_decode_static(problem: Problem, q: torch.Tensor, shards: Sequence[KVShard], o: torch.Tensor,
+                             lse_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """helix_attn_decode without a workspace argument: the library's static device scratch serves (no allocation)."""
+    n = len(shards)
+    assert q.dtype == torch.bfloat16 and q.is_contiguous()
+    assert tuple(q.shape) == (problem.batch, problem.q_heads, problem.dk)
+    _f32(o, (problem.batch, problem.q_heads, problem.dv), "o")
+    if lse_out is not None:
+        _f32(lse_out, (problem.batch, problem.q_heads), "lse_out")
+    p = problem.c()
+    arr = (_CShard * n)(*[s.c() for s in shards])
+    _check(load_library().helix_attn_decode_static(ctypes.byref(p), q.data_ptr(), arr, n, o.data_ptr(),
+                                                   None if lse_out is None else lse_out.data_ptr(),
+                                                   _stream_ptr(stream)),
+           "helix_attn_decode_static")
 
 
 def helix_shard_layout(seq_len: torch.Tensor, n_shards: int, shard_off: torch.Tensor, shard_len: torch.Tensor,

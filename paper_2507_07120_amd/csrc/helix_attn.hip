@@ -30,6 +30,26 @@ static_assert(kMlaHeadsPerWorkgroup == MlaCfg::HPW, "the host plan and the MLA k
 // The request is idempotent, so two threads that both find the flag clear may both make it.
 std::atomic<bool> g_lds_asked[3][64];
 
+// Scratch memory of helix_attn_decode_static: callers that must not allocate get the split records and the
+// per-shard fragments here instead of in a workspace of their own.  Every GPU the library runs on holds its
+// own copy of the array until the process ends.  In host code the array's name is only a handle: the device
+// address comes from hipGetSymbolAddress, once per device, and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[HELIX_STATIC_SCRATCH_BYTES];
+std::atomic<void*> g_scratch_ptr[64];
+
+int static_scratch(void** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return HELIX_ERR_LAUNCH;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return HELIX_ERR_LAUNCH;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);      // the same address whichever thread stores it
+    }
+    *out = p;
+    return HELIX_OK;
+}
+
 // hipEvent_t pair recorded around the streaming attention kernel(s) of a call (the timed entry point), or none
 struct KernelEvents {
     hipEvent_t start = nullptr, stop = nullptr;
@@ -259,6 +279,26 @@ int helix_attn_decode(const helix_problem* problem, const void* q, const helix_k
     if (finished) return HELIX_OK;
     const int64_t rows = (int64_t)problem->batch * problem->q_heads;
     return combine_any(problem->dv, po, pl, o, lse_out, nullptr, n_shards, rows, stream);
+}
+
+int helix_attn_decode_static(const helix_problem* problem, const void* q, const helix_kv_shard* shards, int32_t n_shards,
+                             float* o, float* lse_out, void* hip_stream)
+{
+    if (!q || !o) return HELIX_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(q) % 16 || reinterpret_cast<uintptr_t>(o) % 16) return HELIX_ERR_SHAPE;
+    // validate and size first (a fake, aligned base: nothing is dereferenced), then fetch the device address
+    Plan plan;
+    Workspace ws;
+    if (int rc = prepare(problem, shards, n_shards, reinterpret_cast<void*>(uintptr_t(256)), HELIX_STATIC_SCRATCH_BYTES, &plan, &ws)) return rc;
+    void* base = nullptr;
+    if (int rc = static_scratch(&base)) return rc;
+    if (int rc = prepare(problem, shards, n_shards, base, HELIX_STATIC_SCRATCH_BYTES, &plan, &ws)) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    bool finished = false;
+    if (int rc = run_partials(problem, plan, q, shards, n_shards, ws, ws.part_o, ws.part_lse, stream, o, lse_out, &finished)) return rc;
+    if (finished) return HELIX_OK;
+    const int64_t rows = (int64_t)problem->batch * problem->q_heads;
+    return combine_any(problem->dv, ws.part_o, ws.part_lse, o, lse_out, nullptr, n_shards, rows, stream);
 }
 
 namespace {
