@@ -20,6 +20,7 @@ Inputs are the exact stored bits: bf16 as uint16 arrays, e4m3 as uint8 arrays pl
 """
 import ctypes
 import math
+import os
 
 import numpy as np
 
@@ -51,7 +52,8 @@ class _Problem(ctypes.Structure):
 def lib():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(_build.build())
+        # HELIX_ORACLE_LIB: another build of the same source (the sanitizer job loads an instrumented one)
+        _lib = ctypes.CDLL(os.environ.get("HELIX_ORACLE_LIB") or _build.build())
         _lib.helix_oracle_e4m3_value.restype = ctypes.c_double
         _lib.helix_oracle_e4m3_value.argtypes = [ctypes.c_uint8]
         for name in ("helix_oracle_e2m1_value", "helix_oracle_e8m0_value"):
