@@ -158,6 +158,8 @@ def measure(name, args, budget_macs, extras=False):
     else:
         cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, max_len, kv_scale=inp.kv_scale)
     cache.sum_len = int(inp.lens.sum())       # the host knows the lengths it generated: it declares their sum
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    cache.status = status                     # device word: sequences beyond max_len (bit 0), moved MLA reference exponents (>> 8)
     ws = harness.workspace_for(prob, N, max_len, dev)
     o = torch.empty((w.B, w.Q, w.dv), device=dev)
     lse = torch.empty((w.B, w.Q), device=dev)
@@ -197,12 +199,15 @@ def measure(name, args, budget_macs, extras=False):
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    status.zero_()
+    torch.cuda.synchronize()
     # timed region: exactly K steps, nothing else on the stream
     t0 = time.perf_counter()
     for i in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    status_word = int(status.item())
     # the same K steps again with a hipEvent pair recorded around the streaming kernel of every step
     # (the event packets sit between the kernels and cost a few microseconds per step, so they stay
     # out of the region `value` is computed from; that region's own duration is reported alongside)
@@ -235,6 +240,10 @@ def measure(name, args, budget_macs, extras=False):
     roof["kernel_us_min"] = kern_ms[0] * 1e3
     roof["kernel_timing"] = ("hipEvent pair around the streaming kernel in a second loop of the same K steps "
                              "(helix_attn_decode_kvp_timed); that loop's step time is us_per_step_with_event_hooks")
+    if w.mla:
+        # (wavefront, tile) events in which a head's reference exponent had to move (see the header), per step
+        roof["reference_moves_per_step"] = (status_word >> 8) / args.steps
+    roof["status_bits"] = status_word & 0xFF
     roof["algorithmic_bytes"] = kv_bytes
     roof["hbm_gbs_of_kernel"] = hbm_of_kernel
     roof["hbm_frac_of_kernel"] = hbm_of_kernel / HBM_PEAK_GBS

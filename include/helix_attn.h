@@ -128,6 +128,11 @@ typedef struct helix_kv_shard {
  * len[b] is larger (e.g. after helix_kv_append without raising max_len) has its surplus tokens left out of
  * the attention, and this bit says so. */
 #define HELIX_STATUS_LEN_EXCEEDS_MAX 1
+/* The MLA kernels keep a power-of-two reference exponent per head and move it only in a tile whose scores
+ * (bf16 latent) or fp16 weights (e4m3 / MXFP4 latents) come near the end of their number range -- never on
+ * ordinary logits, a few times per run on sharply peaked ones.  Results do not depend on it, time hardly: every
+ * (wavefront, tile) that moved references adds HELIX_STATUS_REFERENCE_MOVED, so (status >> 8) counts them. */
+#define HELIX_STATUS_REFERENCE_MOVED 256
 
 /* Bytes of workspace helix_attn_partial / helix_attn_decode need for `n_shards` shards whose
  * max_len are all <= `max_len`.  Returns 0 if the problem is invalid or unsupported.

@@ -42,6 +42,7 @@ struct ShardDev {
 };
 
 constexpr int kStatusLenExceedsMax = 1;   // HELIX_STATUS_LEN_EXCEEDS_MAX
+constexpr int kStatusReferenceMoved = 256; // HELIX_STATUS_REFERENCE_MOVED: added once per (wave, tile) in which an MLA kernel moved reference exponents
 
 // The launch holds n_splits runs of split_tokens tokens per sequence (sized from the host's max_len):
 // tokens of a longer sequence are not attended to, which the caller can learn from the status word.
@@ -63,8 +64,29 @@ struct AttnArgs {
     float scale_log2e;    // softmax scale * log2(e)
     int32_t n_shards;
     const uint2* units;   // which (shard << 24 | row, split) each workgroup serves, written by run_order_kernel; NULL: by id
+    // MLA launches that are cut evenly over the token stream (stream_plan_kernel): the (shard, sequence) pairs of
+    // the launch, pair = shard * B + sequence, laid end to end in 32-token tiles
+    const int64_t* tile_prefix;   // [pairs + 1] tiles before pair p; [pairs] = all tiles.  NULL: runs by workgroup id
+    const int32_t* wg_first_pair; // [n_wg] the pair that holds a workgroup's first tile
+    int32_t n_wg;                 // workgroups of the launch
+    int32_t rec_base;             // first record of this launch; the run of workgroup g inside pair p writes record rec_base + g + p
     ShardDev shard[kMaxLaunchShards];
 };
+
+constexpr int kStreamTile = 32;   // tokens per tile of the MLA kernels
+
+// First tile of workgroup g when T tiles are dealt evenly to n_wg workgroups: workgroup g serves tiles
+// [stream_start(g), stream_start(g + 1)), each range T / n_wg tiles long to within one.
+__host__ __device__ __forceinline__ int64_t stream_start(int64_t g, int64_t T, int64_t n_wg) { return g * T / n_wg; }
+
+// The workgroup whose range holds tile x (0 <= x < T): the largest g with stream_start(g) <= x.
+__device__ __forceinline__ int stream_owner(int64_t x, int64_t T, int n_wg)
+{
+    int g = (int)min((int64_t)n_wg - 1, (x * n_wg + n_wg - 1) / T);       // at or just above the answer
+    while (g > 0 && stream_start(g, T, n_wg) > x) g--;
+    while (g + 1 < n_wg && stream_start(g + 1, T, n_wg) <= x) g++;
+    return g;
+}
 
 // Tokens of sequence b this shard holds and the row of the first one.  With kvp_n > 0 the contiguous
 // KVP cut of Sec. 2.1.1 is made here: slice width c = 16 * ceil(ceil(L / N) / 16) tokens (whole blocks of
@@ -208,5 +230,83 @@ __global__ __launch_bounds__(kOrderThreads) void run_order_kernel(const AttnArgs
     }
 }
 
+// Plan of an MLA launch whose workgroups share the work evenly whatever the sequence lengths are.  The slices
+// of all (shard, sequence) pairs of the launch are laid end to end, counted in 32-token tiles, and workgroup g
+// of n_wg takes the tiles [g T / n_wg, (g + 1) T / n_wg): a run of equal length for every workgroup, cut into
+// pieces only where it crosses from one pair into the next.  Every piece ends in one split record, so a pair
+// has one record per workgroup that touches it -- about T / n_wg tokens apart -- instead of one per fixed-size
+// run, and no workgroup is launched for tokens that do not exist.  This kernel (one workgroup) writes what the
+// attention and merge kernels need: the exclusive prefix of the pairs' tile counts, per workgroup the pair that
+// holds its first tile, and per pair the workgroups that hold its tiles; it also records the KVP cut (out_off /
+// out_len) of every pair, empty ones included.
+constexpr int kPlanThreads = 1024;
+
+__global__ __launch_bounds__(kPlanThreads) void stream_plan_kernel(const AttnArgs a, int64_t* tile_prefix, int32_t* wg_first_pair, int2* pair_rec)
+{
+    __shared__ int64_t part[kPlanThreads];
+    const int tid = threadIdx.x;
+    const int pairs = a.n_shards * a.B;
+    const int chunk = (pairs + kPlanThreads - 1) / kPlanThreads;          // consecutive pairs per thread
+    const int p0 = min(tid * chunk, pairs), p1 = min(p0 + chunk, pairs);
+    auto tiles_of = [&](int p) {
+        const int si = p / a.B, b = p - si * a.B;
+        const ShardDev& sh = a.shard[si];
+        int len;
+        int64_t first_row;
+        shard_range(sh, b, len, first_row);
+        if (sh.out_off) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
+        return (int64_t)((max(len, 0) + kStreamTile - 1) / kStreamTile);   // a negative length is an empty sequence
+    };
+    int64_t mine = 0;
+    for (int p = p0; p < p1; p++) mine += tiles_of(p);
+    part[tid] = mine;
+    __syncthreads();
+    // exclusive scan of the per-thread sums (Hillis-Steele over 1024 entries)
+    for (int off = 1; off < kPlanThreads; off <<= 1) {
+        const int64_t add = tid >= off ? part[tid - off] : 0;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    int64_t run = part[tid] - mine;
+    const int64_t T = part[kPlanThreads - 1];
+    for (int p = p0; p < p1; p++) {
+        tile_prefix[p] = run;
+        const int si = p / a.B, b = p - si * a.B;
+        int len;
+        int64_t first_row;
+        shard_range(a.shard[si], b, len, first_row);
+        run += (int64_t)((max(len, 0) + kStreamTile - 1) / kStreamTile);
+    }
+    if (tid == 0) tile_prefix[pairs] = T;
+    __threadfence_block();
+    __syncthreads();                                   // the prefix is complete and visible to the whole workgroup
+    for (int g = tid; g < a.n_wg; g += kPlanThreads) {
+        int first = 0;
+        if (T > 0) {
+            const int64_t s = stream_start(g, T, a.n_wg);
+            // the largest pair p with tile_prefix[p] <= s (it is not empty: the next pair starts beyond s)
+            int lo = 0, hi = pairs - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (tile_prefix[mid] <= s) lo = mid; else hi = mid - 1;
+            }
+            first = lo;
+        }
+        wg_first_pair[g] = first;
+    }
+    // for the merge: the workgroups that hold tiles of pair p are g_first .. g_first + n - 1 (x, y); y is stored
+    // negated when the launch has fewer tiles than workgroups, because then some of them hold no tile at all
+    for (int p = tid; p < pairs; p += kPlanThreads) {
+        const int64_t lo = tile_prefix[p], hi = tile_prefix[p + 1];
+        int2 r = {0, 0};
+        if (hi > lo) {
+            r.x = stream_owner(lo, T, a.n_wg);
+            r.y = stream_owner(hi - 1, T, a.n_wg) - r.x + 1;
+            if (T < a.n_wg) r.y = -r.y;
+        }
+        pair_rec[p] = r;
+    }
+}
 
 }  // namespace helix

@@ -95,13 +95,16 @@ struct KvpCut {
 int run_partials(const helix_problem* p, const Plan& plan, const void* q, const helix_kv_shard* shards, int32_t n,
                  const Workspace& ws, float* o_part, float* lse_part, hipStream_t stream,
                  float* o = nullptr, float* lse_out = nullptr, bool* finished = nullptr, KvpCut cut = KvpCut(),
-                 KernelEvents ev = KernelEvents())
+                 KernelEvents ev = KernelEvents(), bool keep_parts = true)
 {
     const bool fuse = o != nullptr && n <= kMaxLaunchShards;
     if (finished) *finished = fuse;
     const int g = p->q_heads / p->kv_heads;
     const int64_t rows = (int64_t)p->batch * p->kv_heads * plan.head_tiles;
+    static_assert(kMaxLaunchShards == kMaxShardsPerLaunch, "the host plan and the kernels agree on the shards of a launch");
     int32_t split_base = 0;
+    int32_t rec_base = 0;          // stream plan: first record of the launch
+    size_t map_off = 0;            // ... and where its maps start in the workspace
     for (int32_t s0 = 0; s0 < n; s0 += kMaxLaunchShards) {
         const int32_t cnt = std::min<int32_t>(kMaxLaunchShards, n - s0);
         AttnArgs a;
@@ -137,10 +140,33 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             units += plan.path == Path::Mla && !plan.ordered ? mla_units_of_shard(d.n_splits, p->batch, plan.head_tiles)
                                                                    : (int64_t)d.n_splits * rows;
         }
-        // MLA with one head tile: the runs are handed to the workgroups in the order run_order_kernel
+        if (plan.stream) {
+            // MLA with one head tile: the launch is cut evenly over the tokens its sequences have on the device
+            int64_t bound = 0;
+            for (int32_t i = 0; i < cnt; i++) bound += (int64_t)p->batch * shards[s0 + i].max_len;
+            const int64_t n_wg = stream_workgroups(p, bound);
+            const int64_t pairs = (int64_t)cnt * p->batch;
+            int64_t* prefix = reinterpret_cast<int64_t*>(ws.maps + map_off);
+            int2* pair_rec = reinterpret_cast<int2*>(ws.maps + map_off + align_up((size_t)(pairs + 1) * 8, 256));
+            int32_t* first_pair = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(pair_rec) + align_up((size_t)pairs * 8, 256));
+            map_off += stream_map_bytes(pairs, n_wg);
+            a.n_wg = (int32_t)n_wg;
+            a.rec_base = rec_base;
+            hipLaunchKernelGGL(helix::stream_plan_kernel, dim3(1), dim3(helix::kPlanThreads), 0, stream, a, prefix, first_pair, pair_rec);
+            if (int rc = launch_status()) return rc;
+            a.tile_prefix = prefix;
+            a.wg_first_pair = first_pair;
+            m.tile_prefix = prefix;
+            m.pair_rec = pair_rec;
+            m.n_wg = a.n_wg;
+            m.rec_base = rec_base;
+            rec_base += (int32_t)(n_wg + pairs);
+            units = n_wg;
+        }
+        // a streaming batch declared ragged: the runs are handed to the workgroups in the order run_order_kernel
         // writes -- full runs first, then partial ones, then empty ones (see there)
         if (plan.ordered) {
-            uint2* map = reinterpret_cast<uint2*>(ws.units);
+            uint2* map = reinterpret_cast<uint2*>(ws.maps);
             hipLaunchKernelGGL(helix::run_order_kernel, dim3(1), dim3(helix::kOrderThreads), 0, stream, a, map, (int)units);
             if (int rc = launch_status()) return rc;
             a.units = map;
@@ -180,8 +206,13 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
         m.B = p->batch; m.Q = p->q_heads; m.n_shards = cnt; m.shard0 = s0;
         if (fuse) {
             FinishArgs f;
-            f.m = m; f.o = o; f.lse_out = lse_out;
+            f.m = m; f.o = o; f.lse_out = lse_out; f.keep_parts = keep_parts ? 1 : 0;
             const unsigned frows = (unsigned)((int64_t)p->batch * p->q_heads);
+            if (plan.stream) {             // MLA: dv = 512
+                const unsigned threads = helix::kFinishRowThreads * (unsigned)std::min<int32_t>(cnt, helix::kFinishGroups);
+                hipLaunchKernelGGL((finish_stream_kernel<512>), dim3(frows), dim3(threads), 0, stream, f);
+                return launch_status();
+            }
             switch (p->dv) {
                 case 64: hipLaunchKernelGGL((finish_kernel<64>), dim3(frows), dim3(256), 0, stream, f); break;
                 case 128: hipLaunchKernelGGL((finish_kernel<128>), dim3(frows), dim3(256), 0, stream, f); break;
@@ -275,7 +306,8 @@ int helix_attn_decode(const helix_problem* problem, const void* q, const helix_k
     float* pl = lses ? lses : ws.part_lse;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     bool finished = false;
-    if (int rc = run_partials(problem, plan, q, shards, n_shards, ws, po, pl, stream, o, lse_out, &finished)) return rc;
+    if (int rc = run_partials(problem, plan, q, shards, n_shards, ws, po, pl, stream, o, lse_out, &finished, KvpCut(), KernelEvents(),
+                              o_partials != nullptr)) return rc;
     if (finished) return HELIX_OK;
     const int64_t rows = (int64_t)problem->batch * problem->q_heads;
     return combine_any(problem->dv, po, pl, o, lse_out, nullptr, n_shards, rows, stream);
@@ -295,7 +327,8 @@ int helix_attn_decode_static(const helix_problem* problem, const void* q, const 
     if (int rc = prepare(problem, shards, n_shards, base, HELIX_STATIC_SCRATCH_BYTES, &plan, &ws)) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     bool finished = false;
-    if (int rc = run_partials(problem, plan, q, shards, n_shards, ws, ws.part_o, ws.part_lse, stream, o, lse_out, &finished)) return rc;
+    if (int rc = run_partials(problem, plan, q, shards, n_shards, ws, ws.part_o, ws.part_lse, stream, o, lse_out, &finished, KvpCut(), KernelEvents(),
+                              false)) return rc;
     if (finished) return HELIX_OK;
     const int64_t rows = (int64_t)problem->batch * problem->q_heads;
     return combine_any(problem->dv, ws.part_o, ws.part_lse, o, lse_out, nullptr, n_shards, rows, stream);
@@ -414,7 +447,7 @@ int decode_kvp(const helix_problem* problem, const void* q, const helix_kv_shard
     KvpCut cut;
     cut.n = n_shards; cut.off = shard_off; cut.len = shard_len;
     bool finished = false;
-    if (int rc = run_partials(problem, plan, q, slices, n_shards, ws, po, pl, stream, o, lse_out, &finished, cut, ev)) return rc;
+    if (int rc = run_partials(problem, plan, q, slices, n_shards, ws, po, pl, stream, o, lse_out, &finished, cut, ev, o_partials != nullptr)) return rc;
     if (finished) return HELIX_OK;
     const int64_t rows = (int64_t)problem->batch * problem->q_heads;
     return combine_any(problem->dv, po, pl, o, lse_out, nullptr, n_shards, rows, stream);

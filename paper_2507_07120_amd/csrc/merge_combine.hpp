@@ -19,7 +19,23 @@ struct MergeArgs {
     int32_t B, Q, n_shards, shard0;   // shard0: index of the first shard of this launch in o_part
     int32_t split_base[kMaxLaunchShards];
     int32_t n_splits[kMaxLaunchShards];
+    // records of a launch cut by stream_plan_kernel: pair p = (shard, sequence) owns one record per workgroup
+    // whose tile range touches it, record rec_base + g + p, rows [record][Q]
+    const int64_t* tile_prefix;       // NULL: records are [split][B][Q] as split_base / n_splits say
+    const int2* pair_rec;             // [pairs] the workgroups g_first .. g_first + n - 1 that hold tiles of the pair
+    int32_t n_wg, rec_base;
 };
+
+// Where the records of one (shard, b, h) row are: record j (0 <= j < n) sits in row `row(j)` of the record
+// arrays, or nowhere (kNoRecord).
+constexpr size_t kNoRecord = ~(size_t)0;
+
+struct SplitRecords {             // [split][B][Q]: records sb .. sb + n - 1 of row rem = b * Q + h
+    int n;
+    size_t first, stride;
+    __device__ __forceinline__ size_t row(int j) const { return first + (size_t)j * stride; }
+};
+
 
 template <int DV>
 struct MergeSmem {
@@ -47,11 +63,12 @@ __device__ __forceinline__ float lse_of(float M, float L)
 // maximum below changes no bit of the result.  One pass; the O row of an empty record (ragged
 // sequences leave many) is not fetched.
 // Returns the normalised O (valid in threads tid < TPR, 4 columns each); M and L in all threads.
-template <int DV>
+template <int DV, class Records>
 __device__ __forceinline__ f32x4 merge_row(const float* __restrict__ ws_o, const float* __restrict__ ws_m,
-                                           const float* __restrict__ ws_l, int sb, int nsp, int bq, int rem,
+                                           const float* __restrict__ ws_l, const Records& recs,
                                            MergeSmem<DV>& sm, float& M, float& L)
 {
+    const int nsp = recs.n;
     using S = MergeSmem<DV>;
     const int tid = threadIdx.x;
     const int sl = tid / S::TPR, c4 = (tid % S::TPR) * 4;
@@ -63,22 +80,23 @@ __device__ __forceinline__ f32x4 merge_row(const float* __restrict__ ws_o, const
     for (int j0 = sl; j0 < nsp; j0 += S::SL * U) {
         float mj[U], lj[U];
         f32x4 oj[U];
+        size_t rec[U];
 #pragma unroll
         for (int u = 0; u < U; u++) {
             const int j = j0 + u * S::SL;
             mj[u] = -INFINITY;
             lj[u] = 0.f;
-            if (j < nsp) {
-                const size_t rec = (size_t)(sb + j) * bq + rem;
-                mj[u] = ws_m[rec];
-                lj[u] = ws_l[rec];
+            rec[u] = j < nsp ? recs.row(j) : kNoRecord;
+            if (rec[u] != kNoRecord) {
+                mj[u] = ws_m[rec[u]];
+                lj[u] = ws_l[rec[u]];
             }
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
             oj[u] = f32x4{0.f, 0.f, 0.f, 0.f};
             if (mj[u] != -INFINITY)                // an empty record's O was never written: not fetched either
-                oj[u] = *reinterpret_cast<const f32x4*>(ws_o + ((size_t)(sb + j0 + u * S::SL) * bq + rem) * DV + c4);
+                oj[u] = *reinterpret_cast<const f32x4*>(ws_o + rec[u] * DV + c4);
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
@@ -115,6 +133,84 @@ __device__ __forceinline__ f32x4 merge_row(const float* __restrict__ ws_o, const
     return s;
 }
 
+// The same fold for the records of an evenly cut launch (stream_plan_kernel): pair (shard i, sequence b) has one
+// record per workgroup that holds tiles of it -- one to three as a rule.  They are folded by ONE thread per four
+// value columns, record after record in workgroup order, so no shared memory and no barrier is involved and a
+// workgroup can fold several shards side by side.  A thread handles NV groups of four columns, c0 + v * cstride:
+// out[v] receives their normalised O; M, L as above.  (How many columns a thread holds changes no bit.)
+template <int DV, int NV>
+__device__ __forceinline__ void merge_stream_row(const MergeArgs& a, int i, int b, int h, int c0, int cstride, f32x4 (&out)[NV], float& M, float& L)
+{
+    const int p = i * a.B + b;
+    const int2 pr = a.pair_rec[p];
+    const int n = abs(pr.y);
+    const bool gaps = pr.y < 0;
+    int64_t T = 0;
+    if (gaps) T = a.tile_prefix[a.n_shards * a.B];
+    const size_t row0 = (size_t)(a.rec_base + pr.x + p) * a.Q + h;
+    float Mt = -INFINITY, Lt = 0.f;
+    f32x4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; v++) acc[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+    constexpr int U = NV >= 4 ? 2 : 4;    // records in flight: first their (m, l), then the O rows
+    for (int j0 = 0; j0 < n; j0 += U) {
+        float mj[U], lj[U];
+        f32x4 oj[U][NV];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int j = j0 + u;
+            mj[u] = -INFINITY;
+            lj[u] = 0.f;
+            // a workgroup without a tile (launches with fewer tiles than workgroups) wrote no record
+            const bool there = j < n && !(gaps && stream_start(pr.x + j, T, a.n_wg) == stream_start(pr.x + j + 1, T, a.n_wg));
+            if (there) {
+                mj[u] = a.ws_m[row0 + (size_t)j * a.Q];
+                lj[u] = a.ws_l[row0 + (size_t)j * a.Q];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++)
+#pragma unroll
+            for (int v = 0; v < NV; v++) {
+                oj[u][v] = f32x4{0.f, 0.f, 0.f, 0.f};
+                if (mj[u] != -INFINITY)
+                    oj[u][v] = *reinterpret_cast<const f32x4*>(a.ws_o + (row0 + (size_t)(j0 + u) * a.Q) * DV + c0 + v * cstride);
+            }
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            if (mj[u] == -INFINITY) continue;
+            if (mj[u] > Mt) {
+                const float f = __builtin_amdgcn_exp2f(Mt - mj[u]);   // 0 from -inf
+#pragma unroll
+                for (int v = 0; v < NV; v++) acc[v] *= f;
+                Lt *= f;
+                Mt = mj[u];
+            }
+            const float g = __builtin_amdgcn_exp2f(mj[u] - Mt);
+#pragma unroll
+            for (int v = 0; v < NV; v++) acc[v] += oj[u][v] * g;
+            Lt += lj[u] * g;
+        }
+    }
+    M = Mt;
+    L = Lt;
+    const float inv = (Lt > 0.f) ? 1.f / Lt : 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; v++) out[v] = acc[v] * inv;
+}
+
+// The fold of shard i's records of row rem = b * Q + h in the [split][B][Q] layout.
+template <int DV>
+__device__ __forceinline__ f32x4 merge_shard_row(const MergeArgs& a, int i, int rem, MergeSmem<DV>& sm, float& M, float& L)
+{
+    const int bq = a.B * a.Q;
+    SplitRecords r;
+    r.n = a.n_splits[i];
+    r.first = (size_t)a.split_base[i] * bq + rem;
+    r.stride = (size_t)bq;
+    return merge_row<DV>(a.ws_o, a.ws_m, a.ws_l, r, sm, M, L);
+}
+
 // One workgroup per (shard, b, h) row: split records -> the shard's (O_i, lse_i).
 template <int DV>
 __global__ __launch_bounds__(256) void merge_splits_kernel(const MergeArgs a)
@@ -125,8 +221,17 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(const MergeArgs a)
     const int bq = a.B * a.Q;
     const int i = row / bq, rem = row % bq;
     float M, L;
-    const f32x4 o = merge_row<DV>(a.ws_o, a.ws_m, a.ws_l, a.split_base[i], a.n_splits[i], bq, rem, sm, M, L);
     const size_t orow = (size_t)(a.shard0 + i) * bq + rem;
+    if (a.tile_prefix) {
+        if (tid < MergeSmem<DV>::TPR) {
+            f32x4 o[1];
+            merge_stream_row<DV, 1>(a, i, rem / a.Q, rem % a.Q, tid * 4, 0, o, M, L);
+            *reinterpret_cast<f32x4*>(a.o_part + orow * DV + tid * 4) = o[0];
+            if (tid == 0) a.lse_part[orow] = lse_of(M, L);
+        }
+        return;
+    }
+    const f32x4 o = merge_shard_row<DV>(a, i, rem, sm, M, L);
     if (tid < MergeSmem<DV>::TPR) *reinterpret_cast<f32x4*>(a.o_part + orow * DV + tid * 4) = o;
     if (tid == 0) a.lse_part[orow] = lse_of(M, L);
 }
@@ -144,7 +249,64 @@ struct FinishArgs {
     MergeArgs m;          // shard0 must be 0 and m.n_shards the total number of shards (<= kMaxLaunchShards)
     float* o;             // [B][Q][dv]
     float* lse_out;       // [B][Q] or NULL
+    int32_t keep_parts;   // finish_stream_kernel: also store the per-shard fragments (the caller asked for them)
 };
+
+// merge + combine in one launch for an evenly cut launch of at most kMaxLaunchShards shards: one workgroup per
+// (b, h) row, its threads in groups of kFinishRowThreads that fold different shards side by side
+// (merge_stream_row, DV / kFinishRowThreads columns per thread); the fragments meet in shared memory, where the
+// first group combines them in shard order -- the arithmetic of merge_splits_kernel followed by combine_kernel,
+// without the round trip of the fragments through memory.  The path is a chain of dependent memory round trips
+// per row, so what counts is how many rows the part holds at once: few threads per row, each with several loads
+// in flight.  Launched with kFinishRowThreads * min(shards, kFinishGroups) threads.
+constexpr int kFinishRowThreads = 32, kFinishGroups = 8;
+
+template <int DV>
+__global__ __launch_bounds__(kFinishRowThreads * kFinishGroups) void finish_stream_kernel(const FinishArgs f)
+{
+    constexpr int TPR = kFinishRowThreads, NV = DV / (4 * TPR);
+    static_assert(NV >= 1 && NV * 4 * TPR == DV, "whole float4 columns per thread");
+    __shared__ float sm_o[kMaxLaunchShards][DV];
+    __shared__ float sm_lse[kMaxLaunchShards];
+    const MergeArgs& a = f.m;
+    const int tid = threadIdx.x, grp = tid / TPR, c0 = (tid % TPR) * 4, G = blockDim.x / TPR;
+    const int rem = blockIdx.x;          // b*Q + h
+    const int b = rem / a.Q, h = rem % a.Q;
+    const size_t bq = (size_t)a.B * a.Q;
+    for (int i = grp; i < a.n_shards; i += G) {
+        float M, L;
+        f32x4 o[NV];
+        merge_stream_row<DV, NV>(a, i, b, h, c0, 4 * TPR, o, M, L);
+        const float lse = lse_of(M, L);
+#pragma unroll
+        for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(&sm_o[i][c0 + v * 4 * TPR]) = o[v];
+        if (c0 == 0) sm_lse[i] = lse;
+        if (f.keep_parts) {
+#pragma unroll
+            for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(a.o_part + ((size_t)i * bq + rem) * DV + c0 + v * 4 * TPR) = o[v];
+            if (c0 == 0) a.lse_part[(size_t)i * bq + rem] = lse;
+        }
+    }
+    __syncthreads();
+    // the combine, shard after shard as combine_kernel does it; the groups share the columns
+    float top = -INFINITY;
+    for (int i = 0; i < a.n_shards; i++) top = fmaxf(top, sm_lse[i]);
+    float wsum = 0.f;
+    for (int c = tid * 4; c < DV; c += blockDim.x * 4) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        wsum = 0.f;
+        if (top != -INFINITY) {
+            for (int i = 0; i < a.n_shards; i++) {
+                const float li = sm_lse[i];
+                if (li == -INFINITY) continue;
+                combine_accumulate(acc, wsum, *reinterpret_cast<const f32x4*>(&sm_o[i][c]), li, top);
+            }
+            acc *= 1.f / wsum;
+        }
+        *reinterpret_cast<f32x4*>(f.o + (size_t)rem * DV + c) = acc;
+    }
+    if (tid == 0 && f.lse_out) f.lse_out[rem] = (top != -INFINITY) ? top + __logf(wsum) : -INFINITY;
+}
 
 // merge_splits + combine in one launch for calls with at most kMaxLaunchShards shards:
 // one workgroup per (b, h) row; emits the per-shard fragments (O_i, lse_i) AND the combined output.
@@ -159,7 +321,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs f)
     constexpr int TPR = MergeSmem<DV>::TPR;
     if (a.n_shards == 1) {               // the combine of one fragment is the fragment itself, bit for bit
         float M, L;
-        const f32x4 o = merge_row<DV>(a.ws_o, a.ws_m, a.ws_l, a.split_base[0], a.n_splits[0], bq, rem, sm, M, L);
+        const f32x4 o = merge_shard_row<DV>(a, 0, rem, sm, M, L);
         if (tid < TPR) {
             *reinterpret_cast<f32x4*>(a.o_part + (size_t)rem * DV + tid * 4) = o;
             *reinterpret_cast<f32x4*>(f.o + (size_t)rem * DV + tid * 4) = o;
@@ -175,7 +337,7 @@ __global__ __launch_bounds__(256) void finish_kernel(const FinishArgs f)
     float top = -INFINITY;
     for (int i = 0; i < a.n_shards; i++) {
         float M, L;
-        const f32x4 o = merge_row<DV>(a.ws_o, a.ws_m, a.ws_l, a.split_base[i], a.n_splits[i], bq, rem, sm, M, L);
+        const f32x4 o = merge_shard_row<DV>(a, i, rem, sm, M, L);
         const float lse = lse_of(M, L);
         if (tid < TPR) *reinterpret_cast<f32x4*>(a.o_part + ((size_t)i * bq + rem) * DV + tid * 4) = o;
         if (tid == 0) { a.lse_part[(size_t)i * bq + rem] = lse; sh_lse[i] = lse; }

@@ -78,12 +78,18 @@ struct MlaCfg {
     // LDS map
     static constexpr int OFF_K = 0;
     static constexpr int OFF_P = NBUF * TILE_BYTES;               // [pair][hi, lo]
-    static constexpr int OFF_FLAG = OFF_P + (WAVES / 2) * 2 * P_BYTES;   // int: a wave saw a score beyond the limit; + 4, + 8: maxima of the e4m3 set-up
+    static constexpr int OFF_FLAG = OFF_P + (WAVES / 2) * 2 * P_BYTES;   // + 4: largest query magnitude of the workgroup (fp16 set-up)
     static constexpr int OFF_SCALE = OFF_FLAG + 16;               // [NBUF][32] fp32 per-token scales
     static constexpr int OFF_DMA = OFF_SCALE + NBUF * T * 4;      // [THREADS][8] u32: per-lane source offsets of the tile DMA (5 used)
     static constexpr int OFF_STAGE = OFF_DMA + THREADS * 32;      // [WAVES][4 rows][576] e4m3 codes on their way in
-    static constexpr int LDS_BYTES = OFF_STAGE + T * DK;
-    static constexpr float kHeadroom = 32.f, kLimit = 64.f;   // bf16 latent: reference above the first tile's maximum, redo beyond this
+    static constexpr int OFF_RESC = OFF_STAGE + T * DK;           // [WAVES] int: tile (index + 1) in which a wave last moved references; [HPW] fp32 factors
+    static constexpr int LDS_BYTES = OFF_RESC + WAVES * 4 + HPW * 4;
+    // bf16 latent: a head's reference sits kHeadroom octaves above the largest score seen when it was set and moves
+    // when a score comes within 127 - kLimit octaves of fp32's largest power of two (weights and accumulators are fp32-ranged)
+    static constexpr float kHeadroom = 32.f, kLimit = 64.f;
+    // fp16 weights (e4m3 / MXFP4 latents): a head's reference moves when a weight reaches kWeightLimit, so that the
+    // tile's largest weight of that head lands in [2^(kWeightLand-1), 2^kWeightLand]
+    static constexpr float kWeightLimit = 16384.f, kWeightLand = 5.f;
 };
 static_assert(MlaCfg::LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
 
@@ -476,44 +482,77 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     const int r = lane & 15, kc = lane >> 4;
     const int pair = wave >> 1, half = wave & 1;                  // waves 2p, 2p+1 share heads 32p..32p+31
 
-    // which (shard, split, sequence, head tile of HPW heads) this workgroup serves: from the map
-    // run_order_kernel wrote (one head tile), else from its id
-    int u = blockIdx.x, si = 0, split, b, htw = 0;
-    if (a.units) {
-        const uint2 e = a.units[u];
-        si = __builtin_amdgcn_readfirstlane((int)(e.x >> 24));
-        b = __builtin_amdgcn_readfirstlane((int)(e.x & 0xffffffu));
-        split = __builtin_amdgcn_readfirstlane((int)e.y);
+    // Which runs this workgroup serves.  With a stream plan (stream_plan_kernel, one head tile): the tiles
+    // [stream_start(g), stream_start(g + 1)) of the launch's pairs laid end to end -- one run per pair the range
+    // touches.  Otherwise one run, from the workgroup id.
+    // (everything here is the same for all lanes; values loaded from memory are handed on through
+    // readfirstlane so that they, and the addresses derived from them, stay in scalar registers)
+    auto uniform64 = [](int64_t x) {
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x), hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)x >> 32));
+        return (int64_t)((uint64_t)hi << 32 | lo);
+    };
+    const bool stream = a.tile_prefix != nullptr;
+    int64_t tile_cur = 0, tile_end = 0;
+    int kvpair = 0, id_si = 0, id_split = 0, id_b = 0, htw = 0;
+    if (stream) {
+        const int64_t T = uniform64(a.tile_prefix[a.n_shards * a.B]);
+        tile_cur = stream_start(blockIdx.x, T, a.n_wg);
+        tile_end = stream_start(blockIdx.x + 1, T, a.n_wg);
+        kvpair = __builtin_amdgcn_readfirstlane(a.wg_first_pair[blockIdx.x]);
     } else {
-        while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
-        u -= a.shard[si].unit_base;
+        int u = blockIdx.x;
+        while (id_si + 1 < a.n_shards && u >= a.shard[id_si + 1].unit_base) id_si++;
+        u -= a.shard[id_si].unit_base;
         const int ug = u / (8 * a.head_tiles), j8 = u % (8 * a.head_tiles);
         const int logical = ug * 8 + (j8 & 7);
         htw = j8 >> 3;
-        if (logical >= a.shard[si].n_splits * a.B) return;         // padding workgroup
+        if (logical >= a.shard[id_si].n_splits * a.B) return;         // padding workgroup
         // Split index slow, sequence fast, and the sequence rotated by 3 per split: consecutive workgroup
         // ids go to different XCDs, so every XCD sees every split index and a mix of sequences.
-        split = logical / a.B;
-        b = (logical % a.B + 3 * split) % a.B;
+        id_split = logical / a.B;
+        id_b = (logical % a.B + 3 * id_split) % a.B;
+    }
+  for (bool first_run = true;; first_run = false) {
+    int si, b, t0, t1_cap;
+    size_t rec;
+    if (stream) {
+        if (tile_cur >= tile_end) break;
+        int64_t lo = uniform64(a.tile_prefix[kvpair]), hi = uniform64(a.tile_prefix[kvpair + 1]);
+        while (hi <= tile_cur) { kvpair++; lo = hi; hi = uniform64(a.tile_prefix[kvpair + 1]); }     // pairs without tokens
+        const int64_t seg_end = min(tile_end, hi);
+        si = kvpair / a.B;
+        b = kvpair - si * a.B;
+        t0 = (int)(tile_cur - lo) * MlaCfg::T;
+        t1_cap = (int)(seg_end - lo) * MlaCfg::T;
+        rec = (size_t)(a.rec_base + (int)blockIdx.x + kvpair) * a.Q;
+        tile_cur = seg_end;
+        kvpair++;
+    } else {
+        if (!first_run) break;
+        si = id_si;
+        b = id_b;
+        t0 = id_split * a.split_tokens;
+        t1_cap = t0 + a.split_tokens;
+        rec = ((size_t)(a.shard[si].split_base + id_split) * a.B + b) * a.Q + htw * MlaCfg::HPW;
     }
     const ShardDev& sh = a.shard[si];
 
     int len;
     int64_t first_row;
     shard_range(sh, b, len, first_row);
-    if (split == 0 && htw == 0 && threadIdx.x == 0) {
+    len = __builtin_amdgcn_readfirstlane(len);
+    first_row = uniform64(first_row);
+    if (!stream && id_split == 0 && htw == 0 && threadIdx.x == 0) {
         if (sh.out_off) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
         flag_len_overflow(sh, len, a.split_tokens);
     }
-    const int t0 = split * a.split_tokens;
-    const int t1 = min(t0 + a.split_tokens, len);
+    const int t1 = min(t1_cap, len);
     const int h0 = htw * C::HPW;                      // first head of this workgroup
     const int nh = min(C::HPW, a.Q - h0);             // real heads (the rest is zero padding)
-    const size_t rec = ((size_t)(sh.split_base + split) * a.B + b) * a.Q + h0;
 
-    if (t0 >= len) {
+    if (t0 >= len) {                                  // nothing to attend to: an empty record
         if (tid < nh) { a.ws_m[rec + tid] = -INFINITY; a.ws_l[rec + tid] = 0.f; }
-        return;
+        continue;
     }
 
     // Q slice of this wave as the score MFMA's B operand: lane (r,kc) holds head 16*wave + r of the
@@ -577,10 +616,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     const int n_tiles = (n_tok + C::T - 1) / C::T;
 
     float m_ref = -INFINITY;                          // reference exponent of head hl (integer-valued)
-    float m_floor = -INFINITY;                        // lower bound for it in a repeated run
     float l_run = 0.f;                                // this lane's share of sum p (tokens 4kc+i, 16+4kc+i of every tile)
-    float w_scale = 1.f;                              // e4m3: 2^-E, the power of two that brings p_t * f_t into fp16 range (uniform)
-    float w_max = 0.f;                                // e4m3: largest weight this lane handed to the P.V MFMAs in the run
     f32x4 acc[C::DVT][C::NHT];                        // O^T[256half + 16d + 4kc + i][32pair + 16h + r]
 
     auto ktile_of = [&](int slot) { return smem + C::OFF_K + slot * C::TILE_BYTES; };      // slot = tile index mod NBUF
@@ -642,34 +678,71 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         return bmax;
     };
 
+    // A head's reference exponent moved up by `d` octaves (0 for the heads of this wave that stay) in the S phase
+    // of tile `it`: its normaliser follows at once, its accumulators -- spread over the pair's two waves -- when
+    // the P phase finds the factor 2^-d in the mailbox (epoch = it + 1 tells that the factors are this tile's).
+    auto move_reference = [&](int it, float d) {
+        d = fminf(d, 16384.f);                        // (an infinite score: the result is NaN whatever happens here)
+        m_ref += d;
+        l_run = __builtin_ldexpf(l_run, -(int)d);
+        const int l = mla_opaque(lane);
+        if ((l >> 4) == 0) *reinterpret_cast<lds_f32*>(smem + C::OFF_RESC + C::WAVES * 4 + (wave * 16 + (l & 15)) * 4) = __builtin_ldexpf(1.f, -(int)d);
+        if (l == 0) {
+            *reinterpret_cast<lds_i32*>(smem + C::OFF_RESC + wave * 4) = it + 1;
+            if (sh.status) atomicAdd(sh.status, kStatusReferenceMoved);
+        }
+    };
+
     // Softmax of the wave's scores, entirely inside the wave: the lane's 8 weights are exactly the 8
     // k-slots of lane (r,kc) in the P.V MFMA's B operand if slot e < 4 means token 4kc + e and slot
-    // e >= 4 token 16 + 4kc + e - 4 -- the V^T operand is read to match.  The reference is fixed, so
-    // no maximum has to be agreed on across lanes: every lane checks its own scores against the
-    // limit, a ballot turns that into the workgroup's redo flag.
+    // e >= 4 token 16 + 4kc + e - 4 -- the V^T operand is read to match.  A head's reference stays where it is
+    // from tile to tile, so no maximum has to be agreed on across lanes in the common case: every lane checks
+    // its own weights (scores) against the limit, and only a tile in which some lane of the wave exceeds it
+    // takes the branch that moves that head's reference (exact powers of two throughout: which tiles moved a
+    // reference, and by how much, changes no bit of a weight's significand).
     // `masked`: the tile is the ragged last one of the run -- tokens beyond n_valid get exponent -inf,
     // clamped 200 octaves below the reference where the weight is exactly 0.  Full tiles skip both.
-    auto softmax_tile = [&](auto masked, const f32x4& s0, const f32x4& s1, int kb, int n_valid) {
+    auto softmax_tile = [&](auto masked, const f32x4& s0, const f32x4& s1, int kb, int n_valid, int it) {
         constexpr bool M = decltype(masked)::value;
         auto floor_of = [&](float x) { return M ? fmaxf(x, m_ref - 200.f) : x; };
         float t[8], fs[8], p[8];
         if constexpr (FP8) {
-            // One fp16 weight per token, w_t = p_t * f_t * 2^-E (11 significant bits: relative L2 error of
-            // O about 2e-4); the normaliser sums the unrounded p_t * 2^-E in fp32.  Range is checked once per run.
-            // p_t * 2^-E comes straight out of the exponent: the reference used here is m_ref + E, and the
-            // normaliser sums the scaled terms (the record wants l * 2^-E anyway)
+            // One fp16 weight per token, w_t = p_t * f_t (11 significant bits: relative L2 error of O about 2e-4);
+            // the normaliser sums the unrounded p_t in fp32.
             exponents(masked, s0, s1, kb, n_valid, t, fs);
-            const int mi = (int)m_ref - (__builtin_amdgcn_frexp_expf(w_scale) - 1);
-            float lsum = 0.f, wm = w_max;
+            float lsum = 0.f, wm = 0.f;
+            {
+                const int mi = (int)m_ref;
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const float pi = exp2_rel_int(floor_of(t[i]), mi);
-                lsum += pi;
-                p[i] = pi * fs[i];
-                wm = fmaxf(wm, p[i]);
+                for (int i = 0; i < 8; i++) {
+                    const float pi = exp2_rel_int(floor_of(t[i]), mi);
+                    lsum += pi;
+                    p[i] = pi * fs[i];
+                    wm = fmaxf(wm, p[i]);
+                }
+            }
+            if (__builtin_expect(__any(!(wm < C::kWeightLimit)), 0)) {
+                // The tile's scores are computed once more: kept across the branch they would cost every tile
+                // eight registers.  Exponent of the head's largest weight of this tile: log2(p_t f_t) = t + log2 f_t.
+                f32x4 r0, r1;
+                scores(ktile_of(kb), r0, r1);
+                exponents(masked, r0, r1, kb, n_valid, t, fs);
+                float um = -INFINITY;
+#pragma unroll
+                for (int i = 0; i < 8; i++) um = fmaxf(um, floor_of(t[i]) + __builtin_log2f(fs[i]));
+                um = wave_xor_max_16_32(um);
+                const bool hit = !(wave_xor_max_16_32(wm) < C::kWeightLimit);
+                move_reference(it, hit ? fmaxf(__builtin_ceilf(um) - C::kWeightLand - m_ref, 0.f) : 0.f);
+                const int mi = (int)m_ref;
+                lsum = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    const float pi = exp2_rel_int(floor_of(t[i]), mi);
+                    lsum += pi;
+                    p[i] = pi * fs[i];
+                }
             }
             l_run += lsum;
-            w_max = wm;
             u32x4 w;
 #pragma unroll
             for (int j = 0; j < 4; j++) w[j] = pack_f16_rne(p[2 * j], p[2 * j + 1]);
@@ -678,16 +751,16 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             *reinterpret_cast<lds_u32x4*>(pw) = w;
             return;
         }
-        const float top = __builtin_ceilf(exponents(masked, s0, s1, kb, n_valid, t, fs));
-        const bool over = top > m_ref + C::kLimit;
-        if (over) m_floor = fmaxf(m_floor, top + C::kHeadroom);
-        if (__any(over)) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 1;
+        float top = exponents(masked, s0, s1, kb, n_valid, t, fs);
+        if (__builtin_expect(__any(top > m_ref + C::kLimit), 0)) {
+            top = wave_xor_max_16_32(top);
+            move_reference(it, top > m_ref + C::kLimit ? __builtin_ceilf(top) + C::kHeadroom - m_ref : 0.f);
+        }
         float lsum = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             p[i] = exp2_rel(floor_of(t[i]), m_ref);
             lsum += p[i];
-            if (FP8) p[i] *= fs[i];
         }
         l_run += lsum;
         u32x4 hi, lo;
@@ -701,9 +774,9 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         *reinterpret_cast<lds_u32x4*>(pw) = hi;
         *reinterpret_cast<lds_u32x4*>(pw + C::P_BYTES) = lo;
     };
-    auto softmax = [&](const f32x4& s0, const f32x4& s1, int kb, int n_valid) {
-        if (n_valid == C::T) softmax_tile(std::false_type{}, s0, s1, kb, n_valid);
-        else softmax_tile(std::true_type{}, s0, s1, kb, n_valid);
+    auto softmax = [&](const f32x4& s0, const f32x4& s1, int kb, int n_valid, int it) {
+        if (n_valid == C::T) softmax_tile(std::false_type{}, s0, s1, kb, n_valid, it);
+        else softmax_tile(std::true_type{}, s0, s1, kb, n_valid, it);
     };
 
     // O^T[value columns of this wave, 32 heads of the pair] += V^T . P^T for one tile.  The weights
@@ -713,8 +786,21 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     // row & 7 is the same for both reads and touches the low three chunk bits: four per-lane bases
     // (d % 4), immediates for d / 4 and the second row.  `between(j)` runs after the j-th group of
     // three column tiles (the caller spreads its DMA requests there).
-    auto pv = [&](const lds_byte* ktile, auto&& between) {
+    auto pv = [&](const lds_byte* ktile, int it, auto&& between) {
         const int l = mla_opaque(lane), r = l & 15, kc = l >> 4;
+        {   // rare: heads of this pair moved their reference in this tile's S phase (move_reference)
+            const u32x2 ep = *reinterpret_cast<const lds_u32x2*>(smem + C::OFF_RESC + pair * 8);
+            const int e0 = __builtin_amdgcn_readfirstlane((int)ep.x), e1 = __builtin_amdgcn_readfirstlane((int)ep.y);
+            if (__builtin_expect(e0 == it + 1 || e1 == it + 1, 0)) {
+#pragma unroll
+                for (int h = 0; h < C::NHT; h++) {
+                    if ((h == 0 ? e0 : e1) != it + 1) continue;
+                    const float f = *reinterpret_cast<const lds_f32*>(smem + C::OFF_RESC + C::WAVES * 4 + (pair * 32 + h * 16 + r) * 4);
+#pragma unroll
+                    for (int d = 0; d < C::DVT; d++) acc[d][h] *= f;
+                }
+            }
+        }
         const lds_byte* pp = smem + C::OFF_P + pair * 2 * C::P_BYTES + r * (C::T * 2) + kc * 16;
         u32x4 bh[C::NHT], bl[C::NHT];
 #pragma unroll
@@ -795,22 +881,15 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
         }
     };
 
-    // The outer loop runs once unless the reference exponent turned out too low.
-    bool redo = false;                                // e4m3: not the first pass, references already adjusted
-    int repeats_left = 11;                            // e4m3: see the end-of-run check
-    for (;;) {
+    {
         l_run = 0.f;
-        w_max = 0.f;
 #pragma unroll
         for (int d = 0; d < C::DVT; d++)
 #pragma unroll
             for (int h = 0; h < C::NHT; h++) acc[d][h] = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (tid == 0) {
-            *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 0;
-            if (FP8) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG + 8) = 0;     // largest first-tile weight
-        }
+        if (tid < C::WAVES) *reinterpret_cast<lds_i32*>(smem + C::OFF_RESC + tid * 4) = 0;       // no reference has moved yet
 
-        // ---- first tiles on their way; tile 0 fixes the reference exponent of every head ----
+        // ---- first tiles on their way; tile 0 sets the reference exponent of every head ----
         if constexpr (FP8) {
             // the staging area holds one tile: tile 1 is requested once tile 0 has been widened
             stage_issue(0, 0);
@@ -829,25 +908,16 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             scores(ktile_of(0), s0, s1);
             const float top = wave_xor_max_16_32(exponents(std::true_type{}, s0, s1, 0, valid_of(0), t, fs));
             if constexpr (FP8) {
-                if (!redo) {
-                    // fp16 weights: a head's reference sits 4 octaves BELOW its largest exponent of the first
-                    // tile, and E (one for the workgroup: a scalar) puts the largest first-tile weight
-                    // p_t * f_t * 2^-E of any head into [2^4, 2^5) -- ten octaves of headroom to the fp16
-                    // maximum, eighteen down to the smallest normal number
-                    m_ref = __builtin_ceilf(top) - 4.f;
-                    float wm = 0.f;
+                // fp16 weights w_t = 2^(t - m) f_t: the head's reference m puts its largest first-tile weight
+                // into [2^4, 2^5] -- nine octaves below the limit at which the reference moves, eighteen above
+                // the smallest normal fp16 number.  (A tile whose token scales are all zero: by the scores.)
+                float um = -INFINITY;
 #pragma unroll
-                    for (int i = 0; i < 8; i++) wm = fmaxf(wm, exp2_rel(fmaxf(t[i], m_ref - 200.f), m_ref) * fs[i]);
-#pragma unroll
-                    for (int o = 1; o < 64; o <<= 1) wm = fmaxf(wm, __shfl_xor(wm, o));
-                    uint32_t* cell = reinterpret_cast<uint32_t*>(smem_raw + C::OFF_FLAG);
-                    if (lane == 0) atomicMax(&cell[2], as_u32(wm));        // non-negative floats order like their bits
-                    mla_barrier();
-                    const float wg = as_f32(__builtin_amdgcn_readfirstlane(cell[2]));
-                    w_scale = wg > 0.f ? __builtin_ldexpf(1.f, 5 - __builtin_amdgcn_frexp_expf(wg)) : 1.f;
-                }
+                for (int i = 0; i < 8; i++) um = fmaxf(um, t[i] + __builtin_log2f(fs[i]));
+                um = wave_xor_max_16_32(um);
+                m_ref = um > -INFINITY ? __builtin_ceilf(um) - C::kWeightLand : __builtin_ceilf(top);
             } else {
-                m_ref = fmaxf(__builtin_ceilf(top) + C::kHeadroom, m_floor);      // finite: token 0 is valid
+                m_ref = __builtin_ceilf(top) + C::kHeadroom;      // finite: token 0 is valid
             }
         }
 
@@ -857,7 +927,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             {   // S phase
                 f32x4 s0, s1;
                 scores(ktile_of(slot), s0, s1);
-                softmax(s0, s1, slot, valid_of(it));
+                softmax(s0, s1, slot, valid_of(it), it);
                 // the next tile is completed here (bf16: its DMA awaited; MXFP4: widened -- measured 1.6-2 %
                 // faster here than at the start of the P phase, the e4m3 widening 1 % slower)
                 if ((!FP8 || MX) && it + 1 < n_tiles) stage_commit(it + 1, slot1, 0);
@@ -869,47 +939,19 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
                 if (FP8 && !MX && it + 1 < n_tiles) stage_commit(it + 1, slot1, 0);
                 const bool more = it + AHEAD < n_tiles;
                 if (more) stage_begin();
-                pv(ktile_of(slot), [&](int j) { if (more && j < PARTS) stage_issue_part(it + AHEAD, slot2, j); });
+                pv(ktile_of(slot), it, [&](int j) { if (more && j < PARTS) stage_issue_part(it + AHEAD, slot2, j); });
             }
             mla_barrier();
             slot = slot1;
         }
-
-        if constexpr (FP8) {
-            // The run's largest weight per head decides: at or beyond 2^15 an fp16 weight may have
-            // overflowed, below 2^-6 too much of the softmax sat in fp16's denormal range.  Either way the
-            // reference moves so that this largest weight lands in [2^4, 2^5) and the run is repeated
-            // (weights are exact powers of two apart between the passes, so the next pass fits).
-            const float wh = wave_xor_max_16_32(w_max);
-            // !(wh < 2^15) also catches a weight that overflowed fp32: that takes an exponent at least 128
-            // octaves above the reference, so moving the reference by 120 cannot overshoot; further
-            // passes follow until the weight is finite and the exact move is known.
-            const bool bad = repeats_left > 0 && (!(wh < 32768.f) || (wh > 0.f && wh < 0.015625f));
-            if (bad) m_ref += wh < INFINITY ? (float)(__builtin_amdgcn_frexp_expf(wh) - 5) : 120.f;
-            if (__any(bad)) *reinterpret_cast<lds_i32*>(smem + C::OFF_FLAG) = 1;
-            mla_barrier();
-            redo = true;
-            repeats_left--;
-        }
-        if (__builtin_expect(*reinterpret_cast<const lds_i32*>(smem + C::OFF_FLAG) == 0, 1)) break;
-        // Some score went beyond the limit: run again with references above everything seen
-        // (the four lanes of a head saw different tokens).
-        m_floor = wave_xor_max_16_32(m_floor);
-        mla_barrier();                                // everybody has read the flag before it is cleared
     }
 
     // ---- the workgroup's record: un-normalised O, reference exponent and normaliser per head ----
     {
         const float l = wave_xor_sum_16_32(l_run);
         if (kc == 0 && hl < nh) {
-            if constexpr (FP8) {
-                // acc holds sum w_t v_t with w_t = p_t f_t 2^-E: the record's exponent takes the E
-                a.ws_m[rec + hl] = m_ref - (float)(__builtin_amdgcn_frexp_expf(w_scale) - 1);
-                a.ws_l[rec + hl] = l;                       // summed with the 2^-E in it
-            } else {
-                a.ws_m[rec + hl] = m_ref;
-                a.ws_l[rec + hl] = l;
-            }
+            a.ws_m[rec + hl] = m_ref;
+            a.ws_l[rec + hl] = l;
         }
     }
 #pragma unroll
@@ -921,6 +963,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             for (int d = 0; d < C::DVT; d++) *reinterpret_cast<f32x4*>(orow + d * 16) = acc[d][h];
         }
     }
+  }   // the workgroup's next run
 }
 
 }  // namespace helix

@@ -19,9 +19,11 @@ struct Plan {
     int32_t head_tiles;     // workgroups per (b, kv head) along the group
     int32_t granule;        // split_tokens is a multiple of this
     int32_t split_tokens;
-    int64_t total_splits;   // over all shards
+    int64_t total_splits;   // split records of the call, over all shards
     int64_t workgroups;
     bool ordered;           // the workgroups take their runs from a map written on the device (run_order_kernel)
+    bool stream;            // MLA with one head tile: every launch is cut evenly over its token stream (stream_plan_kernel)
+    size_t map_bytes;       // device-written maps of the call (run map, or tile prefix + first pair per workgroup)
 };
 
 constexpr int kMlaHeadsPerWorkgroup = 128;      // checked against the kernel's configuration where both are visible
@@ -38,6 +40,25 @@ inline int64_t target_workgroups(Path path)
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+constexpr int kMaxShardsPerLaunch = 16;         // shard descriptors travel by value in the kernel arguments
+constexpr int64_t kStreamMinTokens = 256;       // an evenly cut MLA launch gives a workgroup at least this many tokens ...
+constexpr int64_t kStreamWorkgroups = 256;      // ... and uses at most one workgroup per CU
+
+// Workgroups of an evenly cut MLA launch over shards whose longest sequences add up to `tokens` per sequence slot
+// (batch * sum of max_len): one per CU unless the launch is small, or as many as the caller's run length asks for.
+inline int64_t stream_workgroups(const helix_problem* p, int64_t tokens)
+{
+    if (p->split_tokens > 0) return std::max<int64_t>(1, ceil_div(tokens, ceil_div(p->split_tokens, 32) * 32));
+    return std::min(kStreamWorkgroups, std::max<int64_t>(1, tokens / kStreamMinTokens));
+}
+
+// Bytes of the maps stream_plan_kernel writes for a launch of `cnt` shards and `n_wg` workgroups, 256-byte aligned
+inline size_t stream_map_bytes(int64_t pairs, int64_t n_wg)
+{
+    // tile prefix [pairs + 1] int64, workgroups of every pair [pairs] 2 x int32, first pair of every workgroup [n_wg] int32
+    return ((size_t)(pairs + 1) * 8 + 255) / 256 * 256 + ((size_t)pairs * 8 + 255) / 256 * 256 + ((size_t)n_wg * 4 + 255) / 256 * 256;
+}
 
 inline int check_problem(const helix_problem* p, Path* path)
 {
@@ -96,9 +117,34 @@ inline int make_plan(const helix_problem* p, Path path, const int32_t* max_lens,
         tokens += told ? sum_lens[i] : full;
         ragged = ragged || told;
     }
-    // MLA launches always take their runs from the map (one head tile); the streaming kernels do so for
-    // a batch that is declared ragged -- the map costs a launch of its own
-    plan->ordered = path == Path::Mla ? plan->head_tiles == 1 : ragged;
+    plan->stream = path == Path::Mla && plan->head_tiles == 1;
+    if (plan->stream) {
+        // One launch per kMaxShardsPerLaunch shards.  Each is cut evenly over the tokens its sequences turn out
+        // to have (the lengths live on the device): the host only decides how many workgroups share them, from
+        // the upper bounds it knows.  A pair has one record per workgroup that touches it: at most n_wg + pairs
+        // records per launch, whatever the lengths are.
+        plan->ordered = false;
+        plan->total_splits = 0;
+        plan->workgroups = 0;
+        plan->map_bytes = 0;
+        int64_t most = 0;
+        for (int s0 = 0; s0 < n; s0 += kMaxShardsPerLaunch) {
+            const int cnt = std::min(kMaxShardsPerLaunch, n - s0);
+            int64_t bound = 0;                              // tokens of the launch if every sequence had max_len
+            for (int i = 0; i < cnt; i++) bound += (int64_t)p->batch * max_lens[s0 + i];
+            const int64_t n_wg = stream_workgroups(p, bound);
+            if (n_wg > (int64_t)1 << 20) return HELIX_ERR_SHAPE;
+            plan->total_splits += n_wg + (int64_t)cnt * p->batch;
+            plan->workgroups += n_wg;
+            plan->map_bytes += stream_map_bytes((int64_t)cnt * p->batch, n_wg);
+            most = std::max(most, ceil_div(bound, n_wg));
+        }
+        plan->split_tokens = (int32_t)std::min<int64_t>(ceil_div(std::max<int64_t>(most, 1), 32) * 32, (int64_t)INT32_MAX / 32 * 32);
+        return HELIX_OK;
+    }
+    // The streaming kernels take their runs from a map for a batch that is declared ragged -- the map costs a
+    // launch of its own; MLA launches with several head tiles go by workgroup id
+    plan->ordered = path != Path::Mla && ragged;
     int64_t split;
     if (p->split_tokens > 0) {
         split = ceil_div(p->split_tokens, plan->granule) * plan->granule;
@@ -128,6 +174,7 @@ inline int make_plan(const helix_problem* p, Path path, const int32_t* max_lens,
     for (int i = 0; i < n; i++) plan->total_splits += std::max<int64_t>(1, ceil_div(max_lens[i], split));
     plan->workgroups = plan->total_splits * rows;   // MLA launches pad this per shard to whole groups of 8
     if (plan->workgroups > (int64_t)1 << 30) return HELIX_ERR_SHAPE;
+    plan->map_bytes = plan->ordered ? (size_t)plan->workgroups * sizeof(uint64_t) : 0;
     return HELIX_OK;
 }
 
@@ -137,23 +184,26 @@ struct Workspace {
     float* ws_l;
     float* part_o;
     float* part_lse;
-    uint64_t* units;        // the run each workgroup serves (run_order_kernel), one 8-byte entry per split record row
+    char* maps;             // what the planning kernels write: the run each workgroup serves, or the stream plan
     size_t bytes;
 };
 
-// Carves a workspace for `total_splits` records and `n` shard partials.  base may be NULL (sizing).
-inline Workspace carve(const helix_problem* p, int64_t total_splits, int64_t rows, int32_t n, void* base)
+// Carves a workspace for `total_splits` records, `n` shard partials and `map_bytes` of maps.  A record holds one
+// row per (sequence, query head), or, for the evenly cut MLA launches (`per_pair`), per query head of the one
+// sequence its run belongs to.  base may be NULL (sizing).
+inline Workspace carve(const helix_problem* p, int64_t total_splits, bool per_pair, size_t map_bytes, int32_t n, void* base)
 {
     const size_t bq = (size_t)p->batch * p->q_heads;
+    const size_t rec_rows = per_pair ? (size_t)p->q_heads : bq;
     char* c = static_cast<char*>(base);
     size_t off = 0;
     Workspace w;
-    w.ws_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * p->dv * 4, 256);
-    w.ws_m = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * 4, 256);
-    w.ws_l = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * bq * 4, 256);
+    w.ws_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * rec_rows * p->dv * 4, 256);
+    w.ws_m = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * rec_rows * 4, 256);
+    w.ws_l = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)total_splits * rec_rows * 4, 256);
     w.part_o = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * p->dv * 4, 256);
     w.part_lse = reinterpret_cast<float*>(c + off); off = align_up(off + (size_t)n * bq * 4, 256);
-    w.units = reinterpret_cast<uint64_t*>(c + off); off = align_up(off + (size_t)total_splits * rows * sizeof(uint64_t), 256);
+    w.maps = c + off; off = align_up(off + map_bytes, 256);
     w.bytes = off;
     return w;
 }
@@ -208,7 +258,7 @@ inline int prepare(const helix_problem* p, const helix_kv_shard* shards, int32_t
         sum_lens[i] = shards[i].sum_len;
     }
     if (int rc = make_plan(p, path, max_lens, sum_lens, n, plan)) return rc;
-    *ws = carve(p, plan->total_splits, (int64_t)p->batch * p->kv_heads * plan->head_tiles, n, workspace);
+    *ws = carve(p, plan->total_splits, plan->stream, plan->map_bytes, n, workspace);
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || ws->bytes > workspace_bytes) return HELIX_ERR_WORKSPACE;
     return HELIX_OK;
 }
@@ -225,13 +275,15 @@ inline size_t workspace_bytes(const helix_problem* problem, int32_t n_shards, in
     for (int i = 0; i < n_shards; i++) lens[i] = max_len;
     Plan plan;
     if (make_plan(problem, path, lens, nullptr, n_shards, &plan) != HELIX_OK) return 0;
+    // an evenly cut MLA launch: workgroups and records only grow with the bounds, so the all-longest plan is the worst
+    if (plan.stream) return carve(problem, plan.total_splits, true, plan.map_bytes, n_shards, nullptr).bytes;
     const int64_t rows = (int64_t)problem->batch * problem->kv_heads * plan.head_tiles;
     int64_t worst = plan.total_splits;
     if (problem->split_tokens == 0) {
         worst = std::max<int64_t>(worst, ceil_div(target_workgroups(path), rows) + n_shards);
         if (path != Path::Mla) worst = std::max<int64_t>(worst, ragged_split_cap(path, rows, n_shards));   // a batch declared ragged
     }
-    return carve(problem, worst, rows, n_shards, nullptr).bytes;
+    return carve(problem, worst, false, (size_t)worst * rows * sizeof(uint64_t), n_shards, nullptr).bytes;
 }
 
 // The N slices helix_attn_decode_kvp hands to the kernels: each describes the whole cache (the kernel

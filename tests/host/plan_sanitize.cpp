@@ -74,19 +74,27 @@ int main()
                 }
                 planned++;
                 CHECK(plan.split_tokens > 0 && plan.split_tokens % plan.granule == 0);
-                int64_t splits = 0;
-                for (int i = 0; i < n; i++) {
-                    const int64_t ns = std::max<int64_t>(1, ceil_div(lens[i], plan.split_tokens));
-                    CHECK(ns * plan.split_tokens >= lens[i]);                     // the runs cover the longest sequence
-                    splits += ns;
-                }
-                CHECK(splits == plan.total_splits);
                 const int64_t rows = (int64_t)p.batch * p.kv_heads * plan.head_tiles;
-                CHECK(plan.workgroups == splits * rows && plan.workgroups <= ((int64_t)1 << 30));
+                if (plan.stream) {
+                    // evenly cut launches of at most 16 shards: a record per workgroup and per (shard, sequence) pair
+                    const int64_t launches = ceil_div(n, kMaxShardsPerLaunch);
+                    CHECK(plan.workgroups >= launches && plan.workgroups <= launches * ((int64_t)1 << 20));
+                    CHECK(plan.total_splits == plan.workgroups + (int64_t)n * p.batch);
+                    CHECK(plan.map_bytes >= (size_t)((int64_t)n * p.batch + launches) * 8 + (size_t)plan.workgroups * 4);
+                } else {
+                    int64_t splits = 0;
+                    for (int i = 0; i < n; i++) {
+                        const int64_t ns = std::max<int64_t>(1, ceil_div(lens[i], plan.split_tokens));
+                        CHECK(ns * plan.split_tokens >= lens[i]);                 // the runs cover the longest sequence
+                        splits += ns;
+                    }
+                    CHECK(splits == plan.total_splits);
+                    CHECK(plan.workgroups == splits * rows && plan.workgroups <= ((int64_t)1 << 30));
+                }
                 // the workspace the sizing call promises covers the call's own carving
-                const Workspace w = carve(&p, plan.total_splits, rows, n, fake_base);
+                const Workspace w = carve(&p, plan.total_splits, plan.stream, plan.map_bytes, n, fake_base);
                 CHECK((unsigned char*)w.ws_o == fake_base);
-                CHECK((size_t)((unsigned char*)w.units - fake_base) <= w.bytes && w.bytes % 256 == 0);
+                CHECK((size_t)((unsigned char*)w.maps - fake_base) + plan.map_bytes <= w.bytes && w.bytes % 256 == 0);
                 // (no bound exists only if n shards that all have the longest length are more than one launch holds)
                 const size_t bound = workspace_bytes(&p, n, longest);
                 if (bound == 0) {

@@ -69,8 +69,12 @@ def test_workspace_bound_covers_shorter_shards(hx):
                 g = prob.q_heads // prob.kv_heads
                 hpw = 128 if prob.v_aliases_k else 16           # query heads one workgroup serves
                 rows = prob.batch * prob.kv_heads * ((g + hpw - 1) // hpw)
-                splits = wgs // rows
-                need = splits * prob.batch * prob.q_heads * (prob.dv + 2) * 4
+                if prob.v_aliases_k and g <= hpw:
+                    # evenly cut MLA launches: one record of q_heads rows per workgroup and per (shard, sequence) pair
+                    need = (wgs + n * prob.batch) * prob.q_heads * (prob.dv + 2) * 4
+                else:
+                    splits = wgs // rows
+                    need = splits * prob.batch * prob.q_heads * (prob.dv + 2) * 4
                 assert need <= bound, (prob, n, max_len, lens)
     del lib
 
@@ -174,6 +178,11 @@ def test_plans_of_batches_declared_ragged(hx):
                     assert need <= bound, (prob, n, max_len, sums, lens)
     mla = hx.Problem(64, 128, 1, 576, 512, 0.07, v_aliases_k=True, kv_dtype=hx.KV_FP8_E4M3)
     assert hx.helix_attn_plan(mla, [32768] * 8, [32768 * 20] * 8) == hx.helix_attn_plan(mla, [32768] * 8)
+    # ... which is cut on the device, evenly over the tokens the sequences have: one workgroup per CU, fewer
+    # for a launch with little work, as many as an explicit run length asks for
+    assert hx.helix_attn_plan(mla, [32768] * 8)[1] == 256
+    assert hx.helix_attn_plan(hx.Problem(1, 128, 1, 576, 512, 0.07, v_aliases_k=True), [1000])[1] == 3
+    assert hx.helix_attn_plan(hx.Problem(2, 128, 1, 576, 512, 0.07, v_aliases_k=True, split_tokens=64), [1000, 24])[1] == 32
 
 
 def test_mxfp4_and_hopb_argument_errors_without_gpu(hx):
@@ -242,7 +251,10 @@ def test_plan_of_many_long_shards_does_not_wrap(hx):
             continue
         assert 0 < split <= 2 ** 31 - 1 and split % granule == 0
         rows = prob.batch * prob.kv_heads
-        assert wgs == rows * sum(max(1, -(-x // split)) for x in lens)
+        if prob.v_aliases_k:            # one launch per 16 shards, each cut evenly over one workgroup per CU
+            assert wgs == 256 * (n // 16)
+        else:
+            assert wgs == rows * sum(max(1, -(-x // split)) for x in lens)
         assert hx.helix_attn_workspace_bytes(prob, n, 2 ** 31 - 1) > 0
     # an explicit run length near the top of the range is rounded down to the granule, not up past 2^31
     prob = hx.Problem(2, 16, 1, 128, 128, 0.088, split_tokens=2 ** 31 - 1)
