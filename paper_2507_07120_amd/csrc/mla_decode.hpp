@@ -722,24 +722,36 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
                 }
             }
             if (__builtin_expect(__any(!(wm < C::kWeightLimit)), 0)) {
-                // The tile's scores are computed once more: kept across the branch they would cost every tile
-                // eight registers.  Exponent of the head's largest weight of this tile: log2(p_t f_t) = t + log2 f_t.
-                f32x4 r0, r1;
-                scores(ktile_of(kb), r0, r1);
-                exponents(masked, r0, r1, kb, n_valid, t, fs);
-                float um = -INFINITY;
+                const float wh = wave_xor_max_16_32(wm);               // the head's largest weight of this tile
+                const bool hit = !(wh < C::kWeightLimit);
+                if (!__any(hit && !(wh < INFINITY && lsum < INFINITY))) {
+                    // the usual case: every weight is a finite fp32 number, so the new reference follows from the
+                    // largest one and the tile's weights move with it by an exact power of two
+                    const int d = hit ? __builtin_amdgcn_frexp_expf(wh) - (int)C::kWeightLand : 0;
+                    move_reference(it, (float)d);
+                    lsum = __builtin_ldexpf(lsum, -d);
 #pragma unroll
-                for (int i = 0; i < 8; i++) um = fmaxf(um, floor_of(t[i]) + __builtin_log2f(fs[i]));
-                um = wave_xor_max_16_32(um);
-                const bool hit = !(wave_xor_max_16_32(wm) < C::kWeightLimit);
-                move_reference(it, hit ? fmaxf(__builtin_ceilf(um) - C::kWeightLand - m_ref, 0.f) : 0.f);
-                const int mi = (int)m_ref;
-                lsum = 0.f;
+                    for (int i = 0; i < 8; i++) p[i] = __builtin_ldexpf(p[i], -d);
+                } else {
+                    // a weight beyond fp32 (a score more than 100 octaves above the reference): the tile's scores
+                    // are computed once more -- kept across the branch they would cost every tile eight registers.
+                    // Exponent of the head's largest weight of this tile: log2(p_t f_t) = t + log2 f_t.
+                    f32x4 r0, r1;
+                    scores(ktile_of(kb), r0, r1);
+                    exponents(masked, r0, r1, kb, n_valid, t, fs);
+                    float um = -INFINITY;
 #pragma unroll
-                for (int i = 0; i < 8; i++) {
-                    const float pi = exp2_rel_int(floor_of(t[i]), mi);
-                    lsum += pi;
-                    p[i] = pi * fs[i];
+                    for (int i = 0; i < 8; i++) um = fmaxf(um, floor_of(t[i]) + __builtin_log2f(fs[i]));
+                    um = wave_xor_max_16_32(um);
+                    move_reference(it, hit ? fmaxf(__builtin_ceilf(um) - C::kWeightLand - m_ref, 0.f) : 0.f);
+                    const int mi = (int)m_ref;
+                    lsum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 8; i++) {
+                        const float pi = exp2_rel_int(floor_of(t[i]), mi);
+                        lsum += pi;
+                        p[i] = pi * fs[i];
+                    }
                 }
             }
             l_run += lsum;

@@ -119,13 +119,24 @@ def quantize_e4m3_per_token(x: torch.Tensor):
     return codes, scale
 
 
-def normal_e4m3_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", row_chunk: int = 1 << 17):
-    """rows x dim N(0,1) values quantised per row to e4m3; returns (codes uint8, scale fp32)."""
+def _peaked(x: torch.Tensor, seed: int, first_row: int, prob: float, factor: float) -> torch.Tensor:
+    """Rows first_row .. of a chunk, each multiplied by ``factor`` with probability ``prob`` (the draw of row r
+    depends on (seed, r) only, as in scale_rows_)."""
+    if prob <= 0:
+        return x
+    hit = uniform_f32(seed, TAG_PEAK, first_row, x.shape[0], x.device) < prob
+    return torch.where(hit[:, None], x * factor, x)
+
+
+def normal_e4m3_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", row_chunk: int = 1 << 17,
+                     peak_prob: float = 0.0, peak_factor: float = 1.0):
+    """rows x dim N(0,1) values (a fraction peak_prob of the rows times peak_factor) quantised per row to e4m3;
+    returns (codes uint8, scale fp32)."""
     codes = torch.empty((rows, dim), dtype=torch.uint8, device=device)
     scale = torch.empty((rows,), dtype=torch.float32, device=device)
     for r in range(0, rows, row_chunk):
         c = min(row_chunk, rows - r)
-        x = normal_f32(seed, tag, r * dim, c * dim, device).view(c, dim)
+        x = _peaked(normal_f32(seed, tag, r * dim, c * dim, device).view(c, dim), seed, r, peak_prob, peak_factor)
         codes[r:r + c], scale[r:r + c] = quantize_e4m3_per_token(x)
         _progress("e4m3 rows", r + c, rows)
     return codes, scale
@@ -156,13 +167,15 @@ def quantize_mxfp4(x: torch.Tensor):
     return packed, (shared + 127).to(torch.uint8)
 
 
-def normal_mxfp4_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", row_chunk: int = 1 << 17):
-    """rows x dim N(0,1) values in MXFP4; returns (codes uint8 [rows, dim/2], scales uint8 [rows, dim/32])."""
+def normal_mxfp4_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", row_chunk: int = 1 << 17,
+                      peak_prob: float = 0.0, peak_factor: float = 1.0):
+    """rows x dim N(0,1) values (a fraction peak_prob of the rows times peak_factor) in MXFP4; returns (codes uint8
+    [rows, dim/2], scales uint8 [rows, dim/32])."""
     codes = torch.empty((rows, dim // 2), dtype=torch.uint8, device=device)
     scales = torch.empty((rows, dim // 32), dtype=torch.uint8, device=device)
     for r in range(0, rows, row_chunk):
         c = min(row_chunk, rows - r)
-        x = normal_f32(seed, tag, r * dim, c * dim, device).view(c, dim)
+        x = _peaked(normal_f32(seed, tag, r * dim, c * dim, device).view(c, dim), seed, r, peak_prob, peak_factor)
         codes[r:r + c], scales[r:r + c] = quantize_mxfp4(x)
         _progress("MXFP4 rows", r + c, rows)
     return codes, scales
@@ -223,6 +236,17 @@ WORKLOADS = {
     "mla_mxfp4_ragged": Workload("mla_mxfp4_ragged", B=64, Q=128, K=1, dk=576, dv=512, n_shards=8,
                                  scale=1 / math.sqrt(192), seed=1005, len_range=(16384, 262144),
                                  mla=True, fp4=True),
+    # the MLA configurations with the sharp softmax peaks of the full GQA configuration (1 % of the latent rows
+    # times 8 before quantisation): the scores of those rows stand 60 octaves and more above the rest
+    "mla_share_peaked": Workload("mla_share_peaked", B=32, Q=128, K=1, dk=576, dv=512, n_shards=1,
+                                 scale=1 / math.sqrt(192), seed=1003, seq_len=131072, mla=True,
+                                 peak_prob=0.01, peak_factor=8.0),
+    "mla_fp8_peaked": Workload("mla_fp8_peaked", B=64, Q=128, K=1, dk=576, dv=512, n_shards=8,
+                               scale=1 / math.sqrt(192), seed=1005, len_range=(16384, 262144),
+                               mla=True, fp8=True, peak_prob=0.01, peak_factor=8.0),
+    "mla_mxfp4_peaked": Workload("mla_mxfp4_peaked", B=64, Q=128, K=1, dk=576, dv=512, n_shards=8,
+                                 scale=1 / math.sqrt(192), seed=1005, len_range=(16384, 262144),
+                                 mla=True, fp4=True, peak_prob=0.01, peak_factor=8.0),
 }
 
 
@@ -259,12 +283,14 @@ def make_inputs(w: Workload, device="cpu") -> Inputs:
         assert w.K == 1 and w.mla, "ragged packed storage is defined for the single-latent case"
         if w.fp4:
             assert not w.fp8
-            kc, ks = normal_mxfp4_rows(w.seed, TAG_K, rows, w.dk, device)
+            kc, ks = normal_mxfp4_rows(w.seed, TAG_K, rows, w.dk, device, peak_prob=w.peak_prob, peak_factor=w.peak_factor)
             return Inputs(w, q, kc, None, None, lens, seq_off, ks, None)
         if w.fp8:
-            k, kv_scale = normal_e4m3_rows(w.seed, TAG_K, rows, w.dk, device)
+            k, kv_scale = normal_e4m3_rows(w.seed, TAG_K, rows, w.dk, device, peak_prob=w.peak_prob, peak_factor=w.peak_factor)
         else:
             k, kv_scale = normal_bf16(w.seed, TAG_K, (rows, w.dk), device), None
+            if w.peak_prob > 0:
+                scale_rows_(k, w.seed, TAG_PEAK, w.peak_prob, w.peak_factor)
         return Inputs(w, q, k, None, kv_scale, lens, seq_off)
     S = w.seq_len
     lens = torch.full((w.B,), S, dtype=torch.int32)
@@ -272,7 +298,7 @@ def make_inputs(w: Workload, device="cpu") -> Inputs:
     if w.fp4 and w.mla:
         # one MXFP4 latent per token: 576 codes (288 bytes) + 18 block scales; the value aliases its first 512 entries
         assert not w.fp8 and w.K == 1
-        kc, ks = normal_mxfp4_rows(w.seed, TAG_K, w.B * S, w.dk, device)
+        kc, ks = normal_mxfp4_rows(w.seed, TAG_K, w.B * S, w.dk, device, peak_prob=w.peak_prob, peak_factor=w.peak_factor)
         return Inputs(w, q, kc.view(w.B, 1, S, w.dk // 2), None, None, lens, None, ks.view(w.B, 1, S, w.dk // 32), None)
     if w.fp4:
         assert not w.fp8
@@ -281,7 +307,7 @@ def make_inputs(w: Workload, device="cpu") -> Inputs:
         return Inputs(w, q, kc.view(w.B, w.K, S, w.dk // 2), vc.view(w.B, w.K, S, w.dv // 2), None, lens, None,
                       ks.view(w.B, w.K, S, w.dk // 32), vs.view(w.B, w.K, S, w.dv // 32))
     if w.fp8:
-        codes, sc = normal_e4m3_rows(w.seed, TAG_K, w.B * w.K * S, w.dk, device)
+        codes, sc = normal_e4m3_rows(w.seed, TAG_K, w.B * w.K * S, w.dk, device, peak_prob=w.peak_prob, peak_factor=w.peak_factor)
         k, kv_scale = codes.view(w.B, w.K, S, w.dk), sc.view(w.B, w.K, S)
     else:
         k = normal_bf16(w.seed, TAG_K, (w.B, w.K, S, w.dk), device)

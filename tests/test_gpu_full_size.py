@@ -277,3 +277,29 @@ def test_mla_mxfp4_ragged_full(hx, oracle):
     assert len(rows) >= 128
     check_rows(o8, lse8, o_ref, lse_ref, rows, "mla_mxfp4_ragged sharded")
     check_as_bench(hx, oracle, w, inp, 8, o8, lse8, o_ref, lse_ref, rows, "mla_mxfp4_ragged sharded")
+
+
+@pytest.mark.parametrize("name", ["mla_fp8_peaked", "mla_mxfp4_peaked"])
+def test_mla_peaked_full(hx, oracle, name):
+    """The ragged MLA configurations with 1 % of the latent rows scaled by 8 before quantisation (the sharp softmax
+    peaks of the full GQA configuration): every head of the shortest sequence and single rows of others against the
+    oracle, and 8 shards against the unsharded run."""
+    w = synth.WORKLOADS[name]
+    inp = synth.make_inputs(w, "cuda")
+    lens = inp.lens.numpy()
+    o8, lse8, _, _, _ = decode(hx, w, inp, 8)
+    assert torch.isfinite(o8).all() and torch.isfinite(lse8).all()
+    o1, lse1, _, _, _ = decode(hx, w, inp, 1)
+    d = (o8 - o1).abs().max().item()
+    print(f"{name}: sharded(8) vs unsharded max-abs {d:.3e}, |o| max {o1.abs().max().item():.2f}")
+    assert d <= SHARD_VS_UNSHARDED * max(1.0, o1.abs().max().item())
+    assert (lse8 - lse1).abs().max().item() <= 1e-4
+    b_short = int(lens.argmin())
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, [b_short], extra_rows=[(int(lens.argmax()), 17), (5, 99)])
+    # one fp16 weight per token: |dO| <= 2^-12 max |v| when the softmax is nearly one-hot (rows of up to 8 x 4.7 sigma)
+    got = np.stack([o8.cpu().numpy()[b, h] for b, h in rows]).astype(np.float64)
+    gl = np.array([lse8.cpu().numpy()[b, h] for b, h in rows], dtype=np.float64)
+    err, rel = np.abs(got - o_ref).max(), np.linalg.norm(got - o_ref) / np.linalg.norm(o_ref)
+    lerr = np.abs(gl - lse_ref).max()
+    print(f"{name}: O max-abs {err:.3e} rel-L2 {rel:.3e}  LSE max-abs {lerr:.3e}  max |o_ref| {np.abs(o_ref).max():.2f}")
+    assert err <= max(O_MAX_ABS, 2.0 ** -11 * np.abs(o_ref).max()) and rel <= O_REL_L2 and lerr <= LSE_MAX_ABS

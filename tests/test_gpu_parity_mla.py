@@ -257,3 +257,51 @@ def test_mla_fp8_query_magnitudes_far_apart(hx, oracle):
     mean_v = (inp.k[0, 0, :257, :512].view(torch.float8_e4m3fn).float() * inp.kv_scale[0, 0, :257, None]).mean(dim=0)
     # 257 equal weights, each rounded to fp16 (2^-12 relative): about 1e-5 rms per output, 3.5 sigma over 512 columns
     assert (o[0, 3] - mean_v).abs().max().item() <= 1e-4
+
+
+@pytest.mark.parametrize("fmt", ["bf16", "e4m3", "mxfp4"])
+def test_mla_peaked_rows_move_the_reference_not_the_result(hx, oracle, fmt):
+    """The full GQA configuration's recipe on a latent: 2 % of the rows times 8 before quantisation, so their scores
+    stand tens of octaves above the rest and arrive at unpredictable tiles.  The kernels move a head's reference
+    exponent in the tile that needs it (the status word counts those events) instead of going over a run again;
+    the result keeps the usual bars against the oracle, for one shard and for several, with short forced runs and
+    with the automatic ones, and sharded and unsharded runs still agree to fp32 summation order."""
+    from paper_2507_07120_amd import harness
+    w = synth.Workload("mla_peaked", B=2, Q=128, K=1, dk=576, dv=512, n_shards=3, scale=1 / math.sqrt(192), seed=77,
+                       seq_len=6000, mla=True, fp8=fmt == "e4m3", fp4=fmt == "mxfp4", peak_prob=0.02, peak_factor=8.0)
+    inp = synth.make_inputs(w, "cuda")
+    inp.lens = torch.tensor([6000, 2345], dtype=torch.int32)
+    dev = "cuda"
+    lens_dev = inp.lens.to(dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    qb, kb = synth.bits(inp.q), synth.bits(inp.k)
+    sc = None if inp.kv_scale is None else inp.kv_scale.cpu().numpy()
+    mx = None if inp.k_mx is None else (inp.k_mx.cpu().numpy(), None)
+    o_ref, lse_ref = oracle.attention(qb, kb, None, inp.lens.numpy(), w.scale, kv_heads=1, dv=w.dv, kv_scale=sc, mx=mx)
+    # fp16 weights carry 2^-12 of relative rounding the normaliser does not share: |dO| <= 2^-12 max |v| on a one-hot softmax
+    vmax = float(np.abs(o_ref).max()) * 1.05
+    max_abs = O_MAX_ABS if fmt == "bf16" else max(O_MAX_ABS, 2.0 ** -11 * vmax)
+    outs = []
+    for n_shards, split in [(1, 0), (3, 0), (3, 256), (1, 96)]:
+        prob = harness.problem_for(w, split)
+        ss = harness.make_shards(inp.k, None, lens_dev, n_shards, kv_scale=inp.kv_scale,
+                                 mx=None if inp.k_mx is None else (inp.k_mx, None))
+        for s in ss.shards:
+            s.status = status
+        ws = harness.workspace_for(prob, n_shards, max(ss.max_lens), dev)
+        ws.view(torch.float32)[: ws.numel() // 4].fill_(float("nan"))
+        o = torch.full((w.B, w.Q, w.dv), float("nan"), device=dev)
+        lse = torch.full((w.B, w.Q), float("nan"), device=dev)
+        status.zero_()
+        hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+        torch.cuda.synchronize()
+        moves = status.item() >> 8
+        print(f"{fmt} N={n_shards} split={split}: {moves} reference moves")
+        assert status.item() & 0xFF == 0
+        if fmt != "bf16":
+            assert moves > 0          # the 9 octaves of headroom of an fp16 weight cannot hold a row scaled by 8
+        check_o(o.cpu().numpy(), o_ref, f"peaked {fmt} N={n_shards} split={split} O", max_abs)
+        check_lse(lse.cpu().numpy(), lse_ref, f"peaked {fmt} N={n_shards} split={split} LSE")
+        outs.append(o)
+    for o in outs[1:]:
+        assert (o - outs[0]).abs().max().item() <= SHARD_VS_UNSHARDED * max(1.0, vmax)
