@@ -157,7 +157,6 @@ def measure(name, args, budget_macs, extras=False):
         cache = hx.KVShard.from_packed(inp.k, lens_dev, max_len, seq_base, kv_scale=inp.kv_scale)
     else:
         cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, max_len, kv_scale=inp.kv_scale)
-    cache.sum_len = int(inp.lens.sum())       # the host knows the lengths it generated: it declares their sum
     status = torch.zeros(1, dtype=torch.int32, device=dev)
     cache.status = status                     # device word: sequences beyond max_len (bit 0), moved MLA reference exponents (>> 8)
     ws = harness.workspace_for(prob, N, max_len, dev)
@@ -166,8 +165,8 @@ def measure(name, args, budget_macs, extras=False):
 
     # the explicit shard descriptors (the two-call form of the step, HOP-B, and the plan that is reported)
     ss = harness.make_shards(inp.k, inp.v, lens_dev, N, kv_scale=inp.kv_scale, seq_base=seq_base,
-                             mx=None if inp.k_mx is None else (inp.k_mx, inp.v_mx), declare_sums=True)
-    split_tokens, workgroups = hx.helix_attn_plan(prob, ss.max_lens, [s.sum_len for s in ss.shards])
+                             mx=None if inp.k_mx is None else (inp.k_mx, inp.v_mx))
+    split_tokens, workgroups = hx.helix_attn_plan(prob, ss.max_lens)
 
     # one step = the whole path over one batch: the KVP cut of every sequence (integer metadata, written
     # out), the per-slice attention fragments, and their combine

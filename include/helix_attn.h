@@ -115,10 +115,6 @@ typedef struct helix_kv_shard {
     int32_t max_len;        /* host copy of an upper bound of len[b] (sizes the grid); >= 0 */
     const uint8_t *k_scale_mx; /* MXFP4 only: E8M0 block scales of k; NULL otherwise */
     const uint8_t *v_scale_mx; /* MXFP4 only: E8M0 block scales of v; NULL otherwise */
-    int64_t sum_len;        /* host copy of an upper bound of the sum of len[b] over the batch, or 0 = unknown
-                               (batch * max_len is assumed).  A ragged batch that says so gets runs sized for
-                               the tokens it has and workgroups that take the non-empty runs first; results
-                               do not depend on it. */
     int32_t *status;        /* device int32 or NULL: the attention kernels OR HELIX_STATUS_* bits into it when they
                                meet device data the host could not check (the caller clears it; it is only ever
                                written when a condition holds) */
@@ -288,9 +284,9 @@ double helix_weight_read_seconds(int64_t H, int64_t Q, int64_t K, int64_t Hsz, i
                                  double bytes_per_param, double mem_bw, int64_t TPA, int64_t TPF);
 
 /* How the library would cut the work: tokens per workgroup and workgroups of the attention launch
- * for the given shards' max_len (host array [N]) and sum_len (host array [N], or NULL = all unknown).
+ * for the given shards' max_len (host array [N]): the tokens a workgroup gets if every sequence is that long.
  * For benchmarks and tests; launches nothing. */
-int helix_attn_plan(const helix_problem *problem, const int32_t *max_lens, const int64_t *sum_lens, int32_t n_shards,
+int helix_attn_plan(const helix_problem *problem, const int32_t *max_lens, int32_t n_shards,
                     int32_t *split_tokens, int64_t *workgroups);
 
 /* helix_attn_decode_kvp for benchmarks: additionally records `start_event` immediately before and `stop_event`

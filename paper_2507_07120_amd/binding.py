@@ -37,7 +37,7 @@ class _CShard(ctypes.Structure):
                 ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_t", ctypes.c_int64),
                 ("s_stride_b", ctypes.c_int64), ("s_stride_h", ctypes.c_int64),
                 ("tok_off", ctypes.c_void_p), ("len", ctypes.c_void_p), ("max_len", ctypes.c_int32),
-                ("k_scale_mx", ctypes.c_void_p), ("v_scale_mx", ctypes.c_void_p), ("sum_len", ctypes.c_int64),
+                ("k_scale_mx", ctypes.c_void_p), ("v_scale_mx", ctypes.c_void_p),
                 ("status", ctypes.c_void_p)]
 
 
@@ -67,7 +67,7 @@ def load_library():
     lib.helix_attn_workspace_bytes.restype = ctypes.c_size_t
     lib.helix_attn_workspace_bytes.argtypes = [ctypes.POINTER(_CProblem), i32, i32]
     lib.helix_attn_plan.restype = ctypes.c_int
-    lib.helix_attn_plan.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(i32), ctypes.POINTER(i64), i32,
+    lib.helix_attn_plan.argtypes = [ctypes.POINTER(_CProblem), ctypes.POINTER(i32), i32,
                                     ctypes.POINTER(i32), ctypes.POINTER(i64)]
     lib.helix_attn_partial.restype = ctypes.c_int
     lib.helix_attn_partial.argtypes = [ctypes.POINTER(_CProblem), vp, ctypes.POINTER(_CShard), vp, vp,
@@ -149,7 +149,6 @@ class KVShard:
     tok_off: Optional[torch.Tensor] = None  # int64 [B] on the device
     k_scale_mx: Optional[torch.Tensor] = None   # MXFP4: uint8 block scales, k / v are uint8 codes and
     v_scale_mx: Optional[torch.Tensor] = None   # the strides count elements (two per byte)
-    sum_len: int = 0                            # host copy of an upper bound of sum(len), 0 = unknown (a hint for ragged batches)
     status: Optional[torch.Tensor] = None       # int32 [1] on the device: HELIX_STATUS_* bits the kernels raise
 
     @staticmethod
@@ -209,7 +208,7 @@ class KVShard:
         return _CShard(ptr(self.k), ptr(self.v), ptr(self.kv_scale), *[int(x) for x in self.k_strides],
                        *[int(x) for x in self.v_strides], *[int(x) for x in self.s_strides],
                        ptr(self.tok_off), ptr(self.len), int(self.max_len), ptr(self.k_scale_mx), ptr(self.v_scale_mx),
-                       int(self.sum_len), ptr(self.status))
+                       ptr(self.status))
 
 
 def _stream_ptr(stream) -> Optional[int]:
@@ -233,16 +232,12 @@ def helix_attn_workspace_bytes(problem: Problem, n_shards: int, max_len: int) ->
     return int(load_library().helix_attn_workspace_bytes(ctypes.byref(p), n_shards, max_len))
 
 
-def helix_attn_plan(problem: Problem, max_lens: Sequence[int], sum_lens: Optional[Sequence[int]] = None):
+def helix_attn_plan(problem: Problem, max_lens: Sequence[int]):
     """(split_tokens, workgroups) the library would use; launches nothing."""
     p = problem.c()
     arr = (ctypes.c_int32 * len(max_lens))(*[int(x) for x in max_lens])
-    sums = None
-    if sum_lens is not None:
-        assert len(sum_lens) == len(max_lens)
-        sums = (ctypes.c_int64 * len(sum_lens))(*[int(x) for x in sum_lens])
     st, wg = ctypes.c_int32(0), ctypes.c_int64(0)
-    _check(load_library().helix_attn_plan(ctypes.byref(p), arr, sums, len(max_lens), ctypes.byref(st), ctypes.byref(wg)),
+    _check(load_library().helix_attn_plan(ctypes.byref(p), arr, len(max_lens), ctypes.byref(st), ctypes.byref(wg)),
            "helix_attn_plan")
     return st.value, wg.value
 

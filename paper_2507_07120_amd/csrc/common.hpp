@@ -63,7 +63,9 @@ struct AttnArgs {
     int32_t split_tokens; // tokens of a shard one workgroup streams
     float scale_log2e;    // softmax scale * log2(e)
     int32_t n_shards;
-    const uint2* units;   // which (shard << 24 | row, split) each workgroup serves, written by run_order_kernel; NULL: by id
+    // streaming GQA launches (every workgroup plans its own share, stream_self_plan): what the merge needs later
+    int64_t* prefix_out;  // [pairs + 1] row tiles before pair p, written by workgroup 0
+    int2* row_rec;        // [rows] first and last workgroup that hold tiles of a row, written by those workgroups
     // MLA launches that are cut evenly over the token stream (stream_plan_kernel): the (shard, sequence) pairs of
     // the launch, pair = shard * B + sequence, laid end to end in 32-token tiles
     const int64_t* tile_prefix;   // [pairs + 1] tiles before pair p; [pairs] = all tiles.  NULL: runs by workgroup id
@@ -75,40 +77,60 @@ struct AttnArgs {
 
 constexpr int kStreamTile = 32;   // tokens per tile of the MLA kernels
 
-// First tile of workgroup g when T tiles are dealt evenly to n_wg workgroups: workgroup g serves tiles
-// [stream_start(g), stream_start(g + 1)), each range T / n_wg tiles long to within one.
-__host__ __device__ __forceinline__ int64_t stream_start(int64_t g, int64_t T, int64_t n_wg) { return g * T / n_wg; }
+// T tiles dealt evenly to n_wg workgroups: the first T % n_wg workgroups serve T / n_wg + 1 consecutive tiles, the
+// others T / n_wg.  With fewer tiles than workgroups the first T workgroups get one tile each, so the workgroups
+// without a tile all sit at the end (the workgroups that hold tiles of one row are always consecutive).
+struct StreamDeal {
+    int64_t q, r;
+    // first tile of workgroup g (0 <= g <= n_wg)
+    __host__ __device__ __forceinline__ int64_t start(int64_t g) const { return g * q + (g < r ? g : r); }
+    // the workgroup that serves tile x (0 <= x < T)
+    __host__ __device__ __forceinline__ int owner(int64_t x) const
+    {
+        const int64_t head = r * (q + 1);                  // tiles of the workgroups with one tile more
+        return x < head ? (int)(x / (q + 1)) : (int)(r + (x - head) / q);
+    }
+};
 
-// The workgroup whose range holds tile x (0 <= x < T): the largest g with stream_start(g) <= x.
-__device__ __forceinline__ int stream_owner(int64_t x, int64_t T, int n_wg)
+__host__ __device__ __forceinline__ StreamDeal stream_deal(int64_t T, int n_wg)
 {
-    int g = (int)min((int64_t)n_wg - 1, (x * n_wg + n_wg - 1) / T);       // at or just above the answer
-    while (g > 0 && stream_start(g, T, n_wg) > x) g--;
-    while (g + 1 < n_wg && stream_start(g + 1, T, n_wg) <= x) g++;
-    return g;
+    StreamDeal d;
+    if (__builtin_expect((uint64_t)T >> 32 != 0, 0)) {
+        d.q = T / n_wg;
+        d.r = T % n_wg;
+    } else {                                               // (the usual sizes: a 32-bit division costs a fraction of the 64-bit one)
+        const uint32_t q = (uint32_t)T / (uint32_t)n_wg;
+        d.q = q;
+        d.r = (uint32_t)T - q * (uint32_t)n_wg;
+    }
+    return d;
 }
 
 // Tokens of sequence b this shard holds and the row of the first one.  With kvp_n > 0 the contiguous
 // KVP cut of Sec. 2.1.1 is made here: slice width c = 16 * ceil(ceil(L / N) / 16) tokens (whole blocks of
 // the append granule of Sec. 2.3), slice i = [min(i c, L), min((i+1) c, L)) -- the same integers the
 // stand-alone layout kernel produces.
-__device__ __forceinline__ void shard_range(const ShardDev& sh, int b, int& len, int64_t& first_row)
+__device__ __forceinline__ void shard_range_of(int64_t L, int64_t base, int kvp_n, int kvp_i, int& len, int64_t& first_row)
 {
-    const int64_t base = sh.tok_off ? sh.tok_off[b] : 0;
-    const int64_t L = sh.len[b];
-    if (sh.kvp_n == 0) {
+    if (kvp_n == 0) {
         len = (int)L;
         first_row = base;
         return;
     }
     // 32-bit unsigned arithmetic for the division (L < 2^31, N <= 1024, so L + N - 1 and c fit); only
     // the product i * c needs 64 bits
-    const uint32_t n = (uint32_t)sh.kvp_n;
+    const uint32_t n = (uint32_t)kvp_n;
     const uint32_t per = ((uint32_t)L + n - 1u) / n;
     const uint32_t c = ((per + 15u) >> 4) << 4;
-    const int64_t lo = min((int64_t)sh.kvp_i * c, L), hi = min((int64_t)(sh.kvp_i + 1) * c, L);
+    const int64_t lo = min((int64_t)kvp_i * c, L), hi = min((int64_t)(kvp_i + 1) * c, L);
     len = (int)(hi - lo);
     first_row = base + lo;
+}
+
+__device__ __forceinline__ void shard_range(const ShardDev& sh, int b, int& len, int64_t& first_row)
+{
+    const int64_t base = sh.tok_off ? sh.tok_off[b] : 0;
+    shard_range_of(sh.len[b], base, sh.kvp_n, sh.kvp_i, len, first_row);
 }
 
 __device__ __forceinline__ uint32_t as_u32(float x) { return __builtin_bit_cast(uint32_t, x); }
@@ -157,77 +179,236 @@ __device__ __forceinline__ float wave_xor_sum_16_32(float x)
     return x;
 }
 
-// The order in which the workgroups of an attention launch take their runs.  Workgroup ids are dealt
-// round-robin to the 8 XCDs (and on to their CUs) for good; an MLA workgroup needs a whole CU whatever it
-// finds to do.  With ragged lengths the runs of a launch are full (split_tokens rows), partial (the last
-// of a sequence's slice) or empty (the grid is sized for the longest sequence), and with a plain
-// id -> (split, row) map the XCDs whose ids happen to hold less work idle at the end (measured: 15 % of
-// the ragged MLA configuration).  This kernel (one workgroup) writes the map instead: all full runs
-// first -- equal cost, so every XCD gets the same share -- then the partial ones by descending length
-// (16 classes), then the empty ones, which only write their empty record.  A row is a (sequence, kv
-// head, head tile): row = (b * K + kv head) * head_tiles + head tile.  Entry i: x = shard << 24 | row,
-// y = split index.  Which workgroup serves which run has no influence on any result.
-constexpr int kOrderThreads = 1024, kOrderClasses = 16;
-
-__global__ __launch_bounds__(kOrderThreads) void run_order_kernel(const AttnArgs a, uint2* units, int n_units)
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (no shared memory): shifts by
+// 1, 2, 4, 8 inside each row of 16 lanes (lanes without a source add 0), then the last lane of rows 0 and 2 is
+// added to rows 1 and 3, then lane 31 to rows 2 and 3.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x)
 {
-    __shared__ int count[kOrderClasses + 2];              // runs per segment: [0] full, [1 + c] partial of class c, [last] empty
-    __shared__ int cursor[kOrderClasses + 2];
-    const int tid = threadIdx.x;
-    const int rows = a.B * a.K * a.head_tiles;
-    const int pairs = a.n_shards * rows;
-    if (tid < kOrderClasses + 2) count[tid] = 0;
-    __syncthreads();
-    // what one (shard, row) pair contributes: nf full runs, one partial run of class cls (or none: -1)
-    auto runs_of = [&](int p, int& si, int& row, int& nf, int& cls, int& n) {
-        si = p / rows;
-        row = p - si * rows;
-        const int b = row / (a.K * a.head_tiles);
-        const ShardDev& sh = a.shard[si];
+    constexpr int kRowShr = 0x110, kRowBcast15 = 0x142, kRowBcast31 = 0x143;
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kRowShr + 1, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kRowShr + 2, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kRowShr + 4, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kRowShr + 8, 0xf, 0xf, true);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kRowBcast15, 0xa, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, kRowBcast31, 0xc, 0xf, false);
+    return x;
+}
+
+// The same even cut, planned by every workgroup for itself (the streaming GQA kernels: a planning launch of its
+// own would cost them 5 % of a step).  The launch's rows -- (shard, sequence, kv head, head tile), rows_per_pair of
+// them per (shard, sequence) pair, all as long as the pair's slice -- are laid end to end in tiles of tile_tokens
+// tokens, and workgroup g of n_wg takes the row tiles [g T / n_wg, (g + 1) T / n_wg).  Every workgroup reads all
+// lengths (one or a few per thread, in parallel: the one dependent memory round trip a workgroup needs anyway
+// before it knows where its keys are), scans them, and finds the pair that holds its first tile.  All results
+// are the same in every lane.
+struct StreamCursor {
+    int64_t cur, end;        // row tiles still to serve: [cur, end)
+    int32_t pair;            // the pair that holds tile `cur` ...
+    int64_t pair_lo;         // ... its first row tile
+    int64_t pair_tiles;      // ... the tiles of one of its rows
+    int64_t first_row;       // ... the row of its slice's first token in the cache
+    int32_t len;             // ... and the slice's length in tokens
+};
+
+__device__ __forceinline__ int64_t uniform_i64(int64_t x)
+{
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x), hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)x >> 32));
+    return (int64_t)((uint64_t)hi << 32 | lo);
+}
+
+// THREADS = threads of the workgroup (a multiple of 64, at most 1024); scratch: THREADS / 64 + 5 int64 in LDS.
+// prefix_out (may be NULL): workgroup 0 stores the exclusive prefix of the pairs' row tiles there, [pairs + 1], for
+// the merge kernel; it also records the KVP cut of every pair (out_off / out_len of the shards).
+// Returns false if this workgroup has no tile to serve.
+template <int THREADS>
+__device__ __forceinline__ bool stream_self_plan(const AttnArgs& a, int tile_tokens, int rows_per_pair, int64_t* scratch,
+                                                 int64_t* prefix_out, StreamCursor& c)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pairs = a.n_shards * a.B;
+    if (__builtin_expect(pairs <= 64, 1)) {
+        // The usual case: every wave plans for itself, lane p looking at pair p -- no shared memory, no barrier.
+        // The loops run over uniform indices, so that the shards' pointers come from scalar loads of the kernel
+        // arguments and the lengths are the only vector loads on the way.
+        // (lanes beyond the last pair look at the last pair too, so that no load sits under a condition; their
+        // tile count is zeroed below)
+        const int pl = min(lane, pairs - 1);
+        const int32_t* len_at = nullptr;
+        const int64_t* off_at = nullptr;
+        int kvp_n = 0, kvp_i = 0;
+        for (int si = 0; si < a.n_shards; si++) {
+            const ShardDev& sh = a.shard[si];
+            const int b = pl - si * a.B;
+            if (b >= 0 && b < a.B) {
+                len_at = sh.len + b;
+                off_at = sh.tok_off ? sh.tok_off + b : nullptr;
+                kvp_n = sh.kvp_n;
+                kvp_i = sh.kvp_i;
+            }
+        }
+        const int64_t L = *len_at;                                                  // both loads in flight together
+        const int64_t base = __builtin_expect(off_at != nullptr, 1) ? *off_at : 0;
         int len;
         int64_t first_row;
-        shard_range(sh, b, len, first_row);
-        len = max(len, 0);                                // a negative length is an empty sequence, as in the attention kernels
-        n = sh.n_splits;
-        nf = min(len / a.split_tokens, n);
-        const int rem = len - nf * a.split_tokens;
-        cls = nf < n && rem > 0 ? kOrderClasses - 1 - min(kOrderClasses - 1, (int)((int64_t)rem * kOrderClasses / a.split_tokens)) : -1;
+        shard_range_of(L, base, kvp_n, kvp_i, len, first_row);
+        const uint32_t t = lane < pairs ? (uint32_t)((max(len, 0) + tile_tokens - 1) / tile_tokens) : 0u;
+        // inclusive sum of the pairs' tile counts over the lanes (at most 64 x 2^24: 32 bits), then times the rows
+        const uint32_t t_incl = wave_inclusive_sum(t);
+        const int64_t T = (int64_t)__builtin_amdgcn_readlane(t_incl, 63) * rows_per_pair;
+        const int64_t excl = (int64_t)(t_incl - t) * rows_per_pair;
+        const int64_t mine = (int64_t)t * rows_per_pair;
+        if (__builtin_expect(blockIdx.x == 0 && wave == 0, 0)) {
+            if (prefix_out && lane < pairs) {
+                prefix_out[lane] = excl;
+                if (lane == pairs - 1) prefix_out[pairs] = T;
+            }
+            for (int si = 0; si < a.n_shards; si++) {                    // the KVP cut, empty slices included
+                const ShardDev& sh = a.shard[si];
+                const int b = lane - si * a.B;
+                if (sh.out_off && b >= 0 && b < a.B) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
+            }
+        }
+        const StreamDeal deal = stream_deal(T, a.n_wg);
+        c.cur = deal.start(blockIdx.x);
+        c.end = deal.start(blockIdx.x + 1);
+        if (c.cur >= c.end) return false;
+        // exactly one lane's pair holds tile `cur` (0 <= cur < T)
+        const uint64_t holds = __ballot(lane < pairs && mine > 0 && excl <= c.cur && c.cur < excl + mine);
+        const int src = __builtin_ctzll(holds | (1ull << 63));
+        auto from = [&](uint32_t v) { return (uint32_t)__builtin_amdgcn_readlane(v, src); };
+        c.pair = src;
+        c.pair_lo = (int64_t)((uint64_t)from((uint32_t)((uint64_t)excl >> 32)) << 32 | from((uint32_t)excl));
+        c.pair_tiles = from(t);
+        c.first_row = (int64_t)((uint64_t)from((uint32_t)((uint64_t)first_row >> 32)) << 32 | from((uint32_t)first_row));
+        c.len = (int32_t)from((uint32_t)len);
+        return true;
+    }
+    const int chunk = (pairs + THREADS - 1) / THREADS;                 // consecutive pairs per thread
+    const int p0 = min(tid * chunk, pairs), p1 = min(p0 + chunk, pairs);
+    // length and first row of a pair, tiles of one of its rows
+    auto look = [&](int p, int& len, int64_t& first_row) {
+        const int si = p / a.B, b = p - si * a.B;
+        shard_range(a.shard[si], b, len, first_row);
+        return (int64_t)((max(len, 0) + tile_tokens - 1) / tile_tokens);
     };
-    // a thread's first pair is looked up once (the usual launch has fewer pairs than threads)
-    int si0 = 0, row0 = 0, nf0 = 0, cls0 = -1, n0 = 0;
-    if (tid < pairs) runs_of(tid, si0, row0, nf0, cls0, n0);
-    for (int p = tid; p < pairs; p += kOrderThreads) {
-        int si = si0, row = row0, nf = nf0, cls = cls0, n = n0;
-        if (p != tid) runs_of(p, si, row, nf, cls, n);
-        if (nf) atomicAdd(&count[0], nf);
-        if (cls >= 0) atomicAdd(&count[1 + cls], 1);
-        if (n - nf - (cls >= 0)) atomicAdd(&count[kOrderClasses + 1], n - nf - (cls >= 0));
+    int64_t mine = 0;
+    int len0 = 0;                                                      // the thread's first pair (its only one, as a rule)
+    int64_t row0 = 0, tiles0 = 0;
+    for (int p = p0; p < p1; p++) {
+        int len;
+        int64_t first_row;
+        const int64_t t = look(p, len, first_row);
+        if (p == p0) { len0 = len; row0 = first_row; tiles0 = t; }
+        mine += t * rows_per_pair;
+    }
+    // inclusive scan inside the wave, then over the waves' totals
+    int64_t incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t lo = __shfl_up((uint32_t)incl, off), hi = __shfl_up((uint32_t)((uint64_t)incl >> 32), off);
+        if (lane >= off) incl += (int64_t)((uint64_t)hi << 32 | lo);
+    }
+    if (lane == 63) scratch[wave] = incl;
+    __syncthreads();
+    int64_t before = 0, T = 0;
+#pragma unroll
+    for (int w = 0; w < THREADS / 64; w++) {
+        const int64_t tw = scratch[w];
+        if (w < wave) before += tw;
+        T += tw;
+    }
+    T = uniform_i64(T);
+    const int64_t excl = before + incl - mine;                         // row tiles before this thread's first pair
+    if (blockIdx.x == 0) {
+        int64_t run = excl;
+        for (int p = p0; p < p1; p++) {
+            if (prefix_out) prefix_out[p] = run;
+            int len = len0;
+            int64_t first_row = row0, t = tiles0;
+            if (p != p0) t = look(p, len, first_row);
+            const ShardDev& sh = a.shard[p / a.B];
+            if (sh.out_off) { sh.out_off[p % a.B] = first_row; sh.out_len[p % a.B] = len; }     // the KVP cut, empty slices included
+            run += t * rows_per_pair;
+        }
+        if (tid == 0 && prefix_out) prefix_out[pairs] = T;
+    }
+    const StreamDeal deal = stream_deal(T, a.n_wg);
+    c.cur = deal.start(blockIdx.x);
+    c.end = deal.start(blockIdx.x + 1);
+    if (c.cur >= c.end) return false;
+    // the thread whose pairs hold tile `cur` tells the others which pair it is, where its rows start and how long they are
+    int64_t* found = scratch + THREADS / 64;
+    if (mine > 0 && excl <= c.cur && c.cur < excl + mine) {
+        int64_t run = excl;
+        for (int p = p0; p < p1; p++) {
+            int len = len0;
+            int64_t first_row = row0, t = tiles0;
+            if (p != p0) t = look(p, len, first_row);
+            if (c.cur < run + t * rows_per_pair) {
+                found[0] = p;
+                found[1] = run;
+                found[2] = t;
+                found[3] = first_row;
+                found[4] = len;
+                break;
+            }
+            run += t * rows_per_pair;
+        }
     }
     __syncthreads();
-    if (tid == 0) {
-        int at = 0;
-        for (int j = 0; j < kOrderClasses + 2; j++) { cursor[j] = at; at += count[j]; }
+    c.pair = (int32_t)uniform_i64(found[0]);
+    c.pair_lo = uniform_i64(found[1]);
+    c.pair_tiles = uniform_i64(found[2]);
+    c.first_row = uniform_i64(found[3]);
+    c.len = (int32_t)uniform_i64(found[4]);
+    return true;
+}
+
+// One run of a streaming workgroup: tokens [t0, t1_cap) of row (shard si, sequence b, kv head kh, head tile ht).
+struct StreamRun {
+    int si, b, kh, ht;
+    int t0, t1_cap;          // t1_cap may lie beyond the slice's end (whole tiles)
+    int slot;                // record slot of the run: workgroup + row index
+    int row;                 // row index within the launch
+    bool first, last;        // the run holds the row's first / last tile
+};
+
+// Takes the next run off the cursor; false when the workgroup's range is used up.  Uniform in all lanes.
+__device__ __forceinline__ bool stream_next_run(const AttnArgs& a, StreamCursor& c, int tile_tokens, int rows_per_pair, StreamRun& r)
+{
+    for (;;) {
+        if (c.cur >= c.end) return false;
+        const int64_t pair_hi = c.pair_lo + c.pair_tiles * rows_per_pair;
+        if (c.cur < pair_hi) break;
+        c.pair++;                                                       // the next pair (one without tokens is skipped)
+        c.pair_lo = pair_hi;
+        const int si = c.pair / a.B;
+        int len;
+        int64_t first_row;
+        shard_range(a.shard[si], c.pair - si * a.B, len, first_row);
+        c.len = __builtin_amdgcn_readfirstlane(len);
+        c.first_row = uniform_i64(first_row);
+        c.pair_tiles = (int64_t)((max(c.len, 0) + tile_tokens - 1) / tile_tokens);
     }
-    __syncthreads();
-    for (int p = tid; p < pairs; p += kOrderThreads) {
-        int si = si0, row = row0, nf = nf0, cls = cls0, n = n0;
-        if (p != tid) runs_of(p, si, row, nf, cls, n);
-        const uint32_t who = (uint32_t)si << 24 | (uint32_t)row;
-        int s = 0;
-        if (nf) {
-            const int at = atomicAdd(&cursor[0], nf);
-            for (; s < nf; s++) if (at + s < n_units) units[at + s] = uint2{who, (uint32_t)s};
-        }
-        if (cls >= 0) {
-            const int at = atomicAdd(&cursor[1 + cls], 1);
-            if (at < n_units) units[at] = uint2{who, (uint32_t)s};
-            s++;
-        }
-        if (s < n) {
-            const int at = atomicAdd(&cursor[kOrderClasses + 1], n - s) - s;
-            for (; s < n; s++) if (at + s < n_units) units[at + s] = uint2{who, (uint32_t)s};
-        }
-    }
+    // row within the pair: kv head, head tile (this sits on the way to a workgroup's first load: divisions only
+    // where they are needed, and in 32 bits where the numbers allow)
+    const int64_t into = c.cur - c.pair_lo;
+    int rr = 0;
+    if (into >= c.pair_tiles) rr = __builtin_expect((into | c.pair_tiles) >> 31 != 0, 0) ? (int)(into / c.pair_tiles) : (int)((uint32_t)into / (uint32_t)c.pair_tiles);
+    const int64_t row_lo = c.pair_lo + (int64_t)rr * c.pair_tiles;
+    const int64_t seg_end = min(c.end, row_lo + c.pair_tiles);
+    r.si = a.n_shards == 1 ? 0 : c.pair / a.B;
+    r.b = c.pair - r.si * a.B;
+    r.kh = a.head_tiles == 1 ? rr : rr / a.head_tiles;
+    r.ht = rr - r.kh * a.head_tiles;
+    r.t0 = (int)(c.cur - row_lo) * tile_tokens;
+    r.t1_cap = (int)(seg_end - row_lo) * tile_tokens;
+    r.row = c.pair * rows_per_pair + rr;
+    r.slot = a.rec_base + (int)blockIdx.x + r.row;
+    r.first = c.cur == row_lo;
+    r.last = seg_end == row_lo + c.pair_tiles;
+    c.cur = seg_end;
+    return true;
 }
 
 // Plan of an MLA launch whose workgroups share the work evenly whatever the sequence lengths are.  The slices
@@ -281,10 +462,11 @@ __global__ __launch_bounds__(kPlanThreads) void stream_plan_kernel(const AttnArg
     if (tid == 0) tile_prefix[pairs] = T;
     __threadfence_block();
     __syncthreads();                                   // the prefix is complete and visible to the whole workgroup
+    const StreamDeal deal = stream_deal(T, a.n_wg);
     for (int g = tid; g < a.n_wg; g += kPlanThreads) {
         int first = 0;
         if (T > 0) {
-            const int64_t s = stream_start(g, T, a.n_wg);
+            const int64_t s = deal.start(g);
             // the largest pair p with tile_prefix[p] <= s (it is not empty: the next pair starts beyond s)
             int lo = 0, hi = pairs - 1;
             while (lo < hi) {
@@ -295,15 +477,13 @@ __global__ __launch_bounds__(kPlanThreads) void stream_plan_kernel(const AttnArg
         }
         wg_first_pair[g] = first;
     }
-    // for the merge: the workgroups that hold tiles of pair p are g_first .. g_first + n - 1 (x, y); y is stored
-    // negated when the launch has fewer tiles than workgroups, because then some of them hold no tile at all
+    // for the merge: the workgroups that hold tiles of pair p are g_first .. g_first + n - 1 (x, y)
     for (int p = tid; p < pairs; p += kPlanThreads) {
         const int64_t lo = tile_prefix[p], hi = tile_prefix[p + 1];
         int2 r = {0, 0};
         if (hi > lo) {
-            r.x = stream_owner(lo, T, a.n_wg);
-            r.y = stream_owner(hi - 1, T, a.n_wg) - r.x + 1;
-            if (T < a.n_wg) r.y = -r.y;
+            r.x = deal.owner(lo);
+            r.y = deal.owner(hi - 1) - r.x + 1;
         }
         pair_rec[p] = r;
     }

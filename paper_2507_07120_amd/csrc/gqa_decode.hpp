@@ -245,49 +245,47 @@ __device__ __forceinline__ void gqa_emit_record(GqaState<D>& st, const AttnArgs&
     }
 }
 
+constexpr int kGqaTile = 128;      // tokens per planning tile of the streaming kernels: one 32-token block per wave
+
+// What a streaming workgroup does around each of its runs: the row's first / last workgroup is noted for the merge.
+__device__ __forceinline__ void gqa_note_run(const AttnArgs& a, const StreamRun& run)
+{
+    if (threadIdx.x == 0) {
+        if (run.first) a.row_rec[run.row].x = (int)blockIdx.x;
+        if (run.last) a.row_rec[run.row].y = (int)blockIdx.x;
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
 {
     using C = GqaCfg<D>;
-    const int tid = threadIdx.x;
+
+    // This workgroup's share of the launch: an equal range of the launch's rows laid end to end (stream_self_plan),
+    // served run by run -- one run, and one split record, per row the range touches.
+    __shared__ int64_t plan_scratch[256 / 64 + 5];
+    const int rows_per_pair = a.K * a.head_tiles;
+    StreamCursor cursor;
+    if (!stream_self_plan<256>(a, kGqaTile, rows_per_pair, plan_scratch, a.prefix_out, cursor)) return;
+    StreamRun run;
+    while (stream_next_run(a, cursor, kGqaTile, rows_per_pair, run)) {
+    // (the lane's coordinates are derived anew in every run: hoisted out of this loop, the address pieces computed
+    // from them would hold two dozen registers for the whole kernel, which the streaming loop has no room for)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
     const int lane = tid & 63, wave = tid >> 6;
     const int r = lane & 15, kc = lane >> 4;
+    gqa_note_run(a, run);
+    const ShardDev& sh = a.shard[run.si];
+    const int b = run.b, kh = run.kh, ht = run.ht;
 
-    // which (shard, split, sequence, kv head, head tile) this workgroup serves
-    int u = blockIdx.x, si = 0, split, rest;
-    if (a.units) {                // a batch declared ragged: the map run_order_kernel wrote (non-empty runs first)
-        const uint2 e = a.units[u];
-        si = __builtin_amdgcn_readfirstlane((int)(e.x >> 24));
-        rest = __builtin_amdgcn_readfirstlane((int)(e.x & 0xffffffu));
-        split = __builtin_amdgcn_readfirstlane((int)e.y);
-    } else {
-        while (si + 1 < a.n_shards && u >= a.shard[si + 1].unit_base) si++;
-        u -= a.shard[si].unit_base;
-        split = u % a.shard[si].n_splits;
-        rest = u / a.shard[si].n_splits;
-    }
-    const ShardDev& sh = a.shard[si];
-    const int ht = rest % a.head_tiles; rest /= a.head_tiles;
-    const int kh = rest % a.K;
-    const int b = rest / a.K;
-
-    int len;
-    int64_t first_row;
-    shard_range(sh, b, len, first_row);
-    if (split == 0 && ht == 0 && kh == 0 && threadIdx.x == 0) {
-        if (sh.out_off) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
-        flag_len_overflow(sh, len, a.split_tokens);
-    }
-    const int t0 = split * a.split_tokens;
-    const int t1 = min(t0 + a.split_tokens, len);
+    const int len = cursor.len;                      // of the slice the run belongs to (the cursor's current pair)
+    const int64_t first_row = cursor.first_row;
+    const int t0 = run.t0;
+    const int t1 = min(run.t1_cap, len);
     const int h0 = kh * a.g + ht * 16;
     const int nh = min(16, a.g - ht * 16);
-    const size_t rec = ((size_t)(sh.split_base + split) * a.B + b) * a.Q + h0;
-
-    if (t0 >= len) {              // nothing to attend to: an empty record
-        if (tid < nh) { a.ws_m[rec + tid] = -INFINITY; a.ws_l[rec + tid] = 0.f; }
-        return;
-    }
+    const size_t rec = (size_t)run.slot * 16;            // a record holds the 16 head rows of the tile
 
     const int64_t tok0 = first_row + t0;
     const char* kbase = reinterpret_cast<const char*>(sh.k) + 2 * ((int64_t)b * sh.k_sb + (int64_t)kh * sh.k_sh + tok0 * sh.k_st);
@@ -300,9 +298,9 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
 #pragma unroll
     for (int c = 0; c < C::CPL; c++) st.o[c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // this wave's blocks: wave, wave+4, wave+8, ... of the split; all but possibly the last are full
-    const int n_tok = t1 - t0;
-    const int n_full = n_tok / C::TB;                 // full blocks in the split
+    // this wave's blocks: wave, wave+4, wave+8, ... of the run; all but possibly the last are full
+    const int n_tok = max(t1 - t0, 0);
+    const int n_full = n_tok / C::TB;                 // full blocks in the run
     const int n_blk = (n_tok + C::TB - 1) / C::TB;
     const size_t k_blk_bytes = (size_t)C::TB * k_row_bytes, v_blk_bytes = (size_t)C::TB * v_row_bytes;
 
@@ -353,6 +351,8 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
     }
 
     gqa_emit_record<D>(st, a, rec, nh, tid, wave, r, kc);
+    __syncthreads();                  // the record's staging area in LDS is free for the next run
+    }
 }
 
 }  // namespace helix

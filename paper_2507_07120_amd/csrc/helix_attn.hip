@@ -100,7 +100,8 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
     const bool fuse = o != nullptr && n <= kMaxLaunchShards;
     if (finished) *finished = fuse;
     const int g = p->q_heads / p->kv_heads;
-    const int64_t rows = (int64_t)p->batch * p->kv_heads * plan.head_tiles;
+    const bool mla = plan.path == Path::Mla;
+    const int64_t rows_per_pair = mla ? 1 : (int64_t)p->kv_heads * plan.head_tiles;
     static_assert(kMaxLaunchShards == kMaxShardsPerLaunch, "the host plan and the kernels agree on the shards of a launch");
     int32_t split_base = 0;
     int32_t rec_base = 0;          // stream plan: first record of the launch
@@ -119,6 +120,7 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
         a.scale_log2e = p->scale * kLog2e;
         a.n_shards = cnt;
         int64_t units = 0;
+        int64_t row_tokens = 0, row_tiles = 0;             // of the launch, if every sequence had max_len
         for (int32_t i = 0; i < cnt; i++) {
             const helix_kv_shard& s = shards[s0 + i];
             ShardDev& d = a.shard[i];
@@ -131,45 +133,47 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             d.kvp_n = cut.n; d.kvp_i = s0 + i;
             d.out_off = cut.off ? cut.off + (int64_t)(s0 + i) * p->batch : nullptr;
             d.out_len = cut.len ? cut.len + (int64_t)(s0 + i) * p->batch : nullptr;
-            d.n_splits = (int32_t)std::max<int64_t>(1, ceil_div(s.max_len, plan.split_tokens));
-            d.split_base = split_base;
-            d.unit_base = (int32_t)units;
-            m.split_base[i] = split_base;
-            m.n_splits[i] = d.n_splits;
-            split_base += d.n_splits;
-            units += plan.path == Path::Mla && !plan.ordered ? mla_units_of_shard(d.n_splits, p->batch, plan.head_tiles)
-                                                                   : (int64_t)d.n_splits * rows;
+            row_tokens += (int64_t)p->batch * rows_per_pair * s.max_len;
+            row_tiles += (int64_t)p->batch * rows_per_pair * ceil_div(s.max_len, plan.granule);
+            if (!plan.stream) {                            // MLA with several head tiles: runs by workgroup id
+                d.n_splits = (int32_t)std::max<int64_t>(1, ceil_div(s.max_len, plan.split_tokens));
+                d.split_base = split_base;
+                d.unit_base = (int32_t)units;
+                m.split_base[i] = split_base;
+                m.n_splits[i] = d.n_splits;
+                split_base += d.n_splits;
+                units += mla_units_of_shard(d.n_splits, p->batch, plan.head_tiles);
+            }
         }
         if (plan.stream) {
-            // MLA with one head tile: the launch is cut evenly over the tokens its sequences have on the device
-            int64_t bound = 0;
-            for (int32_t i = 0; i < cnt; i++) bound += (int64_t)p->batch * shards[s0 + i].max_len;
-            const int64_t n_wg = stream_workgroups(p, bound);
-            const int64_t pairs = (int64_t)cnt * p->batch;
-            int64_t* prefix = reinterpret_cast<int64_t*>(ws.maps + map_off);
-            int2* pair_rec = reinterpret_cast<int2*>(ws.maps + map_off + align_up((size_t)(pairs + 1) * 8, 256));
-            int32_t* first_pair = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(pair_rec) + align_up((size_t)pairs * 8, 256));
-            map_off += stream_map_bytes(pairs, n_wg);
+            // the launch is cut evenly over the tokens its sequences have on the device: by a planning kernel for MLA
+            // (one workgroup per CU, each run worth a set-up), by every workgroup for itself in the streaming kernels
+            const int64_t n_wg = stream_workgroups(p, plan.path, row_tokens, row_tiles);
+            const int64_t pairs = (int64_t)cnt * p->batch, rows = pairs * rows_per_pair;
+            char* maps = ws.maps + map_off;
+            map_off += stream_map_bytes(plan.path, pairs, rows, n_wg);
+            int64_t* prefix = reinterpret_cast<int64_t*>(maps);
             a.n_wg = (int32_t)n_wg;
             a.rec_base = rec_base;
-            hipLaunchKernelGGL(helix::stream_plan_kernel, dim3(1), dim3(helix::kPlanThreads), 0, stream, a, prefix, first_pair, pair_rec);
-            if (int rc = launch_status()) return rc;
-            a.tile_prefix = prefix;
-            a.wg_first_pair = first_pair;
             m.tile_prefix = prefix;
-            m.pair_rec = pair_rec;
             m.n_wg = a.n_wg;
             m.rec_base = rec_base;
-            rec_base += (int32_t)(n_wg + pairs);
+            m.K = p->kv_heads; m.g = g; m.head_tiles = plan.head_tiles;
+            if (mla) {
+                int2* pair_rec = reinterpret_cast<int2*>(maps + align_up((size_t)(pairs + 1) * 8, 256));
+                int32_t* first_pair = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(pair_rec) + align_up((size_t)pairs * 8, 256));
+                hipLaunchKernelGGL(helix::stream_plan_kernel, dim3(1), dim3(helix::kPlanThreads), 0, stream, a, prefix, first_pair, pair_rec);
+                if (int rc = launch_status()) return rc;
+                a.tile_prefix = prefix;
+                a.wg_first_pair = first_pair;
+                m.pair_rec = pair_rec;
+            } else {
+                a.prefix_out = prefix;
+                a.row_rec = reinterpret_cast<int2*>(maps + align_up((size_t)(pairs + 1) * 8, 256));
+                m.row_rec = a.row_rec;
+            }
+            rec_base += (int32_t)(n_wg + rows);
             units = n_wg;
-        }
-        // a streaming batch declared ragged: the runs are handed to the workgroups in the order run_order_kernel
-        // writes -- full runs first, then partial ones, then empty ones (see there)
-        if (plan.ordered) {
-            uint2* map = reinterpret_cast<uint2*>(ws.maps);
-            hipLaunchKernelGGL(helix::run_order_kernel, dim3(1), dim3(helix::kOrderThreads), 0, stream, a, map, (int)units);
-            if (int rc = launch_status()) return rc;
-            a.units = map;
         }
         if (ev.start && s0 == 0 && hipEventRecord(ev.start, stream) != hipSuccess) return HELIX_ERR_LAUNCH;
         switch (plan.path) {
@@ -208,17 +212,18 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             FinishArgs f;
             f.m = m; f.o = o; f.lse_out = lse_out; f.keep_parts = keep_parts ? 1 : 0;
             const unsigned frows = (unsigned)((int64_t)p->batch * p->q_heads);
-            if (plan.stream) {             // MLA: dv = 512
-                const unsigned threads = helix::kFinishRowThreads * (unsigned)std::min<int32_t>(cnt, helix::kFinishGroups);
-                hipLaunchKernelGGL((finish_stream_kernel<512>), dim3(frows), dim3(threads), 0, stream, f);
+            if (plan.stream) {
+                auto threads = [&](int row_threads, int sublanes, int groups) { return dim3((unsigned)(row_threads * sublanes * std::min<int32_t>(cnt, groups))); };
+                switch (p->dv) {
+                    case 64: hipLaunchKernelGGL((finish_stream_kernel<64>), dim3(frows), threads(helix::finish_row_threads<64>(), helix::stream_sublanes<64>(), helix::finish_groups<64>()), 0, stream, f); break;
+                    case 128: hipLaunchKernelGGL((finish_stream_kernel<128>), dim3(frows), threads(helix::finish_row_threads<128>(), helix::stream_sublanes<128>(), helix::finish_groups<128>()), 0, stream, f); break;
+                    case 512: hipLaunchKernelGGL((finish_stream_kernel<512>), dim3(frows), threads(helix::finish_row_threads<512>(), helix::stream_sublanes<512>(), helix::finish_groups<512>()), 0, stream, f); break;
+                    default: return HELIX_ERR_UNSUPPORTED;
+                }
                 return launch_status();
             }
-            switch (p->dv) {
-                case 64: hipLaunchKernelGGL((finish_kernel<64>), dim3(frows), dim3(256), 0, stream, f); break;
-                case 128: hipLaunchKernelGGL((finish_kernel<128>), dim3(frows), dim3(256), 0, stream, f); break;
-                case 512: hipLaunchKernelGGL((finish_kernel<512>), dim3(frows), dim3(256), 0, stream, f); break;
-                default: return HELIX_ERR_UNSUPPORTED;
-            }
+            if (p->dv != 512) return HELIX_ERR_UNSUPPORTED;       // runs by workgroup id exist for the MLA shape only
+            hipLaunchKernelGGL((finish_kernel<512>), dim3(frows), dim3(256), 0, stream, f);
             return launch_status();
         }
         const unsigned mrows = (unsigned)((int64_t)cnt * p->batch * p->q_heads);
@@ -250,7 +255,7 @@ const char* helix_status_string(int status)
     }
 }
 
-int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, const int64_t* sum_lens, int32_t n_shards,
+int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, int32_t n_shards,
                     int32_t* split_tokens, int64_t* workgroups)
 {
     Path path;
@@ -258,7 +263,7 @@ int helix_attn_plan(const helix_problem* problem, const int32_t* max_lens, const
     if (!max_lens) return HELIX_ERR_NULL;
     if (n_shards < 1 || n_shards > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
     Plan plan;
-    if (int rc = make_plan(problem, path, max_lens, sum_lens, n_shards, &plan)) return rc;
+    if (int rc = make_plan(problem, path, max_lens, n_shards, &plan)) return rc;
     if (split_tokens) *split_tokens = plan.split_tokens;
     if (workgroups) *workgroups = plan.workgroups;
     return HELIX_OK;
@@ -437,7 +442,7 @@ int decode_kvp(const helix_problem* problem, const void* q, const helix_kv_shard
     Path path;
     if (int rc = check_problem(problem, &path)) return rc;
     helix_kv_shard slices[HELIX_MAX_SHARDS];               // on the stack: the library allocates nothing
-    kvp_slices(problem, cache, n_shards, slices);
+    kvp_slices(cache, n_shards, slices);
     Plan plan;
     Workspace ws;
     if (int rc = prepare(problem, slices, n_shards, workspace, workspace_bytes, &plan, &ws)) return rc;

@@ -22,9 +22,39 @@ struct MergeArgs {
     // records of a launch cut by stream_plan_kernel: pair p = (shard, sequence) owns one record per workgroup
     // whose tile range touches it, record rec_base + g + p, rows [record][Q]
     const int64_t* tile_prefix;       // NULL: records are [split][B][Q] as split_base / n_splits say
-    const int2* pair_rec;             // [pairs] the workgroups g_first .. g_first + n - 1 that hold tiles of the pair
+    const int2* pair_rec;             // MLA: [pairs] the workgroups g_first .. g_first + n - 1 that hold tiles of the pair
+    const int2* row_rec;              // GQA: [rows] first and last workgroup that hold tiles of row (pair, kv head, head tile)
     int32_t n_wg, rec_base;
+    int32_t K, g, head_tiles;         // GQA: kv heads, query heads per kv head, head tiles per kv head (records of 16 heads)
 };
+
+// Where the records of (shard i, sequence b, query head h) are in an evenly cut launch: n of them, record j in
+// row first + j * stride of the record arrays.
+struct StreamRecords {
+    int n;
+    size_t first, stride;
+};
+
+__device__ __forceinline__ StreamRecords stream_records(const MergeArgs& a, int i, int b, int h)
+{
+    const int p = i * a.B + b;
+    StreamRecords r;
+    r.n = 0; r.first = 0; r.stride = 0;
+    if (a.pair_rec) {                     // MLA: one row per pair, a record holds all Q heads
+        const int2 pr = a.pair_rec[p];
+        r.n = pr.y;
+        r.first = (size_t)(a.rec_base + pr.x + p) * a.Q + h;
+        r.stride = (size_t)a.Q;
+    } else if (a.tile_prefix[p + 1] > a.tile_prefix[p]) {      // GQA: a row per (kv head, head tile), records of 16 heads
+        const int kh = h / a.g, hin = h - kh * a.g, ht = hin >> 4;
+        const int row = (p * a.K + kh) * a.head_tiles + ht;
+        const int2 rr = a.row_rec[row];
+        r.n = rr.y - rr.x + 1;
+        r.first = (size_t)(a.rec_base + rr.x + row) * 16 + (hin & 15);
+        r.stride = 16;
+    }
+    return r;
+}
 
 // Where the records of one (shard, b, h) row are: record j (0 <= j < n) sits in row `row(j)` of the record
 // arrays, or nowhere (kNoRecord).
@@ -45,6 +75,13 @@ struct MergeSmem {
     float l[SL];
     float o[SL][DV];
 };
+
+// Threads that share one row's value columns in the kernels that fold the records of an evenly cut launch, and
+// rows a workgroup of the fused kernel folds side by side.  That path is a chain of dependent memory round trips per
+// row, so what counts is how many rows the part holds at once: few threads per row, each with several loads in flight.
+constexpr int kFinishRowThreads = 32;
+template <int DV>
+constexpr int finish_row_threads() { return DV / 4 < kFinishRowThreads ? DV / 4 : kFinishRowThreads; }
 
 // lse = (M + log2 L) ln 2.  M is an integer and may sit far from the true maximum (the MLA kernel
 // keeps 32 octaves of headroom), so M and log2 L can cancel: L is split into 2^e * mant first, M + e
@@ -133,49 +170,48 @@ __device__ __forceinline__ f32x4 merge_row(const float* __restrict__ ws_o, const
     return s;
 }
 
-// The same fold for the records of an evenly cut launch (stream_plan_kernel): pair (shard i, sequence b) has one
-// record per workgroup that holds tiles of it -- one to three as a rule.  They are folded by ONE thread per four
-// value columns, record after record in workgroup order, so no shared memory and no barrier is involved and a
-// workgroup can fold several shards side by side.  A thread handles NV groups of four columns, c0 + v * cstride:
-// out[v] receives their normalised O; M, L as above.  (How many columns a thread holds changes no bit.)
+// The same fold for the records of an evenly cut launch: row (shard i, sequence b, head h) has one record per
+// workgroup that holds tiles of it -- one to three as a rule for MLA, sixteen on the uniform GQA share.  SUB
+// threads share a row's records (record j goes to sub-lane j % SUB) and each folds its records one after the other,
+// four in flight; the sub-lanes' results are then folded in sub-lane order.  Which SUB a value width uses is fixed
+// (stream_sublanes), so every kernel that folds a row produces the same bits.  A thread handles NV groups of four
+// columns, c0 + v * cstride.
+template <int DV>
+constexpr int stream_sublanes() { return DV >= 512 ? 1 : 8; }
+// shards the fused kernel folds side by side (its workgroup has at most 1024 threads)
+template <int DV>
+constexpr int finish_groups() { return 1024 / (finish_row_threads<DV>() * stream_sublanes<DV>()) < 8 ? 1024 / (finish_row_threads<DV>() * stream_sublanes<DV>()) : 8; }
+
 template <int DV, int NV>
-__device__ __forceinline__ void merge_stream_row(const MergeArgs& a, int i, int b, int h, int c0, int cstride, f32x4 (&out)[NV], float& M, float& L)
+__device__ __forceinline__ void fold_stream_records(const MergeArgs& a, const StreamRecords& recs, int sub, int nsub, int c0, int cstride,
+                                                    f32x4 (&acc)[NV], float& Mt, float& Lt)
 {
-    const int p = i * a.B + b;
-    const int2 pr = a.pair_rec[p];
-    const int n = abs(pr.y);
-    const bool gaps = pr.y < 0;
-    int64_t T = 0;
-    if (gaps) T = a.tile_prefix[a.n_shards * a.B];
-    const size_t row0 = (size_t)(a.rec_base + pr.x + p) * a.Q + h;
-    float Mt = -INFINITY, Lt = 0.f;
-    f32x4 acc[NV];
+    const int n = recs.n;
+    Mt = -INFINITY;
+    Lt = 0.f;
 #pragma unroll
     for (int v = 0; v < NV; v++) acc[v] = f32x4{0.f, 0.f, 0.f, 0.f};
-    constexpr int U = NV >= 4 ? 2 : 4;    // records in flight: first their (m, l), then the O rows
-    for (int j0 = 0; j0 < n; j0 += U) {
+    constexpr int U = 4;                  // records in flight, (m, l) and the O rows together
+    for (int j0 = sub; j0 < n; j0 += U * nsub) {
         float mj[U], lj[U];
         f32x4 oj[U][NV];
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            const int j = j0 + u;
+            const int j = j0 + u * nsub;
             mj[u] = -INFINITY;
             lj[u] = 0.f;
-            // a workgroup without a tile (launches with fewer tiles than workgroups) wrote no record
-            const bool there = j < n && !(gaps && stream_start(pr.x + j, T, a.n_wg) == stream_start(pr.x + j + 1, T, a.n_wg));
-            if (there) {
-                mj[u] = a.ws_m[row0 + (size_t)j * a.Q];
-                lj[u] = a.ws_l[row0 + (size_t)j * a.Q];
+#pragma unroll
+            for (int v = 0; v < NV; v++) oj[u][v] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (j < n) {
+                const size_t at = recs.first + (size_t)j * recs.stride;
+                mj[u] = a.ws_m[at];
+                lj[u] = a.ws_l[at];
+                // (the O row of an empty record was never written: it is read all the same, to keep the two loads
+                // independent, and dropped below)
+#pragma unroll
+                for (int v = 0; v < NV; v++) oj[u][v] = *reinterpret_cast<const f32x4*>(a.ws_o + at * DV + c0 + v * cstride);
             }
         }
-#pragma unroll
-        for (int u = 0; u < U; u++)
-#pragma unroll
-            for (int v = 0; v < NV; v++) {
-                oj[u][v] = f32x4{0.f, 0.f, 0.f, 0.f};
-                if (mj[u] != -INFINITY)
-                    oj[u][v] = *reinterpret_cast<const f32x4*>(a.ws_o + (row0 + (size_t)(j0 + u) * a.Q) * DV + c0 + v * cstride);
-            }
 #pragma unroll
         for (int u = 0; u < U; u++) {
             if (mj[u] == -INFINITY) continue;
@@ -191,6 +227,54 @@ __device__ __forceinline__ void merge_stream_row(const MergeArgs& a, int i, int 
             for (int v = 0; v < NV; v++) acc[v] += oj[u][v] * g;
             Lt += lj[u] * g;
         }
+    }
+}
+
+// Shared memory of one row being folded by SUB sub-lanes.
+template <int DV, int SUB>
+struct StreamFoldSmem {
+    float m[SUB], l[SUB];
+    float o[SUB][DV];
+};
+
+// Folds the records of row (i, b, h) with the workgroup's threads (sub, c0): every thread of the WORKGROUP must call
+// it the same number of times (it holds two barriers when SUB > 1); `active` = this thread has a row to fold.
+// out / M / L are valid in the threads with sub == 0.
+template <int DV, int NV, int SUB>
+__device__ __forceinline__ void merge_stream_row(const MergeArgs& a, bool active, int i, int b, int h, int sub, int c0, int cstride,
+                                                 StreamFoldSmem<DV, SUB>* sm, f32x4 (&out)[NV], float& M, float& L)
+{
+    StreamRecords recs;
+    recs.n = 0; recs.first = 0; recs.stride = 0;
+    if (active) recs = stream_records(a, i, b, h);
+    f32x4 acc[NV];
+    float Mt, Lt;
+    fold_stream_records<DV, NV>(a, recs, sub, SUB, c0, cstride, acc, Mt, Lt);
+    if constexpr (SUB > 1) {
+        if (active) {
+#pragma unroll
+            for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(&sm->o[sub][c0 + v * cstride]) = acc[v];
+            if (c0 == 0) { sm->m[sub] = Mt; sm->l[sub] = Lt; }
+        }
+        __syncthreads();
+        if (active && sub == 0) {
+            Mt = -INFINITY;
+#pragma unroll
+            for (int k = 0; k < SUB; k++) Mt = fmaxf(Mt, sm->m[k]);
+            Lt = 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; v++) acc[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (Mt != -INFINITY) {
+#pragma unroll
+                for (int k = 0; k < SUB; k++) {
+                    const float f = __builtin_amdgcn_exp2f(sm->m[k] - Mt);       // 0 for a sub-lane without records
+                    Lt += sm->l[k] * f;
+#pragma unroll
+                    for (int v = 0; v < NV; v++) acc[v] += *reinterpret_cast<const f32x4*>(&sm->o[k][c0 + v * cstride]) * f;
+                }
+            }
+        }
+        __syncthreads();                  // the staging area is free for the next row
     }
     M = Mt;
     L = Lt;
@@ -223,11 +307,17 @@ __global__ __launch_bounds__(256) void merge_splits_kernel(const MergeArgs a)
     float M, L;
     const size_t orow = (size_t)(a.shard0 + i) * bq + rem;
     if (a.tile_prefix) {
-        if (tid < MergeSmem<DV>::TPR) {
-            f32x4 o[1];
-            merge_stream_row<DV, 1>(a, i, rem / a.Q, rem % a.Q, tid * 4, 0, o, M, L);
-            *reinterpret_cast<f32x4*>(a.o_part + orow * DV + tid * 4) = o[0];
-            if (tid == 0) a.lse_part[orow] = lse_of(M, L);
+        constexpr int TPR = finish_row_threads<DV>(), NV = DV / (4 * TPR), SUB = stream_sublanes<DV>();
+        static_assert(TPR * SUB <= 256, "threads of this kernel");
+        __shared__ StreamFoldSmem<DV, SUB> fold;
+        const bool active = tid < TPR * SUB;
+        const int sub = tid / TPR, c0 = (tid % TPR) * 4;
+        f32x4 o[NV];
+        merge_stream_row<DV, NV, SUB>(a, active, i, rem / a.Q, rem % a.Q, sub, c0, 4 * TPR, &fold, o, M, L);
+        if (active && sub == 0) {
+#pragma unroll
+            for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(a.o_part + orow * DV + c0 + v * 4 * TPR) = o[v];
+            if (c0 == 0) a.lse_part[orow] = lse_of(M, L);
         }
         return;
     }
@@ -253,42 +343,45 @@ struct FinishArgs {
 };
 
 // merge + combine in one launch for an evenly cut launch of at most kMaxLaunchShards shards: one workgroup per
-// (b, h) row, its threads in groups of kFinishRowThreads that fold different shards side by side
-// (merge_stream_row, DV / kFinishRowThreads columns per thread); the fragments meet in shared memory, where the
-// first group combines them in shard order -- the arithmetic of merge_splits_kernel followed by combine_kernel,
-// without the round trip of the fragments through memory.  The path is a chain of dependent memory round trips
-// per row, so what counts is how many rows the part holds at once: few threads per row, each with several loads
-// in flight.  Launched with kFinishRowThreads * min(shards, kFinishGroups) threads.
-constexpr int kFinishRowThreads = 32, kFinishGroups = 8;
-
+// (b, h) row, its threads in groups that fold different shards side by side (merge_stream_row); the fragments meet
+// in shared memory, where they are combined in shard order -- the arithmetic of merge_splits_kernel followed by
+// combine_kernel, without the round trip of the fragments through memory.  Launched with
+// finish_row_threads<DV>() * stream_sublanes<DV>() * min(shards, finish_groups<DV>()) threads.
 template <int DV>
-__global__ __launch_bounds__(kFinishRowThreads * kFinishGroups) void finish_stream_kernel(const FinishArgs f)
+__global__ __launch_bounds__(finish_row_threads<DV>() * stream_sublanes<DV>() * finish_groups<DV>()) void finish_stream_kernel(const FinishArgs f)
 {
-    constexpr int TPR = kFinishRowThreads, NV = DV / (4 * TPR);
+    constexpr int TPR = finish_row_threads<DV>(), NV = DV / (4 * TPR), SUB = stream_sublanes<DV>();
     static_assert(NV >= 1 && NV * 4 * TPR == DV, "whole float4 columns per thread");
+    static_assert(TPR * SUB * finish_groups<DV>() <= 1024, "threads of a workgroup");
     __shared__ float sm_o[kMaxLaunchShards][DV];
     __shared__ float sm_lse[kMaxLaunchShards];
+    __shared__ StreamFoldSmem<DV, SUB> fold[finish_groups<DV>()];
     const MergeArgs& a = f.m;
-    const int tid = threadIdx.x, grp = tid / TPR, c0 = (tid % TPR) * 4, G = blockDim.x / TPR;
+    const int tid = threadIdx.x, G = blockDim.x / (TPR * SUB);
+    const int grp = tid / (TPR * SUB), sub = (tid / TPR) % SUB, c0 = (tid % TPR) * 4;
     const int rem = blockIdx.x;          // b*Q + h
     const int b = rem / a.Q, h = rem % a.Q;
     const size_t bq = (size_t)a.B * a.Q;
-    for (int i = grp; i < a.n_shards; i += G) {
+    for (int i0 = 0; i0 < a.n_shards; i0 += G) {       // the same trip count for every thread: the fold holds barriers
+        const int i = i0 + grp;
+        const bool active = i < a.n_shards;
         float M, L;
         f32x4 o[NV];
-        merge_stream_row<DV, NV>(a, i, b, h, c0, 4 * TPR, o, M, L);
-        const float lse = lse_of(M, L);
+        merge_stream_row<DV, NV, SUB>(a, active, i, b, h, sub, c0, 4 * TPR, &fold[grp], o, M, L);
+        if (active && sub == 0) {
+            const float lse = lse_of(M, L);
 #pragma unroll
-        for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(&sm_o[i][c0 + v * 4 * TPR]) = o[v];
-        if (c0 == 0) sm_lse[i] = lse;
-        if (f.keep_parts) {
+            for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(&sm_o[i][c0 + v * 4 * TPR]) = o[v];
+            if (c0 == 0) sm_lse[i] = lse;
+            if (f.keep_parts) {
 #pragma unroll
-            for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(a.o_part + ((size_t)i * bq + rem) * DV + c0 + v * 4 * TPR) = o[v];
-            if (c0 == 0) a.lse_part[(size_t)i * bq + rem] = lse;
+                for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(a.o_part + ((size_t)i * bq + rem) * DV + c0 + v * 4 * TPR) = o[v];
+                if (c0 == 0) a.lse_part[(size_t)i * bq + rem] = lse;
+            }
         }
     }
     __syncthreads();
-    // the combine, shard after shard as combine_kernel does it; the groups share the columns
+    // the combine, shard after shard as combine_kernel does it; the threads share the columns
     float top = -INFINITY;
     for (int i = 0; i < a.n_shards; i++) top = fmaxf(top, sm_lse[i]);
     float wsum = 0.f;

@@ -27,15 +27,19 @@
 //     the matrix cores and LDS, so executed MFMAs and LDS bytes per useful flop are what counts.
 //
 // Workgroup = 8 wavefronts = one CU, HPW = 128 heads (all heads of the usual MLA configuration: the
-// latent is read from HBM and copied into LDS once), a run of `split_tokens` latent rows in tiles
-// of 32 tokens kept in a ring of three LDS slots (in use, next, in flight).  Per tile:
+// latent is read from HBM and copied into LDS once).  A launch with one head tile is cut evenly over its
+// token stream (stream_plan_kernel in common.hpp): every workgroup serves one equally long range of the
+// launch's (shard, sequence) pairs laid end to end -- a run per pair it touches, a split record per run.
+// A run goes through its latent rows in tiles of 32 tokens kept in a ring of three LDS slots (in use, next,
+// in flight).  Per tile:
 //   S phase  scores S^T[token, head] = K . Q^T: wave w owns heads 16w..16w+15 and both token halves
 //            (two independent MFMA chains); its Q slice (16 x 576 bf16 = 72 registers) never moves,
 //            the K operands come from LDS.  Softmax stays inside the wave, with an integer reference
-//            exponent that is FIXED for the whole run (bf16: 32 octaves above the first tile's maximum): no
-//            rescale of accumulators, no cross-lane maximum in the loop.  A tile that exceeds the
-//            reference by more than 64 octaves raises a flag; the workgroup then redoes the run with
-//            a reference raised above everything it saw (never on real logits, exercised by a test).
+//            exponent per head that stays put from tile to tile (bf16: 32 octaves above the largest score
+//            seen when it was set): no rescale of accumulators, no cross-lane maximum in the common tile.
+//            A tile in which a score comes within reach of the number range's end moves that head's
+//            reference -- an exact power-of-two rescale of its normaliser at once and of its accumulators in
+//            the P phase, behind a wave-uniform branch (never on ordinary logits; a test forces it).
 //            The lane's 8 weights go to LDS as bf16 hi + lo, already in the P.V operand's layout.
 //   barrier
 //   P phase  O^T[dv, head] += V^T . P^T: waves 2p and 2p+1 share heads 32p..32p+31 and split the value
@@ -49,11 +53,11 @@
 // e4m3 latent: the raw codes are DMA-ed into a per-wave staging area and widened to fp16 (exact) by
 // the wave that requested them when the tile is due, and both contractions run on the fp16 MFMA (same
 // rate as bf16, 11 significant bits): the query rows are scaled into fp16 range by a power of two, and
-// ONE fp16 weight w_t = p_t * f_t * 2^-E per token replaces the bf16 hi/lo pair -- half the P.V MFMAs.
+// ONE fp16 weight w_t = p_t * f_t per token replaces the bf16 hi/lo pair -- half the P.V MFMAs.
 // The per-token scale f_t multiplies the score (s_t = f_t * q.k8_t) and the weight; the normaliser sums
-// the unrounded p_t (times 2^-E, exactly) in fp32.  fp16's range is narrow: a head's reference sits 4 octaves below its first-tile
-// maximum, E is chosen from the first tile, and a run whose largest weight of some head left
-// [2^-6, 2^15) is repeated once with that head's reference moved.
+// the unrounded p_t in fp32.  fp16's range is narrow: a head's reference puts its largest first-tile weight
+// into [2^4, 2^5], and a tile in which a weight reaches 2^14 moves the reference so that this weight lands
+// there again.
 #pragma once
 #include <type_traits>
 
@@ -483,7 +487,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     const int pair = wave >> 1, half = wave & 1;                  // waves 2p, 2p+1 share heads 32p..32p+31
 
     // Which runs this workgroup serves.  With a stream plan (stream_plan_kernel, one head tile): the tiles
-    // [stream_start(g), stream_start(g + 1)) of the launch's pairs laid end to end -- one run per pair the range
+    // [start(g), start(g + 1)) of the even deal (StreamDeal) of the launch's pairs laid end to end -- one run per pair the range
     // touches.  Otherwise one run, from the workgroup id.
     // (everything here is the same for all lanes; values loaded from memory are handed on through
     // readfirstlane so that they, and the addresses derived from them, stay in scalar registers)
@@ -496,8 +500,9 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
     int kvpair = 0, id_si = 0, id_split = 0, id_b = 0, htw = 0;
     if (stream) {
         const int64_t T = uniform64(a.tile_prefix[a.n_shards * a.B]);
-        tile_cur = stream_start(blockIdx.x, T, a.n_wg);
-        tile_end = stream_start(blockIdx.x + 1, T, a.n_wg);
+        const StreamDeal deal = stream_deal(T, a.n_wg);
+        tile_cur = deal.start(blockIdx.x);
+        tile_end = deal.start(blockIdx.x + 1);
         kvpair = __builtin_amdgcn_readfirstlane(a.wg_first_pair[blockIdx.x]);
     } else {
         int u = blockIdx.x;

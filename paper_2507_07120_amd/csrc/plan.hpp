@@ -17,47 +17,53 @@ struct Plan {
     Path path;
     int32_t heads_per_wg;   // query heads one workgroup serves
     int32_t head_tiles;     // workgroups per (b, kv head) along the group
-    int32_t granule;        // split_tokens is a multiple of this
-    int32_t split_tokens;
-    int64_t total_splits;   // split records of the call, over all shards
+    int32_t granule;        // tokens per planning tile: runs start and end on multiples of it
+    int32_t split_tokens;   // tokens a workgroup streams (at most)
+    int64_t total_splits;   // split records of the call, over all launches
+    int32_t rec_rows;       // head rows of one record
     int64_t workgroups;
-    bool ordered;           // the workgroups take their runs from a map written on the device (run_order_kernel)
-    bool stream;            // MLA with one head tile: every launch is cut evenly over its token stream (stream_plan_kernel)
-    size_t map_bytes;       // device-written maps of the call (run map, or tile prefix + first pair per workgroup)
+    bool stream;            // every launch is cut evenly over its token stream on the device (all but MLA with several head tiles)
+    size_t map_bytes;       // what the kernels tell each other about the cut (tile prefix, workgroups of a row, ...)
 };
 
 constexpr int kMlaHeadsPerWorkgroup = 128;      // checked against the kernel's configuration where both are visible
-constexpr int64_t kTargetWorkgroups = 256;      // CUs of an MI355X
-constexpr int64_t kMinSplitTokens = 128;        // one block per wave: a launch too small to fill the CUs is latency-bound, shorter runs end sooner
+constexpr int kMaxShardsPerLaunch = 16;         // shard descriptors travel by value in the kernel arguments
+constexpr int64_t kTargetWorkgroups = 256;      // CUs of an MI355X: the streaming kernels read fastest with one long-lived workgroup per CU
 constexpr int64_t kTargetWorkgroupsMx = 768;    // MXFP4 streams 3.8x fewer bytes per token: three workgroups resident per CU
-constexpr int64_t kTargetWorkgroupsMla = 4096;  // upper end: keeps the split records of a call near 1 GB at most
+constexpr int64_t kStreamMinTokensMla = 256;    // an MLA launch gives a workgroup at least this many tokens (a run costs ~10 us of set-up)
+constexpr int64_t kTargetWorkgroupsMla = 4096;  // MLA with several head tiles (runs by workgroup id): keeps the records of a call near 1 GB
 constexpr int64_t kMinSplitTokensMla = 4096;
-
-inline int64_t target_workgroups(Path path)
-{
-    return path == Path::Mla ? kTargetWorkgroupsMla : path == Path::GqaMx128 ? kTargetWorkgroupsMx : kTargetWorkgroups;
-}
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-constexpr int kMaxShardsPerLaunch = 16;         // shard descriptors travel by value in the kernel arguments
-constexpr int64_t kStreamMinTokens = 256;       // an evenly cut MLA launch gives a workgroup at least this many tokens ...
-constexpr int64_t kStreamWorkgroups = 256;      // ... and uses at most one workgroup per CU
-
-// Workgroups of an evenly cut MLA launch over shards whose longest sequences add up to `tokens` per sequence slot
-// (batch * sum of max_len): one per CU unless the launch is small, or as many as the caller's run length asks for.
-inline int64_t stream_workgroups(const helix_problem* p, int64_t tokens)
+// Workgroups of an evenly cut launch over `rows` rows whose lengths add up to at most `row_tokens`, in tiles of
+// `tile` tokens: one per CU (three for MXFP4 K/V) unless the launch is small, or as many as the caller's run
+// length asks for.  Measured on the 1 GiB GQA share: 256 sequential streams read 6.8 TB/s, 512 6.5, 1024 6.2.
+inline int64_t stream_workgroups(const helix_problem* p, Path path, int64_t row_tokens, int64_t row_tiles)
 {
-    if (p->split_tokens > 0) return std::max<int64_t>(1, ceil_div(tokens, ceil_div(p->split_tokens, 32) * 32));
-    return std::min(kStreamWorkgroups, std::max<int64_t>(1, tokens / kStreamMinTokens));
+    int64_t n;
+    if (p->split_tokens > 0) {
+        const int64_t tile = path == Path::Mla ? 32 : 128;
+        n = std::max<int64_t>(1, ceil_div(row_tokens, ceil_div(p->split_tokens, tile) * tile));
+    } else if (path == Path::Mla) {
+        n = std::min(kTargetWorkgroups, std::max<int64_t>(1, row_tokens / kStreamMinTokensMla));
+    } else {
+        n = std::min(path == Path::GqaMx128 ? kTargetWorkgroupsMx : kTargetWorkgroups, std::max<int64_t>(1, row_tiles));
+    }
+    // the MXFP4 kernel addresses a run with 32-bit byte offsets
+    if (path == Path::GqaMx128) n = std::max(n, ceil_div(row_tokens, (int64_t)1 << 25));
+    return n;
 }
 
-// Bytes of the maps stream_plan_kernel writes for a launch of `cnt` shards and `n_wg` workgroups, 256-byte aligned
-inline size_t stream_map_bytes(int64_t pairs, int64_t n_wg)
+// Bytes of the maps of one evenly cut launch, 256-byte aligned: the tile prefix [pairs + 1] int64, then MLA: the
+// workgroups of every pair [pairs] 2 x int32 and the first pair of every workgroup [n_wg] int32; GQA: the first
+// and last workgroup of every row [rows] 2 x int32.
+inline size_t stream_map_bytes(Path path, int64_t pairs, int64_t rows, int64_t n_wg)
 {
-    // tile prefix [pairs + 1] int64, workgroups of every pair [pairs] 2 x int32, first pair of every workgroup [n_wg] int32
-    return ((size_t)(pairs + 1) * 8 + 255) / 256 * 256 + ((size_t)pairs * 8 + 255) / 256 * 256 + ((size_t)n_wg * 4 + 255) / 256 * 256;
+    const size_t prefix = align_up((size_t)(pairs + 1) * 8, 256);
+    if (path == Path::Mla) return prefix + align_up((size_t)pairs * 8, 256) + align_up((size_t)n_wg * 4, 256);
+    return prefix + align_up((size_t)rows * 8, 256);
 }
 
 inline int check_problem(const helix_problem* p, Path* path)
@@ -86,95 +92,67 @@ inline int check_problem(const helix_problem* p, Path* path)
     return HELIX_ERR_UNSUPPORTED;
 }
 
-// Split records a GQA plan may use per (sequence, kv head, head tile) row when a ragged batch asks for
-// runs shorter than its longest sequence needs at one workgroup per CU; the sizing call covers it.
-inline int64_t ragged_split_cap(Path path, int64_t rows, int32_t n)
-{
-    return ceil_div(4 * target_workgroups(path), rows) + n;
-}
-
-// Cuts the launch into workgroups.  The streaming kernels are HBM-bound with no reuse.  Measured on
-// MI355X, the read rate is highest with about one long-lived workgroup per CU (256 sequential
-// streams: 6.8 TB/s at 256 workgroups, 6.5 at 512, 6.2 at 1024 on the 1 GiB GQA share), so the
-// target is one workgroup per CU, never less than one per (shard, sequence, kv head, head tile) row,
-// with split records that stay small next to the KV bytes a workgroup streams.
-inline int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, const int64_t* sum_lens, int32_t n, Plan* plan)
+// Cuts a call into launches and workgroups.  Only upper bounds of the lengths are known here (they live on the
+// device): the host decides how many workgroups share a launch, the kernels find out which tokens each one gets.
+inline int make_plan(const helix_problem* p, Path path, const int32_t* max_lens, int32_t n, Plan* plan)
 {
     plan->path = path;
     plan->heads_per_wg = path == Path::Mla ? kMlaHeadsPerWorkgroup : 16;
     plan->granule = path == Path::Mla ? 32 : 128;         // MLA: 32-token tiles; GQA: 4 waves x 32-token blocks
     const int g = p->q_heads / p->kv_heads;
     plan->head_tiles = (int32_t)ceil_div(g, plan->heads_per_wg);
-    const int64_t rows = (int64_t)p->batch * p->kv_heads * plan->head_tiles;
-    int64_t total = 0;       // tokens of a row if every sequence had max_len
-    int64_t tokens = 0;      // tokens of all sequences, as far as the caller has told
-    bool ragged = false;
-    for (int i = 0; i < n; i++) {
-        if (max_lens[i] < 0 || (sum_lens && sum_lens[i] < 0)) return HELIX_ERR_SHAPE;
-        total += max_lens[i];
-        const int64_t full = (int64_t)p->batch * max_lens[i];
-        const bool told = sum_lens && sum_lens[i] > 0 && sum_lens[i] < full;
-        tokens += told ? sum_lens[i] : full;
-        ragged = ragged || told;
-    }
-    plan->stream = path == Path::Mla && plan->head_tiles == 1;
+    plan->rec_rows = path == Path::Mla ? p->q_heads : 16;
+    const int64_t rows_per_pair = path == Path::Mla ? 1 : (int64_t)p->kv_heads * plan->head_tiles;
+    for (int i = 0; i < n; i++)
+        if (max_lens[i] < 0) return HELIX_ERR_SHAPE;
+    plan->stream = path != Path::Mla || plan->head_tiles == 1;
+    plan->map_bytes = 0;
     if (plan->stream) {
-        // One launch per kMaxShardsPerLaunch shards.  Each is cut evenly over the tokens its sequences turn out
-        // to have (the lengths live on the device): the host only decides how many workgroups share them, from
-        // the upper bounds it knows.  A pair has one record per workgroup that touches it: at most n_wg + pairs
-        // records per launch, whatever the lengths are.
-        plan->ordered = false;
+        // One launch per kMaxShardsPerLaunch shards, each cut evenly over the tokens its sequences turn out to have.
+        // A row has one record per workgroup that touches it: at most n_wg + rows records per launch, whatever
+        // the lengths are.
         plan->total_splits = 0;
         plan->workgroups = 0;
-        plan->map_bytes = 0;
         int64_t most = 0;
         for (int s0 = 0; s0 < n; s0 += kMaxShardsPerLaunch) {
             const int cnt = std::min(kMaxShardsPerLaunch, n - s0);
-            int64_t bound = 0;                              // tokens of the launch if every sequence had max_len
-            for (int i = 0; i < cnt; i++) bound += (int64_t)p->batch * max_lens[s0 + i];
-            const int64_t n_wg = stream_workgroups(p, bound);
-            if (n_wg > (int64_t)1 << 20) return HELIX_ERR_SHAPE;
-            plan->total_splits += n_wg + (int64_t)cnt * p->batch;
+            int64_t row_tokens = 0, row_tiles = 0;         // if every sequence had max_len
+            for (int i = 0; i < cnt; i++) {
+                row_tokens += (int64_t)p->batch * rows_per_pair * max_lens[s0 + i];
+                row_tiles += (int64_t)p->batch * rows_per_pair * ceil_div(max_lens[s0 + i], plan->granule);
+            }
+            const int64_t n_wg = stream_workgroups(p, path, row_tokens, row_tiles);
+            const int64_t pairs = (int64_t)cnt * p->batch, rows = pairs * rows_per_pair;
+            if (n_wg > (int64_t)1 << 20 || rows > (int64_t)1 << 28) return HELIX_ERR_SHAPE;
+            plan->total_splits += n_wg + rows;
             plan->workgroups += n_wg;
-            plan->map_bytes += stream_map_bytes((int64_t)cnt * p->batch, n_wg);
-            most = std::max(most, ceil_div(bound, n_wg));
+            plan->map_bytes += stream_map_bytes(path, pairs, rows, n_wg);
+            most = std::max(most, ceil_div(row_tokens, n_wg));
         }
-        plan->split_tokens = (int32_t)std::min<int64_t>(ceil_div(std::max<int64_t>(most, 1), 32) * 32, (int64_t)INT32_MAX / 32 * 32);
+        plan->split_tokens = (int32_t)std::min<int64_t>(ceil_div(std::max<int64_t>(most, 1), plan->granule) * plan->granule,
+                                                        (int64_t)INT32_MAX / plan->granule * plan->granule);
         return HELIX_OK;
     }
-    // The streaming kernels take their runs from a map for a batch that is declared ragged -- the map costs a
-    // launch of its own; MLA launches with several head tiles go by workgroup id
-    plan->ordered = path != Path::Mla && ragged;
+    // MLA with several head tiles: fixed runs of 4096 tokens, one workgroup per (run, sequence, head tile), by id
+    const int64_t rows = (int64_t)p->batch * plan->head_tiles;
     int64_t split;
     if (p->split_tokens > 0) {
         split = ceil_div(p->split_tokens, plan->granule) * plan->granule;
     } else {
-        // MLA is compute-bound, one workgroup per CU at a time, and sequence lengths may be ragged (the
-        // host only knows the longest): short runs of 4096 tokens let the dispatcher balance the CUs.
-        // Measured (runs ordered by run_order_kernel): the ragged e4m3 workload takes 2.81 ms with 4096-token
-        // runs, 2.90 with 3072 or 8192, 3.00 with 2048; the uniform bf16 share loses 1 % (3 % of the whole
-        // step) against its best (8192).  The 256 KB record of a run is 5-11 % of the latent bytes it reads.
-        const int64_t target = target_workgroups(path);
-        const int64_t floor_tokens = path == Path::Mla ? kMinSplitTokensMla : kMinSplitTokens;
-        const int64_t work = path == Path::Mla ? rows * total : rows / p->batch * tokens;   // token rows to stream
-        split = ceil_div(ceil_div(work, target), plan->granule) * plan->granule;
-        split = std::max<int64_t>(split, floor_tokens);
-        if (path != Path::Mla && ragged) {
-            // the longest sequence decides how many records a row needs: keep them within the sizing call's bound
-            const int64_t cap = ragged_split_cap(path, rows, n) - n;
-            split = std::max<int64_t>(split, ceil_div(ceil_div(total, cap), plan->granule) * plan->granule);
-        }
+        int64_t total = 0;
+        for (int i = 0; i < n; i++) total += max_lens[i];
+        split = ceil_div(ceil_div(rows * total, kTargetWorkgroupsMla), plan->granule) * plan->granule;
+        split = std::max<int64_t>(split, kMinSplitTokensMla);
     }
-    if (path == Path::GqaMx128) split = std::min<int64_t>(split, (int64_t)1 << 25);   // 32-bit byte offsets inside a split
     // split_tokens is a 32-bit field of the kernel arguments: many shards of many long sequences must not wrap it
     // (no sequence is longer than INT32_MAX tokens, so a run of this length already holds any of them)
     split = std::min<int64_t>(split, (int64_t)INT32_MAX / plan->granule * plan->granule);
     plan->split_tokens = (int32_t)split;
     plan->total_splits = 0;
     for (int i = 0; i < n; i++) plan->total_splits += std::max<int64_t>(1, ceil_div(max_lens[i], split));
-    plan->workgroups = plan->total_splits * rows;   // MLA launches pad this per shard to whole groups of 8
-    if (plan->workgroups > (int64_t)1 << 30) return HELIX_ERR_SHAPE;
-    plan->map_bytes = plan->ordered ? (size_t)plan->workgroups * sizeof(uint64_t) : 0;
+    plan->workgroups = plan->total_splits * rows;   // the launch pads this per shard to whole groups of 8
+    plan->rec_rows = p->batch * p->q_heads;         // records [split][B][Q]
+    if (plan->workgroups > (int64_t)1 << 30 || (int64_t)p->batch * p->q_heads > INT32_MAX) return HELIX_ERR_SHAPE;
     return HELIX_OK;
 }
 
@@ -188,13 +166,11 @@ struct Workspace {
     size_t bytes;
 };
 
-// Carves a workspace for `total_splits` records, `n` shard partials and `map_bytes` of maps.  A record holds one
-// row per (sequence, query head), or, for the evenly cut MLA launches (`per_pair`), per query head of the one
-// sequence its run belongs to.  base may be NULL (sizing).
-inline Workspace carve(const helix_problem* p, int64_t total_splits, bool per_pair, size_t map_bytes, int32_t n, void* base)
+// Carves a workspace for `total_splits` records of `rec_rows` head rows each, `n` shard partials and `map_bytes`
+// of maps.  base may be NULL (sizing).
+inline Workspace carve(const helix_problem* p, int64_t total_splits, int64_t rec_rows, size_t map_bytes, int32_t n, void* base)
 {
     const size_t bq = (size_t)p->batch * p->q_heads;
-    const size_t rec_rows = per_pair ? (size_t)p->q_heads : bq;
     char* c = static_cast<char*>(base);
     size_t off = 0;
     Workspace w;
@@ -214,7 +190,7 @@ inline int check_shard(const helix_problem* p, const helix_kv_shard* s)
     if (p->v_aliases_k ? s->v != nullptr : s->v == nullptr) return p->v_aliases_k ? HELIX_ERR_SHAPE : HELIX_ERR_NULL;
     const bool fp8 = p->kv_dtype == HELIX_KV_FP8_E4M3;
     if (fp8 ? s->kv_scale == nullptr : false) return HELIX_ERR_NULL;
-    if (s->max_len < 0 || s->sum_len < 0) return HELIX_ERR_SHAPE;
+    if (s->max_len < 0) return HELIX_ERR_SHAPE;
     if (reinterpret_cast<uintptr_t>(s->status) % 4) return HELIX_ERR_SHAPE;
     if (p->kv_dtype == HELIX_KV_MXFP4) {
         // strides count elements; a row is dk/2 code bytes and dk/32 scale bytes, token rows dense
@@ -251,14 +227,12 @@ inline int prepare(const helix_problem* p, const helix_kv_shard* shards, int32_t
     if (!shards) return HELIX_ERR_NULL;
     if (n < 1 || n > HELIX_MAX_SHARDS) return HELIX_ERR_SHAPE;
     int32_t max_lens[HELIX_MAX_SHARDS];
-    int64_t sum_lens[HELIX_MAX_SHARDS];
     for (int32_t i = 0; i < n; i++) {
         if (int rc = check_shard(p, &shards[i])) return rc;
         max_lens[i] = shards[i].max_len;
-        sum_lens[i] = shards[i].sum_len;
     }
-    if (int rc = make_plan(p, path, max_lens, sum_lens, n, plan)) return rc;
-    *ws = carve(p, plan->total_splits, plan->stream, plan->map_bytes, n, workspace);
+    if (int rc = make_plan(p, path, max_lens, n, plan)) return rc;
+    *ws = carve(p, plan->total_splits, plan->rec_rows, plan->map_bytes, n, workspace);
     if (!workspace || reinterpret_cast<uintptr_t>(workspace) % 256 || ws->bytes > workspace_bytes) return HELIX_ERR_WORKSPACE;
     return HELIX_OK;
 }
@@ -274,21 +248,17 @@ inline size_t workspace_bytes(const helix_problem* problem, int32_t n_shards, in
     int32_t lens[HELIX_MAX_SHARDS];
     for (int i = 0; i < n_shards; i++) lens[i] = max_len;
     Plan plan;
-    if (make_plan(problem, path, lens, nullptr, n_shards, &plan) != HELIX_OK) return 0;
-    // an evenly cut MLA launch: workgroups and records only grow with the bounds, so the all-longest plan is the worst
-    if (plan.stream) return carve(problem, plan.total_splits, true, plan.map_bytes, n_shards, nullptr).bytes;
-    const int64_t rows = (int64_t)problem->batch * problem->kv_heads * plan.head_tiles;
-    int64_t worst = plan.total_splits;
-    if (problem->split_tokens == 0) {
-        worst = std::max<int64_t>(worst, ceil_div(target_workgroups(path), rows) + n_shards);
-        if (path != Path::Mla) worst = std::max<int64_t>(worst, ragged_split_cap(path, rows, n_shards));   // a batch declared ragged
-    }
-    return carve(problem, worst, false, (size_t)worst * rows * sizeof(uint64_t), n_shards, nullptr).bytes;
+    if (make_plan(problem, path, lens, n_shards, &plan) != HELIX_OK) return 0;
+    // an evenly cut launch: workgroups and records only grow with the bounds, so the all-longest plan is the worst
+    if (plan.stream) return carve(problem, plan.total_splits, plan.rec_rows, plan.map_bytes, n_shards, nullptr).bytes;
+    // runs by workgroup id: shorter shards keep their one record each
+    const int64_t worst = std::max<int64_t>(plan.total_splits, ceil_div(kTargetWorkgroupsMla, (int64_t)problem->batch * plan.head_tiles) + n_shards);
+    return carve(problem, worst, plan.rec_rows, 0, n_shards, nullptr).bytes;
 }
 
 // The N slices helix_attn_decode_kvp hands to the kernels: each describes the whole cache (the kernel
 // cuts slice i out of it) with the slice's own upper bounds.  `slices` has room for n_shards entries.
-inline void kvp_slices(const helix_problem* problem, const helix_kv_shard* cache, int32_t n_shards, helix_kv_shard* slices)
+inline void kvp_slices(const helix_kv_shard* cache, int32_t n_shards, helix_kv_shard* slices)
 {
     // every slice is at most c = 16 * ceil(ceil(max_len / N) / 16) tokens long
     const int64_t per = ceil_div(cache->max_len, n_shards);
@@ -296,9 +266,6 @@ inline void kvp_slices(const helix_problem* problem, const helix_kv_shard* cache
     for (int32_t i = 0; i < n_shards; i++) {
         slices[i] = *cache;
         slices[i].max_len = c;
-        // a slice holds a N-th of every sequence, rounded up to whole 16-token blocks
-        if (cache->sum_len > 0)
-            slices[i].sum_len = std::min<int64_t>(ceil_div(cache->sum_len, n_shards) + 16 * (int64_t)problem->batch, (int64_t)problem->batch * c);
     }
 }
 

@@ -28,14 +28,13 @@ class ShardSet:
 
 def make_shards(k: torch.Tensor, v: Optional[torch.Tensor], lens_dev: torch.Tensor, n_shards: int,
                 kv_scale: Optional[torch.Tensor] = None, seq_base: Optional[torch.Tensor] = None,
-                mx=None, declare_sums: bool = False) -> ShardSet:
+                mx=None) -> ShardSet:
     """Cuts every sequence into ``n_shards`` KVP slices with the library's layout kernel and wraps
     each slice as a view (tok_off) into the unsharded tensors.
 
     Padded storage: k [B,K,S,dk], v [B,K,S,dv] or None (MLA), kv_scale [B,K,S].
     Packed storage: k [rows,dk], seq_base int64 [B] = first row of each sequence, kv_scale [rows].
     MXFP4: k, v uint8 codes [B,K,S,d/2] and mx = (k_mx, v_mx) uint8 block scales [B,K,S,d/32].
-    declare_sums: also hand every slice's total length to the library (the hint for ragged batches).
     """
     B = lens_dev.numel()
     dev = lens_dev.device
@@ -43,7 +42,6 @@ def make_shards(k: torch.Tensor, v: Optional[torch.Tensor], lens_dev: torch.Tens
     shard_len = torch.empty((n_shards, B), dtype=torch.int32, device=dev)
     hx.helix_shard_layout(lens_dev, n_shards, shard_off, shard_len, seq_base=seq_base)
     max_lens = shard_len.max(dim=1).values.cpu().tolist()      # harness-side sync, not in the library
-    sums = shard_len.sum(dim=1, dtype=torch.int64).cpu().tolist() if declare_sums else [0] * n_shards
     shards = []
     for i in range(n_shards):
         if mx is not None:
@@ -52,7 +50,6 @@ def make_shards(k: torch.Tensor, v: Optional[torch.Tensor], lens_dev: torch.Tens
             s = hx.KVShard.from_packed(k, shard_len[i], max_lens[i], shard_off[i], kv_scale=kv_scale)
         else:
             s = hx.KVShard.from_padded(k, v, shard_len[i], max_lens[i], tok_off=shard_off[i], kv_scale=kv_scale)
-        s.sum_len = int(sums[i])
         shards.append(s)
     return ShardSet(shards, shard_off, shard_len, max_lens)
 

@@ -46,7 +46,6 @@ int main()
     const int32_t shard_counts[] = {1, 2, 3, 8, 16, 17, 64, 1024};
     std::vector<helix_kv_shard> shards(HELIX_MAX_SHARDS);
     std::vector<int32_t> lens(HELIX_MAX_SHARDS);
-    std::vector<int64_t> sums(HELIX_MAX_SHARDS);
     alignas(256) static unsigned char fake_base[256];      // never dereferenced: carve() only does address arithmetic
     for (const helix_problem& p : shapes) {
         Path path;
@@ -58,8 +57,6 @@ int main()
                 for (int i = 0; i < n; i++) {
                     lens[i] = lens_pool[rnd() % n_pool];
                     if (rep % 4 == 0) lens[i] = lens_pool[(rep / 4) % n_pool];          // uniform sets as well
-                    const int64_t full = (int64_t)p.batch * lens[i];
-                    sums[i] = rep % 3 == 0 ? 0 : rep % 3 == 1 ? (int64_t)(rnd() % (uint64_t)(full + 1)) : full + 5;
                     longest = lens[i] > longest ? lens[i] : longest;
                 }
                 if (prc != HELIX_OK) {
@@ -67,20 +64,21 @@ int main()
                     continue;
                 }
                 Plan plan;
-                const int rc = make_plan(&p, path, lens.data(), rep % 2 ? sums.data() : nullptr, n, &plan);
+                const int rc = make_plan(&p, path, lens.data(), n, &plan);
                 if (rc != HELIX_OK) {
                     CHECK(rc == HELIX_ERR_SHAPE);          // too many workgroups for one launch: refused, not wrapped
                     continue;
                 }
                 planned++;
                 CHECK(plan.split_tokens > 0 && plan.split_tokens % plan.granule == 0);
-                const int64_t rows = (int64_t)p.batch * p.kv_heads * plan.head_tiles;
+                const int64_t rows = (int64_t)p.batch * (path == Path::Mla ? 1 : p.kv_heads) * plan.head_tiles;
                 if (plan.stream) {
-                    // evenly cut launches of at most 16 shards: a record per workgroup and per (shard, sequence) pair
+                    // evenly cut launches of at most 16 shards: a record per workgroup and per row of the launch
                     const int64_t launches = ceil_div(n, kMaxShardsPerLaunch);
                     CHECK(plan.workgroups >= launches && plan.workgroups <= launches * ((int64_t)1 << 20));
-                    CHECK(plan.total_splits == plan.workgroups + (int64_t)n * p.batch);
-                    CHECK(plan.map_bytes >= (size_t)((int64_t)n * p.batch + launches) * 8 + (size_t)plan.workgroups * 4);
+                    CHECK(plan.total_splits == plan.workgroups + (int64_t)n * (path == Path::Mla ? p.batch : rows));
+                    CHECK(plan.map_bytes >= (size_t)((int64_t)n * p.batch + launches) * 8);
+                    CHECK(plan.rec_rows == (path == Path::Mla ? p.q_heads : 16));
                 } else {
                     int64_t splits = 0;
                     for (int i = 0; i < n; i++) {
@@ -92,7 +90,7 @@ int main()
                     CHECK(plan.workgroups == splits * rows && plan.workgroups <= ((int64_t)1 << 30));
                 }
                 // the workspace the sizing call promises covers the call's own carving
-                const Workspace w = carve(&p, plan.total_splits, plan.stream, plan.map_bytes, n, fake_base);
+                const Workspace w = carve(&p, plan.total_splits, plan.rec_rows, plan.map_bytes, n, fake_base);
                 CHECK((unsigned char*)w.ws_o == fake_base);
                 CHECK((size_t)((unsigned char*)w.maps - fake_base) + plan.map_bytes <= w.bytes && w.bytes % 256 == 0);
                 // (no bound exists only if n shards that all have the longest length are more than one launch holds)
@@ -100,10 +98,10 @@ int main()
                 if (bound == 0) {
                     std::vector<int32_t> all(n, longest);
                     Plan worst;
-                    CHECK(make_plan(&p, path, all.data(), nullptr, n, &worst) == HELIX_ERR_SHAPE);
+                    CHECK(make_plan(&p, path, all.data(), n, &worst) == HELIX_ERR_SHAPE);
                     continue;
                 }
-                if (p.split_tokens == 0) CHECK(w.bytes <= bound);
+                if (p.split_tokens == 0 || plan.stream) CHECK(w.bytes <= bound);
                 // descriptors: a valid one passes, each broken field is caught
                 helix_kv_shard s{};
                 const bool fp4 = p.kv_dtype == HELIX_KV_MXFP4, fp8 = p.kv_dtype == HELIX_KV_FP8_E4M3;
@@ -127,17 +125,16 @@ int main()
                 bad = s; bad.status = reinterpret_cast<int32_t*>(fake_base + 1);
                 CHECK(check_shard(&p, &bad) == HELIX_ERR_SHAPE);
                 // the whole call path short of the launch, incl. the fused cut's slice bounds
-                for (int i = 0; i < n; i++) { shards[i] = s; shards[i].max_len = lens[i]; shards[i].sum_len = rep % 2 ? sums[i] : 0; }
+                for (int i = 0; i < n; i++) { shards[i] = s; shards[i].max_len = lens[i]; }
                 Plan plan2;
                 Workspace ws2;
                 const int rc2 = prepare(&p, shards.data(), n, fake_base, bound, &plan2, &ws2);
                 CHECK(rc2 == HELIX_OK || rc2 == HELIX_ERR_WORKSPACE || rc2 == HELIX_ERR_SHAPE);
-                if (p.split_tokens == 0 && rep % 2 == 0) CHECK(rc2 == HELIX_OK);
+                if (p.split_tokens == 0 || plan.stream) CHECK(rc2 == HELIX_OK);
                 CHECK(prepare(&p, shards.data(), n, fake_base, 16, &plan2, &ws2) != HELIX_OK || ws2.bytes <= 16);
                 helix_kv_shard cache = s;
-                cache.sum_len = rep % 2 ? sums[0] : 0;
-                kvp_slices(&p, &cache, n, shards.data());
-                for (int i = 0; i < n; i++) CHECK(shards[i].max_len >= 0 && shards[i].max_len <= cache.max_len && shards[i].sum_len >= 0);
+                kvp_slices(&cache, n, shards.data());
+                for (int i = 0; i < n; i++) CHECK(shards[i].max_len >= 0 && shards[i].max_len <= cache.max_len);
             }
         }
     }

@@ -147,18 +147,17 @@ def test_mxfp4_fused_cut(hx, oracle):
     run_both(hx, oracle, w, inp, 3)
 
 
-def test_fused_cut_of_a_batch_declared_ragged(hx, oracle):
-    """helix_attn_decode_kvp on a cache that states the sum of its lengths: every slice is planned for its
-    share of it; the cut and the results are those of the oracle."""
+def test_fused_cut_of_a_ragged_batch(hx, oracle):
+    """helix_attn_decode_kvp on a ragged batch (the host knows only the longest sequence): the cut and the results
+    are those of the oracle."""
     from paper_2507_07120_amd import harness
     lens = [50000, 1000, 0, 333, 20000, 4096, 77, 15000]
-    w = synth.Workload("kvp_ragged_hint", B=8, Q=16, K=1, dk=128, dv=128, n_shards=4, scale=1 / math.sqrt(128), seed=71, seq_len=50000)
+    w = synth.Workload("kvp_ragged", B=8, Q=16, K=1, dk=128, dv=128, n_shards=4, scale=1 / math.sqrt(128), seed=71, seq_len=50000)
     inp = synth.make_inputs(w, "cuda")
     inp.lens = torch.tensor(lens, dtype=torch.int32)
     prob = harness.problem_for(w)
     lens_dev = inp.lens.cuda()
     cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, 50000)
-    cache.sum_len = int(sum(lens))
     ws = harness.workspace_for(prob, 4, 50000, "cuda")
     o = torch.full((8, 16, 128), float("nan"), device="cuda")
     lse = torch.full((8, 16), float("nan"), device="cuda")

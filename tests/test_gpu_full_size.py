@@ -56,7 +56,6 @@ def decode_as_bench(hx, w, inp, n_shards):
         cache = hx.KVShard.from_packed(inp.k, lens_dev, max_len, seq_base, kv_scale=inp.kv_scale)
     else:
         cache = hx.KVShard.from_padded(inp.k, inp.v, lens_dev, max_len, kv_scale=inp.kv_scale)
-    cache.sum_len = int(inp.lens.sum())
     ws = harness.workspace_for(prob, n_shards, max_len, dev)
     o = torch.full((w.B, w.Q, w.dv), float("nan"), device=dev)
     lse = torch.full((w.B, w.Q), float("nan"), device=dev)
