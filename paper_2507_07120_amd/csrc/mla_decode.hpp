@@ -40,7 +40,9 @@
 //            A tile in which a score comes within reach of the number range's end moves that head's
 //            reference -- an exact power-of-two rescale of its normaliser at once and of its accumulators in
 //            the P phase, behind a wave-uniform branch (never on ordinary logits; a test forces it).
-//            The lane's 8 weights go to LDS as bf16 hi + lo, already in the P.V operand's layout.
+//            The lane's 8 weights go to LDS as bf16 hi + lo, already in the P.V operand's layout (a head's row is
+//            64 bytes: its four 16-byte slots are XOR-ed with (head >> 1) & 3, so that the eight lanes an LDS
+//            access serves per cycle fall on distinct banks).
 //   barrier
 //   P phase  O^T[dv, head] += V^T . P^T: waves 2p and 2p+1 share heads 32p..32p+31 and split the value
 //            columns (256 each: 16 column tiles x 2 head tiles = 128 accumulator registers); the
@@ -764,7 +766,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
 #pragma unroll
             for (int j = 0; j < 4; j++) w[j] = pack_f16_rne(p[2 * j], p[2 * j + 1]);
             const int l = mla_opaque(lane);
-            lds_byte* pw = smem + C::OFF_P + pair * 2 * C::P_BYTES + (half * 16 + (l & 15)) * (C::T * 2) + (l >> 4) * 16;
+            lds_byte* pw = smem + C::OFF_P + pair * 2 * C::P_BYTES + (half * 16 + (l & 15)) * (C::T * 2) + (((l >> 4) ^ ((l >> 1) & 3)) << 4);
             *reinterpret_cast<lds_u32x4*>(pw) = w;
             return;
         }
@@ -787,7 +789,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
             lo[j] = pack_bf16_rne(p[2 * j] - as_f32(hi[j] << 16), p[2 * j + 1] - as_f32(hi[j] & 0xffff0000u));
         }
         const int l = mla_opaque(lane);
-        lds_byte* pw = smem + C::OFF_P + pair * 2 * C::P_BYTES + (half * 16 + (l & 15)) * (C::T * 2) + (l >> 4) * 16;
+        lds_byte* pw = smem + C::OFF_P + pair * 2 * C::P_BYTES + (half * 16 + (l & 15)) * (C::T * 2) + (((l >> 4) ^ ((l >> 1) & 3)) << 4);
         *reinterpret_cast<lds_u32x4*>(pw) = hi;
         *reinterpret_cast<lds_u32x4*>(pw + C::P_BYTES) = lo;
     };
@@ -818,7 +820,7 @@ __global__ __launch_bounds__(MlaCfg::THREADS, 1) void mla_decode_kernel(const At
                 }
             }
         }
-        const lds_byte* pp = smem + C::OFF_P + pair * 2 * C::P_BYTES + r * (C::T * 2) + kc * 16;
+        const lds_byte* pp = smem + C::OFF_P + pair * 2 * C::P_BYTES + r * (C::T * 2) + ((kc ^ ((r >> 1) & 3)) << 4);
         u32x4 bh[C::NHT], bl[C::NHT];
 #pragma unroll
         for (int h = 0; h < C::NHT; h++) {
