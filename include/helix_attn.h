@@ -72,7 +72,8 @@ typedef enum {
     HELIX_KV_MXFP4 = 2         /* OCP microscaling FP4 (the precision Sec. 3 evaluates in): E2M1 codes, two per byte
                                   (even element in the low nibble); every 32 consecutive elements of a
                                   row share one E8M0 scale byte; value = 2^(scale - 127) * e2m1(code).
-                                  Scale codes 0 and 255 (2^-127, NaN) are not supported. */
+                                  A block with scale code 0 (2^-127) is taken as zero, which is its value to
+                                  within 2^-124; scale code 255 (NaN) is not supported. */
 } helix_kv_dtype;
 
 #define HELIX_MAX_SHARDS 1024

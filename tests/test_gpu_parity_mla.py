@@ -91,10 +91,10 @@ def test_mla_bf16_against_oracle(hx, oracle, B, Q, S, N, lens, split):
     assert (o_n - o_1).abs().max().item() <= SHARD_VS_UNSHARDED
 
 
-def test_mla_many_short_sequences_run_order(hx, oracle):
-    """More (shard, sequence) pairs than the run-ordering kernel has threads (1200 > 1024), lengths from 0 to
-    three runs of 64 tokens: every run -- full, partial or empty -- must be served exactly once, whatever
-    workgroup it lands on (an unserved one leaves the NaN the records were filled with)."""
+def test_mla_many_short_sequences(hx, oracle):
+    """More (shard, sequence) pairs than the planning kernel has threads (1200 > 1024), lengths from 0 to
+    three runs of 64 tokens: every pair -- long, short or empty -- must be served exactly once, whatever
+    workgroups its tiles land on (an unserved one leaves the NaN the records were filled with)."""
     from paper_2507_07120_amd import harness
     B, N = 300, 4
     w = synth.Workload("mla_many", B=B, Q=16, K=1, dk=576, dv=512, n_shards=N, scale=1 / math.sqrt(192), seed=404,
@@ -182,10 +182,11 @@ def _mla_fp8_padded(seed, lens, S):
     return w, inp
 
 
-def test_mla_fp8_weight_beyond_fp16_range_restarts(hx, oracle):
+def test_mla_fp8_weight_beyond_fp16_range_moves_the_reference(hx, oracle):
     """The e4m3 path hands fp16 weights to the P.V MFMA, scaled from the first tile.  A key far down
     the run that is aligned with one head's query weighs ~2^120 times more than anything in the first
-    tile: the run must be repeated with that head's reference moved, and the result stays exact."""
+    tile: that head's reference must move in the tile that holds the key (accumulators and normaliser rescaled by
+    the same exact power of two), and the result stays exact."""
     w, inp = _mla_fp8_padded(78, [400], 400)
     codes, sc = synth.quantize_e4m3_per_token(inp.q[0, 5].float() * 2.0)
     inp.k[0, 0, 150] = codes
@@ -197,10 +198,10 @@ def test_mla_fp8_weight_beyond_fp16_range_restarts(hx, oracle):
     run_mla(hx, oracle, w, inp, 3, check_partials=True)
 
 
-def test_mla_fp8_weight_beyond_fp32_range_restarts(hx, oracle):
+def test_mla_fp8_weight_beyond_fp32_range_moves_the_reference(hx, oracle):
     """As above with a key three times as long: its weight relative to the first tile's reference is ~2^360,
-    infinite in fp32.  The kernel still knows the exponent and repeats the run from there (a third pass
-    then settles the fp16 range exactly)."""
+    infinite in fp32.  The tile's scores are computed once more to get the exponent the weight lost, and the
+    reference moves by that much."""
     w, inp = _mla_fp8_padded(82, [400], 400)
     codes, sc = synth.quantize_e4m3_per_token(inp.q[0, 77].float() * 6.0)
     inp.k[0, 0, 300] = codes
@@ -227,11 +228,10 @@ def test_mla_fp8_token_scales_spread_over_octaves(hx, oracle):
 
 
 def test_mla_fp8_head_far_below_the_shared_weight_scale(hx, oracle):
-    """The fp16 weight scale is one per workgroup, taken from the largest first-tile weight p_t * f_t of any
-    head.  Token 3 carries an ordinary row quantised with a scale 2^11 times larger than needed (valid, just
-    coarse codes), so it sets that scale for every head that looks at it -- except head 7, whose query points
-    away from it: head 7's weights all sit 2^-7 below the shared scale's target and its reference has to be
-    moved in a second pass."""
+    """Every head sets its own fp16 weight range from its largest first-tile weight p_t * f_t.  Token 3 carries an
+    ordinary row quantised with a scale 2^11 times larger than needed (valid, just coarse codes), so it dominates
+    the first tile of every head that looks at it -- except head 7, whose query points away from it and whose
+    weights sit 2^-7 below the others': a range shared by the workgroup would push them towards fp16's denormals."""
     w, inp = _mla_fp8_padded(80, [200], 200)
     x = inp.k[0, 0, 3].view(torch.float8_e4m3fn).float() * inp.kv_scale[0, 0, 3]
     big = inp.kv_scale[0, 0, 3] * 2048.0

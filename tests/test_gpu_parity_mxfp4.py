@@ -168,7 +168,7 @@ def test_mxfp4_ragged_batch(hx, oracle):
     """The MXFP4 streaming kernel on a ragged batch: the workgroups share the tokens that exist evenly."""
     from paper_2507_07120_amd import harness
     lens = [30000, 2000, 0, 700, 12000, 64]
-    w = synth.Workload("mx_ragged_hint", B=6, Q=16, K=1, dk=128, dv=128, n_shards=2, scale=1 / math.sqrt(128), seed=29,
+    w = synth.Workload("mx_ragged", B=6, Q=16, K=1, dk=128, dv=128, n_shards=2, scale=1 / math.sqrt(128), seed=29,
                        seq_len=30000, fp4=True)
     inp = synth.make_inputs(w, "cuda")
     inp.lens = torch.tensor(lens, dtype=torch.int32)
