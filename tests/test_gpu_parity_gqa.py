@@ -103,6 +103,48 @@ def test_gqa_ragged_batch(hx, oracle, B, Q, K, D, S, N, lens):
     assert torch.equal(o_t, o_p) and torch.equal(lse_t, lse_p)
 
 
+@pytest.mark.parametrize("B,Q,K,D,N,S,split", [
+    (40, 8, 2, 64, 3, 700, 0),          # 120 pairs: every thread of the planning scan has at most one
+    (5, 16, 1, 128, 16, 3000, 0),       # 80 pairs in one launch of 16 shards
+    (300, 4, 1, 64, 4, 500, 128),       # 1200 pairs: several per thread; short forced runs
+    (70, 40, 2, 128, 1, 260, 0),        # 70 pairs, two head tiles per KV head
+])
+def test_gqa_many_pairs_plan_through_shared_memory(hx, oracle, B, Q, K, D, N, S, split):
+    """More than 64 (shard, sequence) pairs in a launch: the workgroups scan the lengths in chunks through shared
+    memory instead of one pair per lane.  Lengths from 0 to S incl. 1-token sequences; the workspace is filled with
+    NaN, so a record that nobody wrote, or a row served twice or not at all, shows in the result."""
+    from paper_2507_07120_amd import harness
+    w = synth.Workload("gqa_many", B=B, Q=Q, K=K, dk=D, dv=D, n_shards=N, scale=1 / math.sqrt(D), seed=900 + B, seq_len=S)
+    inp = synth.make_inputs(w, "cuda")
+    lens = synth.uniform_lengths(13, 5, B, 0, S)
+    lens[:4] = torch.tensor([0, S, 1, 129], dtype=torch.int32)
+    inp.lens = lens
+    prob = harness.problem_for(w, split)
+    ss = harness.make_shards(inp.k, inp.v, inp.lens.cuda(), N)
+    ws = harness.workspace_for(prob, N, max(ss.max_lens), "cuda")
+    ws.view(torch.float32)[: ws.numel() // 4].fill_(float("nan"))
+    o = torch.full((B, Q, D), float("nan"), device="cuda")
+    lse = torch.full((B, Q), float("nan"), device="cuda")
+    hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+    torch.cuda.synchronize()
+    ln = inp.lens.numpy()
+    o_ref, lse_ref = oracle.attention(synth.bits(inp.q), synth.bits(inp.k), synth.bits(inp.v), ln, w.scale, kv_heads=K, dv=D)
+    has = ln > 0
+    check_o(o.cpu().numpy()[has], o_ref[has], f"{B * N} pairs O")
+    check_lse(lse.cpu().numpy(), lse_ref, f"{B * N} pairs LSE")
+    assert np.all(o.cpu().numpy()[~has] == 0)
+    # the fused cut on the unsharded cache (sized from another bound, so cut at other tokens): fp32 summation order apart
+    cache = hx.KVShard.from_padded(inp.k, inp.v, inp.lens.cuda(), S)
+    ws2 = harness.workspace_for(prob, N, S, "cuda")
+    ws2.view(torch.float32)[: ws2.numel() // 4].fill_(float("nan"))
+    o2 = torch.full_like(o, float("nan"))
+    lse2 = torch.full_like(lse, float("nan"))
+    hx.helix_attn_decode_kvp(prob, inp.q, cache, N, o2, ws2, lse_out=lse2)
+    torch.cuda.synchronize()
+    assert (o2 - o).abs().max().item() <= SHARD_VS_UNSHARDED
+    assert (lse2[torch.from_numpy(has).cuda()] - lse[torch.from_numpy(has).cuda()]).abs().max().item() <= 1e-5
+
+
 def test_tiny_gqa_config(hx, oracle):
     """B=1, 8 query / 2 KV heads, d=64, S=4096 in 4 equal shards: the full first configuration."""
     w = synth.WORKLOADS["tiny_gqa"]

@@ -164,6 +164,33 @@ def test_mxfp4_decode_loop_round_robin(hx, oracle):
     assert overflow.item() == 0
 
 
+def test_mxfp4_many_pairs_plan_through_shared_memory(hx, oracle):
+    """The MXFP4 streaming kernel with more than 64 (shard, sequence) pairs in a launch (the chunked planning scan),
+    lengths from 0 up, NaN-filled workspace."""
+    from paper_2507_07120_amd import harness
+    B, N, S = 45, 2, 900
+    w = synth.Workload("mx_many", B=B, Q=16, K=1, dk=128, dv=128, n_shards=N, scale=1 / math.sqrt(128), seed=31, seq_len=S, fp4=True)
+    inp = synth.make_inputs(w, "cuda")
+    lens = synth.uniform_lengths(17, 3, B, 0, S)
+    lens[:3] = torch.tensor([0, S, 1], dtype=torch.int32)
+    inp.lens = lens
+    prob = harness.problem_for(w)
+    ss = harness.make_shards(inp.k, inp.v, inp.lens.cuda(), N, mx=(inp.k_mx, inp.v_mx))
+    ws = harness.workspace_for(prob, N, max(ss.max_lens), "cuda")
+    ws.view(torch.float32)[: ws.numel() // 4].fill_(float("nan"))
+    o = torch.full((B, 16, 128), float("nan"), device="cuda")
+    lse = torch.full((B, 16), float("nan"), device="cuda")
+    hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+    torch.cuda.synchronize()
+    ln = inp.lens.numpy()
+    o_ref, lse_ref = oracle.attention(synth.bits(inp.q), inp.k.cpu().numpy(), inp.v.cpu().numpy(), ln, w.scale,
+                                      kv_heads=1, mx=(inp.k_mx.cpu().numpy(), inp.v_mx.cpu().numpy()))
+    has = ln > 0
+    check_o(o.cpu().numpy()[has], o_ref[has], "MXFP4 90 pairs O")
+    check_lse(lse.cpu().numpy(), lse_ref, "MXFP4 90 pairs LSE")
+    assert np.all(o.cpu().numpy()[~has] == 0)
+
+
 def test_mxfp4_ragged_batch(hx, oracle):
     """The MXFP4 streaming kernel on a ragged batch: the workgroups share the tokens that exist evenly."""
     from paper_2507_07120_amd import harness
