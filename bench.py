@@ -323,6 +323,13 @@ def ceilings(args):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e-3 / reps
 
+    # untimed, as before every workload: the driver clears memory a process has just given back (the previous
+    # workload's tensors) in the background for a second or so, and a read probe started meanwhile measures 4-5 % low
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < args.settle_seconds:
+        for _ in range(20):
+            hx.helix_probe_stream_read(buf, 256, True)
+        torch.cuda.synchronize()
     for label, nt in (("stream_read_nontemporal", True), ("stream_read_plain", False)):
         nbytes = buf.numel() * 2
         s = timed(lambda: hx.helix_probe_stream_read(buf, 256, nt), max(5, min(args.steps, 50)))
