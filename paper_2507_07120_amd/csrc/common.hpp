@@ -55,12 +55,15 @@ __device__ __forceinline__ void flag_len_overflow(const ShardDev& sh, int len, i
 // Arguments of an attention launch over up to kMaxLaunchShards shards.
 struct AttnArgs {
     const uint16_t* q;    // bf16 [B,Q,dk]
-    float* ws_o;          // split records: un-normalised sum_t p_t v_t, [split][B][Q][dv]
-    float* ws_m;          // integer power-of-two reference exponent of the record, [split][B][Q]
-    float* ws_l;          // sum_t p_t, [split][B][Q]
+    // split records: un-normalised sum_t p_t v_t (ws_o, rows of dv), the integer power-of-two reference exponent of
+    // the row (ws_m) and sum_t p_t (ws_l).  Rows of an evenly cut launch: [record][16 heads] (GQA), [record][Q] (MLA),
+    // record = rec_base + workgroup + row (GQA) / pair (MLA) index; of a launch cut by workgroup id: [split][B][Q]
+    float* ws_o;
+    float* ws_m;
+    float* ws_l;
     int32_t B, Q, K, g;
     int32_t head_tiles;   // ceil(g / heads per workgroup)
-    int32_t split_tokens; // tokens of a shard one workgroup streams
+    int32_t split_tokens; // launches cut by workgroup id: tokens of a shard one workgroup serves
     float scale_log2e;    // softmax scale * log2(e)
     int32_t n_shards;
     // streaming GQA launches (every workgroup plans its own share, stream_self_plan): what the merge needs later
