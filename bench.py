@@ -44,6 +44,8 @@ def kv_bytes_per_step(w, lens) -> int:
         per_token = w.dk * (1 if w.fp8 else 2) + (4 if w.fp8 else 0)
     elif getattr(w, "fp4", False):
         per_token = (w.dk + w.dv) // 2 + (w.dk + w.dv) // 32
+    elif w.fp8:
+        per_token = (w.dk + w.dv) + 4
     else:
         per_token = (w.dk + w.dv) * 2
     return tokens * w.K * per_token
@@ -130,7 +132,7 @@ def read_traffic(workload: str):
 def kernel_name(w) -> str:
     if w.mla:
         return "mla_decode_kernel<" + ("mxfp4" if getattr(w, "fp4", False) else "e4m3" if w.fp8 else "bf16") + ">"
-    return "gqa_mxfp4_kernel" if getattr(w, "fp4", False) else f"gqa_decode_kernel<{w.dk}>"
+    return "gqa_mxfp4_kernel" if getattr(w, "fp4", False) else "gqa_fp8_kernel" if w.fp8 else f"gqa_decode_kernel<{w.dk}>"
 
 
 def measure(name, args, budget_macs, extras=False):

@@ -31,16 +31,17 @@
  *   - Every call returns a helix_status.  Arguments are validated on the host before anything
  *     is launched, so an error return means no kernel ran.
  *   - Supported shapes: (dk,dv) = (64,64) or (128,128) with bf16 K/V and any Q/K group size
- *     (the GQA path), (128,128) with MXFP4 K/V (the FP4 of the paper's evaluation, Sec. 3), and
+ *     (the GQA path), (128,128) with e4m3 K/V + one fp32 scale per (sequence, kv head, token) that the
+ *     token's key and value row share, (128,128) with MXFP4 K/V (the FP4 of the paper's evaluation, Sec. 3), and
  *     (dk,dv) = (576,512) with v_aliases_k = 1, kv_heads = 1, bf16, e4m3 + per-token fp32
  *     scale, or MXFP4 (the MLA path).  q is always bf16.
  *   - Alignment: q, k, v rows must start on 16-byte boundaries: base pointers 16-byte aligned and
  *     all strides multiples of 16 bytes.
  *   - Arithmetic: scores are exact products of the stored values accumulated in fp32; softmax weights
  *     are computed in fp32 relative to an integer power-of-two reference, so results do not depend on
- *     how a sequence is cut into shards beyond fp32 summation order (1e-5 on O(1) outputs).  The bf16
- *     and MXFP4 paths hand each weight to the matrix cores as a bf16 hi + lo pair (relative error
- *     2^-17); the e4m3 and MXFP4 MLA paths contract in fp16 with ONE fp16 weight per token (relative
+ *     how a sequence is cut into shards beyond fp32 summation order (1e-5 on O(1) outputs).  The bf16,
+ *     e4m3 and MXFP4 GQA paths and the bf16 MLA path hand each weight to the matrix cores as a bf16 hi + lo
+ *     pair (relative error 2^-17; an e4m3 token's scale multiplies its score and its weight in fp32); the e4m3 and MXFP4 MLA paths contract in fp16 with ONE fp16 weight per token (relative
  *     error up to 2^-12 that the normaliser does not share: |error of O| <= 2^-12 * max |v| for a peaked
  *     softmax, about 2e-4 relative L2 otherwise).  An MXFP4 latent row is held as fp16 entries times a
  *     power of two taken from its largest block scale: exact for blocks within 21 octaves of that scale,
@@ -68,7 +69,7 @@ typedef enum {
 
 typedef enum {
     HELIX_KV_BF16 = 0,
-    HELIX_KV_FP8_E4M3 = 1,     /* OCP e4m3 codes, value = code * kv_scale[token] */
+    HELIX_KV_FP8_E4M3 = 1,     /* OCP e4m3 codes, value = code * kv_scale[token] (key and value row of a token alike) */
     HELIX_KV_MXFP4 = 2         /* OCP microscaling FP4 (the precision Sec. 3 evaluates in): E2M1 codes, two per byte
                                   (even element in the low nibble); every 32 consecutive elements of a
                                   row share one E8M0 scale byte; value = 2^(scale - 127) * e2m1(code).

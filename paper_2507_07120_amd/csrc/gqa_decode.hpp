@@ -96,11 +96,13 @@ struct GqaState {
 // One 32-token block: scores, online softmax update, P.V.  `kop(a, s)` supplies the score MFMA's A
 // operand (16-token tile a, k-step s), `vop(c)` the P.V MFMA's A operand for value column c of the
 // lane (8 tokens of that column); the callers differ in how the operands come out of the loaded
-// block (bf16 as loaded / transposed, MXFP4 converted on the fly).
-template <int D, bool TAIL, class KOp, class VOp>
+// block (bf16 as loaded / transposed, MXFP4 or e4m3 converted on the fly).  SCALED: token slot e of the lane
+// (token (e / 4) * 16 + 4kc + e % 4) carries a dequantisation factor fs[e] that multiplies its score and its weight,
+// both in fp32; the normaliser sums the weights without it.
+template <int D, bool TAIL, bool SCALED = false, class KOp, class VOp>
 __device__ __forceinline__ void gqa_compute_core(GqaState<D>& st, KOp&& kop, VOp&& vop,
                                                  const bf16x8 (&qb)[GqaCfg<D>::KS],
-                                                 float scale_log2e, int kc, int n_valid)
+                                                 float scale_log2e, int kc, int n_valid, const float* fs = nullptr)
 {
     using C = GqaCfg<D>;
     // scores: lane (r,kc) gets head r, tokens a*16 + kc*4 + i
@@ -112,7 +114,10 @@ __device__ __forceinline__ void gqa_compute_core(GqaState<D>& st, KOp&& kop, VOp
         for (int s = 0; s < C::KS; s++)
             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kop(a, s), qb[s], acc, 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; i++) t[a * 4 + i] = acc[i] * scale_log2e;
+        for (int i = 0; i < 4; i++) {
+            t[a * 4 + i] = acc[i] * scale_log2e;
+            if (SCALED) t[a * 4 + i] *= fs[a * 4 + i];
+        }
     }
     bool valid[8];
     if (TAIL) {
@@ -148,15 +153,19 @@ __device__ __forceinline__ void gqa_compute_core(GqaState<D>& st, KOp&& kop, VOp
             p0 = exp2_rel_int(t[e], mi);
             p1 = exp2_rel_int(t[e + 1], mi);
         }
+        // l sums the unsplit weights: hi + lo differs from p by at most 2^-17 p, far below the bars,
+        // and re-adding the split would cost three more VALU instructions per weight pair
+        lsum += p0 + p1;
+        if (SCALED) {
+            p0 *= fs[e];
+            p1 *= fs[e + 1];
+        }
         const uint32_t h = pack_bf16_rne(p0, p1);
         const float r0 = p0 - as_f32(h << 16);
         const float r1 = p1 - as_f32(h & 0xffff0000u);
         const uint32_t lo = pack_bf16_rne(r0, r1);
         phi[e >> 1] = h;
         plo[e >> 1] = lo;
-        // l sums the unsplit weights: hi + lo differs from p by at most 2^-17 p, far below the bars,
-        // and re-adding the split would cost three more VALU instructions per weight pair
-        lsum += p0 + p1;
     }
     st.l += lsum;
     const bf16x8 bhi = __builtin_bit_cast(bf16x8, u32x4{phi[0], phi[1], phi[2], phi[3]});

@@ -14,6 +14,7 @@
 #include "common.hpp"
 #include "gqa_decode.hpp"
 #include "gqa_mxfp4.hpp"
+#include "gqa_fp8.hpp"
 #include "merge_combine.hpp"
 #include "mla_decode.hpp"
 #include "probes.hpp"
@@ -185,6 +186,9 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
                 break;
             case Path::GqaMx128:
                 hipLaunchKernelGGL(gqa_mxfp4_kernel, dim3((unsigned)units), dim3(256), 0, stream, a);
+                break;
+            case Path::GqaF8_128:
+                hipLaunchKernelGGL(gqa_fp8_kernel, dim3((unsigned)units), dim3(256), 0, stream, a);
                 break;
             case Path::Mla: {
                 const int kind = p->kv_dtype == HELIX_KV_FP8_E4M3 ? 1 : p->kv_dtype == HELIX_KV_MXFP4 ? 2 : 0;

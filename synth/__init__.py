@@ -142,6 +142,24 @@ def normal_e4m3_rows(seed: int, tag: int, rows: int, dim: int, device="cpu", row
     return codes, scale
 
 
+def normal_e4m3_kv_rows(seed: int, tag_k: int, tag_v: int, rows: int, dk: int, dv: int, device="cpu", row_chunk: int = 1 << 17,
+                        peak_prob: float = 0.0, peak_factor: float = 1.0):
+    """rows x dk key rows and rows x dv value rows of N(0,1) values (a fraction peak_prob of the key rows times
+    peak_factor), quantised to e4m3 with ONE scale per row pair -- a token's key row and value row share it, as the
+    GQA fp8 cache does; returns (k codes uint8, v codes uint8, scale fp32)."""
+    kc = torch.empty((rows, dk), dtype=torch.uint8, device=device)
+    vc = torch.empty((rows, dv), dtype=torch.uint8, device=device)
+    scale = torch.empty((rows,), dtype=torch.float32, device=device)
+    for r in range(0, rows, row_chunk):
+        c = min(row_chunk, rows - r)
+        xk = _peaked(normal_f32(seed, tag_k, r * dk, c * dk, device).view(c, dk), seed, r, peak_prob, peak_factor)
+        xv = normal_f32(seed, tag_v, r * dv, c * dv, device).view(c, dv)
+        codes, scale[r:r + c] = quantize_e4m3_per_token(torch.cat([xk, xv], dim=1))
+        kc[r:r + c], vc[r:r + c] = codes[:, :dk], codes[:, dk:]
+        _progress("e4m3 kv rows", r + c, rows)
+    return kc, vc, scale
+
+
 def quantize_mxfp4(x: torch.Tensor):
     """Rounds rows to the OCP microscaling FP4 format: blocks of 32 consecutive entries of the last
     axis share one E8M0 scale 2^(floor(log2 max|x|) - 2) (2 = exponent of the largest E2M1 value, 6),
@@ -229,6 +247,10 @@ WORKLOADS = {
     # 4x longer context, which keeps the cache near 1 GiB: KVP=8 of a 4M-token context
     "gqa_share_mxfp4": Workload("gqa_share_mxfp4", B=16, Q=16, K=1, dk=128, dv=128, n_shards=1,
                                 scale=1 / math.sqrt(128), seed=1006, seq_len=524288, fp4=True),
+    # the GQA share with the KV cache in e4m3 (one fp32 scale per token for its key and value row) and twice the
+    # context, which keeps the cache near 1 GiB: KVP=8 of a 2M-token context
+    "gqa_share_fp8": Workload("gqa_share_fp8", B=16, Q=16, K=1, dk=128, dv=128, n_shards=1,
+                              scale=1 / math.sqrt(128), seed=1009, seq_len=262144, fp8=True),
     # the MLA share with the latent in MXFP4 (DeepSeek-R1 with FP4 KV states is the paper's second model, Sec. 3)
     "mla_share_mxfp4": Workload("mla_share_mxfp4", B=32, Q=128, K=1, dk=576, dv=512, n_shards=1,
                                 scale=1 / math.sqrt(192), seed=1007, seq_len=131072, mla=True, fp4=True),
@@ -306,6 +328,10 @@ def make_inputs(w: Workload, device="cpu") -> Inputs:
         vc, vs = normal_mxfp4_rows(w.seed, TAG_V, w.B * w.K * S, w.dv, device)
         return Inputs(w, q, kc.view(w.B, w.K, S, w.dk // 2), vc.view(w.B, w.K, S, w.dv // 2), None, lens, None,
                       ks.view(w.B, w.K, S, w.dk // 32), vs.view(w.B, w.K, S, w.dv // 32))
+    if w.fp8 and not w.mla:
+        # GQA fp8 cache: separate key and value rows, one scale per (sequence, kv head, token) for both
+        kc, vc, sc = normal_e4m3_kv_rows(w.seed, TAG_K, TAG_V, w.B * w.K * S, w.dk, w.dv, device, peak_prob=w.peak_prob, peak_factor=w.peak_factor)
+        return Inputs(w, q, kc.view(w.B, w.K, S, w.dk), vc.view(w.B, w.K, S, w.dv), sc.view(w.B, w.K, S), lens, None)
     if w.fp8:
         codes, sc = normal_e4m3_rows(w.seed, TAG_K, w.B * w.K * S, w.dk, device, peak_prob=w.peak_prob, peak_factor=w.peak_factor)
         k, kv_scale = codes.view(w.B, w.K, S, w.dk), sc.view(w.B, w.K, S)
@@ -315,8 +341,6 @@ def make_inputs(w: Workload, device="cpu") -> Inputs:
             scale_rows_(k, w.seed, TAG_PEAK, w.peak_prob, w.peak_factor)
     v = None
     if not w.mla:
-        if w.fp8:
-            raise NotImplementedError("fp8 storage is defined for the MLA latent only")
         v = normal_bf16(w.seed, TAG_V, (w.B, w.K, S, w.dv), device)
     return Inputs(w, q, k, v, kv_scale, lens, None)
 

@@ -49,7 +49,8 @@ def test_problem_validation_without_gpu(hx):
     assert hx.helix_attn_workspace_bytes(mla, 1, 131072) > 0
     assert hx.helix_attn_workspace_bytes(hx.Problem(32, 128, 1, 576, 512, 0.07, v_aliases_k=True, kv_dtype=hx.KV_FP8_E4M3), 8, 32768) > 0
     assert hx.helix_attn_workspace_bytes(hx.Problem(32, 128, 2, 576, 512, 0.07, v_aliases_k=True), 1, 1024) == 0   # one latent only
-    assert hx.helix_attn_workspace_bytes(hx.Problem(1, 8, 2, 128, 128, 0.1, kv_dtype=hx.KV_FP8_E4M3), 1, 1024) == 0  # fp8 is MLA-only
+    assert hx.helix_attn_workspace_bytes(hx.Problem(1, 8, 2, 128, 128, 0.1, kv_dtype=hx.KV_FP8_E4M3), 1, 1024) > 0   # e4m3 K/V, head width 128
+    assert hx.helix_attn_workspace_bytes(hx.Problem(1, 8, 2, 64, 64, 0.1, kv_dtype=hx.KV_FP8_E4M3), 1, 1024) == 0     # ... and no other
     assert hx.helix_attn_workspace_bytes(ok, 0, 1024) == 0
     assert hx.helix_attn_workspace_bytes(ok, 1, -5) == 0
 

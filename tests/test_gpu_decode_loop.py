@@ -62,7 +62,10 @@ def run_loop(hx, oracle, w, prefill_lens, n_steps, cap):
     lse = torch.empty((B, w.Q), device=dev)
     for t in range(n_steps):
         q = synth.normal_bf16(w.seed, 1000 + t, (B, w.Q, w.dk), dev)
-        if w.fp8:
+        if w.fp8 and not w.mla:
+            kc, vc, sc = synth.normal_e4m3_kv_rows(w.seed, 2000 + t, 3000 + t, B * w.K, w.dk, w.dv, dev)
+            k_new, v_new, s_new = kc.view(B, w.K, w.dk), vc.view(B, w.K, w.dv), sc.view(B, w.K)
+        elif w.fp8:
             codes, sc = synth.normal_e4m3_rows(w.seed, 2000 + t, B * w.K, w.dk, dev)
             k_new, s_new, v_new = codes.view(B, w.K, w.dk), sc.view(B, w.K), None
         else:
@@ -127,3 +130,10 @@ def test_mla_fp8_decode_loop_round_robin(hx, oracle):
     w = synth.Workload("loop_mla", B=2, Q=128, K=1, dk=576, dv=512, n_shards=2, scale=1 / math.sqrt(192), seed=62,
                        seq_len=1, mla=True, fp8=True)
     run_loop(hx, oracle, w, prefill_lens=[70, 33], n_steps=40, cap=96)
+
+
+def test_gqa_fp8_decode_loop_round_robin(hx, oracle):
+    """The e4m3 GQA cache grows by one key row, one value row and their shared scale per step."""
+    w = synth.Workload("loop_gqa_fp8", B=2, Q=16, K=2, dk=128, dv=128, n_shards=3, scale=1 / math.sqrt(128), seed=63,
+                       seq_len=1, fp8=True)
+    run_loop(hx, oracle, w, prefill_lens=[90, 41], n_steps=16 * 3 + 9, cap=128)

@@ -1,5 +1,5 @@
 """Seeded random shapes through the C ABI against the CPU oracle: batch, head grouping, head width, shard count,
-forced run lengths and ragged lengths (empty and one-token sequences included) drawn per case, for the bf16 and the
+forced run lengths and ragged lengths (empty and one-token sequences included) drawn per case, for the bf16, e4m3 and
 MXFP4 GQA kernels and the three MLA latent formats.  The fixed cases of the other test files aim at known edges;
 these look for the ones nobody thought of.  Usual bars: O max-abs 2e-3 / relative L2 1e-3, LSE 1e-4, per-shard
 fragments and the argmax bookkeeping included (the helpers of the parity tests do the checking)."""
@@ -14,6 +14,7 @@ from test_gpu_parity_gqa import run_sharded
 from test_gpu_parity_mla import O_MAX_ABS, run_mla
 from test_gpu_parity_mla_mxfp4 import run as run_mla_mx
 from test_gpu_parity_mxfp4 import run_mx
+from test_gpu_parity_gqa_fp8 import run_f8
 
 pytestmark = pytest.mark.gpu
 
@@ -68,6 +69,21 @@ def test_random_gqa_mxfp4(hx, oracle, case):
     inp = synth.make_inputs(w, "cuda")
     inp.lens = torch.tensor(_lens(rng, B, S), dtype=torch.int32)
     run_mx(hx, oracle, w, inp, N, split_tokens=_split(rng, 128))
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_gqa_fp8(hx, oracle, case):
+    rng = random.Random(4000 + case)
+    K = rng.choice([1, 2, 4])
+    g = rng.choice([1, 4, 16, 16, 24])
+    B = rng.randint(1, 7)
+    S = rng.choice([1, 33, 128, 500, 3000])
+    N = rng.choice([1, 2, 3, 6, 18])
+    w = synth.Workload(f"rand_f8_{case}", B=B, Q=K * g, K=K, dk=128, dv=128, n_shards=N, scale=1 / math.sqrt(128), seed=8000 + case,
+                       seq_len=S, fp8=True)
+    inp = synth.make_inputs(w, "cuda")
+    inp.lens = torch.tensor(_lens(rng, B, S), dtype=torch.int32)
+    run_f8(hx, oracle, w, inp, N, split_tokens=_split(rng, 128))
 
 
 @pytest.mark.parametrize("case", range(18))

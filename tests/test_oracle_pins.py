@@ -359,6 +359,37 @@ def test_fp8_attention_against_dequantised_bf16_free_reference(oracle):
         assert np.abs(lse[b] - torch.logsumexp(s, -1).numpy()).max() <= 1e-12
 
 
+def test_fp8_attention_with_separate_value_rows_and_kv_heads(oracle):
+    """The GQA fp8 cache: separate key and value code rows per kv head, ONE scale per (sequence, kv head, token)
+    that both rows share; query head h reads kv head h // (Q / K).  Against torch float64 softmax on
+    library-dequantised values."""
+    rng = np.random.default_rng(151)
+    B, Q, K, dk, dv, S = 2, 6, 3, 16, 8, 23
+    q, qf = bf16_bits(rng.standard_normal((B, Q, dk)))
+    kc = rng.integers(0, 256, size=(B, K, S, dk)).astype(np.uint8)
+    vc = rng.integers(0, 256, size=(B, K, S, dv)).astype(np.uint8)
+    kc[(kc & 0x7F) == 0x7F] = 0x3A                                         # no NaN codes
+    vc[(vc & 0x7F) == 0x7F] = 0x41
+    sc = rng.uniform(0.001, 0.02, size=(B, K, S)).astype(np.float32)
+    lens = np.array([S, S - 9], np.int32)
+    scale = 0.9
+    o, lse = oracle.attention(q, kc, vc, lens, scale, kv_heads=K, kv_scale=sc)
+    f = torch.as_tensor(sc).to(torch.float64)[..., None]
+    kd = torch.as_tensor(kc).view(torch.float8_e4m3fn).to(torch.float64) * f
+    vd = torch.as_tensor(vc).view(torch.float8_e4m3fn).to(torch.float64) * f
+    for b in range(B):
+        L = lens[b]
+        for h in range(Q):
+            kh = h // (Q // K)
+            s = torch.as_tensor(qf[b, h]) @ kd[b, kh, :L].T * scale
+            ref = torch.softmax(s, -1) @ vd[b, kh, :L]
+            assert np.abs(o[b, h] - ref.numpy()).max() <= 1e-12
+            assert abs(lse[b, h] - torch.logsumexp(s, -1).item()) <= 1e-12
+    # the value rows really are their own array: swapping them for the key rows' first dv entries changes O
+    o2, _ = oracle.attention(q, kc, np.ascontiguousarray(kc[..., :dv]), lens, scale, kv_heads=K, kv_scale=sc)
+    assert np.abs(o2 - o).max() > 1e-3
+
+
 # ---------------------------------------------------------------- P13 combine alone
 def test_combine_closed_forms(oracle):
     rng = np.random.default_rng(16)
