@@ -239,6 +239,23 @@ def test_gqa_share_mxfp4_full(hx, oracle):
     assert d <= SHARD_VS_UNSHARDED and (lse4 - lse).abs().max().item() <= 1e-5
 
 
+def test_gqa_share_fp8_full(hx, oracle):
+    """The e4m3-KV share (2M-token context at KVP=8): whole sequences against the oracle, and the same cache cut
+    into 4 shards against the unsharded run."""
+    w = synth.WORKLOADS["gqa_share_fp8"]
+    inp = synth.make_inputs(w, "cuda")
+    o, lse, _, _, _ = decode(hx, w, inp, 1)
+    assert torch.isfinite(o).all() and torch.isfinite(lse).all()
+    rows, o_ref, lse_ref = oracle_sequences(oracle, w, inp, range(w.B))           # the whole output: 256 rows
+    assert len(rows) == w.B * w.Q
+    check_rows(o, lse, o_ref, lse_ref, rows, "gqa_share_fp8")
+    check_as_bench(hx, oracle, w, inp, 1, o, lse, o_ref, lse_ref, rows, "gqa_share_fp8")
+    o4, lse4, _, _, _ = decode(hx, w, inp, 4)
+    d = (o4 - o).abs().max().item()
+    print(f"gqa_share_fp8: 4 shards vs unsharded max-abs {d:.3e}")
+    assert d <= SHARD_VS_UNSHARDED and (lse4 - lse).abs().max().item() <= 1e-5
+
+
 def test_mla_share_mxfp4_full(hx, oracle):
     """The MXFP4 latent share: sampled rows against the oracle, and the same cache cut into 8 shards
     against the unsharded run."""
