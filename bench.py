@@ -10,7 +10,8 @@ workload's shapes) divided by the step time.
 
 The headline (`value`, `config`, `roofline`, `cpu_baseline`) is the workload given by --workload.  With
 the default workload the same line also carries, under `configs`, one entry per remaining benchmark
-configuration (same K and W, each with its own roofline and a bounded cpu_baseline) and, under
+configuration (same K and W, each with its own roofline and a bounded cpu_baseline), under `kv_formats`
+the same for the GQA / MLA shares with an e4m3 or MXFP4 cache, and, under
 `ceilings`, what the part sustains for a bare streaming read with the GQA launch shape and for an
 LDS-fed MFMA loop (the two probes of the library) -- so that every fraction quoted anywhere is on
 the clock of this one run.
@@ -31,6 +32,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 and fp16
 HEADLINE = "gqa_share"
 OTHER_CONFIGS = ["tiny_gqa", "mla_share", "gqa_full", "mla_fp8_ragged"]   # the remaining benchmark configurations
+# the GQA and MLA shares with the KV cache in the low-precision formats the library also streams (Sec. 3: FP4 KV states)
+KV_FORMATS = ["gqa_share_fp8", "gqa_share_mxfp4", "mla_share_mxfp4"]
 
 
 def kv_bytes_per_step(w, lens) -> int:
@@ -412,6 +415,11 @@ def main():
             torch.cuda.empty_cache()
             # a smaller oracle sample per extra configuration keeps the whole run within a couple of minutes
             out["configs"].append(measure(name, args, budget_macs=4e10))
+        out["kv_formats"] = []
+        for name in KV_FORMATS:
+            gc.collect()
+            torch.cuda.empty_cache()
+            out["kv_formats"].append(measure(name, args, budget_macs=2e10))
         gc.collect()
         torch.cuda.empty_cache()
         out["ceilings"] = ceilings(args)
