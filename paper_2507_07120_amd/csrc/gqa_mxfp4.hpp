@@ -4,8 +4,9 @@
 // of codes plus 4 scale bytes, 3.8x fewer HBM bytes per token than bf16.
 //
 // Same decomposition and the same arithmetic after dequantisation as the bf16 kernel
-// (gqa_decode.hpp): one workgroup of 4 waves per (shard, sequence, kv head, split), waves take
-// alternating 32-token blocks, scores / integer-reference softmax / P.V on 16x16x32 bf16 MFMAs.
+// (gqa_decode.hpp): a workgroup of 4 waves serves runs of consecutive tokens of (shard, sequence, kv head,
+// head tile) rows, the waves take alternating 32-token blocks, scores / integer-reference softmax / P.V run on
+// 16x16x32 bf16 MFMAs.
 // What differs is how the operands get into registers:
 //   K   lane (r = token, kc) loads the 16 bytes holding dims 32kc .. 32kc+31 of its token: exactly
 //       one scale block.  The score contraction does not care about the order of the dims as long
@@ -20,8 +21,8 @@
 //   scales  K: one dword (the 4 block scales of a token) per lane, byte kc selected; V: two 16-byte
 //       loads cover the 4 scales of the lane's 8 tokens, byte r/4 selected; the code becomes the float's
 //       exponent field (codes 1..254).
-// A block is only 4.3 KB per wave, so three waves per SIMD are kept resident (at most 168 registers,
-// two raw blocks of 26 registers each); loads are never issued under a condition of their own (the
+// A block is only 4.3 KB per wave, so three waves per SIMD are kept resident (at most 168 registers;
+// the kernel takes 162, two raw blocks of 26 registers each among them); loads are never issued under a condition of their own (the
 // index is clamped instead), which keeps the compiler's wait counts exact.  The kernel is bound by
 // vector-ALU issue, not by HBM, so full blocks are fetched with buffer loads whose addresses cost no
 // vector instruction (Mx4Streams).
