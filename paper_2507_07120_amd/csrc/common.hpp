@@ -67,13 +67,14 @@ struct AttnArgs {
     float scale_log2e;    // softmax scale * log2(e)
     int32_t n_shards;
     // streaming GQA launches (every workgroup plans its own share, stream_self_plan): what the merge needs later
-    int64_t* prefix_out;  // [pairs + 1] row tiles before pair p, written by workgroup 0
-    int2* row_rec;        // [rows] first and last workgroup that hold tiles of a row, written by those workgroups
+    int64_t* prefix_out;  // [pairs + 1] row tiles of one head tile before pair p, written by workgroup 0
+    int2* row_rec;        // [rows] first and last seat (StreamSeat::seat) that hold tiles of a row, written by those workgroups
     // MLA launches that are cut evenly over the token stream (stream_plan_kernel): the (shard, sequence) pairs of
     // the launch, pair = shard * B + sequence, laid end to end in 32-token tiles
     const int64_t* tile_prefix;   // [pairs + 1] tiles before pair p; [pairs] = all tiles.  NULL: runs by workgroup id
     const int32_t* wg_first_pair; // [n_wg] the pair that holds a workgroup's first tile
     int32_t n_wg;                 // workgroups of the launch
+    int32_t n_base;               // streaming GQA launches: workgroups per head tile (n_wg / head_tiles, see StreamSeat)
     int32_t rec_base;             // first record of this launch; the run of workgroup g inside pair p writes record rec_base + g + p
     ShardDev shard[kMaxLaunchShards];
 };
@@ -134,6 +135,16 @@ __device__ __forceinline__ void shard_range(const ShardDev& sh, int b, int& len,
 {
     const int64_t base = sh.tok_off ? sh.tok_off[b] : 0;
     shard_range_of(sh.len[b], base, sh.kvp_n, sh.kvp_i, len, first_row);
+}
+
+// A load of the K/V stream.  NT: non-temporal -- every byte is used once (measured on MI355X: plain loads of a 1 GiB
+// stream top out near 6.2 TB/s, non-temporal ones reach 7.0 TB/s).  Launches whose head tiles share their reads
+// through the L2 (StreamSeat) load the ordinary way.
+template <bool NT, class T>
+__device__ __forceinline__ T stream_load(const T* p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
 }
 
 __device__ __forceinline__ uint32_t as_u32(float x) { return __builtin_bit_cast(uint32_t, x); }
@@ -197,10 +208,45 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x)
     return x;
 }
 
+// Where a workgroup of a streaming GQA launch sits.  A kv head with more than 16 query heads has several head
+// tiles, and every one of them needs the kv head's keys and values: the launch then consists of head_tiles equal
+// sets of n_base workgroups, set t serving head tile t of every row, all sets cut in exactly the same way -- so the
+// head_tiles workgroups with the same index `wg` inside their sets read the same tokens at the same time.  With
+// n_base a multiple of 8 their workgroup ids are 8 apart, which puts them on the same XCD (consecutive ids go round
+// robin over the 8 XCDs): one of them fetches a key from HBM, the others find it in that XCD's L2 (these launches
+// use ordinary loads, not non-temporal ones).  seat = ht * n_base + wg numbers the workgroups in the order their
+// rows have in the record arrays.
+struct StreamSeat {
+    int wg, n_wg;            // index inside the set, workgroups of a set
+    int ht, seat;
+};
+
+__device__ __forceinline__ StreamSeat stream_seat(const AttnArgs& a)
+{
+    StreamSeat s;
+    s.wg = (int)blockIdx.x;
+    s.n_wg = a.n_wg;
+    s.ht = 0;
+    if (a.head_tiles > 1) {
+        s.n_wg = a.n_base;
+        if ((a.n_base & 7) == 0) {
+            const int grp = (int)blockIdx.x / (8 * a.head_tiles), in = (int)blockIdx.x - grp * 8 * a.head_tiles;
+            s.ht = in >> 3;
+            s.wg = grp * 8 + (in & 7);
+        } else {
+            s.ht = (int)blockIdx.x / a.n_base;
+            s.wg = (int)blockIdx.x - s.ht * a.n_base;
+        }
+    }
+    s.seat = s.ht * s.n_wg + s.wg;
+    return s;
+}
+
 // The same even cut, planned by every workgroup for itself (the streaming GQA kernels: a planning launch of its
-// own would cost them 5 % of a step).  The launch's rows -- (shard, sequence, kv head, head tile), rows_per_pair of
+// own would cost them 5 % of a step).  The rows of one head tile -- (shard, sequence, kv head), rows_per_pair of
 // them per (shard, sequence) pair, all as long as the pair's slice -- are laid end to end in tiles of tile_tokens
-// tokens, and workgroup g of n_wg takes the row tiles [g T / n_wg, (g + 1) T / n_wg).  Every workgroup reads all
+// tokens, and workgroup g of the n_wg that serve the head tile (StreamSeat) takes the row tiles
+// [g T / n_wg, (g + 1) T / n_wg).  Every workgroup reads all
 // lengths (one or a few per thread, in parallel: the one dependent memory round trip a workgroup needs anyway
 // before it knows where its keys are), scans them, and finds the pair that holds its first tile.  All results
 // are the same in every lane.
@@ -211,6 +257,8 @@ struct StreamCursor {
     int64_t pair_tiles;      // ... the tiles of one of its rows
     int64_t first_row;       // ... the row of its slice's first token in the cache
     int32_t len;             // ... and the slice's length in tokens
+    int32_t ht, seat;        // the workgroup's head tile and seat (StreamSeat)
+    int32_t row0;            // index of the head tile's first row among the launch's rows
 };
 
 __device__ __forceinline__ int64_t uniform_i64(int64_t x)
@@ -229,6 +277,10 @@ __device__ __forceinline__ bool stream_self_plan(const AttnArgs& a, int tile_tok
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pairs = a.n_shards * a.B;
+    const StreamSeat seat = stream_seat(a);
+    c.ht = seat.ht;
+    c.seat = seat.seat;
+    c.row0 = seat.ht * pairs * rows_per_pair;
     if (__builtin_expect(pairs <= 64, 1)) {
         // The usual case: every wave plans for itself, lane p looking at pair p -- no shared memory, no barrier.
         // The loops run over uniform indices, so that the shards' pointers come from scalar loads of the kernel
@@ -271,9 +323,9 @@ __device__ __forceinline__ bool stream_self_plan(const AttnArgs& a, int tile_tok
                 if (sh.out_off && b >= 0 && b < a.B) { sh.out_off[b] = first_row; sh.out_len[b] = len; }
             }
         }
-        const StreamDeal deal = stream_deal(T, a.n_wg);
-        c.cur = deal.start(blockIdx.x);
-        c.end = deal.start(blockIdx.x + 1);
+        const StreamDeal deal = stream_deal(T, seat.n_wg);
+        c.cur = deal.start(seat.wg);
+        c.end = deal.start(seat.wg + 1);
         if (c.cur >= c.end) return false;
         // exactly one lane's pair holds tile `cur` (0 <= cur < T)
         const uint64_t holds = __ballot(lane < pairs && mine > 0 && excl <= c.cur && c.cur < excl + mine);
@@ -335,9 +387,9 @@ __device__ __forceinline__ bool stream_self_plan(const AttnArgs& a, int tile_tok
         }
         if (tid == 0 && prefix_out) prefix_out[pairs] = T;
     }
-    const StreamDeal deal = stream_deal(T, a.n_wg);
-    c.cur = deal.start(blockIdx.x);
-    c.end = deal.start(blockIdx.x + 1);
+    const StreamDeal deal = stream_deal(T, seat.n_wg);
+    c.cur = deal.start(seat.wg);
+    c.end = deal.start(seat.wg + 1);
     if (c.cur >= c.end) return false;
     // the thread whose pairs hold tile `cur` tells the others which pair it is, where its rows start and how long they are
     int64_t* found = scratch + THREADS / 64;
@@ -371,8 +423,9 @@ __device__ __forceinline__ bool stream_self_plan(const AttnArgs& a, int tile_tok
 struct StreamRun {
     int si, b, kh, ht;
     int t0, t1_cap;          // t1_cap may lie beyond the slice's end (whole tiles)
-    int slot;                // record slot of the run: workgroup + row index
-    int row;                 // row index within the launch
+    int slot;                // record slot of the run: seat + row index
+    int row;                 // row index within the launch: (head tile, pair, kv head)
+    int seat;                // the workgroup's seat
     bool first, last;        // the run holds the row's first / last tile
 };
 
@@ -393,8 +446,8 @@ __device__ __forceinline__ bool stream_next_run(const AttnArgs& a, StreamCursor&
         c.first_row = uniform_i64(first_row);
         c.pair_tiles = (int64_t)((max(c.len, 0) + tile_tokens - 1) / tile_tokens);
     }
-    // row within the pair: kv head, head tile (this sits on the way to a workgroup's first load: divisions only
-    // where they are needed, and in 32 bits where the numbers allow)
+    // row within the pair = kv head (this sits on the way to a workgroup's first load: divisions only where they
+    // are needed, and in 32 bits where the numbers allow)
     const int64_t into = c.cur - c.pair_lo;
     int rr = 0;
     if (into >= c.pair_tiles) rr = __builtin_expect((into | c.pair_tiles) >> 31 != 0, 0) ? (int)(into / c.pair_tiles) : (int)((uint32_t)into / (uint32_t)c.pair_tiles);
@@ -402,12 +455,13 @@ __device__ __forceinline__ bool stream_next_run(const AttnArgs& a, StreamCursor&
     const int64_t seg_end = min(c.end, row_lo + c.pair_tiles);
     r.si = a.n_shards == 1 ? 0 : c.pair / a.B;
     r.b = c.pair - r.si * a.B;
-    r.kh = a.head_tiles == 1 ? rr : rr / a.head_tiles;
-    r.ht = rr - r.kh * a.head_tiles;
+    r.kh = rr;
+    r.ht = c.ht;
     r.t0 = (int)(c.cur - row_lo) * tile_tokens;
     r.t1_cap = (int)(seg_end - row_lo) * tile_tokens;
-    r.row = c.pair * rows_per_pair + rr;
-    r.slot = a.rec_base + (int)blockIdx.x + r.row;
+    r.row = c.row0 + c.pair * rows_per_pair + rr;
+    r.seat = c.seat;
+    r.slot = a.rec_base + c.seat + r.row;
     r.first = c.cur == row_lo;
     r.last = seg_end == row_lo + c.pair_tiles;
     c.cur = seg_end;

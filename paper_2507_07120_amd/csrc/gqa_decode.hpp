@@ -43,26 +43,26 @@ struct GqaBlock {
     uint32_t v[8][GqaCfg<D>::VDW];       // 8 tokens x CPL columns
 };
 
-template <int N>
+template <int N, bool NT>
 __device__ __forceinline__ void load_dwords(uint32_t (&dst)[N], const char* p)
 {
     if constexpr (N == 4) {
-        u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        u32x4 t = stream_load<NT>(reinterpret_cast<const u32x4*>(p));
         dst[0] = t.x; dst[1] = t.y; dst[2] = t.z; dst[3] = t.w;
     } else if constexpr (N == 2) {
-        u32x2 t = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+        u32x2 t = stream_load<NT>(reinterpret_cast<const u32x2*>(p));
         dst[0] = t.x; dst[1] = t.y;
     } else {
         static_assert(N == 2 || N == 4, "unsupported value width");
     }
 }
 
-// K/V are read exactly once, so every load is non-temporal: measured on MI355X, plain loads of a
-// 1 GiB stream top out near 6.2 TB/s while non-temporal ones reach 7.0 TB/s.
+// K/V are read exactly once, so the loads are non-temporal (NT) -- unless the launch has several head tiles per
+// kv head, whose workgroups share their reads through the L2 (StreamSeat).
 // Loads the block of 32 tokens starting at shard token `tb`.  kblk / vblk point at the block's
 // first token row (wave-uniform); tokens >= t1 are redirected to the last valid row so that every
 // address stays inside the shard (their weights are forced to zero later).
-template <int D, bool TAIL>
+template <int D, bool TAIL, bool NT>
 __device__ __forceinline__ void gqa_load_block(GqaBlock<D>& blk, const char* kblk, const char* vblk,
                                                uint32_t k_row_bytes, uint32_t v_row_bytes,
                                                int r, int kc, int n_valid)
@@ -75,14 +75,14 @@ __device__ __forceinline__ void gqa_load_block(GqaBlock<D>& blk, const char* kbl
         const char* p = kblk + (uint32_t)tok * k_row_bytes + (uint32_t)kc * 16u;
 #pragma unroll
         for (int s = 0; s < C::KS; s++)
-            blk.k[a][s] = __builtin_bit_cast(bf16x8, __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + s * 64)));
+            blk.k[a][s] = __builtin_bit_cast(bf16x8, stream_load<NT>(reinterpret_cast<const u32x4*>(p + s * 64)));
     }
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         int tok = (j >> 2) * 16 + kc * 4 + (j & 3);
         if (TAIL) tok = min(tok, n_valid - 1);
         const char* p = vblk + (uint32_t)tok * v_row_bytes + (uint32_t)r * (C::CPL * 2);
-        load_dwords<C::VDW>(blk.v[j], p);
+        load_dwords<C::VDW, NT>(blk.v[j], p);
     }
 }
 
@@ -260,20 +260,23 @@ constexpr int kGqaTile = 128;      // tokens per planning tile of the streaming 
 __device__ __forceinline__ void gqa_note_run(const AttnArgs& a, const StreamRun& run)
 {
     if (threadIdx.x == 0) {
-        if (run.first) a.row_rec[run.row].x = (int)blockIdx.x;
-        if (run.last) a.row_rec[run.row].y = (int)blockIdx.x;
+        if (run.first) a.row_rec[run.row].x = run.seat;
+        if (run.last) a.row_rec[run.row].y = run.seat;
     }
 }
 
-template <int D>
+// SHARED: the launch has several head tiles per kv head (more than 16 query heads share a kv head); their
+// workgroups sit side by side (StreamSeat) and load the ordinary way.
+template <int D, bool SHARED>
 __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
 {
     using C = GqaCfg<D>;
+    constexpr bool NT = !SHARED;
 
-    // This workgroup's share of the launch: an equal range of the launch's rows laid end to end (stream_self_plan),
+    // This workgroup's share of the launch: an equal range of its head tile's rows laid end to end (stream_self_plan),
     // served run by run -- one run, and one split record, per row the range touches.
     __shared__ int64_t plan_scratch[256 / 64 + 5];
-    const int rows_per_pair = a.K * a.head_tiles;
+    const int rows_per_pair = a.K;
     StreamCursor cursor;
     if (!stream_self_plan<256>(a, kGqaTile, rows_per_pair, plan_scratch, a.prefix_out, cursor)) return;
     StreamRun run;
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
     const int nw = n_full > wave ? (n_full - wave + 3) / 4 : 0;
     auto kptr = [&](int i) { return kbase + (size_t)(wave + 4 * i) * k_blk_bytes; };
     auto vptr = [&](int i) { return vbase + (size_t)(wave + 4 * i) * v_blk_bytes; };
-    if (nw > 0) gqa_load_block<D, false>(b0, kptr(0), vptr(0), k_row_bytes, v_row_bytes, r, kc, C::TB);
+    if (nw > 0) gqa_load_block<D, false, NT>(b0, kptr(0), vptr(0), k_row_bytes, v_row_bytes, r, kc, C::TB);
 
     // (fetched after the first K/V block is on its way: the stream does not depend on Q)
     // Q as the score MFMA's B operand: lane (r,kc) holds head r, dims s*32 + kc*8 .. +8
@@ -339,13 +342,13 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
     if (nw > 0) {
         int i = 0;
         for (; i + 2 < nw; i += 2) {
-            gqa_load_block<D, false>(b1, kptr(i + 1), vptr(i + 1), k_row_bytes, v_row_bytes, r, kc, C::TB);
+            gqa_load_block<D, false, NT>(b1, kptr(i + 1), vptr(i + 1), k_row_bytes, v_row_bytes, r, kc, C::TB);
             gqa_compute_block<D, false>(st, b0, qb, a.scale_log2e, kc, C::TB);
-            gqa_load_block<D, false>(b0, kptr(i + 2), vptr(i + 2), k_row_bytes, v_row_bytes, r, kc, C::TB);
+            gqa_load_block<D, false, NT>(b0, kptr(i + 2), vptr(i + 2), k_row_bytes, v_row_bytes, r, kc, C::TB);
             gqa_compute_block<D, false>(st, b1, qb, a.scale_log2e, kc, C::TB);
         }
         if (i + 1 < nw) {
-            gqa_load_block<D, false>(b1, kptr(i + 1), vptr(i + 1), k_row_bytes, v_row_bytes, r, kc, C::TB);
+            gqa_load_block<D, false, NT>(b1, kptr(i + 1), vptr(i + 1), k_row_bytes, v_row_bytes, r, kc, C::TB);
             gqa_compute_block<D, false>(st, b0, qb, a.scale_log2e, kc, C::TB);
             gqa_compute_block<D, false>(st, b1, qb, a.scale_log2e, kc, C::TB);
         } else {
@@ -355,7 +358,7 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
     // the ragged last block, if any, belongs to wave (n_full % 4)
     if (n_blk > n_full && (n_full & 3) == wave) {
         const int nv = n_tok - n_full * C::TB;
-        gqa_load_block<D, true>(b0, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, k_row_bytes, v_row_bytes, r, kc, nv);
+        gqa_load_block<D, true, NT>(b0, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, k_row_bytes, v_row_bytes, r, kc, nv);
         gqa_compute_block<D, true>(st, b0, qb, a.scale_log2e, kc, nv);
     }
 

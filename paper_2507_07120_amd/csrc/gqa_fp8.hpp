@@ -34,7 +34,7 @@ struct F8Raw {
 
 // Loads the block of 32 tokens whose first rows are kblk / vblk (codes, row strides in bytes) and whose first scale
 // is sblk.  TAIL: tokens >= n_valid are redirected to the last valid row (their weights are zero later).
-template <bool TAIL>
+template <bool TAIL, bool NT>
 __device__ __forceinline__ void f8_load_block(F8Raw& raw, const char* kblk, const char* vblk, const float* sblk,
                                               uint32_t k_row_bytes, uint32_t v_row_bytes, int r, int kc, int n_valid)
 {
@@ -43,24 +43,28 @@ __device__ __forceinline__ void f8_load_block(F8Raw& raw, const char* kblk, cons
         int tok = a * 16 + r;
         if (TAIL) tok = min(tok, n_valid - 1);
         const char* p = kblk + (uint32_t)((uint32_t)tok * k_row_bytes + (uint32_t)kc * 32u);
-        raw.k[a][0] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-        raw.k[a][1] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + 16));
+        raw.k[a][0] = stream_load<NT>(reinterpret_cast<const u32x4*>(p));
+        raw.k[a][1] = stream_load<NT>(reinterpret_cast<const u32x4*>(p + 16));
     }
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         int tok = (j >> 2) * 16 + kc * 4 + (j & 3);
         if (TAIL) tok = min(tok, n_valid - 1);
-        raw.v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(vblk + (uint32_t)((uint32_t)tok * v_row_bytes + (uint32_t)r * 8u)));
+        raw.v[j] = stream_load<NT>(reinterpret_cast<const u32x2*>(vblk + (uint32_t)((uint32_t)tok * v_row_bytes + (uint32_t)r * 8u)));
     }
     if (TAIL) {
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const int tok = min((j >> 2) * 16 + kc * 4 + (j & 3), n_valid - 1);
-            raw.fs[j >> 2][j & 3] = __builtin_nontemporal_load(sblk + tok);
+            raw.fs[j >> 2][j & 3] = stream_load<NT>(sblk + tok);
         }
     } else {
 #pragma unroll
-        for (int a = 0; a < 2; a++) raw.fs[a] = __builtin_nontemporal_load(reinterpret_cast<const f8_f32x4_a4*>(sblk + a * 16 + kc * 4));
+        for (int a = 0; a < 2; a++) {
+            const f8_f32x4_a4* sp = reinterpret_cast<const f8_f32x4_a4*>(sblk + a * 16 + kc * 4);     // (dword aligned only)
+            if constexpr (NT) raw.fs[a] = __builtin_nontemporal_load(sp);
+            else raw.fs[a] = *sp;
+        }
     }
 }
 
@@ -97,15 +101,18 @@ __device__ __forceinline__ void f8_compute_block(GqaState<128>& st, const F8Raw&
         qb, scale_log2e, kc, n_valid, fs);
 }
 
+// SHARED: several head tiles per kv head, side by side (StreamSeat), ordinary loads.
+template <bool SHARED>
 __global__ __launch_bounds__(256, 2) void gqa_fp8_kernel(const AttnArgs a)
 {
     constexpr int D = 128;
+    constexpr bool NT = !SHARED;
     using C = GqaCfg<D>;
 
-    // This workgroup's share of the launch: an equal range of the launch's rows laid end to end (stream_self_plan),
+    // This workgroup's share of the launch: an equal range of its head tile's rows laid end to end (stream_self_plan),
     // served run by run -- one run, and one split record, per row the range touches.
     __shared__ int64_t plan_scratch[256 / 64 + 5];
-    const int rows_per_pair = a.K * a.head_tiles;
+    const int rows_per_pair = a.K;
     StreamCursor cursor;
     if (!stream_self_plan<256>(a, kGqaTile, rows_per_pair, plan_scratch, a.prefix_out, cursor)) return;
     StreamRun run;
@@ -150,7 +157,7 @@ __global__ __launch_bounds__(256, 2) void gqa_fp8_kernel(const AttnArgs a)
     // stay exact): a prefetch past the end re-reads the wave's last block
     auto load = [&](F8Raw& raw, int i) {
         const size_t blk = (size_t)(wave + 4 * min(i, nw - 1));
-        f8_load_block<false>(raw, kbase + blk * k_blk_bytes, vbase + blk * v_blk_bytes, sbase + blk * C::TB, k_row_bytes, v_row_bytes, r, kc, C::TB);
+        f8_load_block<false, NT>(raw, kbase + blk * k_blk_bytes, vbase + blk * v_blk_bytes, sbase + blk * C::TB, k_row_bytes, v_row_bytes, r, kc, C::TB);
     };
     F8Raw r0, r1;
     if (nw > 0) load(r0, 0);
@@ -181,7 +188,7 @@ __global__ __launch_bounds__(256, 2) void gqa_fp8_kernel(const AttnArgs a)
     // the ragged last block, if any, belongs to wave (n_full % 4)
     if (n_blk > n_full && (n_full & 3) == wave) {
         const int nv = n_tok - n_full * C::TB;
-        f8_load_block<true>(r0, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, sbase + (size_t)n_full * C::TB, k_row_bytes, v_row_bytes, r, kc, nv);
+        f8_load_block<true, NT>(r0, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, sbase + (size_t)n_full * C::TB, k_row_bytes, v_row_bytes, r, kc, nv);
         f8_compute_block<true>(st, r0, qb, a.scale_log2e, kc, nv);
     }
 

@@ -46,7 +46,7 @@ constexpr int kMxScaleRow = 4; // scale bytes per row
 
 // Loads the block of 32 tokens whose first rows are kblk / vblk (codes) and ksc / vsc (scales).
 // TAIL: tokens >= n_valid are redirected to the last valid row (their weights are zero later).
-template <bool TAIL>
+template <bool TAIL, bool NT>
 __device__ __forceinline__ void mx4_load_block(Mx4Raw& raw, const char* kblk, const char* vblk, const char* ksc, const char* vsc,
                                                uint32_t k_row_bytes, uint32_t v_row_bytes, int r, int kc, int n_valid)
 {
@@ -54,26 +54,29 @@ __device__ __forceinline__ void mx4_load_block(Mx4Raw& raw, const char* kblk, co
     for (int a = 0; a < 2; a++) {
         int tok = a * 16 + r;
         if (TAIL) tok = min(tok, n_valid - 1);
-        raw.k[a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kblk + (uint32_t)((uint32_t)tok * k_row_bytes + (uint32_t)kc * 16u)));
-        raw.ks[a] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(ksc + (uint32_t)tok * (k_row_bytes / 16u)));
+        raw.k[a] = stream_load<NT>(reinterpret_cast<const u32x4*>(kblk + (uint32_t)((uint32_t)tok * k_row_bytes + (uint32_t)kc * 16u)));
+        raw.ks[a] = stream_load<NT>(reinterpret_cast<const uint32_t*>(ksc + (uint32_t)tok * (k_row_bytes / 16u)));
     }
 #pragma unroll
     for (int j = 0; j < 8; j++) {
         int tok = (j >> 2) * 16 + kc * 4 + (j & 3);
         if (TAIL) tok = min(tok, n_valid - 1);
-        raw.v[j] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(vblk + (uint32_t)((uint32_t)tok * v_row_bytes + (uint32_t)r * 4u)));
+        raw.v[j] = stream_load<NT>(reinterpret_cast<const uint32_t*>(vblk + (uint32_t)((uint32_t)tok * v_row_bytes + (uint32_t)r * 4u)));
     }
     if (TAIL) {
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             const int tok = min((j >> 2) * 16 + kc * 4 + (j & 3), n_valid - 1);
-            raw.vs[j >> 2][j & 3] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(vsc + (uint32_t)tok * (v_row_bytes / 16u)));
+            raw.vs[j >> 2][j & 3] = stream_load<NT>(reinterpret_cast<const uint32_t*>(vsc + (uint32_t)tok * (v_row_bytes / 16u)));
         }
     } else {
         // rows of a value block that are contiguous in memory have contiguous scale rows
 #pragma unroll
-        for (int a = 0; a < 2; a++)
-            raw.vs[a] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_a4*>(vsc + (uint32_t)(a * 16 + kc * 4) * (v_row_bytes / 16u)));
+        for (int a = 0; a < 2; a++) {
+            const u32x4_a4* sp = reinterpret_cast<const u32x4_a4*>(vsc + (uint32_t)(a * 16 + kc * 4) * (v_row_bytes / 16u));     // (dword aligned only)
+            if constexpr (NT) raw.vs[a] = __builtin_nontemporal_load(sp);
+            else raw.vs[a] = *sp;
+        }
     }
 }
 
@@ -103,9 +106,10 @@ struct Mx4Streams {
     }
 
     // the full block of 32 tokens that starts `tok` rows into the split (uniform)
+    template <bool NONTEMPORAL>
     __device__ __forceinline__ void load(Mx4Raw& raw, uint32_t tok) const
     {
-        constexpr int NT = 2;                             // non-temporal: every byte is used once
+        constexpr int NT = NONTEMPORAL ? 2 : 0;           // cache policy bits of the buffer load: 2 = non-temporal
         const uint32_t sk = tok * k_row_bytes, sv = tok * v_row_bytes, sks = tok * (k_row_bytes / 16u), svs = tok * (v_row_bytes / 16u);
 #pragma unroll
         for (int a = 0; a < 2; a++) {
@@ -170,9 +174,12 @@ __device__ __forceinline__ void mx4_compute_block(GqaState<128>& st, const Mx4Ra
         qb, scale_log2e, kc, n_valid);
 }
 
+// SHARED: several head tiles per kv head, side by side (StreamSeat), ordinary loads.
+template <bool SHARED>
 __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
 {
     constexpr int D = 128;
+    constexpr bool NT = !SHARED;
     using C = GqaCfg<D>;
     const int tid = threadIdx.x;
     // the wave index as a scalar: block addresses then stay in scalar registers and the loads take a
@@ -180,10 +187,10 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 15, kc = lane >> 4;
 
-    // This workgroup's share of the launch: an equal range of the launch's rows laid end to end (stream_self_plan),
+    // This workgroup's share of the launch: an equal range of its head tile's rows laid end to end (stream_self_plan),
     // served run by run -- one run, and one split record, per row the range touches.
     __shared__ int64_t plan_scratch[256 / 64 + 5];
-    const int rows_per_pair = a.K * a.head_tiles;
+    const int rows_per_pair = a.K;
     StreamCursor cursor;
     if (!stream_self_plan<256>(a, kGqaTile, rows_per_pair, plan_scratch, a.prefix_out, cursor)) return;
     StreamRun run;
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
     // block i of this wave; the index is clamped, so a prefetch past the end re-reads the last block
     Mx4Streams in;
     in.init(kbase, vbase, ksbase, vsbase, k_row_bytes, v_row_bytes, r, kc);
-    auto load = [&](Mx4Raw& raw, int i) { in.load(raw, (uint32_t)(wave + 4 * min(i, nw - 1)) * C::TB); };
+    auto load = [&](Mx4Raw& raw, int i) { in.template load<NT>(raw, (uint32_t)(wave + 4 * min(i, nw - 1)) * C::TB); };
     Mx4Raw r0, r1;
     if (nw > 0) load(r0, 0);
 
@@ -255,7 +262,7 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
     if (n_blk > n_full && (n_full & 3) == wave) {
         const int nv = n_tok - n_full * C::TB;
         const size_t blk0 = (size_t)n_full * C::TB;
-        mx4_load_block<true>(r0, kbase + blk0 * k_row_bytes, vbase + blk0 * v_row_bytes, ksbase + blk0 * (k_row_bytes / 16u),
+        mx4_load_block<true, NT>(r0, kbase + blk0 * k_row_bytes, vbase + blk0 * v_row_bytes, ksbase + blk0 * (k_row_bytes / 16u),
                              vsbase + blk0 * (v_row_bytes / 16u), k_row_bytes, v_row_bytes, r, kc, nv);
         mx4_compute_block<true>(st, r0, qb, a.scale_log2e, r, kc, nv);
     }

@@ -149,12 +149,13 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
         if (plan.stream) {
             // the launch is cut evenly over the tokens its sequences have on the device: by a planning kernel for MLA
             // (one workgroup per CU, each run worth a set-up), by every workgroup for itself in the streaming kernels
-            const int64_t n_wg = stream_workgroups(p, plan.path, row_tokens, row_tiles);
+            const int64_t n_wg = stream_workgroups(p, plan.path, mla ? 1 : plan.head_tiles, row_tokens, row_tiles);
             const int64_t pairs = (int64_t)cnt * p->batch, rows = pairs * rows_per_pair;
             char* maps = ws.maps + map_off;
             map_off += stream_map_bytes(plan.path, pairs, rows, n_wg);
             int64_t* prefix = reinterpret_cast<int64_t*>(maps);
             a.n_wg = (int32_t)n_wg;
+            a.n_base = (int32_t)(n_wg / (mla ? 1 : plan.head_tiles));
             a.rec_base = rec_base;
             m.tile_prefix = prefix;
             m.n_wg = a.n_wg;
@@ -178,17 +179,22 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
         }
         if (ev.start && s0 == 0 && hipEventRecord(ev.start, stream) != hipSuccess) return HELIX_ERR_LAUNCH;
         switch (plan.path) {
+            // (several head tiles per kv head: the kernels whose workgroups share their reads through the L2)
             case Path::Gqa64:
-                hipLaunchKernelGGL((gqa_decode_kernel<64>), dim3((unsigned)units), dim3(256), 0, stream, a);
+                if (plan.head_tiles > 1) hipLaunchKernelGGL((gqa_decode_kernel<64, true>), dim3((unsigned)units), dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL((gqa_decode_kernel<64, false>), dim3((unsigned)units), dim3(256), 0, stream, a);
                 break;
             case Path::Gqa128:
-                hipLaunchKernelGGL((gqa_decode_kernel<128>), dim3((unsigned)units), dim3(256), 0, stream, a);
+                if (plan.head_tiles > 1) hipLaunchKernelGGL((gqa_decode_kernel<128, true>), dim3((unsigned)units), dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL((gqa_decode_kernel<128, false>), dim3((unsigned)units), dim3(256), 0, stream, a);
                 break;
             case Path::GqaMx128:
-                hipLaunchKernelGGL(gqa_mxfp4_kernel, dim3((unsigned)units), dim3(256), 0, stream, a);
+                if (plan.head_tiles > 1) hipLaunchKernelGGL(gqa_mxfp4_kernel<true>, dim3((unsigned)units), dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL(gqa_mxfp4_kernel<false>, dim3((unsigned)units), dim3(256), 0, stream, a);
                 break;
             case Path::GqaF8_128:
-                hipLaunchKernelGGL(gqa_fp8_kernel, dim3((unsigned)units), dim3(256), 0, stream, a);
+                if (plan.head_tiles > 1) hipLaunchKernelGGL(gqa_fp8_kernel<true>, dim3((unsigned)units), dim3(256), 0, stream, a);
+                else hipLaunchKernelGGL(gqa_fp8_kernel<false>, dim3((unsigned)units), dim3(256), 0, stream, a);
                 break;
             case Path::Mla: {
                 const int kind = p->kv_dtype == HELIX_KV_FP8_E4M3 ? 1 : p->kv_dtype == HELIX_KV_MXFP4 ? 2 : 0;

@@ -23,7 +23,7 @@ struct MergeArgs {
     // whose tile range touches it, record rec_base + g + p, rows [record][Q]
     const int64_t* tile_prefix;       // NULL: records are [split][B][Q] as split_base / n_splits say
     const int2* pair_rec;             // MLA: [pairs] the workgroups g_first .. g_first + n - 1 that hold tiles of the pair
-    const int2* row_rec;              // GQA: [rows] first and last workgroup that hold tiles of row (pair, kv head, head tile)
+    const int2* row_rec;              // GQA: [rows] first and last seat (StreamSeat) that hold tiles of row (head tile, pair, kv head)
     int32_t n_wg, rec_base;
     int32_t K, g, head_tiles;         // GQA: kv heads, query heads per kv head, head tiles per kv head (records of 16 heads)
 };
@@ -45,9 +45,9 @@ __device__ __forceinline__ StreamRecords stream_records(const MergeArgs& a, int 
         r.n = pr.y;
         r.first = (size_t)(a.rec_base + pr.x + p) * a.Q + h;
         r.stride = (size_t)a.Q;
-    } else if (a.tile_prefix[p + 1] > a.tile_prefix[p]) {      // GQA: a row per (kv head, head tile), records of 16 heads
+    } else if (a.tile_prefix[p + 1] > a.tile_prefix[p]) {      // GQA: a row per (head tile, pair, kv head), records of 16 heads
         const int kh = h / a.g, hin = h - kh * a.g, ht = hin >> 4;
-        const int row = (p * a.K + kh) * a.head_tiles + ht;
+        const int row = (ht * a.n_shards * a.B + p) * a.K + kh;
         const int2 rr = a.row_rec[row];
         r.n = rr.y - rr.x + 1;
         r.first = (size_t)(a.rec_base + rr.x + row) * 16 + (hin & 15);

@@ -37,24 +37,31 @@ constexpr int64_t kMinSplitTokensMla = 4096;
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Workgroups of an evenly cut launch over `rows` rows whose lengths add up to at most `row_tokens`, in tiles of
-// `tile` tokens: one per CU (three for MXFP4 K/V) unless the launch is small, or as many as the caller's run
+// Workgroups of an evenly cut launch over rows whose lengths add up to at most `row_tokens`, `row_tiles` tiles:
+// one per CU (three for MXFP4 K/V) unless the launch is small, or as many as the caller's run
 // length asks for.  Measured on the 1 GiB GQA share: 256 sequential streams read 6.8 TB/s, 512 6.5, 1024 6.2.
-inline int64_t stream_workgroups(const helix_problem* p, Path path, int64_t row_tokens, int64_t row_tiles)
+// A GQA launch with several head tiles per kv head (row_tokens and row_tiles count every head tile) consists of
+// head_tiles equal sets of workgroups, one per head tile, cut alike; a set has a multiple of 8 workgroups where the
+// launch is large enough, so that the workgroups that read the same tokens land on the same XCD.
+inline int64_t stream_workgroups(const helix_problem* p, Path path, int64_t head_tiles, int64_t row_tokens, int64_t row_tiles)
 {
+    if (path == Path::Mla) {
+        if (p->split_tokens > 0) return std::max<int64_t>(1, ceil_div(row_tokens, ceil_div(p->split_tokens, 32) * 32));
+        return std::min(kTargetWorkgroups, std::max<int64_t>(1, row_tokens / kStreamMinTokensMla));
+    }
+    const int64_t set_tokens = row_tokens / head_tiles, set_tiles = row_tiles / head_tiles;      // of one head tile
     int64_t n;
     if (p->split_tokens > 0) {
-        const int64_t tile = path == Path::Mla ? 32 : 128;
-        n = std::max<int64_t>(1, ceil_div(row_tokens, ceil_div(p->split_tokens, tile) * tile));
-    } else if (path == Path::Mla) {
-        n = std::min(kTargetWorkgroups, std::max<int64_t>(1, row_tokens / kStreamMinTokensMla));
+        n = std::max<int64_t>(1, ceil_div(set_tokens, ceil_div(p->split_tokens, 128) * 128));
     } else {
         // (e4m3 K/V stream like bf16 ones: measured 6.8 TB/s with 256 workgroups, 6.5 with 512, 6.2 with 768 and more)
-        n = std::min(path == Path::GqaMx128 ? kTargetWorkgroupsMx : kTargetWorkgroups, std::max<int64_t>(1, row_tiles));
+        int64_t target = std::max<int64_t>(1, (path == Path::GqaMx128 ? kTargetWorkgroupsMx : kTargetWorkgroups) / head_tiles);
+        if (head_tiles > 1 && target >= 8) target = target / 8 * 8;
+        n = std::min(target, std::max<int64_t>(1, set_tiles));
     }
     // the MXFP4 kernel addresses a run with 32-bit byte offsets
-    if (path == Path::GqaMx128) n = std::max(n, ceil_div(row_tokens, (int64_t)1 << 25));
-    return n;
+    if (path == Path::GqaMx128) n = std::max(n, ceil_div(set_tokens, (int64_t)1 << 25));
+    return n * head_tiles;
 }
 
 // Bytes of the maps of one evenly cut launch, 256-byte aligned: the tile prefix [pairs + 1] int64, then MLA: the
@@ -126,7 +133,7 @@ inline int make_plan(const helix_problem* p, Path path, const int32_t* max_lens,
                 row_tokens += (int64_t)p->batch * rows_per_pair * max_lens[s0 + i];
                 row_tiles += (int64_t)p->batch * rows_per_pair * ceil_div(max_lens[s0 + i], plan->granule);
             }
-            const int64_t n_wg = stream_workgroups(p, path, row_tokens, row_tiles);
+            const int64_t n_wg = stream_workgroups(p, path, path == Path::Mla ? 1 : plan->head_tiles, row_tokens, row_tiles);
             const int64_t pairs = (int64_t)cnt * p->batch, rows = pairs * rows_per_pair;
             if (n_wg > (int64_t)1 << 20 || rows > (int64_t)1 << 28) return HELIX_ERR_SHAPE;
             plan->total_splits += n_wg + rows;

@@ -173,6 +173,13 @@ def test_plans_follow_from_the_upper_bounds(hx):
     assert hx.helix_attn_plan(hx.Problem(2, 128, 1, 576, 512, 0.07, v_aliases_k=True, split_tokens=64), [1000, 24])[1] == 32
     # more shards than one launch carries: a plan per launch
     assert hx.helix_attn_plan(gqa, [131072] * 20)[1] == 512
+    # more than 16 query heads per KV head: one set of workgroups per head tile, a multiple of 8 each where the launch
+    # is large enough (the workgroups that read the same tokens then share an XCD), the sets cut alike
+    assert hx.helix_attn_plan(hx.Problem(2, 32, 1, 128, 128, 0.088), [524288]) == (8192, 256)          # 2 x 128
+    assert hx.helix_attn_plan(hx.Problem(2, 80, 2, 128, 128, 0.088), [524288])[1] == 240               # 3 x 80
+    assert hx.helix_attn_plan(hx.Problem(1, 128, 1, 128, 128, 0.088), [1 << 20])[1] == 256             # 8 x 32
+    assert hx.helix_attn_plan(hx.Problem(1, 40, 1, 64, 64, 0.125), [600])[1] == 15                     # 3 x 5 tiles
+    assert hx.helix_attn_plan(hx.Problem(2, 32, 1, 128, 128, 0.088, split_tokens=1000), [10000])[1] == 40
 
 
 def test_mxfp4_and_hopb_argument_errors_without_gpu(hx):

@@ -145,6 +145,48 @@ def test_gqa_many_pairs_plan_through_shared_memory(hx, oracle, B, Q, K, D, N, S,
     assert (lse2[torch.from_numpy(has).cuda()] - lse[torch.from_numpy(has).cuda()]).abs().max().item() <= 1e-5
 
 
+@pytest.mark.parametrize("fmt", ["bf16", "e4m3", "mxfp4"])
+@pytest.mark.parametrize("B,Q,K,N,S,split", [
+    (3, 80, 2, 2, 9000, 0),             # three head tiles (the last with 8 heads), sets of 80 workgroups: ids 8 apart share tokens
+    (1, 128, 1, 1, 40000, 0),           # multi-query attention with 128 heads: eight sets of 32
+    (2, 34, 1, 3, 700, 0),              # a small launch: sets of fewer than 8 workgroups, head tile after head tile
+    (2, 64, 2, 1, 5000, 384),           # forced short runs
+])
+def test_gqa_head_tiles_side_by_side(hx, oracle, fmt, B, Q, K, N, S, split):
+    """More than 16 query heads per KV head: the launch is head_tiles equal sets of workgroups that are cut alike, so
+    that the workgroups of different head tiles read the same tokens at the same time (through one XCD's L2 where
+    the sets are multiples of 8).  Ragged lengths incl. an empty sequence where the batch allows; the workspace is
+    filled with NaN, so a record nobody wrote, or a row served twice or not at all, shows in the result."""
+    from paper_2507_07120_amd import harness
+    D = 128
+    w = synth.Workload("gqa_tiles", B=B, Q=Q, K=K, dk=D, dv=D, n_shards=N, scale=1 / math.sqrt(D), seed=1300 + Q, seq_len=S,
+                       fp8=fmt == "e4m3", fp4=fmt == "mxfp4")
+    inp = synth.make_inputs(w, "cuda")
+    lens = [S, S // 3 + 1, 0][:B]
+    inp.lens = torch.tensor(lens, dtype=torch.int32)
+    prob = harness.problem_for(w, split)
+    ss = harness.make_shards(inp.k, inp.v, inp.lens.cuda(), N, kv_scale=inp.kv_scale, mx=(inp.k_mx, inp.v_mx) if fmt == "mxfp4" else None)
+    ws = harness.workspace_for(prob, N, max(ss.max_lens), "cuda")
+    ws.view(torch.float32)[: ws.numel() // 4].fill_(float("nan"))
+    o = torch.full((B, Q, D), float("nan"), device="cuda")
+    lse = torch.full((B, Q), float("nan"), device="cuda")
+    hx.helix_attn_decode(prob, inp.q, ss.shards, o, ws, lse_out=lse)
+    torch.cuda.synchronize()
+    ln = inp.lens.numpy()
+    if fmt == "mxfp4":
+        o_ref, lse_ref = oracle.attention(synth.bits(inp.q), inp.k.cpu().numpy(), inp.v.cpu().numpy(), ln, w.scale, kv_heads=K,
+                                          mx=(inp.k_mx.cpu().numpy(), inp.v_mx.cpu().numpy()))
+    elif fmt == "e4m3":
+        o_ref, lse_ref = oracle.attention(synth.bits(inp.q), inp.k.cpu().numpy(), inp.v.cpu().numpy(), ln, w.scale, kv_heads=K,
+                                          kv_scale=inp.kv_scale.cpu().numpy())
+    else:
+        o_ref, lse_ref = oracle.attention(synth.bits(inp.q), synth.bits(inp.k), synth.bits(inp.v), ln, w.scale, kv_heads=K, dv=D)
+    has = ln > 0
+    check_o(o.cpu().numpy()[has], o_ref[has], f"{fmt} g={Q // K} O")
+    check_lse(lse.cpu().numpy(), lse_ref, f"{fmt} g={Q // K} LSE")
+    assert np.all(o.cpu().numpy()[~has] == 0)
+
+
 def test_tiny_gqa_config(hx, oracle):
     """B=1, 8 query / 2 KV heads, d=64, S=4096 in 4 equal shards: the full first configuration."""
     w = synth.WORKLOADS["tiny_gqa"]
