@@ -222,6 +222,12 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             FinishArgs f;
             f.m = m; f.o = o; f.lse_out = lse_out; f.keep_parts = keep_parts ? 1 : 0;
             const unsigned frows = (unsigned)((int64_t)p->batch * p->q_heads);
+            if (plan.stream && p->dv != 512 && (int64_t)frows >= helix::kManyRows) {
+                // many rows: a thread group per row instead of a workgroup per row
+                if (p->dv == 64) hipLaunchKernelGGL((finish_rows_kernel<64>), dim3((frows + 15) / 16), dim3(256), 0, stream, f);
+                else hipLaunchKernelGGL((finish_rows_kernel<128>), dim3((frows + 7) / 8), dim3(256), 0, stream, f);
+                return launch_status();
+            }
             if (plan.stream) {
                 auto threads = [&](int row_threads, int sublanes, int groups) { return dim3((unsigned)(row_threads * sublanes * std::min<int32_t>(cnt, groups))); };
                 switch (p->dv) {
@@ -237,6 +243,12 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             return launch_status();
         }
         const unsigned mrows = (unsigned)((int64_t)cnt * p->batch * p->q_heads);
+        if (plan.stream && p->dv != 512 && (int64_t)mrows >= helix::kManyRows) {
+            if (p->dv == 64) hipLaunchKernelGGL((merge_rows_kernel<64>), dim3((mrows + 15) / 16), dim3(256), 0, stream, m);
+            else hipLaunchKernelGGL((merge_rows_kernel<128>), dim3((mrows + 7) / 8), dim3(256), 0, stream, m);
+            if (int rc = launch_status()) return rc;
+            continue;
+        }
         switch (p->dv) {
             case 64: hipLaunchKernelGGL((merge_splits_kernel<64>), dim3(mrows), dim3(256), 0, stream, m); break;
             case 128: hipLaunchKernelGGL((merge_splits_kernel<128>), dim3(mrows), dim3(256), 0, stream, m); break;

@@ -182,7 +182,9 @@ constexpr int stream_sublanes() { return DV >= 512 ? 1 : 8; }
 template <int DV>
 constexpr int finish_groups() { return 1024 / (finish_row_threads<DV>() * stream_sublanes<DV>()) < 8 ? 1024 / (finish_row_threads<DV>() * stream_sublanes<DV>()) : 8; }
 
-template <int DV, int NV>
+// WITH_O = false folds the reference exponents and normalisers only (the same operations on them, hence the same
+// Mt and Lt, without touching the O rows).
+template <int DV, int NV, bool WITH_O = true>
 __device__ __forceinline__ void fold_stream_records(const MergeArgs& a, const StreamRecords& recs, int sub, int nsub, int c0, int cstride,
                                                     f32x4 (&acc)[NV], float& Mt, float& Lt)
 {
@@ -208,8 +210,10 @@ __device__ __forceinline__ void fold_stream_records(const MergeArgs& a, const St
                 lj[u] = a.ws_l[at];
                 // (the O row of an empty record was never written: it is read all the same, to keep the two loads
                 // independent, and dropped below)
+                if constexpr (WITH_O) {
 #pragma unroll
-                for (int v = 0; v < NV; v++) oj[u][v] = *reinterpret_cast<const f32x4*>(a.ws_o + at * DV + c0 + v * cstride);
+                    for (int v = 0; v < NV; v++) oj[u][v] = *reinterpret_cast<const f32x4*>(a.ws_o + at * DV + c0 + v * cstride);
+                }
             }
         }
 #pragma unroll
@@ -275,6 +279,46 @@ __device__ __forceinline__ void merge_stream_row(const MergeArgs& a, bool active
             }
         }
         __syncthreads();                  // the staging area is free for the next row
+    }
+    M = Mt;
+    L = Lt;
+    const float inv = (Lt > 0.f) ? 1.f / Lt : 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; v++) out[v] = acc[v] * inv;
+}
+
+// merge_stream_row done by ONE thread group on its own, without shared memory or barriers: the sub-lanes' folds one
+// after the other, then their results in sub-lane order -- the same operations on the same values as
+// merge_stream_row, hence the same bits.  For launches with so many rows that a workgroup per row would be bound by
+// the rate at which workgroups start (a row then has one or two records as a rule).
+template <int DV, int NV, int SUB, bool WITH_O = true>
+__device__ __forceinline__ void merge_stream_row_alone(const MergeArgs& a, int i, int b, int h, int c0, int cstride,
+                                                       f32x4 (&out)[NV], float& M, float& L)
+{
+    const StreamRecords recs = stream_records(a, i, b, h);
+    f32x4 acc[NV];
+    float Mt, Lt;
+    if constexpr (SUB == 1) {
+        fold_stream_records<DV, NV, WITH_O>(a, recs, 0, 1, c0, cstride, acc, Mt, Lt);
+    } else {
+        // the largest reference exponent of the row's records is what the sub-lanes' results are scaled to
+        Mt = -INFINITY;
+        for (int j = 0; j < recs.n; j++) Mt = fmaxf(Mt, a.ws_m[recs.first + (size_t)j * recs.stride]);
+        Lt = 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; v++) acc[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (Mt != -INFINITY) {
+#pragma unroll 1
+            for (int k = 0; k < SUB && k < recs.n; k++) {             // (a sub-lane without records adds zeros)
+                f32x4 pk[NV];
+                float mk, lk;
+                fold_stream_records<DV, NV, WITH_O>(a, recs, k, SUB, c0, cstride, pk, mk, lk);
+                const float f = __builtin_amdgcn_exp2f(mk - Mt);       // 0 for a sub-lane whose records are all empty
+                Lt += lk * f;
+#pragma unroll
+                for (int v = 0; v < NV; v++) acc[v] += pk[v] * f;
+            }
+        }
     }
     M = Mt;
     L = Lt;
@@ -399,6 +443,83 @@ __global__ __launch_bounds__(finish_row_threads<DV>() * stream_sublanes<DV>() * 
         *reinterpret_cast<f32x4*>(f.o + (size_t)rem * DV + c) = acc;
     }
     if (tid == 0 && f.lse_out) f.lse_out[rem] = (top != -INFINITY) ? top + __logf(wsum) : -INFINITY;
+}
+
+// finish_stream_kernel for launches with many (b, h) rows: 256 / finish_row_threads rows per workgroup, every row
+// folded and combined by its own thread group (merge_stream_row_alone) -- two passes over the shards, the first over
+// the normalisers only, for the largest lse, the second folding every fragment once more and weighing it at once,
+// in shard order: the operations of finish_stream_kernel on the same values.
+constexpr int64_t kManyRows = 2048;       // from this many rows on the launch is cut by rows, not by workgroups per row
+
+template <int DV>
+__global__ __launch_bounds__(256) void finish_rows_kernel(const FinishArgs f)
+{
+    constexpr int TPR = finish_row_threads<DV>(), NV = DV / (4 * TPR), SUB = stream_sublanes<DV>(), RPW = 256 / TPR;
+    static_assert(DV == 64 || DV == 128, "the host launches 256 / (DV / 4) rows per workgroup");
+    const MergeArgs& a = f.m;
+    const int tid = threadIdx.x, c0 = (tid % TPR) * 4;
+    const int64_t bq = (int64_t)a.B * a.Q;
+    const int64_t rem = (int64_t)blockIdx.x * RPW + tid / TPR;       // b*Q + h
+    if (rem >= bq) return;
+    const int b = (int)(rem / a.Q), h = (int)(rem - (int64_t)b * a.Q);
+    float top = -INFINITY;
+    for (int i = 0; i < a.n_shards; i++) {
+        f32x4 none[NV];
+        float M, L;
+        merge_stream_row_alone<DV, NV, SUB, false>(a, i, b, h, c0, 4 * TPR, none, M, L);
+        top = fmaxf(top, lse_of(M, L));
+    }
+    f32x4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; v++) acc[v] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float wsum = 0.f;
+    for (int i = 0; i < a.n_shards; i++) {
+        f32x4 o[NV];
+        float M, L;
+        merge_stream_row_alone<DV, NV, SUB>(a, i, b, h, c0, 4 * TPR, o, M, L);
+        const float lse = lse_of(M, L);
+        if (f.keep_parts) {
+#pragma unroll
+            for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(a.o_part + ((size_t)i * bq + rem) * DV + c0 + v * 4 * TPR) = o[v];
+            if (c0 == 0) a.lse_part[(size_t)i * bq + rem] = lse;
+        }
+        if (top == -INFINITY || lse == -INFINITY) continue;
+        float wnext = wsum;               // (every column group of the thread takes the same step)
+#pragma unroll
+        for (int v = 0; v < NV; v++) {
+            wnext = wsum;
+            combine_accumulate(acc[v], wnext, o[v], lse, top);
+        }
+        wsum = wnext;
+    }
+    if (top != -INFINITY) {
+#pragma unroll
+        for (int v = 0; v < NV; v++) acc[v] *= 1.f / wsum;
+    }
+#pragma unroll
+    for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(f.o + (size_t)rem * DV + c0 + v * 4 * TPR) = acc[v];
+    if (c0 == 0 && f.lse_out) f.lse_out[rem] = (top != -INFINITY) ? top + __logf(wsum) : -INFINITY;
+}
+
+// merge_splits_kernel for evenly cut launches with many rows: a thread group per (shard, b, h) row.
+template <int DV>
+__global__ __launch_bounds__(256) void merge_rows_kernel(const MergeArgs a)
+{
+    constexpr int TPR = finish_row_threads<DV>(), NV = DV / (4 * TPR), SUB = stream_sublanes<DV>(), RPW = 256 / TPR;
+    const int tid = threadIdx.x, c0 = (tid % TPR) * 4;
+    const int64_t bq = (int64_t)a.B * a.Q;
+    const int64_t row = (int64_t)blockIdx.x * RPW + tid / TPR;       // (i*B + b)*Q + h
+    if (row >= bq * a.n_shards) return;
+    const int i = (int)(row / bq);
+    const int64_t rem = row - (int64_t)i * bq;
+    const int b = (int)(rem / a.Q), h = (int)(rem - (int64_t)b * a.Q);
+    f32x4 o[NV];
+    float M, L;
+    merge_stream_row_alone<DV, NV, SUB>(a, i, b, h, c0, 4 * TPR, o, M, L);
+    const size_t orow = (size_t)(a.shard0 + i) * bq + rem;
+#pragma unroll
+    for (int v = 0; v < NV; v++) *reinterpret_cast<f32x4*>(a.o_part + orow * DV + c0 + v * 4 * TPR) = o[v];
+    if (c0 == 0) a.lse_part[orow] = lse_of(M, L);
 }
 
 // merge_splits + combine in one launch for calls with at most kMaxLaunchShards shards:

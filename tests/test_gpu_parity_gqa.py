@@ -187,6 +187,49 @@ def test_gqa_head_tiles_side_by_side(hx, oracle, fmt, B, Q, K, N, S, split):
     assert np.all(o.cpu().numpy()[~has] == 0)
 
 
+@pytest.mark.parametrize("B,Q,K,D,N,S,split", [
+    (600, 8, 2, 64, 3, 400, 0),         # 4800 rows of one or two records, three shards, d=64
+    (150, 16, 1, 128, 1, 3000, 128),    # 2400 rows of up to 24 records each: several per sub-lane of the fold
+    (300, 8, 1, 128, 20, 2000, 0),      # more shards than one launch carries: fragments per launch, then the combine
+])
+def test_gqa_many_rows_are_finished_by_thread_groups(hx, oracle, B, Q, K, D, N, S, split):
+    """From 2048 (b, h) rows on, the records of a row are folded and the shards combined by one thread group per row
+    instead of one workgroup per row (a workgroup per row is bound by the rate at which workgroups start).  Same
+    operations on the same values: the usual bars against the oracle for output, fragments and LSEs, and the public
+    combine on the stored fragments reproduces the fused output bit for bit (run_sharded checks both)."""
+    w = synth.Workload("many_rows", B=B, Q=Q, K=K, dk=D, dv=D, n_shards=N, scale=1 / math.sqrt(D), seed=700 + B, seq_len=S)
+    inp = synth.make_inputs(w, "cuda")
+    lens = synth.uniform_lengths(17, 3, B, 0, S)
+    lens[:4] = torch.tensor([0, S, 1, 129], dtype=torch.int32)
+    inp.lens = lens
+    run_sharded(hx, oracle, w, inp, N, split_tokens=split)
+
+
+def test_gqa_partial_of_many_rows(hx, oracle):
+    """helix_attn_partial on a batch with 2400 (b, h) rows: the split records are merged by thread groups."""
+    from paper_2507_07120_amd import harness
+    B, Q, S = 300, 8, 1500
+    w = synth.Workload("many_rows_partial", B=B, Q=Q, K=1, dk=128, dv=128, n_shards=1, scale=1 / math.sqrt(128), seed=41, seq_len=S)
+    inp = synth.make_inputs(w, "cuda")
+    lens = synth.uniform_lengths(19, 3, B, 0, S)
+    lens[:3] = torch.tensor([0, S, 1], dtype=torch.int32)
+    inp.lens = lens
+    prob = harness.problem_for(w)
+    shard = hx.KVShard.from_padded(inp.k, inp.v, inp.lens.cuda(), S)
+    ws = harness.workspace_for(prob, 1, S, "cuda")
+    ws.view(torch.float32)[: ws.numel() // 4].fill_(float("nan"))
+    o = torch.full((B, Q, 128), float("nan"), device="cuda")
+    lse = torch.full((B, Q), float("nan"), device="cuda")
+    hx.helix_attn_partial(prob, inp.q, shard, o, lse, ws)
+    torch.cuda.synchronize()
+    ln = inp.lens.numpy()
+    o_ref, lse_ref = oracle.attention(synth.bits(inp.q), synth.bits(inp.k), synth.bits(inp.v), ln, w.scale, kv_heads=1, dv=128)
+    has = ln > 0
+    check_o(o.cpu().numpy()[has], o_ref[has], "partial of many rows O")
+    check_lse(lse.cpu().numpy(), lse_ref, "partial of many rows LSE")
+    assert np.all(o.cpu().numpy()[~has] == 0)
+
+
 def test_tiny_gqa_config(hx, oracle):
     """B=1, 8 query / 2 KV heads, d=64, S=4096 in 4 equal shards: the full first configuration."""
     w = synth.WORKLOADS["tiny_gqa"]
