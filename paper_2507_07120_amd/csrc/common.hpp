@@ -147,6 +147,15 @@ __device__ __forceinline__ T stream_load(const T* p)
     else return *p;
 }
 
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait for the wave's global
+// loads and stores (a record's stores take a microsecond or two to be acknowledged).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __device__ __forceinline__ uint32_t as_u32(float x) { return __builtin_bit_cast(uint32_t, x); }
 __device__ __forceinline__ float as_f32(uint32_t x) { return __builtin_bit_cast(float, x); }
 

@@ -225,14 +225,14 @@ __device__ __forceinline__ void gqa_emit_record(GqaState<D>& st, const AttnArgs&
     __shared__ float sm_o[4][16][D];
     st.l = wave_xor_sum_16_32(st.l);
     if (kc == 0) { sm_m[wave][r] = st.m; sm_l[wave][r] = st.l; }
-    __syncthreads();
+    lds_barrier();
     const float M = max_of_waves(sm_m, r);
     const float f = (st.m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(st.m - M);
 #pragma unroll
     for (int c = 0; c < C::CPL; c++)
 #pragma unroll
         for (int i = 0; i < 4; i++) sm_o[wave][r][(kc * 4 + i) * C::CPL + c] = st.o[c][i] * f;
-    __syncthreads();
+    lds_barrier();
     if (tid < nh) {
         float L = 0.f;
 #pragma unroll
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
     }
 
     gqa_emit_record<D>(st, a, rec, nh, tid, wave, r, kc);
-    __syncthreads();                  // the record's staging area in LDS is free for the next run
+    lds_barrier();                    // the record's staging area in LDS is free for the next run (its stores may still be on their way)
     }
 }
 

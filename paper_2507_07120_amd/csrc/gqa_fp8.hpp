@@ -193,7 +193,7 @@ __global__ __launch_bounds__(256, 2) void gqa_fp8_kernel(const AttnArgs a)
     }
 
     gqa_emit_record<D>(st, a, rec, nh, tid, wave, r, kc);
-    __syncthreads();                  // the record's staging area in LDS is free for the next run
+    lds_barrier();                    // the record's staging area in LDS is free for the next run (its stores may still be on their way)
     }
 }
 

@@ -146,14 +146,8 @@ __device__ __forceinline__ int mla_opaque(int x)
 // Byte offset of (row, 16-byte chunk c) inside an LDS tile.
 __device__ __forceinline__ int mla_swz(int row, int c) { return row * MlaCfg::ROW + ((c ^ (row & 7)) << 4); }
 
-// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it leaves global loads and
-// LDS DMA in flight.
-__device__ __forceinline__ void mla_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
+// (the workgroup barrier that orders LDS traffic only and leaves global loads and LDS DMA in flight)
+__device__ __forceinline__ void mla_barrier() { lds_barrier(); }
 
 // Waits until at most N of this wave's vector memory loads (LDS DMA included) are outstanding.
 template <int N>
