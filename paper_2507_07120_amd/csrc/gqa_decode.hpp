@@ -324,6 +324,11 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
     const int nw = n_full > wave ? (n_full - wave + 3) / 4 : 0;
     auto kptr = [&](int i) { return kbase + (size_t)(wave + 4 * i) * k_blk_bytes; };
     auto vptr = [&](int i) { return vbase + (size_t)(wave + 4 * i) * v_blk_bytes; };
+    // The ragged last block of the run, if any, belongs to wave (n_full % 4), which takes it FIRST: requested
+    // together with the wave's first full block, it is not waited for at the end of the run by the three other waves.
+    const bool tail_mine = n_blk > n_full && (n_full & 3) == wave;
+    const int n_tail = n_tok - n_full * C::TB;
+    if (tail_mine) gqa_load_block<D, true, NT>(b1, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, k_row_bytes, v_row_bytes, r, kc, n_tail);
     if (nw > 0) gqa_load_block<D, false, NT>(b0, kptr(0), vptr(0), k_row_bytes, v_row_bytes, r, kc, C::TB);
 
     // (fetched after the first K/V block is on its way: the stream does not depend on Q)
@@ -339,6 +344,7 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
         }
     }
 
+    if (tail_mine) gqa_compute_block<D, true>(st, b1, qb, a.scale_log2e, kc, n_tail);
     if (nw > 0) {
         int i = 0;
         for (; i + 2 < nw; i += 2) {
@@ -354,12 +360,6 @@ __global__ __launch_bounds__(256, 2) void gqa_decode_kernel(const AttnArgs a)
         } else {
             gqa_compute_block<D, false>(st, b0, qb, a.scale_log2e, kc, C::TB);
         }
-    }
-    // the ragged last block, if any, belongs to wave (n_full % 4)
-    if (n_blk > n_full && (n_full & 3) == wave) {
-        const int nv = n_tok - n_full * C::TB;
-        gqa_load_block<D, true, NT>(b0, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, k_row_bytes, v_row_bytes, r, kc, nv);
-        gqa_compute_block<D, true>(st, b0, qb, a.scale_log2e, kc, nv);
     }
 
     gqa_emit_record<D>(st, a, rec, nh, tid, wave, r, kc);

@@ -160,6 +160,11 @@ __global__ __launch_bounds__(256, 2) void gqa_fp8_kernel(const AttnArgs a)
         f8_load_block<false, NT>(raw, kbase + blk * k_blk_bytes, vbase + blk * v_blk_bytes, sbase + blk * C::TB, k_row_bytes, v_row_bytes, r, kc, C::TB);
     };
     F8Raw r0, r1;
+    // the ragged last block of the run, if any, belongs to wave (n_full % 4), which takes it first (requested together
+    // with the wave's first full block, so that nobody waits for it at the end of the run)
+    const bool tail_mine = n_blk > n_full && (n_full & 3) == wave;
+    const int n_tail = n_tok - n_full * C::TB;
+    if (tail_mine) f8_load_block<true, NT>(r1, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, sbase + (size_t)n_full * C::TB, k_row_bytes, v_row_bytes, r, kc, n_tail);
     if (nw > 0) load(r0, 0);
 
     // Q as the score MFMA's B operand, in the dim order of the K operand: lane (r,kc) holds head r,
@@ -175,6 +180,7 @@ __global__ __launch_bounds__(256, 2) void gqa_fp8_kernel(const AttnArgs a)
         }
     }
 
+    if (tail_mine) f8_compute_block<true>(st, r1, qb, a.scale_log2e, kc, n_tail);
     if (nw > 0) {
         int i = 0;
         for (; i + 2 <= nw; i += 2) {
@@ -184,12 +190,6 @@ __global__ __launch_bounds__(256, 2) void gqa_fp8_kernel(const AttnArgs a)
             f8_compute_block<false>(st, r1, qb, a.scale_log2e, kc, C::TB);
         }
         if (i < nw) f8_compute_block<false>(st, r0, qb, a.scale_log2e, kc, C::TB);
-    }
-    // the ragged last block, if any, belongs to wave (n_full % 4)
-    if (n_blk > n_full && (n_full & 3) == wave) {
-        const int nv = n_tok - n_full * C::TB;
-        f8_load_block<true, NT>(r0, kbase + n_full * k_blk_bytes, vbase + n_full * v_blk_bytes, sbase + (size_t)n_full * C::TB, k_row_bytes, v_row_bytes, r, kc, nv);
-        f8_compute_block<true>(st, r0, qb, a.scale_log2e, kc, nv);
     }
 
     gqa_emit_record<D>(st, a, rec, nh, tid, wave, r, kc);

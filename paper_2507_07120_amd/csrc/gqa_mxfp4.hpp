@@ -233,6 +233,15 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
     in.init(kbase, vbase, ksbase, vsbase, k_row_bytes, v_row_bytes, r, kc);
     auto load = [&](Mx4Raw& raw, int i) { in.template load<NT>(raw, (uint32_t)(wave + 4 * min(i, nw - 1)) * C::TB); };
     Mx4Raw r0, r1;
+    // the ragged last block of the run, if any, belongs to wave (n_full % 4), which takes it first (requested together
+    // with the wave's first full block, so that nobody waits for it at the end of the run)
+    const bool tail_mine = n_blk > n_full && (n_full & 3) == wave;
+    const int n_tail = n_tok - n_full * C::TB;
+    if (tail_mine) {
+        const size_t blk0 = (size_t)n_full * C::TB;
+        mx4_load_block<true, NT>(r1, kbase + blk0 * k_row_bytes, vbase + blk0 * v_row_bytes, ksbase + blk0 * (k_row_bytes / 16u),
+                                 vsbase + blk0 * (v_row_bytes / 16u), k_row_bytes, v_row_bytes, r, kc, n_tail);
+    }
     if (nw > 0) load(r0, 0);
 
     // Q as the score MFMA's B operand, in the dim order of the K operand: lane (r,kc) holds head r,
@@ -248,6 +257,7 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
         }
     }
 
+    if (tail_mine) mx4_compute_block<true>(st, r1, qb, a.scale_log2e, r, kc, n_tail);
     if (nw > 0) {
         int i = 0;
         for (; i + 2 <= nw; i += 2) {
@@ -258,15 +268,6 @@ __global__ __launch_bounds__(256, 3) void gqa_mxfp4_kernel(const AttnArgs a)
         }
         if (i < nw) mx4_compute_block<false>(st, r0, qb, a.scale_log2e, r, kc, C::TB);
     }
-    // the ragged last block, if any, belongs to wave (n_full % 4)
-    if (n_blk > n_full && (n_full & 3) == wave) {
-        const int nv = n_tok - n_full * C::TB;
-        const size_t blk0 = (size_t)n_full * C::TB;
-        mx4_load_block<true, NT>(r0, kbase + blk0 * k_row_bytes, vbase + blk0 * v_row_bytes, ksbase + blk0 * (k_row_bytes / 16u),
-                             vsbase + blk0 * (v_row_bytes / 16u), k_row_bytes, v_row_bytes, r, kc, nv);
-        mx4_compute_block<true>(st, r0, qb, a.scale_log2e, r, kc, nv);
-    }
-
     gqa_emit_record<D>(st, a, rec, nh, tid, wave, r, kc);
     lds_barrier();                    // the record's staging area in LDS is free for the next run (its stores may still be on their way)
     }
