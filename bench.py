@@ -135,7 +135,10 @@ def read_traffic(workload: str):
 def kernel_name(w) -> str:
     if w.mla:
         return "mla_decode_kernel<" + ("mxfp4" if getattr(w, "fp4", False) else "e4m3" if w.fp8 else "bf16") + ">"
-    return "gqa_mxfp4_kernel" if getattr(w, "fp4", False) else "gqa_fp8_kernel" if w.fp8 else f"gqa_decode_kernel<{w.dk}>"
+    shared = "true" if w.Q // w.K > 16 else "false"        # several head tiles per KV head: the variant whose loads stay in the L2
+    if getattr(w, "fp4", False):
+        return f"gqa_mxfp4_kernel<{shared}>"
+    return f"gqa_fp8_kernel<{shared}>" if w.fp8 else f"gqa_decode_kernel<{w.dk}, {shared}>"
 
 
 def measure(name, args, budget_macs, extras=False):
