@@ -1,5 +1,6 @@
 // Shared device-side types and helpers of the gfx950 decode-attention kernels.
 #pragma once
+#include "seat.hpp"
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -237,15 +238,10 @@ __device__ __forceinline__ StreamSeat stream_seat(const AttnArgs& a)
     s.n_wg = a.n_wg;
     s.ht = 0;
     if (a.head_tiles > 1) {
+        const SeatOf at = seat_of((int)blockIdx.x, a.head_tiles, a.n_base);
         s.n_wg = a.n_base;
-        if ((a.n_base & 7) == 0) {
-            const int grp = (int)blockIdx.x / (8 * a.head_tiles), in = (int)blockIdx.x - grp * 8 * a.head_tiles;
-            s.ht = in >> 3;
-            s.wg = grp * 8 + (in & 7);
-        } else {
-            s.ht = (int)blockIdx.x / a.n_base;
-            s.wg = (int)blockIdx.x - s.ht * a.n_base;
-        }
+        s.ht = at.ht;
+        s.wg = at.wg;
     }
     s.seat = s.ht * s.n_wg + s.wg;
     return s;

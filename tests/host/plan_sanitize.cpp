@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "../../paper_2507_07120_amd/csrc/plan.hpp"
+#include "../../paper_2507_07120_amd/csrc/seat.hpp"
 
 using namespace helix_host;
 
@@ -136,6 +137,24 @@ int main()
                 kvp_slices(&cache, n, shards.data());
                 for (int i = 0; i < n; i++) CHECK(shards[i].max_len >= 0 && shards[i].max_len <= cache.max_len);
             }
+        }
+    }
+    // streaming GQA launches with several head tiles: the map from workgroup id to (head tile, place in the set) is
+    // one to one, and with sets of a multiple of 8 the workgroups of one place share their id modulo 8 (one XCD)
+    for (int head_tiles = 2; head_tiles <= 9; head_tiles++) {
+        for (int n_base : {1, 2, 5, 8, 13, 16, 24, 80, 128}) {
+            std::vector<int> seen((size_t)head_tiles * n_base, -1);
+            for (int id = 0; id < head_tiles * n_base; id++) {
+                const helix::SeatOf at = helix::seat_of(id, head_tiles, n_base);
+                CHECK(at.ht >= 0 && at.ht < head_tiles && at.wg >= 0 && at.wg < n_base);
+                int& slot = seen[(size_t)at.ht * n_base + at.wg];
+                CHECK(slot == -1);
+                slot = id;
+            }
+            if (n_base % 8 == 0)
+                for (int wg = 0; wg < n_base; wg++)
+                    for (int ht = 1; ht < head_tiles; ht++) CHECK(seen[(size_t)ht * n_base + wg] % 8 == seen[wg] % 8);
+            cases++;
         }
     }
     std::printf("ok: %ld cases, %ld planned\n", cases, planned);
