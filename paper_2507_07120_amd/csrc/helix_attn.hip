@@ -222,10 +222,15 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             FinishArgs f;
             f.m = m; f.o = o; f.lse_out = lse_out; f.keep_parts = keep_parts ? 1 : 0;
             const unsigned frows = (unsigned)((int64_t)p->batch * p->q_heads);
-            if (plan.stream && p->dv != 512 && (int64_t)frows >= helix::kManyRows) {
+            if (plan.stream && (int64_t)frows >= helix::kManyRows) {
                 // many rows: a thread group per row instead of a workgroup per row
-                if (p->dv == 64) hipLaunchKernelGGL((finish_rows_kernel<64>), dim3((frows + 15) / 16), dim3(256), 0, stream, f);
-                else hipLaunchKernelGGL((finish_rows_kernel<128>), dim3((frows + 7) / 8), dim3(256), 0, stream, f);
+                auto grid = [&](int rows_per_wg) { return dim3((frows + rows_per_wg - 1) / rows_per_wg); };
+                switch (p->dv) {
+                    case 64: hipLaunchKernelGGL((finish_rows_kernel<64>), grid(helix::finish_rows_per_workgroup<64>()), dim3(256), 0, stream, f); break;
+                    case 128: hipLaunchKernelGGL((finish_rows_kernel<128>), grid(helix::finish_rows_per_workgroup<128>()), dim3(256), 0, stream, f); break;
+                    case 512: hipLaunchKernelGGL((finish_rows_kernel<512>), grid(helix::finish_rows_per_workgroup<512>()), dim3(256), 0, stream, f); break;
+                    default: return HELIX_ERR_UNSUPPORTED;
+                }
                 return launch_status();
             }
             if (plan.stream) {
@@ -243,9 +248,14 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             return launch_status();
         }
         const unsigned mrows = (unsigned)((int64_t)cnt * p->batch * p->q_heads);
-        if (plan.stream && p->dv != 512 && (int64_t)mrows >= helix::kManyRows) {
-            if (p->dv == 64) hipLaunchKernelGGL((merge_rows_kernel<64>), dim3((mrows + 15) / 16), dim3(256), 0, stream, m);
-            else hipLaunchKernelGGL((merge_rows_kernel<128>), dim3((mrows + 7) / 8), dim3(256), 0, stream, m);
+        if (plan.stream && (int64_t)mrows >= helix::kManyRows) {
+            auto grid = [&](int rows_per_wg) { return dim3((mrows + rows_per_wg - 1) / rows_per_wg); };
+            switch (p->dv) {
+                case 64: hipLaunchKernelGGL((merge_rows_kernel<64>), grid(helix::finish_rows_per_workgroup<64>()), dim3(256), 0, stream, m); break;
+                case 128: hipLaunchKernelGGL((merge_rows_kernel<128>), grid(helix::finish_rows_per_workgroup<128>()), dim3(256), 0, stream, m); break;
+                case 512: hipLaunchKernelGGL((merge_rows_kernel<512>), grid(helix::finish_rows_per_workgroup<512>()), dim3(256), 0, stream, m); break;
+                default: return HELIX_ERR_UNSUPPORTED;
+            }
             if (int rc = launch_status()) return rc;
             continue;
         }

@@ -450,12 +450,14 @@ __global__ __launch_bounds__(finish_row_threads<DV>() * stream_sublanes<DV>() * 
 // the normalisers only, for the largest lse, the second folding every fragment once more and weighing it at once,
 // in shard order: the operations of finish_stream_kernel on the same values.
 constexpr int64_t kManyRows = 2048;       // from this many rows on the launch is cut by rows, not by workgroups per row
+template <int DV>
+constexpr int finish_rows_per_workgroup() { return 256 / finish_row_threads<DV>(); }
 
 template <int DV>
 __global__ __launch_bounds__(256) void finish_rows_kernel(const FinishArgs f)
 {
     constexpr int TPR = finish_row_threads<DV>(), NV = DV / (4 * TPR), SUB = stream_sublanes<DV>(), RPW = 256 / TPR;
-    static_assert(DV == 64 || DV == 128, "the host launches 256 / (DV / 4) rows per workgroup");
+    static_assert(RPW * TPR == 256, "rows of a workgroup (finish_rows_per_workgroup)");
     const MergeArgs& a = f.m;
     const int tid = threadIdx.x, c0 = (tid % TPR) * 4;
     const int64_t bq = (int64_t)a.B * a.Q;
