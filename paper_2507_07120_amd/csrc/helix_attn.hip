@@ -222,8 +222,9 @@ int run_partials(const helix_problem* p, const Plan& plan, const void* q, const 
             FinishArgs f;
             f.m = m; f.o = o; f.lse_out = lse_out; f.keep_parts = keep_parts ? 1 : 0;
             const unsigned frows = (unsigned)((int64_t)p->batch * p->q_heads);
-            if (plan.stream && (int64_t)frows >= helix::kManyRows) {
-                // many rows: a thread group per row instead of a workgroup per row
+            // many rows: a thread group per row instead of a workgroup per row (on the MLA width the workgroup version
+            // folds the shards side by side, so with more shards it stays ahead for longer)
+            if (plan.stream && (int64_t)frows >= helix::kManyRows * (p->dv == 512 ? cnt : 1)) {
                 auto grid = [&](int rows_per_wg) { return dim3((frows + rows_per_wg - 1) / rows_per_wg); };
                 switch (p->dv) {
                     case 64: hipLaunchKernelGGL((finish_rows_kernel<64>), grid(helix::finish_rows_per_workgroup<64>()), dim3(256), 0, stream, f); break;

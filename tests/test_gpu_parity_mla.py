@@ -120,13 +120,13 @@ def test_mla_many_short_sequences(hx, oracle):
 
 
 @pytest.mark.parametrize("fmt,B,N,S,split", [
-    ("bf16", 20, 3, 500, 0),            # 2560 (b, h) rows, three shards: fragments kept, combined in the same launch
+    ("bf16", 50, 3, 300, 0),            # 6400 (b, h) rows, three shards: fragments kept, combined in the same launch
     ("e4m3", 18, 1, 900, 96),           # forced short runs: up to ten records per row
     ("bf16", 17, 20, 700, 0),           # more shards than one launch carries: fragments per launch, then the combine
 ])
 def test_mla_many_rows_are_finished_by_thread_groups(hx, oracle, fmt, B, N, S, split):
-    """From 2048 (b, h) rows on (B >= 16 with 128 heads) the records are folded and the shards combined by one thread
-    group per row instead of one workgroup per row.  Usual bars for output, fragments and LSEs; the public combine on
+    """From 2048 (b, h) rows per shard on (B >= 16 with 128 heads) the records are folded and the shards combined by one
+    thread group per row instead of one workgroup per row.  Usual bars for output, fragments and LSEs; the public combine on
     the stored fragments reproduces the fused output bit for bit (run_mla checks both)."""
     w = synth.Workload("mla_rows", B=B, Q=128, K=1, dk=576, dv=512, n_shards=N, scale=1 / math.sqrt(192), seed=1700 + B, seq_len=S,
                        mla=True, fp8=fmt == "e4m3")
